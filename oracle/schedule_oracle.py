@@ -1,0 +1,197 @@
+"""CPU oracle for the per-rank pipeline op order, offload selection and residency.
+
+TEST INFRASTRUCTURE ONLY: the product path never imports this module.  It is an
+independent model, in plain Python integers, of what one pipeline rank executes:
+
+* 1F1B: rank i of d runs d-i-1 warm-up forwards, then alternates one forward
+  and one backward, then drains the remaining backwards (Table 1, first row;
+  Appendix A).
+* Interleaved 1F1B: v chunks per rank, bi-level order (Section 2: the outer
+  loop walks the chunks, the inner loop repeats d microbatches), with
+  d(v-1) + 2(d-i) - 1 forwards before the first backward on rank i and a peak
+  of dv + d - 1 units in flight on rank 0 (Section 3.1, warm-up paragraph).
+* Offload: a selected unit is offloaded right after its forward and reloaded
+  ``prefetch`` compute passes ahead of its backward (Section 4.2: earliest
+  slot after the forward, latest slot before the backward; on a single rank
+  with a dedicated copy queue these collapse to these two rules).
+
+Op tuples are (kind, mb, chunk) with kind in {"F", "B", "OFFLOAD", "RELOAD"}.
+"""
+from __future__ import annotations
+
+import math
+
+
+def one_f_one_b(d, rank, m):
+    """Compute passes of 1F1B on ``rank`` for m microbatches (one chunk)."""
+    warm = min(d - rank - 1, m)
+    ops = [("F", j, 0) for j in range(warm)]
+    for j in range(m - warm):
+        ops.append(("F", warm + j, 0))
+        ops.append(("B", j, 0))
+    for j in range(m - warm, m):
+        ops.append(("B", j, 0))
+    return ops
+
+
+def _interleaved_unit(k, d, v, backward):
+    group, within = divmod(k, d * v)
+    chunk = within // d
+    mb = group * d + within % d
+    return (mb, v - 1 - chunk) if backward else (mb, chunk)
+
+
+def interleaved_one_f_one_b(d, rank, v, m):
+    """Compute passes of interleaved 1F1B on ``rank``: m microbatches (m % d == 0),
+    v chunks.  The k-th forward handles microbatch group k // (d v), chunk
+    (k // d) % v; backwards walk the chunks in reverse."""
+    if m % d:
+        raise ValueError("interleaved 1F1B needs m to be a multiple of d")
+    total = m * v
+    warm = min((v - 1) * d + 2 * (d - rank - 1), total)
+    ops = []
+    for k in range(warm):
+        ops.append(("F",) + _interleaved_unit(k, d, v, False))
+    for j in range(total - warm):
+        ops.append(("F",) + _interleaved_unit(warm + j, d, v, False))
+        ops.append(("B",) + _interleaved_unit(j, d, v, True))
+    for j in range(total - warm, total):
+        ops.append(("B",) + _interleaved_unit(j, d, v, True))
+    return ops
+
+
+def compute_passes(schedule, d, rank, v, m):
+    if schedule == "1f1b":
+        if v != 1:
+            raise ValueError("1F1B has one chunk per rank")
+        return one_f_one_b(d, rank, m)
+    if schedule == "1f1b-interleaved":
+        return interleaved_one_f_one_b(d, rank, v, m)
+    raise ValueError(schedule)
+
+
+def selected_units(m, v, ratio, policy="alternate-mb"):
+    """Which (mb, chunk) units are offloaded for a whole-job offload ratio.
+
+    alternate-mb: microbatch j is offloaded iff floor((j+1) r) > floor(j r)
+    (r = 1 all, r = 0.5 the odd ones, r = 0 none), all of its chunks.
+    longest-lifespan (Section 2: prefer the chunks whose forward-to-backward gap
+    is longest, i.e. the lowest chunk indices): chunks 0 .. ceil(r v) - 1 of
+    every microbatch; with one chunk it degenerates to alternate-mb.
+    """
+    if not 0.0 <= ratio <= 1.0:
+        raise ValueError("ratio must be in [0, 1]")
+    sel = set()
+    if policy == "longest-lifespan" and v > 1:
+        n = math.ceil(ratio * v - 1e-9)
+        for j in range(m):
+            for c in range(n):
+                sel.add((j, c))
+        return sel
+    for j in range(m):
+        if math.floor((j + 1) * ratio + 1e-9) > math.floor(j * ratio + 1e-9):
+            for c in range(v):
+                sel.add((j, c))
+    return sel
+
+
+def with_offload(passes, selected, prefetch=1):
+    """Insert OFFLOAD / RELOAD ops into a list of compute passes.
+
+    OFFLOAD(u) directly follows F(u).  RELOAD(u) is placed directly before the
+    compute pass that runs ``prefetch`` passes ahead of B(u) (prefetch = 0:
+    directly before B(u) itself), but never before OFFLOAD(u).
+    """
+    pos_f = {(mb, c): n for n, (kind, mb, c) in enumerate(passes) if kind == "F"}
+    reload_before = {}
+    for n, (kind, mb, c) in enumerate(passes):
+        if kind == "B" and (mb, c) in selected:
+            at = max(n - prefetch, pos_f[(mb, c)] + 1)
+            reload_before.setdefault(at, []).append((mb, c))
+    ops = []
+    for n, (kind, mb, c) in enumerate(passes):
+        for u in reload_before.get(n, []):
+            ops.append(("RELOAD",) + u)
+        ops.append((kind, mb, c))
+        if kind == "F" and (mb, c) in selected:
+            ops.append(("OFFLOAD", mb, c))
+    return ops
+
+
+def simulate(ops):
+    """Walk an op list with zero-time copies.  Returns a dict with the peak
+    number of units in flight (forwarded, not yet backwarded), the peak number
+    resident on the device, forwards before the first backward, and a list of
+    violated invariants (empty when the list is a valid schedule)."""
+    state = {}
+    errors = []
+    in_flight = resident = peak_in_flight = peak_resident = 0
+    forwards_before_first_backward = None
+    n_forward = 0
+    for n, (kind, mb, c) in enumerate(ops):
+        u = (mb, c)
+        st = state.get(u, "EMPTY")
+        if kind == "F":
+            if st != "EMPTY":
+                errors.append(f"op {n}: forward of live unit {u}")
+            state[u] = "RESIDENT"
+            in_flight += 1
+            resident += 1
+            n_forward += 1
+        elif kind == "OFFLOAD":
+            if st != "RESIDENT":
+                errors.append(f"op {n}: offload of unit {u} in state {st}")
+            state[u] = "HOST"
+            resident -= 1
+        elif kind == "RELOAD":
+            if st != "HOST":
+                errors.append(f"op {n}: reload of unit {u} in state {st}")
+            state[u] = "RESIDENT"
+            resident += 1
+        elif kind == "B":
+            if st != "RESIDENT":
+                errors.append(f"op {n}: backward of unit {u} in state {st}")
+            if forwards_before_first_backward is None:
+                forwards_before_first_backward = n_forward
+            state[u] = "DONE"
+            in_flight -= 1
+            resident -= 1
+        else:
+            errors.append(f"op {n}: unknown kind {kind}")
+        peak_in_flight = max(peak_in_flight, in_flight)
+        peak_resident = max(peak_resident, resident)
+    for u, st in state.items():
+        if st != "DONE":
+            errors.append(f"unit {u} ends in state {st}")
+    return dict(peak_in_flight=peak_in_flight, peak_resident=peak_resident,
+                forwards_before_first_backward=forwards_before_first_backward, errors=errors)
+
+
+def check_dependencies(passes, v):
+    """Within one microbatch a rank must forward chunk c before chunk c+1 and
+    backward chunk c+1 before chunk c, and forward a unit before its backward."""
+    pos = {(kind, mb, c): n for n, (kind, mb, c) in enumerate(passes)}
+    bad = []
+    for (kind, mb, c), n in pos.items():
+        if kind == "F" and c + 1 < v and pos[("F", mb, c + 1)] < n:
+            bad.append(("F-order", mb, c))
+        if kind == "B" and c + 1 < v and pos[("B", mb, c + 1)] > n:
+            bad.append(("B-order", mb, c))
+        if kind == "B" and pos[("F", mb, c)] > n:
+            bad.append(("B-before-F", mb, c))
+    return bad
+
+
+def offload_ratio_k(h, s, compute_flops_per_s, link_bytes_per_s):
+    """Eq. 1: round-trip offload time over forward+backward compute time of one
+    layer, k = 10 / (3 (6h + s)) * B_c / B_o."""
+    return 10.0 / (3.0 * (6.0 * h + s)) * compute_flops_per_s / link_bytes_per_s
+
+
+def saved_bytes_per_layer(s, h, n_heads, elem_bytes):
+    """Appendix C: 20 b s h bytes per layer at 2-byte elements once LayerNorm,
+    GeLU and dropout outputs are recomputed, i.e. 10 s h elements: layer input,
+    q, k, v, attention output, second LayerNorm's input and the 4h-wide MLP
+    pre-activation.  This build also keeps the softmax log-sum-exp per head and
+    row in fp32 (needed by a score-free attention backward)."""
+    return 10 * s * h * elem_bytes + 4 * n_heads * s

@@ -1,0 +1,113 @@
+"""Pins for the schedule / residency oracle: the closed forms the paper states
+(Section 3.1 warm-up counts and rank-0 peaks, Table 1's 1F1B row, Eq. 1 with the
+Fig. 1 constants, Appendix C's 20 b s h) and structural invariants."""
+import itertools
+
+import pytest
+
+from oracle import schedule_oracle as sch
+
+
+@pytest.mark.parametrize("d,m", [(2, 4), (4, 8), (8, 16), (16, 16), (8, 32), (4, 2)])
+def test_1f1b_warmup_and_peak(d, m):
+    for rank in range(d):
+        ops = sch.one_f_one_b(d, rank, m)
+        assert len(ops) == 2 * m
+        r = sch.simulate(ops)
+        assert r["errors"] == []
+        assert r["forwards_before_first_backward"] == min(d - rank, m)
+        assert r["peak_in_flight"] == min(d - rank, m)
+        # backwards come in microbatch order, and so do forwards
+        assert [mb for k, mb, c in ops if k == "F"] == list(range(m))
+        assert [mb for k, mb, c in ops if k == "B"] == list(range(m))
+
+
+@pytest.mark.parametrize("d,v,m", [(8, 2, 32), (4, 2, 8), (4, 3, 12), (2, 4, 6), (8, 2, 16)])
+def test_interleaved_warmup_and_rank0_peak(d, v, m):
+    for rank in range(d):
+        ops = sch.interleaved_one_f_one_b(d, rank, v, m)
+        assert len(ops) == 2 * m * v
+        r = sch.simulate(ops)
+        assert r["errors"] == []
+        assert sch.check_dependencies(ops, v) == []
+        # Section 3.1: d(v-1) + 2(d-i) - 1 forwards in the warm-up of rank i
+        assert r["forwards_before_first_backward"] == min(d * (v - 1) + 2 * (d - rank) - 1, m * v)
+        if rank == 0 and m * v >= d * v + d - 1:
+            assert r["peak_in_flight"] == d * v + d - 1
+        # every unit once forward, once backward
+        assert sorted((mb, c) for k, mb, c in ops if k == "F") == sorted(itertools.product(range(m), range(v)))
+        assert sorted((mb, c) for k, mb, c in ops if k == "B") == sorted(itertools.product(range(m), range(v)))
+
+
+def test_config4_numbers():
+    ops = sch.interleaved_one_f_one_b(8, 0, 2, 32)
+    r = sch.simulate(ops)
+    assert len(ops) == 128 and r["peak_in_flight"] == 23 and r["forwards_before_first_backward"] == 23
+
+
+def test_selection_rules():
+    assert sch.selected_units(8, 1, 0.0) == set()
+    assert sch.selected_units(8, 1, 1.0) == {(j, 0) for j in range(8)}
+    assert sch.selected_units(8, 1, 0.5) == {(j, 0) for j in (1, 3, 5, 7)}
+    assert sch.selected_units(4, 2, 0.5) == {(1, 0), (1, 1), (3, 0), (3, 1)}
+    assert sch.selected_units(4, 2, 0.5, "longest-lifespan") == {(j, 0) for j in range(4)}
+    assert len(sch.selected_units(12, 1, 0.25)) == 3
+    assert len(sch.selected_units(100, 1, 0.37)) == 37
+    with pytest.raises(ValueError):
+        sch.selected_units(4, 1, 1.5)
+
+
+@pytest.mark.parametrize("schedule,d,v,m", [("1f1b", 4, 1, 8), ("1f1b", 8, 1, 16), ("1f1b", 16, 1, 16),
+                                            ("1f1b-interleaved", 8, 2, 32), ("1f1b", 2, 1, 4)])
+@pytest.mark.parametrize("ratio", [0.0, 0.5, 1.0])
+@pytest.mark.parametrize("prefetch", [0, 1, 2])
+def test_offload_invariants(schedule, d, v, m, ratio, prefetch):
+    for rank in (0, d - 1):
+        passes = sch.compute_passes(schedule, d, rank, v, m)
+        sel = sch.selected_units(m, v, ratio)
+        ops = sch.with_offload(passes, sel, prefetch)
+        r = sch.simulate(ops)
+        assert r["errors"] == []  # every offloaded unit is reloaded before its backward, none used while away
+        assert [o for o in ops if o[0] in "FB"] == passes  # compute order untouched
+        assert sum(o[0] == "OFFLOAD" for o in ops) == len(sel) == sum(o[0] == "RELOAD" for o in ops)
+        base = sch.simulate(passes)
+        assert r["peak_in_flight"] == base["peak_in_flight"]
+        assert r["peak_resident"] <= base["peak_in_flight"]
+        if ratio == 0.0:
+            assert r["peak_resident"] == base["peak_in_flight"]
+        # each reload sits exactly `prefetch` compute passes ahead of its backward (or right after its offload)
+        for n, (k, mb, c) in enumerate(ops):
+            if k == "RELOAD":
+                between = [o for o in ops[n + 1:] if o[0] in "FB"]
+                gap = between.index(("B", mb, c))
+                assert gap == prefetch or ops[n - 1] == ("OFFLOAD", mb, c) or \
+                    all(o[0] in ("RELOAD", "OFFLOAD") for o in ops[ops.index(("OFFLOAD", mb, c)):n])
+
+
+@pytest.mark.parametrize("d", [2, 4, 8, 16, 32])
+def test_full_offload_residency_is_a_constant_independent_of_depth(d):
+    # Section 5.3: under full offload the resident activation does not grow with the pipeline degree
+    m = 2 * d
+    ops = sch.with_offload(sch.one_f_one_b(d, 0, m), sch.selected_units(m, 1, 1.0), prefetch=1)
+    r = sch.simulate(ops)
+    assert r["errors"] == []
+    assert r["peak_in_flight"] == d
+    assert r["peak_resident"] == 2  # the unit being computed + the one being prefetched
+
+
+def test_eq1_spot_values_with_fig1_constants():
+    bc, bo = 220e12, 15e9
+    assert abs(sch.offload_ratio_k(8192, 4096, bc, bo) - 0.918) < 1e-3
+    assert abs(sch.offload_ratio_k(4096, 4096, bc, bo) - 1.705) < 1e-3
+    assert abs(sch.offload_ratio_k(5120, 16384, bc, bo) - 1.038) < 1e-3
+    # Section 1: k <= 1 once the hidden size exceeds 8k (at s = 4k) ...
+    assert sch.offload_ratio_k(8192, 4096, bc, bo) <= 1 < sch.offload_ratio_k(4096, 4096, bc, bo)
+    # Eq. 1 is T_o / T_c with T_o = 2 * 20 s h / B_o and T_c = 12 s h (6h + s) / B_c
+    h, s = 6144, 2048
+    assert abs(sch.offload_ratio_k(h, s, bc, bo) - (2 * 20 * s * h / bo) / (12 * s * h * (6 * h + s) / bc)) < 1e-12
+
+
+def test_saved_bytes_is_20sh_plus_lse():
+    # Appendix C: 20 b s h bytes per layer at two bytes per element
+    assert sch.saved_bytes_per_layer(4096, 4096, 32, 2) == 20 * 4096 * 4096 + 4 * 32 * 4096
+    assert sch.saved_bytes_per_layer(2048, 2048, 16, 2) - 4 * 16 * 2048 == 20 * 2048 * 2048
