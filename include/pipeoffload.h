@@ -1,0 +1,223 @@
+/*
+ * pipeoffload.h -- C ABI of the MI355X stage + activation-offload library.
+ *
+ * One pipeline rank's share of a GPT-style model (a "stage": L decoder layers,
+ * split into v chunks) runs forward and backward over a stream of in-flight
+ * microbatches.  After a unit's forward (a unit = one microbatch of one chunk)
+ * its saved activations -- 10 s h elements per layer, the paper's 20 b s h
+ * bytes at two bytes per element (Appendix C, selective recomputation), plus the
+ * attention log-sum-exp -- can be offloaded to pinned host memory and are
+ * reloaded before the unit's backward (Section 1; Section 4.2; Appendix A).
+ *
+ * Conventions
+ *  - Every pointer argument says whether it is HOST or DEVICE memory.  Device
+ *    pointers must be on the device that was current at po_stage_create.
+ *  - Matrices are row-major.  b = 1: an activation is [s, h].
+ *  - Calls enqueue work and return; results are valid after po_synchronize (or
+ *    a synchronisation of the compute stream for forward/backward outputs).
+ *  - The caller owns parameters, gradients, inputs, outputs and the compute
+ *    stream.  The library owns activation slabs, pinned host buffers, its copy
+ *    streams, events and workspaces; only the stage itself is ever freed by the
+ *    caller (po_stage_destroy).
+ *  - Return value 0 = success, negative = po_error; po_last_error() gives text.
+ *    No exception crosses this boundary and nothing aborts.
+ *  - A stage is not thread-safe; use it from one host thread.
+ */
+#ifndef PIPEOFFLOAD_H
+#define PIPEOFFLOAD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct po_stage po_stage; /* opaque */
+
+typedef enum { PO_F32 = 0, PO_BF16 = 1 } po_dtype;
+
+/* Rank-local op order.  1F1B: Table 1 first row / Appendix A.  Interleaved 1F1B:
+ * Section 3.1 (warm-up d(v-1) + 2(d-i) - 1 forwards on rank i). */
+typedef enum { PO_SCHED_1F1B = 0, PO_SCHED_1F1B_INTERLEAVED = 1 } po_schedule;
+
+/* How a whole-job offload ratio picks units.  ALTERNATE_MB: microbatch j is
+ * offloaded iff floor((j+1) r) > floor(j r).  LONGEST_LIFESPAN (Section 2):
+ * chunks 0 .. ceil(r v) - 1 of every microbatch; equals ALTERNATE_MB if v == 1. */
+typedef enum { PO_SEL_ALTERNATE_MB = 0, PO_SEL_LONGEST_LIFESPAN = 1 } po_select;
+
+typedef enum {
+  PO_OK = 0,
+  PO_E_INVAL = -1,      /* bad argument or unsupported shape */
+  PO_E_STATE = -2,      /* call not legal in the unit's state (e.g. backward of a unit still on the host) */
+  PO_E_DEVICE_OOM = -3, /* device slab pool cap reached, or hipMalloc failed */
+  PO_E_HOST_OOM = -4,   /* pinned host pool cap reached, or hipHostMalloc failed */
+  PO_E_HIP = -5         /* a HIP call failed; text in po_last_error() */
+} po_error;
+
+typedef struct po_config {
+  int32_t n_layers;        /* L: decoder layers held by this rank */
+  int32_t n_chunks;        /* v: virtual chunks; L % v == 0 */
+  int32_t hidden;          /* h; h % 64 == 0 */
+  int32_t n_heads;         /* a; h % a == 0; head size 64 or 128 in bf16 mode */
+  int32_t ffn;             /* f; f % 64 == 0 */
+  int32_t seq;             /* s */
+  int32_t vocab;           /* > 0: chunk 0 starts with wte[token] + wpe[position] and takes int32 tokens */
+  int32_t dtype;           /* po_dtype of parameters and activations; gradients are always fp32 */
+  int32_t pipeline_degree; /* d of the simulated pipeline */
+  int32_t rank;            /* i in [0, d): rank 0 holds the most units in flight */
+  int32_t prefetch_passes; /* run_schedule issues a unit's reload this many compute passes before its backward */
+  int32_t copy_streams;    /* 2: separate offload and reload streams; 1: one shared copy stream (Section 4.2) */
+  int32_t select_policy;   /* po_select */
+  int32_t staged_copies;   /* 0: copy slabs in place; 1: pack into a staging buffer before D2H, unpack after H2D */
+  int32_t debug_poison;    /* 1: fill a slab with a NaN pattern whenever it is released */
+  float ln_eps;            /* LayerNorm epsilon */
+  uint64_t host_pool_cap_bytes;   /* 0 = unlimited; else PO_E_HOST_OOM beyond it */
+  uint64_t device_pool_cap_bytes; /* 0 = unlimited; else PO_E_DEVICE_OOM beyond it */
+} po_config;
+
+/* One tensor of the flat parameter (and gradient) buffer. */
+typedef struct po_param_desc {
+  char name[32];        /* "wte", "wpe", or per layer: ln1_g ln1_b w_qkv b_qkv w_o b_o ln2_g ln2_b w_fc1 b_fc1 w_fc2 b_fc2 */
+  int32_t layer;        /* -1 for embeddings */
+  int32_t reserved;
+  int64_t offset_elems; /* offset into the flat buffer, in elements */
+  int64_t rows, cols;   /* vectors have rows == 1 */
+} po_param_desc;
+
+/* kind: 0 forward, 1 backward, 2 offload, 3 reload. */
+typedef struct po_op {
+  int32_t kind, mb, chunk;
+  float ratio; /* offload: fraction of the unit's layers (rounded up, lowest layers first) */
+} po_op;
+
+typedef struct po_stats {
+  double wall_s;            /* host wall time of the last po_run_schedule, enqueue to drained */
+  double tokens_per_s;      /* m * s / wall_s */
+  double compute_busy_s;    /* sum of compute-pass durations (HIP events on the compute stream) */
+  double d2h_busy_s;        /* sum of offload copy durations */
+  double h2d_busy_s;        /* sum of reload copy durations */
+  double pack_busy_s;       /* sum of pack + unpack kernel durations (staged copies only) */
+  double compute_span_s;    /* first compute pass start to last compute pass end */
+  uint64_t bytes_d2h, bytes_h2d;
+  uint64_t peak_slab_bytes;      /* high-water mark of activation slab bytes in use (incl. staging) */
+  uint64_t pool_bytes_allocated; /* device bytes the slab pool holds */
+  uint64_t host_bytes_allocated; /* pinned bytes the host pool holds */
+  uint64_t workspace_bytes;      /* temporaries: recompute buffers, gradient workspaces */
+  int32_t peak_resident_units;   /* high-water mark of units with at least one layer resident */
+  int32_t peak_in_flight_units;  /* forwarded and not yet backwarded */
+  int32_t n_compute_passes, n_offloads, n_reloads, reserved;
+} po_stats;
+
+/* Fills *cfg with defaults (1 chunk, fp32, d = 1, prefetch 1, two copy streams, eps 1e-5). HOST. */
+void po_config_default(po_config* cfg);
+
+/* Thread-local text of the last error. */
+const char* po_last_error(void);
+
+/* ---- parameter layout (pure host code; usable without a GPU) ------------- */
+/* Total elements of the flat parameter buffer of this config. */
+int po_param_count(const po_config* cfg, int64_t* n_elems);
+/* Writes up to *n descriptors into out (HOST) and sets *n to the number of tensors.
+ * Call with out == NULL to query the count. */
+int po_param_layout(const po_config* cfg, po_param_desc* out, int32_t* n);
+/* Bytes of saved activations per layer: 10 s h elements + 4 a s (fp32 log-sum-exp), each tensor 256-byte aligned. */
+int po_saved_bytes_per_layer(const po_config* cfg, uint64_t* bytes);
+
+/* ---- schedule (pure host code; usable without a GPU) --------------------- */
+/* The op list one rank executes, offload and reload ops included (Section 4.2 on a
+ * single rank: offload right after the forward, reload `prefetch` compute passes
+ * ahead of the backward).  out may be NULL to query *n. */
+int po_schedule_ops(int32_t schedule, int32_t d, int32_t rank, int32_t v, int32_t m, float ratio,
+                    int32_t policy, int32_t prefetch, po_op* out, int32_t* n);
+
+/* Eq. 1: k = 10 / (3 (6h + s)) * B_c / B_o, with B_c in flop/s and B_o in byte/s. */
+double po_offload_k(int32_t h, int32_t s, double compute_flops_per_s, double link_bytes_per_s);
+
+/* ---- stage ---------------------------------------------------------------- */
+/* compute_stream: a hipStream_t (as void*) on the current device, NULL = default
+ * stream.  Creates copy streams, events and workspaces; slabs and pinned buffers
+ * grow on demand and are kept until destroy. */
+int po_stage_create(const po_config* cfg, void* compute_stream, po_stage** out);
+void po_stage_destroy(po_stage* st);
+
+/* params: DEVICE, po_param_count elements of cfg.dtype.  grads: DEVICE, the same
+ * number of fp32 elements; backward ADDS into it, the caller zeroes it. */
+int po_bind_params(po_stage* st, const void* params, float* grads);
+
+/* Forward of unit (mb, chunk) on the compute stream (rows a0-a7: LN, QKV, causal
+ * attention, out-proj + residual, LN, FC1 + GeLU, FC2 + residual per layer).
+ * x_in: DEVICE [s, h] of cfg.dtype, or int32 tokens [s] when vocab > 0 and chunk == 0.
+ * y_out: DEVICE [s, h].  The unit becomes RESIDENT. */
+int po_stage_forward(po_stage* st, int32_t mb, int32_t chunk, const void* x_in, void* y_out);
+
+/* Backward of a RESIDENT unit (waits for an outstanding reload).  dy: DEVICE [s, h].
+ * dx: DEVICE [s, h], may be NULL when the unit starts with the embedding.
+ * LayerNorm and GeLU outputs are recomputed (Appendix C).  Frees the unit. */
+int po_stage_backward(po_stage* st, int32_t mb, int32_t chunk, const void* dy, void* dx);
+
+/* Asynchronously moves ceil(ratio * Lu) layers (lowest first) of a RESIDENT unit
+ * to pinned host memory on the offload stream once its forward has finished, and
+ * releases their device slabs (Section 4.2; Appendix C buffer management). */
+int po_offload(po_stage* st, int32_t mb, int32_t chunk, float ratio);
+
+/* Asynchronously brings an offloaded unit back on the reload stream; a no-op for
+ * a unit with nothing offloaded. */
+int po_reload(po_stage* st, int32_t mb, int32_t chunk);
+
+/* Runs a whole rank-local schedule: po_schedule_ops(schedule, d, rank, v, m, ratio, ...)
+ * executed with the four calls above.  Arrays are HOST arrays of DEVICE pointers,
+ * indexed [chunk * m + mb], length m * v.  dx entries may be NULL for embedding
+ * units.  stats (HOST) may be NULL.  Returns after everything has drained. */
+int po_run_schedule(po_stage* st, int32_t schedule, int32_t n_microbatches, float offload_ratio,
+                    const void* const* x_in, void* const* y_out, const void* const* dy, void* const* dx,
+                    po_stats* stats);
+
+int po_synchronize(po_stage* st);
+int po_get_stats(const po_stage* st, po_stats* out);
+
+/* ---- single operations (what the stage is built from; for tests and
+ * micro-benchmarks).  All pointers DEVICE, stream = hipStream_t or NULL. ----- */
+
+/* y = LN(x) * gain + shift, rows x h (row a1/a5). */
+int po_op_layernorm_forward(int32_t dtype, const void* x, const void* gain, const void* shift, void* y,
+                            int32_t rows, int32_t h, float eps, void* stream);
+/* dx = dres + LNbwd(dn; x, gain); dgain += ..., dshift += ... (fp32) (rows a14/a18).
+ * partials: fp32 workspace of po_op_layernorm_backward_workspace(rows, h) bytes. */
+int po_op_layernorm_backward(int32_t dtype, const void* dn, const void* x, const void* gain, const void* dres,
+                             void* dx, float* dgain, float* dshift, float* partials, int32_t rows, int32_t h,
+                             float eps, void* stream);
+uint64_t po_op_layernorm_backward_workspace(int32_t rows, int32_t h);
+
+/* C = op(A) op(B) with the epilogues of the stage (rows a2, a4, a6, a7, a12-a17).
+ * trans_a == 0: A is [M, K]; 1: A is [K, M].  trans_b == 0: B is [K, N]; 1: B is [N, K].
+ * bias [N] and residual [M, N] may be NULL.  out [M, N] of dtype may be NULL.
+ * gelu_out: if not NULL receives gelu(out).  gelu_u: if not NULL, out = result * gelu'(gelu_u)
+ * and gelu_out = gelu(gelu_u).  acc_f32: if not NULL, acc_f32 [M, N] += result. */
+int po_op_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32_t N, int32_t K,
+               const void* A, int32_t lda, const void* B, int32_t ldb, const void* bias, const void* residual,
+               void* out, void* gelu_out, const void* gelu_u, float* acc_f32, int32_t force_generic, void* stream);
+
+/* Causal attention forward (row a3): qkv [s, 3h] (q | k | v blocks), o [s, h], lse [a, s] fp32. */
+int po_op_attention_forward(int32_t dtype, const void* qkv, void* o, float* lse, int32_t s, int32_t h,
+                            int32_t n_heads, int32_t force_generic, void* stream);
+/* Causal attention backward (row a16): dqkv [s, 3h]; delta: fp32 workspace [a, s]. */
+int po_op_attention_backward(int32_t dtype, const void* qkv, const void* o, const float* lse, const void* d_o,
+                             void* dqkv, float* delta, int32_t s, int32_t h, int32_t n_heads,
+                             int32_t force_generic, void* stream);
+
+/* acc[N] += column sums of x [rows, N] (bias gradients, rows a12-a17), deterministic: row chunks
+ * are reduced to partials in `workspace` (fp32, po_op_colsum_workspace bytes), then added in chunk order. */
+uint64_t po_op_colsum_workspace(int32_t rows, int32_t n);
+int po_op_colsum_accumulate(int32_t dtype, const void* x, float* acc, float* workspace, int32_t rows, int32_t n,
+                            void* stream);
+
+/* Gather n_seg segments into one contiguous buffer / scatter them back (rows a8/a11).
+ * seg_ptrs: HOST array of DEVICE pointers; seg_bytes: HOST array, each a multiple of 16.
+ * Segments land back to back in `packed` in array order. */
+int po_op_pack(const void* const* seg_ptrs, const uint64_t* seg_bytes, int32_t n_seg, void* packed, void* stream);
+int po_op_unpack(void* const* seg_ptrs, const uint64_t* seg_bytes, int32_t n_seg, const void* packed, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PIPEOFFLOAD_H */

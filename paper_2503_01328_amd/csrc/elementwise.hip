@@ -1,0 +1,480 @@
+// HBM-bound kernels of the stage: LayerNorm forward / recompute+backward,
+// deterministic column reductions (bias and LayerNorm parameter gradients),
+// embedding, activation pack/unpack, fills and copies.
+//
+// LayerNorm rows are reduced with wavefront (64-lane) shuffles: one wave owns
+// one row, lanes read 16 bytes each, so a row of h elements is covered by
+// coalesced 1 KiB wave accesses.  Column reductions never use atomics: rows are
+// split into chunks, each chunk writes a partial, and a second kernel adds the
+// partials in chunk order, so results do not depend on scheduling.
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "kernels.h"
+
+namespace po {
+
+static thread_local char g_error[512] = "";
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_error, sizeof(g_error), fmt, ap);
+  va_end(ap);
+}
+const char* get_error() { return g_error; }
+
+// --------------------------------------------------------------------------
+// LayerNorm forward: y = (x - mean) * rstd * gain + shift, one wave per row.
+// --------------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ void row_stats(const T* xr, int h, int lane, float eps, float& mean, float& rstd) {
+  constexpr int V = Vec16<T>::N;
+  float sum = 0.f;
+  for (int c = lane * V; c < h; c += kWave * V) {
+    Vec16<T> v = load16(xr + c);
+#pragma unroll
+    for (int i = 0; i < V; ++i) sum += to_f32(v.v[i]);
+  }
+  mean = wave_sum(sum) / (float)h;
+  float sq = 0.f;
+  for (int c = lane * V; c < h; c += kWave * V) {
+    Vec16<T> v = load16(xr + c);
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      float d = to_f32(v.v[i]) - mean;
+      sq += d * d;
+    }
+  }
+  rstd = 1.0f / sqrtf(wave_sum(sq) / (float)h + eps);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void ln_forward_kernel(const T* __restrict__ x, const T* __restrict__ gain,
+                                                         const T* __restrict__ shift, T* __restrict__ y, int rows,
+                                                         int h, float eps) {
+  constexpr int V = Vec16<T>::N;
+  int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  int lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const T* xr = x + (size_t)row * h;
+  T* yr = y + (size_t)row * h;
+  float mean, rstd;
+  row_stats(xr, h, lane, eps, mean, rstd);
+  for (int c = lane * V; c < h; c += kWave * V) {
+    Vec16<T> v = load16(xr + c), g = load16(gain + c), b = load16(shift + c), o;
+#pragma unroll
+    for (int i = 0; i < V; ++i)
+      o.v[i] = from_f32<T>((to_f32(v.v[i]) - mean) * rstd * to_f32(g.v[i]) + to_f32(b.v[i]));
+    store16(yr + c, o);
+  }
+}
+
+bool layernorm_forward(int dtype, const void* x, const void* gain, const void* shift, void* y, int rows, int h,
+                       float eps, hipStream_t stream) {
+  if (rows <= 0 || h <= 0 || h % 8 != 0) {
+    set_error("layernorm_forward: rows=%d h=%d (h must be a positive multiple of 8)", rows, h);
+    return false;
+  }
+  dim3 grid(ceil_div(rows, 4)), block(256);
+  if (dtype == kF32)
+    ln_forward_kernel<float><<<grid, block, 0, stream>>>((const float*)x, (const float*)gain, (const float*)shift,
+                                                         (float*)y, rows, h, eps);
+  else
+    ln_forward_kernel<bf16><<<grid, block, 0, stream>>>((const bf16*)x, (const bf16*)gain, (const bf16*)shift,
+                                                        (bf16*)y, rows, h, eps);
+  return launch_ok("ln_forward_kernel");
+}
+
+// --------------------------------------------------------------------------
+// LayerNorm backward with recomputed statistics.
+//   xhat = (x - mean) rstd ; dxhat = dn * gain
+//   dx = dres + rstd (dxhat - mean(dxhat) - xhat mean(dxhat xhat))
+//   dgain += colsum(dn * xhat) ; dshift += colsum(dn)
+// Kernel 1 (wave per row) writes dx and the row statistics; kernel 2 builds
+// per-row-chunk column partials; kernel 3 adds them in chunk order.
+// --------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void ln_backward_rows_kernel(const T* __restrict__ dn, const T* __restrict__ x,
+                                                               const T* __restrict__ gain,
+                                                               const T* __restrict__ dres, T* __restrict__ dx,
+                                                               float* __restrict__ stats, int rows, int h,
+                                                               float eps) {
+  constexpr int V = Vec16<T>::N;
+  int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  int lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const T* xr = x + (size_t)row * h;
+  const T* dnr = dn + (size_t)row * h;
+  float mean, rstd;
+  row_stats(xr, h, lane, eps, mean, rstd);
+  float s1 = 0.f, s2 = 0.f;
+  for (int c = lane * V; c < h; c += kWave * V) {
+    Vec16<T> v = load16(xr + c), d = load16(dnr + c), g = load16(gain + c);
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      float dxh = to_f32(d.v[i]) * to_f32(g.v[i]);
+      s1 += dxh;
+      s2 += dxh * (to_f32(v.v[i]) - mean) * rstd;
+    }
+  }
+  float c1 = wave_sum(s1) / (float)h, c2 = wave_sum(s2) / (float)h;
+  for (int c = lane * V; c < h; c += kWave * V) {
+    Vec16<T> v = load16(xr + c), d = load16(dnr + c), g = load16(gain + c), r, o;
+    if (dres) r = load16(dres + (size_t)row * h + c);
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      float xh = (to_f32(v.v[i]) - mean) * rstd;
+      float dxh = to_f32(d.v[i]) * to_f32(g.v[i]);
+      float val = rstd * (dxh - c1 - xh * c2);
+      if (dres) val += to_f32(r.v[i]);
+      o.v[i] = from_f32<T>(val);
+    }
+    store16(dx + (size_t)row * h + c, o);
+  }
+  if (lane == 0) {
+    stats[2 * row] = mean;
+    stats[2 * row + 1] = rstd;
+  }
+}
+
+// Block: 256 threads = 4 waves; a lane owns 2 adjacent columns of a 128-column
+// tile; wave w walks rows chunk_start + w, + 4, ...  Partials: [chunk][2][h].
+template <typename T>
+__global__ __launch_bounds__(256) void ln_backward_cols_kernel(const T* __restrict__ dn, const T* __restrict__ x,
+                                                               const float* __restrict__ stats,
+                                                               float* __restrict__ partials, int rows, int h,
+                                                               int rows_per_chunk) {
+  __shared__ float red[4][128][2];
+  int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  int col = blockIdx.x * 128 + lane * 2;
+  int r0 = blockIdx.y * rows_per_chunk;
+  int r1 = min(rows, r0 + rows_per_chunk);
+  float g0 = 0.f, g1 = 0.f, b0 = 0.f, b1 = 0.f;
+  if (col < h) {
+    for (int r = r0 + wave; r < r1; r += 4) {
+      float mean = stats[2 * r], rstd = stats[2 * r + 1];
+      float d0 = to_f32(dn[(size_t)r * h + col]), d1 = to_f32(dn[(size_t)r * h + col + 1]);
+      float x0 = to_f32(x[(size_t)r * h + col]), x1 = to_f32(x[(size_t)r * h + col + 1]);
+      g0 += d0 * (x0 - mean) * rstd;
+      g1 += d1 * (x1 - mean) * rstd;
+      b0 += d0;
+      b1 += d1;
+    }
+  }
+  red[wave][lane * 2][0] = g0;
+  red[wave][lane * 2 + 1][0] = g1;
+  red[wave][lane * 2][1] = b0;
+  red[wave][lane * 2 + 1][1] = b1;
+  __syncthreads();
+  if (threadIdx.x < 128) {
+    int c = blockIdx.x * 128 + threadIdx.x;
+    if (c < h) {
+      float sg = 0.f, sb = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        sg += red[w][threadIdx.x][0];
+        sb += red[w][threadIdx.x][1];
+      }
+      partials[((size_t)blockIdx.y * 2 + 0) * h + c] = sg;
+      partials[((size_t)blockIdx.y * 2 + 1) * h + c] = sb;
+    }
+  }
+}
+
+__global__ void ln_backward_final_kernel(const float* __restrict__ partials, float* __restrict__ dgain,
+                                         float* __restrict__ dshift, int h, int n_chunks) {
+  int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= h) return;
+  float sg = 0.f, sb = 0.f;
+  for (int k = 0; k < n_chunks; ++k) {
+    sg += partials[((size_t)k * 2 + 0) * h + c];
+    sb += partials[((size_t)k * 2 + 1) * h + c];
+  }
+  dgain[c] += sg;
+  dshift[c] += sb;
+}
+
+static int reduce_chunks(int rows) { return max(1, min(64, ceil_div(rows, 32))); }
+
+size_t layernorm_backward_workspace(int rows, int h) {
+  return ((size_t)rows * 2 + (size_t)reduce_chunks(rows) * 2 * h) * sizeof(float);
+}
+
+bool layernorm_backward(int dtype, const void* dn, const void* x, const void* gain, const void* dres, void* dx,
+                        float* dgain, float* dshift, float* workspace, int rows, int h, float eps,
+                        hipStream_t stream) {
+  if (rows <= 0 || h <= 0 || h % 8 != 0 || !workspace) {
+    set_error("layernorm_backward: rows=%d h=%d workspace=%p", rows, h, (void*)workspace);
+    return false;
+  }
+  float* stats = workspace;
+  float* partials = workspace + (size_t)rows * 2;
+  int n_chunks = reduce_chunks(rows);
+  int rows_per_chunk = ceil_div(rows, n_chunks);
+  dim3 g1(ceil_div(rows, 4)), g2(ceil_div(h, 128), n_chunks), g3(ceil_div(h, 256));
+  if (dtype == kF32) {
+    ln_backward_rows_kernel<float><<<g1, 256, 0, stream>>>((const float*)dn, (const float*)x, (const float*)gain,
+                                                           (const float*)dres, (float*)dx, stats, rows, h, eps);
+    ln_backward_cols_kernel<float><<<g2, 256, 0, stream>>>((const float*)dn, (const float*)x, stats, partials,
+                                                           rows, h, rows_per_chunk);
+  } else {
+    ln_backward_rows_kernel<bf16><<<g1, 256, 0, stream>>>((const bf16*)dn, (const bf16*)x, (const bf16*)gain,
+                                                          (const bf16*)dres, (bf16*)dx, stats, rows, h, eps);
+    ln_backward_cols_kernel<bf16><<<g2, 256, 0, stream>>>((const bf16*)dn, (const bf16*)x, stats, partials, rows,
+                                                          h, rows_per_chunk);
+  }
+  ln_backward_final_kernel<<<g3, 256, 0, stream>>>(partials, dgain, dshift, h, n_chunks);
+  return launch_ok("layernorm_backward kernels");
+}
+
+// --------------------------------------------------------------------------
+// acc[n] += sum over rows of x[r, n]   (bias gradients)
+// --------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict__ x, float* __restrict__ partials,
+                                                             int rows, int n, int rows_per_chunk) {
+  __shared__ float red[4][128];
+  int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  int col = blockIdx.x * 128 + lane * 2;
+  int r0 = blockIdx.y * rows_per_chunk;
+  int r1 = min(rows, r0 + rows_per_chunk);
+  float a0 = 0.f, a1 = 0.f;
+  if (col < n) {
+    for (int r = r0 + wave; r < r1; r += 4) {
+      a0 += to_f32(x[(size_t)r * n + col]);
+      a1 += to_f32(x[(size_t)r * n + col + 1]);
+    }
+  }
+  red[wave][lane * 2] = a0;
+  red[wave][lane * 2 + 1] = a1;
+  __syncthreads();
+  if (threadIdx.x < 128) {
+    int c = blockIdx.x * 128 + threadIdx.x;
+    if (c < n)
+      partials[(size_t)blockIdx.y * n + c] =
+          red[0][threadIdx.x] + red[1][threadIdx.x] + red[2][threadIdx.x] + red[3][threadIdx.x];
+  }
+}
+
+__global__ void colsum_final_kernel(const float* __restrict__ partials, float* __restrict__ acc, int n,
+                                    int n_chunks) {
+  int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= n) return;
+  float s = 0.f;
+  for (int k = 0; k < n_chunks; ++k) s += partials[(size_t)k * n + c];
+  acc[c] += s;
+}
+
+size_t colsum_workspace(int rows, int n) { return (size_t)reduce_chunks(rows) * n * sizeof(float); }
+
+bool colsum_accumulate(int dtype, const void* x, float* acc, float* workspace, int rows, int n,
+                       hipStream_t stream) {
+  if (rows <= 0 || n <= 0 || n % 2 != 0 || !workspace) {
+    set_error("colsum_accumulate: rows=%d n=%d workspace=%p (n must be even)", rows, n, (void*)workspace);
+    return false;
+  }
+  int n_chunks = reduce_chunks(rows);
+  int rows_per_chunk = ceil_div(rows, n_chunks);
+  dim3 g(ceil_div(n, 128), n_chunks);
+  if (dtype == kF32)
+    colsum_partial_kernel<float><<<g, 256, 0, stream>>>((const float*)x, workspace, rows, n, rows_per_chunk);
+  else
+    colsum_partial_kernel<bf16><<<g, 256, 0, stream>>>((const bf16*)x, workspace, rows, n, rows_per_chunk);
+  colsum_final_kernel<<<ceil_div(n, 256), 256, 0, stream>>>(workspace, acc, n, n_chunks);
+  return launch_ok("colsum kernels");
+}
+
+// --------------------------------------------------------------------------
+// Embedding: x[p] = wte[tok[p]] + wpe[p]; backward adds dx into dwpe row by row
+// and into dwte with one block per vocabulary row scanning positions in order
+// (repeated tokens are summed in position order: deterministic, no atomics).
+// --------------------------------------------------------------------------
+template <typename T>
+__global__ void embedding_forward_kernel(const int32_t* __restrict__ tok, const T* __restrict__ wte,
+                                         const T* __restrict__ wpe, T* __restrict__ x, int s, int h, int vocab) {
+  int p = blockIdx.x;
+  int t = tok[p];
+  t = min(max(t, 0), vocab - 1);
+  for (int c = threadIdx.x; c < h; c += blockDim.x)
+    x[(size_t)p * h + c] = from_f32<T>(to_f32(wte[(size_t)t * h + c]) + to_f32(wpe[(size_t)p * h + c]));
+}
+
+template <typename T>
+__global__ void embedding_backward_kernel(const int32_t* __restrict__ tok, const T* __restrict__ dx,
+                                          float* __restrict__ dwte, float* __restrict__ dwpe, int s, int h,
+                                          int vocab) {
+  int row = blockIdx.x;
+  if (row < vocab) {
+    for (int p = 0; p < s; ++p) {
+      int t = min(max(tok[p], 0), vocab - 1);
+      if (t != row) continue;  // uniform across the block
+      for (int c = threadIdx.x; c < h; c += blockDim.x) dwte[(size_t)row * h + c] += to_f32(dx[(size_t)p * h + c]);
+    }
+  } else {
+    int p = row - vocab;
+    for (int c = threadIdx.x; c < h; c += blockDim.x) dwpe[(size_t)p * h + c] += to_f32(dx[(size_t)p * h + c]);
+  }
+}
+
+bool embedding_forward(int dtype, const int32_t* tok, const void* wte, const void* wpe, void* x, int s, int h,
+                       int vocab, hipStream_t stream) {
+  if (s <= 0 || h <= 0 || vocab <= 0) {
+    set_error("embedding_forward: s=%d h=%d vocab=%d", s, h, vocab);
+    return false;
+  }
+  if (dtype == kF32)
+    embedding_forward_kernel<float><<<s, 256, 0, stream>>>(tok, (const float*)wte, (const float*)wpe, (float*)x,
+                                                           s, h, vocab);
+  else
+    embedding_forward_kernel<bf16><<<s, 256, 0, stream>>>(tok, (const bf16*)wte, (const bf16*)wpe, (bf16*)x, s, h,
+                                                          vocab);
+  return launch_ok("embedding_forward_kernel");
+}
+
+bool embedding_backward(int dtype, const int32_t* tok, const void* dx, float* dwte, float* dwpe, int s, int h,
+                        int vocab, hipStream_t stream) {
+  if (s <= 0 || h <= 0 || vocab <= 0) {
+    set_error("embedding_backward: s=%d h=%d vocab=%d", s, h, vocab);
+    return false;
+  }
+  if (dtype == kF32)
+    embedding_backward_kernel<float><<<vocab + s, 256, 0, stream>>>(tok, (const float*)dx, dwte, dwpe, s, h, vocab);
+  else
+    embedding_backward_kernel<bf16><<<vocab + s, 256, 0, stream>>>(tok, (const bf16*)dx, dwte, dwpe, s, h, vocab);
+  return launch_ok("embedding_backward_kernel");
+}
+
+// --------------------------------------------------------------------------
+// Fill / copy
+// --------------------------------------------------------------------------
+__global__ void fill_u32_kernel(uint32_t* p, uint32_t pattern, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) p[i] = pattern;
+}
+
+bool fill_u32(void* p, uint32_t pattern, size_t bytes, hipStream_t stream) {
+  if (bytes % 4 != 0) {
+    set_error("fill_u32: %zu bytes is not a multiple of 4", bytes);
+    return false;
+  }
+  if (bytes == 0) return true;
+  size_t n = bytes / 4;
+  int grid = (int)min((size_t)4096, (n + 255) / 256);
+  fill_u32_kernel<<<grid, 256, 0, stream>>>((uint32_t*)p, pattern, n);
+  return launch_ok("fill_u32_kernel");
+}
+
+__global__ __launch_bounds__(256) void copy16_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src,
+                                                     size_t n) {
+  size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x;
+  uint4 v[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    if (i + u * 256 < n) v[u] = src[i + u * 256];
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    if (i + u * 256 < n) dst[i + u * 256] = v[u];
+}
+
+bool copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t stream) {
+  if (bytes % 16 != 0 || ((uintptr_t)dst | (uintptr_t)src) % 16 != 0) {
+    set_error("copy_bytes: %zu bytes / pointers must be multiples of 16", bytes);
+    return false;
+  }
+  if (bytes == 0) return true;
+  size_t n = bytes / 16;
+  copy16_kernel<<<(unsigned)((n + 1023) / 1024), 256, 0, stream>>>((uint4*)dst, (const uint4*)src, n);
+  return launch_ok("copy16_kernel");
+}
+
+// --------------------------------------------------------------------------
+// Pack / unpack: n_seg segments <-> one contiguous buffer, 16 bytes per lane,
+// four loads in flight per lane.  The segment table travels as a kernel argument.
+// --------------------------------------------------------------------------
+struct SegTable {
+  char* ptr[kMaxPackSegments];
+  uint64_t first_chunk[kMaxPackSegments + 1];  // prefix sums in 16-byte chunks
+  int n;
+};
+
+template <bool kPack>
+__global__ __launch_bounds__(256) void pack_kernel(SegTable tab, uint4* __restrict__ packed) {
+  uint64_t total = tab.first_chunk[tab.n];
+  uint64_t base = (uint64_t)blockIdx.x * 1024 + threadIdx.x;
+  // segment holding the block's first chunk; later chunks only move forward
+  int seg = 0;
+  {
+    uint64_t b0 = (uint64_t)blockIdx.x * 1024;
+    while (seg + 1 < tab.n && tab.first_chunk[seg + 1] <= b0) ++seg;
+  }
+  uint4 v[4];
+  uint4* where[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    uint64_t i = base + (uint64_t)u * 256;
+    where[u] = nullptr;
+    if (i < total) {
+      int sg = seg;
+      while (tab.first_chunk[sg + 1] <= i) ++sg;
+      where[u] = reinterpret_cast<uint4*>(tab.ptr[sg]) + (i - tab.first_chunk[sg]);
+      v[u] = kPack ? *where[u] : packed[i];
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    uint64_t i = base + (uint64_t)u * 256;
+    if (i < total) {
+      if (kPack)
+        packed[i] = v[u];
+      else
+        *where[u] = v[u];
+    }
+  }
+}
+
+static bool build_table(const void* const* seg_ptrs, const uint64_t* seg_bytes, int n_seg, const void* packed,
+                        SegTable& tab) {
+  if (n_seg < 0 || n_seg > kMaxPackSegments) {
+    set_error("pack: %d segments (at most %d)", n_seg, kMaxPackSegments);
+    return false;
+  }
+  if ((uintptr_t)packed % 16 != 0) {
+    set_error("pack: packed buffer is not 16-byte aligned");
+    return false;
+  }
+  tab.n = n_seg;
+  tab.first_chunk[0] = 0;
+  for (int i = 0; i < n_seg; ++i) {
+    if (seg_bytes[i] % 16 != 0 || (uintptr_t)seg_ptrs[i] % 16 != 0 || (seg_bytes[i] && !seg_ptrs[i])) {
+      set_error("pack: segment %d (%p, %llu bytes) must be 16-byte aligned and sized", i, seg_ptrs[i],
+                (unsigned long long)seg_bytes[i]);
+      return false;
+    }
+    tab.ptr[i] = (char*)seg_ptrs[i];
+    tab.first_chunk[i + 1] = tab.first_chunk[i] + seg_bytes[i] / 16;
+  }
+  return true;
+}
+
+bool pack_segments(const void* const* seg_ptrs, const uint64_t* seg_bytes, int n_seg, void* packed,
+                   hipStream_t stream) {
+  SegTable tab;
+  if (!build_table(seg_ptrs, seg_bytes, n_seg, packed, tab)) return false;
+  uint64_t total = tab.first_chunk[n_seg];
+  if (total == 0) return true;
+  pack_kernel<true><<<(unsigned)((total + 1023) / 1024), 256, 0, stream>>>(tab, (uint4*)packed);
+  return launch_ok("pack_kernel");
+}
+
+bool unpack_segments(void* const* seg_ptrs, const uint64_t* seg_bytes, int n_seg, const void* packed,
+                     hipStream_t stream) {
+  SegTable tab;
+  if (!build_table((const void* const*)seg_ptrs, seg_bytes, n_seg, packed, tab)) return false;
+  uint64_t total = tab.first_chunk[n_seg];
+  if (total == 0) return true;
+  pack_kernel<false><<<(unsigned)((total + 1023) / 1024), 256, 0, stream>>>(tab, (uint4*)const_cast<void*>(packed));
+  return launch_ok("unpack_kernel");
+}
+
+}  // namespace po

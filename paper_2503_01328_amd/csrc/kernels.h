@@ -1,0 +1,80 @@
+// Host-side launchers of the HIP kernels.  Every launcher validates its shapes
+// on the host, enqueues on `stream`, and returns false with po::set_error text
+// when the arguments do not fit what the kernel assumes.
+#pragma once
+
+#include "po_common.h"
+
+namespace po {
+
+void set_error(const char* fmt, ...);
+const char* get_error();
+
+// ---- elementwise / normalisation (elementwise.hip) -------------------------
+bool layernorm_forward(int dtype, const void* x, const void* gain, const void* shift, void* y, int rows, int h,
+                       float eps, hipStream_t stream);
+size_t layernorm_backward_workspace(int rows, int h);
+bool layernorm_backward(int dtype, const void* dn, const void* x, const void* gain, const void* dres, void* dx,
+                        float* dgain, float* dshift, float* workspace, int rows, int h, float eps,
+                        hipStream_t stream);
+size_t colsum_workspace(int rows, int n);
+bool colsum_accumulate(int dtype, const void* x, float* acc, float* workspace, int rows, int n, hipStream_t stream);
+bool embedding_forward(int dtype, const int32_t* tok, const void* wte, const void* wpe, void* x, int s, int h,
+                       int vocab, hipStream_t stream);
+bool embedding_backward(int dtype, const int32_t* tok, const void* dx, float* dwte, float* dwpe, int s, int h,
+                        int vocab, hipStream_t stream);
+bool fill_u32(void* p, uint32_t pattern, size_t bytes, hipStream_t stream);
+bool copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t stream);
+
+constexpr int kMaxPackSegments = 48;
+bool pack_segments(const void* const* seg_ptrs, const uint64_t* seg_bytes, int n_seg, void* packed,
+                   hipStream_t stream);
+bool unpack_segments(void* const* seg_ptrs, const uint64_t* seg_bytes, int n_seg, const void* packed,
+                     hipStream_t stream);
+
+// ---- GEMM (gemm_generic.hip, gemm_mfma.hip) ---------------------------------
+// C[M,N] = op(A) op(B): trans_a == 0: A [M,K] (lda >= K); 1: A [K,M] (lda >= M).
+// trans_b == 0: B [K,N] (ldb >= N); 1: B [N,K] (ldb >= K).
+bool gemm_generic(int dtype, int trans_a, int trans_b, int M, int N, int K, const void* A, int lda, const void* B,
+                  int ldb, const Epilogue& ep, hipStream_t stream);
+// bf16 MFMA path; returns false (with error text) if the shape is not supported.
+bool gemm_mfma_supported(int trans_a, int trans_b, int M, int N, int K, int lda, int ldb, int ldc);
+bool gemm_mfma_bf16(int trans_a, int trans_b, int M, int N, int K, const void* A, int lda, const void* B, int ldb,
+                    const Epilogue& ep, hipStream_t stream);
+// Picks the MFMA kernel for bf16 when the shape allows it, else the generic one.
+bool gemm(int dtype, int trans_a, int trans_b, int M, int N, int K, const void* A, int lda, const void* B, int ldb,
+          const Epilogue& ep, bool force_generic, hipStream_t stream);
+
+// ---- attention (attention_generic.hip, attention_mfma.hip) -------------------
+bool attention_forward_generic(int dtype, const void* qkv, void* o, float* lse, int s, int h, int n_heads,
+                               hipStream_t stream);
+bool attention_backward_generic(int dtype, const void* qkv, const void* o, const float* lse, const void* d_o,
+                                void* dqkv, float* delta, int s, int h, int n_heads, hipStream_t stream);
+bool attention_mfma_supported(int s, int h, int n_heads);
+bool attention_forward_mfma(const void* qkv, void* o, float* lse, int s, int h, int n_heads, hipStream_t stream);
+bool attention_backward_mfma(const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv,
+                             float* delta, int s, int h, int n_heads, hipStream_t stream);
+bool attention_forward(int dtype, const void* qkv, void* o, float* lse, int s, int h, int n_heads,
+                       bool force_generic, hipStream_t stream);
+bool attention_backward(int dtype, const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv,
+                        float* delta, int s, int h, int n_heads, bool force_generic, hipStream_t stream);
+
+#define PO_HIP_OK(expr)                                                                  \
+  do {                                                                                   \
+    hipError_t e__ = (expr);                                                             \
+    if (e__ != hipSuccess) {                                                             \
+      po::set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e__), __FILE__, __LINE__); \
+      return false;                                                                      \
+    }                                                                                    \
+  } while (0)
+
+inline bool launch_ok(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    set_error("launch of %s failed: %s", what, hipGetErrorString(e));
+    return false;
+  }
+  return true;
+}
+
+}  // namespace po

@@ -1,0 +1,103 @@
+// Shared device/host helpers of the HIP path (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace po {
+
+typedef __bf16 bf16;
+
+constexpr int kWave = 64;
+
+enum DType : int { kF32 = 0, kBF16 = 1 };
+
+template <typename T> __device__ __forceinline__ float to_f32(T v);
+template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f32<bf16>(bf16 v) { return (float)v; }
+
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }
+
+// 16-byte vector of T for coalesced global access.
+template <typename T> struct Vec16;
+template <> struct Vec16<float> {
+  static constexpr int N = 4;
+  float v[4];
+};
+template <> struct Vec16<bf16> {
+  static constexpr int N = 8;
+  bf16 v[8];
+};
+
+template <typename T> __device__ __forceinline__ Vec16<T> load16(const T* p) {
+  Vec16<T> r;
+  *reinterpret_cast<uint4*>(&r) = *reinterpret_cast<const uint4*>(p);
+  return r;
+}
+template <typename T> __device__ __forceinline__ void store16(T* p, const Vec16<T>& r) {
+  *reinterpret_cast<uint4*>(p) = *reinterpret_cast<const uint4*>(&r);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// GeLU in its tanh form, and its derivative.  tanh(z) = 1 - 2 / (1 + exp(2z)).
+__device__ __forceinline__ float tanh_fast(float z) { return 1.0f - 2.0f / (1.0f + __expf(2.0f * z)); }
+__device__ __forceinline__ float gelu_f(float u) {
+  const float c = 0.7978845608028654f;
+  return 0.5f * u * (1.0f + tanh_fast(c * (u + 0.044715f * u * u * u)));
+}
+__device__ __forceinline__ float gelu_grad_f(float u) {
+  const float c = 0.7978845608028654f;
+  float t = tanh_fast(c * (u + 0.044715f * u * u * u));
+  float dz = c * (1.0f + 3.0f * 0.044715f * u * u);
+  return 0.5f * (1.0f + t) + 0.5f * u * (1.0f - t * t) * dz;
+}
+
+// What a GEMM does with its fp32 accumulators (all pointers may be null).
+struct Epilogue {
+  const void* bias;      // [N] of T
+  const void* residual;  // [M, N] of T, leading dimension ldc
+  void* out;             // [M, N] of T
+  void* gelu_out;        // [M, N] of T: gelu(out) or gelu(gelu_u)
+  const void* gelu_u;    // [M, N] of T: out = acc * gelu'(gelu_u)
+  float* acc_f32;        // [M, N] fp32: += acc
+  int ldc;               // leading dimension of all [M, N] operands above
+};
+
+// Applies the epilogue to one accumulator value at (m, n).
+template <typename T>
+__device__ __forceinline__ void epilogue_store(const Epilogue& e, int m, int n, float acc) {
+  size_t idx = (size_t)m * e.ldc + n;
+  if (e.acc_f32) {
+    e.acc_f32[idx] += acc;
+    return;
+  }
+  if (e.bias) acc += to_f32(static_cast<const T*>(e.bias)[n]);
+  if (e.residual) acc += to_f32(static_cast<const T*>(e.residual)[idx]);
+  if (e.gelu_u) {
+    float u = to_f32(static_cast<const T*>(e.gelu_u)[idx]);
+    if (e.gelu_out) static_cast<T*>(e.gelu_out)[idx] = from_f32<T>(gelu_f(u));
+    acc *= gelu_grad_f(u);
+    static_cast<T*>(e.out)[idx] = from_f32<T>(acc);
+    return;
+  }
+  T o = from_f32<T>(acc);
+  if (e.out) static_cast<T*>(e.out)[idx] = o;
+  if (e.gelu_out) static_cast<T*>(e.gelu_out)[idx] = from_f32<T>(gelu_f(to_f32(o)));
+}
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+}  // namespace po

@@ -1,0 +1,118 @@
+// Rank-local op order of the pipeline schedules and the placement of offload /
+// reload ops around the compute passes.  Pure host code.
+//
+// 1F1B (Table 1, first row; Appendix A): rank i of d runs d-i-1 warm-up forwards,
+// then one-forward-one-backward pairs, then drains the backwards.
+// Interleaved 1F1B (Section 3.1): v chunks per rank; the n-th forward works on
+// microbatch group n / (d v), chunk (n / d) % v, microbatch n % d within the
+// group; backwards visit the chunks in reverse.  Warm-up is d(v-1) + 2(d-i-1)
+// forwards, which gives the paper's d(v-1) + 2(d-i) - 1 forwards before the
+// first backward and dv + d - 1 units in flight on rank 0.
+// Offload placement (Section 4.2 collapsed to one rank with its own copy queues):
+// OFFLOAD directly after the unit's forward; RELOAD `prefetch` compute passes
+// before the unit's backward, never before its OFFLOAD.
+#include <math.h>
+
+#include <vector>
+
+#include "../../include/pipeoffload.h"
+#include "kernels.h"
+
+namespace po {
+
+struct Pass {
+  int kind, mb, chunk;
+};
+
+static void unit_of(int n, int d, int v, bool backward, int& mb, int& chunk) {
+  int group = n / (d * v), within = n % (d * v);
+  chunk = within / d;
+  if (backward) chunk = v - 1 - chunk;
+  mb = group * d + within % d;
+}
+
+static bool compute_passes(int schedule, int d, int rank, int v, int m, std::vector<Pass>& out) {
+  if (d < 1 || rank < 0 || rank >= d || v < 1 || m < 1) {
+    set_error("schedule: d=%d rank=%d v=%d m=%d", d, rank, v, m);
+    return false;
+  }
+  int total, warm;
+  if (schedule == PO_SCHED_1F1B) {
+    if (v != 1) {
+      set_error("schedule: 1F1B runs one chunk per rank (v=%d)", v);
+      return false;
+    }
+    total = m;
+    warm = d - rank - 1;
+  } else if (schedule == PO_SCHED_1F1B_INTERLEAVED) {
+    if (m % d != 0) {
+      set_error("schedule: interleaved 1F1B needs m (%d) to be a multiple of d (%d)", m, d);
+      return false;
+    }
+    total = m * v;
+    warm = (v - 1) * d + 2 * (d - rank - 1);
+  } else {
+    set_error("schedule: unknown schedule %d", schedule);
+    return false;
+  }
+  if (warm > total) warm = total;
+  auto emit = [&](int kind, int n) {
+    Pass p;
+    p.kind = kind;
+    if (schedule == PO_SCHED_1F1B) {
+      p.mb = n;
+      p.chunk = 0;
+    } else {
+      unit_of(n, d, v, kind == 1, p.mb, p.chunk);
+    }
+    out.push_back(p);
+  };
+  for (int n = 0; n < warm; ++n) emit(0, n);
+  for (int n = 0; n + warm < total; ++n) {
+    emit(0, warm + n);
+    emit(1, n);
+  }
+  for (int n = total - warm; n < total; ++n) emit(1, n);
+  return true;
+}
+
+static bool unit_selected(int mb, int chunk, int v, float ratio, int policy) {
+  const double eps = 1e-9;
+  if (policy == PO_SEL_LONGEST_LIFESPAN && v > 1) return chunk < (int)ceil((double)ratio * v - eps);
+  return floor((mb + 1) * (double)ratio + eps) > floor(mb * (double)ratio + eps);
+}
+
+bool build_schedule(int schedule, int d, int rank, int v, int m, float ratio, int policy, int prefetch,
+                    std::vector<po_op>& ops) {
+  if (!(ratio >= 0.f && ratio <= 1.f) || prefetch < 0 || (policy != PO_SEL_ALTERNATE_MB && policy != PO_SEL_LONGEST_LIFESPAN)) {
+    set_error("schedule: ratio=%g prefetch=%d policy=%d", ratio, prefetch, policy);
+    return false;
+  }
+  std::vector<Pass> passes;
+  if (!compute_passes(schedule, d, rank, v, m, passes)) return false;
+  int np = (int)passes.size();
+  // position of each unit's forward
+  std::vector<int> fpos((size_t)m * v, -1);
+  for (int n = 0; n < np; ++n)
+    if (passes[n].kind == 0) fpos[(size_t)passes[n].chunk * m + passes[n].mb] = n;
+  // reloads to emit before pass n
+  std::vector<std::vector<Pass>> before(np);
+  for (int n = 0; n < np; ++n) {
+    const Pass& p = passes[n];
+    if (p.kind != 1 || !unit_selected(p.mb, p.chunk, v, ratio, policy)) continue;
+    int at = n - prefetch;
+    int lo = fpos[(size_t)p.chunk * m + p.mb] + 1;
+    if (at < lo) at = lo;
+    before[at].push_back(p);
+  }
+  ops.clear();
+  for (int n = 0; n < np; ++n) {
+    for (const Pass& r : before[n]) ops.push_back(po_op{3, r.mb, r.chunk, 1.0f});
+    ops.push_back(po_op{passes[n].kind, passes[n].mb, passes[n].chunk, 0.f});
+    if (passes[n].kind == 0 && unit_selected(passes[n].mb, passes[n].chunk, v, ratio, policy))
+      ops.push_back(po_op{2, passes[n].mb, passes[n].chunk, 1.0f});
+  }
+  return true;
+}
+
+}  // namespace po

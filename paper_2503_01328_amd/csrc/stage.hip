@@ -1,0 +1,1141 @@
+// The stage runtime: parameter layout, activation slabs, pinned host slabs, the
+// copy streams with their event dependencies, the per-layer forward / backward
+// sequences and the schedule executor.
+//
+// Memory plan.  A layer's saved activations (Appendix C: layer input, q|k|v,
+// attention output, second LayerNorm's input, MLP pre-activation; plus the
+// attention log-sum-exp) live in one contiguous "layer slab" that the forward
+// kernels write directly.  Slabs come from a pool that grows on demand and is
+// never shrunk; a unit holds Lu of them.  Offload moves a slab to a pinned host
+// slab of the same size and hands the device slab back to the pool at once (in
+// host order); the pool remembers, per slab, the event after which it may be
+// overwritten, and whoever takes the slab next makes its stream wait for that
+// event (Appendix C, deterministic device memory management: buffers are
+// handed out in host order and guarded by events, not by deferred frees).
+//
+// Streams.  Compute runs on the caller's stream.  D2H copies run on the offload
+// stream after the unit's forward-done event; H2D copies run on the reload
+// stream (the same stream when copy_streams == 1, Section 4.2) after an event
+// recorded on the compute stream when po_reload is called, so a reload never
+// starts earlier than the compute work enqueued before it.  Backward waits for
+// the reload-done events of the layers it reads.
+#include <algorithm>
+#include <chrono>
+#include <deque>
+#include <map>
+#include <string.h>
+#include <vector>
+
+#include "../../include/pipeoffload.h"
+#include "kernels.h"
+
+namespace po {
+
+bool build_schedule(int schedule, int d, int rank, int v, int m, float ratio, int policy, int prefetch,
+                    std::vector<po_op>& ops);
+
+#define PO_HIP(expr)                                                                          \
+  do {                                                                                        \
+    hipError_t e__ = (expr);                                                                  \
+    if (e__ != hipSuccess) {                                                                  \
+      set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e__), __FILE__, __LINE__);  \
+      return PO_E_HIP;                                                                        \
+    }                                                                                         \
+  } while (0)
+
+#define PO_K(call)                   \
+  do {                               \
+    if (!(call)) return PO_E_HIP;    \
+  } while (0)
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ------------------------------------------------------------------------------
+// Parameter layout
+// ------------------------------------------------------------------------------
+struct ParamLayout {
+  std::vector<po_param_desc> descs;
+  int64_t total = 0;
+  int64_t emb_wte = -1, emb_wpe = -1;
+  int64_t layer_stride = 0, layer0 = 0;
+  // per-layer offsets relative to the layer's base
+  int64_t ln1_g, ln1_b, w_qkv, b_qkv, w_o, b_o, ln2_g, ln2_b, w_fc1, b_fc1, w_fc2, b_fc2;
+};
+
+int validate_config(const po_config* c) {
+  if (!c) {
+    set_error("config is NULL");
+    return PO_E_INVAL;
+  }
+  if (c->n_layers < 1 || c->n_chunks < 1 || c->n_layers % c->n_chunks != 0 || c->hidden < 64 ||
+      c->hidden % 64 != 0 || c->n_heads < 1 || c->hidden % c->n_heads != 0 || c->ffn < 64 || c->ffn % 64 != 0 ||
+      c->seq < 1 || c->vocab < 0 || (c->dtype != PO_F32 && c->dtype != PO_BF16) || c->pipeline_degree < 1 ||
+      c->rank < 0 || c->rank >= c->pipeline_degree || c->prefetch_passes < 0 ||
+      (c->copy_streams != 1 && c->copy_streams != 2) || c->hidden / c->n_heads > 256 ||
+      (c->hidden / c->n_heads) % 8 != 0 || !(c->ln_eps > 0.f)) {
+    set_error("invalid config: L=%d v=%d h=%d a=%d f=%d s=%d vocab=%d dtype=%d d=%d rank=%d prefetch=%d copy_streams=%d",
+              c->n_layers, c->n_chunks, c->hidden, c->n_heads, c->ffn, c->seq, c->vocab, c->dtype,
+              c->pipeline_degree, c->rank, c->prefetch_passes, c->copy_streams);
+    return PO_E_INVAL;
+  }
+  return PO_OK;
+}
+
+static void add_desc(ParamLayout& pl, const char* name, int layer, int64_t rows, int64_t cols, int64_t* rel,
+                     int64_t base) {
+  po_param_desc d;
+  memset(&d, 0, sizeof(d));
+  strncpy(d.name, name, sizeof(d.name) - 1);
+  d.layer = layer;
+  d.offset_elems = pl.total;
+  d.rows = rows;
+  d.cols = cols;
+  if (rel) *rel = pl.total - base;
+  pl.total += rows * cols;
+  pl.descs.push_back(d);
+}
+
+void build_param_layout(const po_config& c, ParamLayout& pl) {
+  int64_t h = c.hidden, f = c.ffn;
+  pl.descs.clear();
+  pl.total = 0;
+  if (c.vocab > 0) {
+    pl.emb_wte = pl.total;
+    add_desc(pl, "wte", -1, c.vocab, h, nullptr, 0);
+    pl.emb_wpe = pl.total;
+    add_desc(pl, "wpe", -1, c.seq, h, nullptr, 0);
+  }
+  pl.layer0 = pl.total;
+  for (int l = 0; l < c.n_layers; ++l) {
+    int64_t base = pl.total;
+    int64_t dummy;
+    bool first = l == 0;
+    add_desc(pl, "ln1_g", l, 1, h, first ? &pl.ln1_g : &dummy, base);
+    add_desc(pl, "ln1_b", l, 1, h, first ? &pl.ln1_b : &dummy, base);
+    add_desc(pl, "w_qkv", l, h, 3 * h, first ? &pl.w_qkv : &dummy, base);
+    add_desc(pl, "b_qkv", l, 1, 3 * h, first ? &pl.b_qkv : &dummy, base);
+    add_desc(pl, "w_o", l, h, h, first ? &pl.w_o : &dummy, base);
+    add_desc(pl, "b_o", l, 1, h, first ? &pl.b_o : &dummy, base);
+    add_desc(pl, "ln2_g", l, 1, h, first ? &pl.ln2_g : &dummy, base);
+    add_desc(pl, "ln2_b", l, 1, h, first ? &pl.ln2_b : &dummy, base);
+    add_desc(pl, "w_fc1", l, h, f, first ? &pl.w_fc1 : &dummy, base);
+    add_desc(pl, "b_fc1", l, 1, f, first ? &pl.b_fc1 : &dummy, base);
+    add_desc(pl, "w_fc2", l, f, h, first ? &pl.w_fc2 : &dummy, base);
+    add_desc(pl, "b_fc2", l, 1, h, first ? &pl.b_fc2 : &dummy, base);
+    if (first) pl.layer_stride = pl.total - base;
+  }
+}
+
+// ------------------------------------------------------------------------------
+// Saved-activation layout of one layer slab
+// ------------------------------------------------------------------------------
+struct SlabLayout {
+  size_t off_x, off_qkv, off_o, off_x1, off_u, off_lse, bytes;
+  size_t sz_x, sz_qkv, sz_o, sz_x1, sz_u, sz_lse;
+  size_t packed_bytes;  // segments back to back, no alignment padding
+};
+
+void build_slab_layout(const po_config& c, SlabLayout& sl) {
+  size_t E = c.dtype == PO_BF16 ? 2 : 4;
+  size_t s = c.seq, h = c.hidden, f = c.ffn, a = c.n_heads;
+  sl.sz_x = s * h * E;
+  sl.sz_qkv = s * 3 * h * E;
+  sl.sz_o = s * h * E;
+  sl.sz_x1 = s * h * E;
+  sl.sz_u = s * f * E;
+  sl.sz_lse = a * s * 4;
+  size_t off = 0;
+  sl.off_x = off;
+  off = align_up(off + sl.sz_x, 256);
+  sl.off_qkv = off;
+  off = align_up(off + sl.sz_qkv, 256);
+  sl.off_o = off;
+  off = align_up(off + sl.sz_o, 256);
+  sl.off_x1 = off;
+  off = align_up(off + sl.sz_x1, 256);
+  sl.off_u = off;
+  off = align_up(off + sl.sz_u, 256);
+  sl.off_lse = off;
+  off = align_up(off + sl.sz_lse, 256);
+  sl.bytes = off;
+  sl.packed_bytes = align_up(sl.sz_x, 16) + align_up(sl.sz_qkv, 16) + align_up(sl.sz_o, 16) +
+                    align_up(sl.sz_x1, 16) + align_up(sl.sz_u, 16) + align_up(sl.sz_lse, 16);
+}
+
+// ------------------------------------------------------------------------------
+// Pools
+// ------------------------------------------------------------------------------
+struct PoolBuf {
+  char* ptr = nullptr;
+  hipEvent_t free_event = nullptr;  // work after which the buffer may be overwritten
+  bool guarded = false;
+};
+
+struct Pool {
+  bool host = false;
+  size_t buf_bytes = 0;
+  uint64_t cap = 0;
+  std::vector<PoolBuf> bufs;
+  std::deque<int> free_list;
+  int in_use = 0;
+
+  uint64_t allocated() const { return (uint64_t)bufs.size() * buf_bytes; }
+
+  // Takes a buffer; `stream` (the first stream that will write it) waits for the guard event.
+  int acquire(hipStream_t stream, int* out) {
+    int idx;
+    if (!free_list.empty()) {
+      idx = free_list.front();
+      free_list.pop_front();
+      if (bufs[idx].guarded) PO_HIP(hipStreamWaitEvent(stream, bufs[idx].free_event, 0));
+    } else {
+      if (cap && allocated() + buf_bytes > cap) {
+        set_error("%s pool cap of %llu bytes reached (%zu buffers of %zu bytes in use)", host ? "host" : "device",
+                  (unsigned long long)cap, bufs.size(), buf_bytes);
+        return host ? PO_E_HOST_OOM : PO_E_DEVICE_OOM;
+      }
+      PoolBuf b;
+      hipError_t e = host ? hipHostMalloc((void**)&b.ptr, buf_bytes, hipHostMallocDefault)
+                          : hipMalloc((void**)&b.ptr, buf_bytes);
+      if (e != hipSuccess) {
+        (void)hipGetLastError();
+        set_error("%s of %zu bytes failed: %s", host ? "hipHostMalloc" : "hipMalloc", buf_bytes,
+                  hipGetErrorString(e));
+        return host ? PO_E_HOST_OOM : PO_E_DEVICE_OOM;
+      }
+      PO_HIP(hipEventCreateWithFlags(&b.free_event, hipEventDisableTiming));
+      bufs.push_back(b);
+      idx = (int)bufs.size() - 1;
+    }
+    ++in_use;
+    *out = idx;
+    return PO_OK;
+  }
+
+  // Hands a buffer back; it may be overwritten once the work enqueued on `stream` so far is done.
+  int release(int idx, hipStream_t stream) {
+    PO_HIP(hipEventRecord(bufs[idx].free_event, stream));
+    bufs[idx].guarded = true;
+    free_list.push_back(idx);
+    --in_use;
+    return PO_OK;
+  }
+
+  void destroy() {
+    for (PoolBuf& b : bufs) {
+      if (b.free_event) (void)hipEventDestroy(b.free_event);
+      if (b.ptr) (void)(host ? hipHostFree(b.ptr) : hipFree(b.ptr));
+    }
+    bufs.clear();
+    free_list.clear();
+    in_use = 0;
+  }
+};
+
+// Reusable events (timing enabled where asked).
+struct EventBank {
+  std::vector<hipEvent_t> ev;
+  size_t next = 0;
+  unsigned flags = 0;
+  int get(hipEvent_t* out) {
+    if (next == ev.size()) {
+      hipEvent_t e;
+      PO_HIP(hipEventCreateWithFlags(&e, flags));
+      ev.push_back(e);
+    }
+    *out = ev[next++];
+    return PO_OK;
+  }
+  void reset() { next = 0; }
+  void destroy() {
+    for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+    ev.clear();
+    next = 0;
+  }
+};
+
+enum LayerState { L_EMPTY = 0, L_RESIDENT, L_HOST };
+
+struct UnitLayer {
+  int state = L_EMPTY;
+  int dev = -1;              // device slab index
+  int hostbuf = -1;          // host slab index
+  hipEvent_t d2h_done = nullptr;
+  hipEvent_t h2d_done = nullptr;  // non-null: backward must wait for it
+};
+
+struct Unit {
+  bool live = false;
+  std::vector<UnitLayer> layers;
+  hipEvent_t fwd_done = nullptr;
+  const void* x_in = nullptr;  // tokens pointer for embedding units (needed again in backward)
+};
+
+struct TimedSpan {
+  hipEvent_t start, stop;
+  int kind;  // 0 compute, 1 d2h, 2 h2d, 3 pack/unpack
+};
+
+}  // namespace po
+
+using namespace po;
+
+struct po_stage {
+  po_config cfg;
+  ParamLayout pl;
+  SlabLayout sl;
+  int Lu = 0;
+  size_t E = 2;
+  hipStream_t compute = nullptr, offload = nullptr, reload = nullptr;
+  bool own_reload_stream = false;
+  const char* params = nullptr;
+  float* grads = nullptr;
+  Pool dev_pool, host_pool;
+  EventBank sync_events, time_events;
+  std::map<int64_t, Unit> units;
+  std::vector<TimedSpan> spans;
+  // workspaces
+  char* ws = nullptr;
+  size_t ws_bytes = 0;
+  char *w_n, *w_g, *w_du, *w_dqkv, *w_do, *w_dx1, *w_dn, *w_dy[2], *w_x0;
+  float *w_delta, *w_lnws, *w_colws;
+  // accounting
+  int resident_units = 0, in_flight_units = 0;
+  po_stats stats;
+  bool collect_timing = false;
+
+  void note_usage() {
+    uint64_t b = (uint64_t)dev_pool.in_use * sl.bytes;
+    if (b > stats.peak_slab_bytes) stats.peak_slab_bytes = b;
+    if (resident_units > stats.peak_resident_units) stats.peak_resident_units = resident_units;
+    if (in_flight_units > stats.peak_in_flight_units) stats.peak_in_flight_units = in_flight_units;
+  }
+  const char* P(int layer, int64_t rel) const {
+    return params + (size_t)(pl.layer0 + (int64_t)layer * pl.layer_stride + rel) * E;
+  }
+  float* G(int layer, int64_t rel) const { return grads + pl.layer0 + (int64_t)layer * pl.layer_stride + rel; }
+};
+
+namespace po {
+
+static int64_t unit_key(int mb, int chunk) { return ((int64_t)chunk << 32) | (uint32_t)mb; }
+
+static int span_begin(po_stage* st, hipStream_t stream, int kind, size_t* idx) {
+  if (!st->collect_timing) {
+    *idx = (size_t)-1;
+    return PO_OK;
+  }
+  TimedSpan sp;
+  sp.kind = kind;
+  int rc = st->time_events.get(&sp.start);
+  if (rc) return rc;
+  rc = st->time_events.get(&sp.stop);
+  if (rc) return rc;
+  PO_HIP(hipEventRecord(sp.start, stream));
+  st->spans.push_back(sp);
+  *idx = st->spans.size() - 1;
+  return PO_OK;
+}
+static int span_end(po_stage* st, hipStream_t stream, size_t idx) {
+  if (idx == (size_t)-1) return PO_OK;
+  PO_HIP(hipEventRecord(st->spans[idx].stop, stream));
+  return PO_OK;
+}
+
+static bool unit_has_resident_layer(const Unit& u) {
+  for (const UnitLayer& l : u.layers)
+    if (l.state == L_RESIDENT) return true;
+  return false;
+}
+
+// ------------------------------------------------------------------------------
+// Layer forward / backward
+// ------------------------------------------------------------------------------
+static Epilogue make_ep(int ldc) {
+  Epilogue e;
+  memset(&e, 0, sizeof(e));
+  e.ldc = ldc;
+  return e;
+}
+
+static int layer_forward(po_stage* st, int layer, char* slab, void* y_out) {
+  const po_config& c = st->cfg;
+  const ParamLayout& pl = st->pl;
+  const SlabLayout& sl = st->sl;
+  int s = c.seq, h = c.hidden, f = c.ffn, dt = c.dtype;
+  hipStream_t q = st->compute;
+  char* x = slab + sl.off_x;
+  char* qkv = slab + sl.off_qkv;
+  char* o = slab + sl.off_o;
+  char* x1 = slab + sl.off_x1;
+  char* u = slab + sl.off_u;
+  float* lse = (float*)(slab + sl.off_lse);
+
+  PO_K(layernorm_forward(dt, x, st->P(layer, pl.ln1_g), st->P(layer, pl.ln1_b), st->w_n, s, h, c.ln_eps, q));
+  Epilogue e = make_ep(3 * h);
+  e.bias = st->P(layer, pl.b_qkv);
+  e.out = qkv;
+  PO_K(gemm(dt, 0, 0, s, 3 * h, h, st->w_n, h, st->P(layer, pl.w_qkv), 3 * h, e, false, q));
+  PO_K(attention_forward(dt, qkv, o, lse, s, h, c.n_heads, false, q));
+  e = make_ep(h);
+  e.bias = st->P(layer, pl.b_o);
+  e.residual = x;
+  e.out = x1;
+  PO_K(gemm(dt, 0, 0, s, h, h, o, h, st->P(layer, pl.w_o), h, e, false, q));
+  PO_K(layernorm_forward(dt, x1, st->P(layer, pl.ln2_g), st->P(layer, pl.ln2_b), st->w_n, s, h, c.ln_eps, q));
+  e = make_ep(f);
+  e.bias = st->P(layer, pl.b_fc1);
+  e.out = u;
+  e.gelu_out = st->w_g;
+  PO_K(gemm(dt, 0, 0, s, f, h, st->w_n, h, st->P(layer, pl.w_fc1), f, e, false, q));
+  e = make_ep(h);
+  e.bias = st->P(layer, pl.b_fc2);
+  e.residual = x1;
+  e.out = y_out;
+  PO_K(gemm(dt, 0, 0, s, h, f, st->w_g, f, st->P(layer, pl.w_fc2), h, e, false, q));
+  return PO_OK;
+}
+
+// dy: gradient of the layer output; dx_out: where the gradient of the layer input goes.
+static int layer_backward(po_stage* st, int layer, const char* slab, const void* dy, void* dx_out) {
+  const po_config& c = st->cfg;
+  const ParamLayout& pl = st->pl;
+  const SlabLayout& sl = st->sl;
+  int s = c.seq, h = c.hidden, f = c.ffn, dt = c.dtype;
+  hipStream_t q = st->compute;
+  const char* x = slab + sl.off_x;
+  const char* qkv = slab + sl.off_qkv;
+  const char* o = slab + sl.off_o;
+  const char* x1 = slab + sl.off_x1;
+  const char* u = slab + sl.off_u;
+  const float* lse = (const float*)(slab + sl.off_lse);
+
+  // FC2: du = (dy W2^T) * gelu'(u), g = gelu(u) recomputed; dW2 += g^T dy; db2 += colsum(dy)
+  Epilogue e = make_ep(f);
+  e.out = st->w_du;
+  e.gelu_u = u;
+  e.gelu_out = st->w_g;
+  PO_K(gemm(dt, 0, 1, s, f, h, dy, h, st->P(layer, pl.w_fc2), h, e, false, q));
+  e = make_ep(h);
+  e.acc_f32 = st->G(layer, pl.w_fc2);
+  PO_K(gemm(dt, 1, 0, f, h, s, st->w_g, f, dy, h, e, false, q));
+  PO_K(colsum_accumulate(dt, dy, st->G(layer, pl.b_fc2), st->w_colws, s, h, q));
+  // FC1: n2 recomputed; dW1 += n2^T du; db1 += colsum(du); dn2 = du W1^T
+  PO_K(layernorm_forward(dt, x1, st->P(layer, pl.ln2_g), st->P(layer, pl.ln2_b), st->w_n, s, h, c.ln_eps, q));
+  e = make_ep(f);
+  e.acc_f32 = st->G(layer, pl.w_fc1);
+  PO_K(gemm(dt, 1, 0, h, f, s, st->w_n, h, st->w_du, f, e, false, q));
+  PO_K(colsum_accumulate(dt, st->w_du, st->G(layer, pl.b_fc1), st->w_colws, s, f, q));
+  e = make_ep(h);
+  e.out = st->w_dn;
+  PO_K(gemm(dt, 0, 1, s, h, f, st->w_du, f, st->P(layer, pl.w_fc1), f, e, false, q));
+  // LN2 backward + residual: dx1 = dy + LNbwd(dn2)
+  PO_K(layernorm_backward(dt, st->w_dn, x1, st->P(layer, pl.ln2_g), dy, st->w_dx1, st->G(layer, pl.ln2_g),
+                          st->G(layer, pl.ln2_b), st->w_lnws, s, h, c.ln_eps, q));
+  // Out-proj: dWo += O^T dx1; dbo += colsum(dx1); dO = dx1 Wo^T
+  e = make_ep(h);
+  e.acc_f32 = st->G(layer, pl.w_o);
+  PO_K(gemm(dt, 1, 0, h, h, s, o, h, st->w_dx1, h, e, false, q));
+  PO_K(colsum_accumulate(dt, st->w_dx1, st->G(layer, pl.b_o), st->w_colws, s, h, q));
+  e = make_ep(h);
+  e.out = st->w_do;
+  PO_K(gemm(dt, 0, 1, s, h, h, st->w_dx1, h, st->P(layer, pl.w_o), h, e, false, q));
+  // Attention backward
+  PO_K(attention_backward(dt, qkv, o, lse, st->w_do, st->w_dqkv, st->w_delta, s, h, c.n_heads, false, q));
+  // QKV: n1 recomputed; dWqkv += n1^T dqkv; dbqkv += colsum(dqkv); dn1 = dqkv Wqkv^T
+  PO_K(layernorm_forward(dt, x, st->P(layer, pl.ln1_g), st->P(layer, pl.ln1_b), st->w_n, s, h, c.ln_eps, q));
+  e = make_ep(3 * h);
+  e.acc_f32 = st->G(layer, pl.w_qkv);
+  PO_K(gemm(dt, 1, 0, h, 3 * h, s, st->w_n, h, st->w_dqkv, 3 * h, e, false, q));
+  PO_K(colsum_accumulate(dt, st->w_dqkv, st->G(layer, pl.b_qkv), st->w_colws, s, 3 * h, q));
+  e = make_ep(h);
+  e.out = st->w_dn;
+  PO_K(gemm(dt, 0, 1, s, h, 3 * h, st->w_dqkv, 3 * h, st->P(layer, pl.w_qkv), 3 * h, e, false, q));
+  // LN1 backward + residual: dx = dx1 + LNbwd(dn1)
+  PO_K(layernorm_backward(dt, st->w_dn, x, st->P(layer, pl.ln1_g), st->w_dx1, dx_out, st->G(layer, pl.ln1_g),
+                          st->G(layer, pl.ln1_b), st->w_lnws, s, h, c.ln_eps, q));
+  return PO_OK;
+}
+
+// ------------------------------------------------------------------------------
+// Unit-level operations
+// ------------------------------------------------------------------------------
+int stage_forward(po_stage* st, int mb, int chunk, const void* x_in, void* y_out) {
+  const po_config& c = st->cfg;
+  if (!st->params) {
+    set_error("forward before po_bind_params");
+    return PO_E_STATE;
+  }
+  if (mb < 0 || chunk < 0 || chunk >= c.n_chunks || !x_in || !y_out) {
+    set_error("forward: mb=%d chunk=%d x_in=%p y_out=%p", mb, chunk, x_in, y_out);
+    return PO_E_INVAL;
+  }
+  Unit& u = st->units[unit_key(mb, chunk)];
+  if (u.live) {
+    set_error("forward of unit (mb %d, chunk %d) that is still in flight", mb, chunk);
+    return PO_E_STATE;
+  }
+  u.layers.assign(st->Lu, UnitLayer());
+  for (int l = 0; l < st->Lu; ++l) {
+    int rc = st->dev_pool.acquire(st->compute, &u.layers[l].dev);
+    if (rc) {
+      for (int k = 0; k < l; ++k) st->dev_pool.release(u.layers[k].dev, st->compute);
+      u.layers.clear();
+      return rc;
+    }
+    u.layers[l].state = L_RESIDENT;
+  }
+  u.live = true;
+  u.x_in = x_in;
+  ++st->in_flight_units;
+  ++st->resident_units;
+  st->note_usage();
+
+  size_t span;
+  int rc = span_begin(st, st->compute, 0, &span);
+  if (rc) return rc;
+  bool embed = c.vocab > 0 && chunk == 0;
+  char* slab0 = st->dev_pool.bufs[u.layers[0].dev].ptr;
+  if (embed) {
+    PO_K(embedding_forward(c.dtype, (const int32_t*)x_in, st->params + (size_t)st->pl.emb_wte * st->E,
+                           st->params + (size_t)st->pl.emb_wpe * st->E, slab0 + st->sl.off_x, c.seq, c.hidden,
+                           c.vocab, st->compute));
+  } else {
+    PO_K(copy_bytes(slab0 + st->sl.off_x, x_in, st->sl.sz_x, st->compute));
+  }
+  for (int l = 0; l < st->Lu; ++l) {
+    char* slab = st->dev_pool.bufs[u.layers[l].dev].ptr;
+    void* out = (l + 1 < st->Lu) ? (void*)(st->dev_pool.bufs[u.layers[l + 1].dev].ptr + st->sl.off_x) : y_out;
+    rc = layer_forward(st, chunk * st->Lu + l, slab, out);
+    if (rc) return rc;
+  }
+  rc = span_end(st, st->compute, span);
+  if (rc) return rc;
+  rc = st->sync_events.get(&u.fwd_done);
+  if (rc) return rc;
+  PO_HIP(hipEventRecord(u.fwd_done, st->compute));
+  ++st->stats.n_compute_passes;
+  return PO_OK;
+}
+
+static Unit* find_live_unit(po_stage* st, int mb, int chunk, const char* what) {
+  auto it = st->units.find(unit_key(mb, chunk));
+  if (it == st->units.end() || !it->second.live) {
+    set_error("%s of unit (mb %d, chunk %d) that was not forwarded", what, mb, chunk);
+    return nullptr;
+  }
+  return &it->second;
+}
+
+static void slab_segments(const SlabLayout& sl, char* slab, void** ptrs, uint64_t* bytes) {
+  size_t offs[6] = {sl.off_x, sl.off_qkv, sl.off_o, sl.off_x1, sl.off_u, sl.off_lse};
+  size_t szs[6] = {sl.sz_x, sl.sz_qkv, sl.sz_o, sl.sz_x1, sl.sz_u, sl.sz_lse};
+  for (int i = 0; i < 6; ++i) {
+    ptrs[i] = slab + offs[i];
+    bytes[i] = align_up(szs[i], 16);
+  }
+}
+
+int stage_offload(po_stage* st, int mb, int chunk, float ratio) {
+  if (!(ratio >= 0.f && ratio <= 1.f)) {
+    set_error("offload: ratio %g outside [0, 1]", ratio);
+    return PO_E_INVAL;
+  }
+  Unit* u = find_live_unit(st, mb, chunk, "offload");
+  if (!u) return PO_E_STATE;
+  int n = (int)ceil((double)ratio * st->Lu - 1e-9);
+  for (int l = 0; l < n; ++l)
+    if (u->layers[l].state != L_RESIDENT) {
+      set_error("offload of unit (mb %d, chunk %d): layer %d is not resident", mb, chunk, l);
+      return PO_E_STATE;
+    }
+  bool was_resident = unit_has_resident_layer(*u);
+  hipStream_t q = st->offload;
+  if (n > 0) PO_HIP(hipStreamWaitEvent(q, u->fwd_done, 0));
+  for (int l = 0; l < n; ++l) {
+    UnitLayer& L = u->layers[l];
+    if (L.h2d_done) {  // reloaded and offloaded again without a backward in between
+      PO_HIP(hipStreamWaitEvent(q, L.h2d_done, 0));
+      L.h2d_done = nullptr;
+    }
+    int rc = st->host_pool.acquire(q, &L.hostbuf);
+    if (rc) return rc;
+    char* dev = st->dev_pool.bufs[L.dev].ptr;
+    char* host = st->host_pool.bufs[L.hostbuf].ptr;
+    size_t span;
+    if (st->cfg.staged_copies) {
+      int stg;
+      rc = st->dev_pool.acquire(q, &stg);
+      if (rc) return rc;
+      st->note_usage();
+      char* staging = st->dev_pool.bufs[stg].ptr;
+      void* ptrs[6];
+      uint64_t bytes[6];
+      slab_segments(st->sl, dev, ptrs, bytes);
+      rc = span_begin(st, q, 3, &span);
+      if (rc) return rc;
+      PO_K(pack_segments(ptrs, bytes, 6, staging, q));
+      rc = span_end(st, q, span);
+      if (rc) return rc;
+      if (st->cfg.debug_poison) PO_K(fill_u32(dev, 0x7fc07fc0u, st->sl.bytes, q));
+      rc = st->dev_pool.release(L.dev, q);  // the slab is free as soon as it is packed
+      if (rc) return rc;
+      rc = span_begin(st, q, 1, &span);
+      if (rc) return rc;
+      PO_HIP(hipMemcpyAsync(host, staging, st->sl.packed_bytes, hipMemcpyDeviceToHost, q));
+      rc = span_end(st, q, span);
+      if (rc) return rc;
+      rc = st->dev_pool.release(stg, q);
+      if (rc) return rc;
+      st->stats.bytes_d2h += st->sl.packed_bytes;
+    } else {
+      rc = span_begin(st, q, 1, &span);
+      if (rc) return rc;
+      PO_HIP(hipMemcpyAsync(host, dev, st->sl.bytes, hipMemcpyDeviceToHost, q));
+      rc = span_end(st, q, span);
+      if (rc) return rc;
+      if (st->cfg.debug_poison) PO_K(fill_u32(dev, 0x7fc07fc0u, st->sl.bytes, q));
+      rc = st->dev_pool.release(L.dev, q);
+      if (rc) return rc;
+      st->stats.bytes_d2h += st->sl.bytes;
+    }
+    rc = st->sync_events.get(&L.d2h_done);
+    if (rc) return rc;
+    PO_HIP(hipEventRecord(L.d2h_done, q));
+    L.dev = -1;
+    L.state = L_HOST;
+    ++st->stats.n_offloads;
+  }
+  if (was_resident && !unit_has_resident_layer(*u)) --st->resident_units;
+  return PO_OK;
+}
+
+int stage_reload(po_stage* st, int mb, int chunk) {
+  Unit* u = find_live_unit(st, mb, chunk, "reload");
+  if (!u) return PO_E_STATE;
+  bool any = false;
+  for (const UnitLayer& L : u->layers) any |= L.state == L_HOST;
+  if (!any) return PO_OK;
+  bool was_resident = unit_has_resident_layer(*u);
+  hipStream_t q = st->reload;
+  // The reload may start once the compute work enqueued so far has been reached.
+  hipEvent_t gate;
+  int rc = st->sync_events.get(&gate);
+  if (rc) return rc;
+  PO_HIP(hipEventRecord(gate, st->compute));
+  PO_HIP(hipStreamWaitEvent(q, gate, 0));
+  for (int l = 0; l < st->Lu; ++l) {
+    UnitLayer& L = u->layers[l];
+    if (L.state != L_HOST) continue;
+    if (q != st->offload) PO_HIP(hipStreamWaitEvent(q, L.d2h_done, 0));
+    rc = st->dev_pool.acquire(q, &L.dev);
+    if (rc) return rc;
+    st->note_usage();
+    char* dev = st->dev_pool.bufs[L.dev].ptr;
+    char* host = st->host_pool.bufs[L.hostbuf].ptr;
+    size_t span;
+    if (st->cfg.staged_copies) {
+      int stg;
+      rc = st->dev_pool.acquire(q, &stg);
+      if (rc) return rc;
+      st->note_usage();
+      char* staging = st->dev_pool.bufs[stg].ptr;
+      rc = span_begin(st, q, 2, &span);
+      if (rc) return rc;
+      PO_HIP(hipMemcpyAsync(staging, host, st->sl.packed_bytes, hipMemcpyHostToDevice, q));
+      rc = span_end(st, q, span);
+      if (rc) return rc;
+      void* ptrs[6];
+      uint64_t bytes[6];
+      slab_segments(st->sl, dev, ptrs, bytes);
+      rc = span_begin(st, q, 3, &span);
+      if (rc) return rc;
+      PO_K(unpack_segments(ptrs, bytes, 6, staging, q));
+      rc = span_end(st, q, span);
+      if (rc) return rc;
+      rc = st->dev_pool.release(stg, q);
+      if (rc) return rc;
+      st->stats.bytes_h2d += st->sl.packed_bytes;
+    } else {
+      rc = span_begin(st, q, 2, &span);
+      if (rc) return rc;
+      PO_HIP(hipMemcpyAsync(dev, host, st->sl.bytes, hipMemcpyHostToDevice, q));
+      rc = span_end(st, q, span);
+      if (rc) return rc;
+      st->stats.bytes_h2d += st->sl.bytes;
+    }
+    rc = st->sync_events.get(&L.h2d_done);
+    if (rc) return rc;
+    PO_HIP(hipEventRecord(L.h2d_done, q));
+    rc = st->host_pool.release(L.hostbuf, q);
+    if (rc) return rc;
+    L.hostbuf = -1;
+    L.state = L_RESIDENT;
+    ++st->stats.n_reloads;
+  }
+  if (!was_resident) ++st->resident_units;
+  st->note_usage();
+  return PO_OK;
+}
+
+int stage_backward(po_stage* st, int mb, int chunk, const void* dy, void* dx) {
+  const po_config& c = st->cfg;
+  if (!st->grads) {
+    set_error("backward before po_bind_params");
+    return PO_E_STATE;
+  }
+  Unit* u = find_live_unit(st, mb, chunk, "backward");
+  if (!u) return PO_E_STATE;
+  bool embed = c.vocab > 0 && chunk == 0;
+  if (!dy || (!dx && !embed)) {
+    set_error("backward: dy=%p dx=%p", dy, dx);
+    return PO_E_INVAL;
+  }
+  for (int l = 0; l < st->Lu; ++l)
+    if (u->layers[l].state != L_RESIDENT) {
+      set_error("backward of unit (mb %d, chunk %d): layer %d is on the host and no reload was issued", mb, chunk,
+                l);
+      return PO_E_STATE;
+    }
+  for (UnitLayer& L : u->layers)
+    if (L.h2d_done) {
+      PO_HIP(hipStreamWaitEvent(st->compute, L.h2d_done, 0));
+      L.h2d_done = nullptr;
+    }
+  size_t span;
+  int rc = span_begin(st, st->compute, 0, &span);
+  if (rc) return rc;
+  const void* grad = dy;
+  for (int l = st->Lu - 1; l >= 0; --l) {
+    const char* slab = st->dev_pool.bufs[u->layers[l].dev].ptr;
+    void* out;
+    if (l > 0)
+      out = st->w_dy[l & 1];
+    else
+      out = embed ? (void*)st->w_dy[0] : dx;
+    rc = layer_backward(st, chunk * st->Lu + l, slab, grad, out);
+    if (rc) return rc;
+    grad = out;
+  }
+  if (embed)
+    PO_K(embedding_backward(c.dtype, (const int32_t*)u->x_in, grad, st->grads + st->pl.emb_wte,
+                            st->grads + st->pl.emb_wpe, c.seq, c.hidden, c.vocab, st->compute));
+  rc = span_end(st, st->compute, span);
+  if (rc) return rc;
+  for (UnitLayer& L : u->layers) {
+    if (c.debug_poison) PO_K(fill_u32(st->dev_pool.bufs[L.dev].ptr, 0x7fc07fc0u, st->sl.bytes, st->compute));
+    rc = st->dev_pool.release(L.dev, st->compute);
+    if (rc) return rc;
+    L = UnitLayer();
+  }
+  u->live = false;
+  --st->in_flight_units;
+  --st->resident_units;
+  ++st->stats.n_compute_passes;
+  return PO_OK;
+}
+
+int stage_synchronize(po_stage* st) {
+  PO_HIP(hipStreamSynchronize(st->compute));
+  PO_HIP(hipStreamSynchronize(st->offload));
+  if (st->reload != st->offload) PO_HIP(hipStreamSynchronize(st->reload));
+  return PO_OK;
+}
+
+// Folds the recorded spans into the stats (all streams must be drained).
+static int collect_spans(po_stage* st) {
+  double busy[4] = {0, 0, 0, 0};
+  hipEvent_t first = nullptr, last = nullptr;
+  for (const TimedSpan& sp : st->spans) {
+    float ms = 0.f;
+    PO_HIP(hipEventElapsedTime(&ms, sp.start, sp.stop));
+    busy[sp.kind] += ms * 1e-3;
+    if (sp.kind == 0) {
+      if (!first) first = sp.start;
+      last = sp.stop;
+    }
+  }
+  st->stats.compute_busy_s = busy[0];
+  st->stats.d2h_busy_s = busy[1];
+  st->stats.h2d_busy_s = busy[2];
+  st->stats.pack_busy_s = busy[3];
+  if (first && last) {
+    float ms = 0.f;
+    PO_HIP(hipEventElapsedTime(&ms, first, last));
+    st->stats.compute_span_s = ms * 1e-3;
+  }
+  return PO_OK;
+}
+
+static void reset_run_stats(po_stage* st) {
+  uint64_t pool = st->dev_pool.allocated(), host = st->host_pool.allocated();
+  memset(&st->stats, 0, sizeof(st->stats));
+  st->stats.pool_bytes_allocated = pool;
+  st->stats.host_bytes_allocated = host;
+  st->stats.workspace_bytes = st->ws_bytes;
+  st->spans.clear();
+  st->time_events.reset();
+}
+
+int stage_run_schedule(po_stage* st, int schedule, int m, float ratio, const void* const* x_in, void* const* y_out,
+                       const void* const* dy, void* const* dx, po_stats* out) {
+  const po_config& c = st->cfg;
+  if (!x_in || !y_out || !dy || !dx) {
+    set_error("run_schedule: NULL pointer array");
+    return PO_E_INVAL;
+  }
+  std::vector<po_op> ops;
+  if (!build_schedule(schedule, c.pipeline_degree, c.rank, c.n_chunks, m, ratio, c.select_policy,
+                      c.prefetch_passes, ops))
+    return PO_E_INVAL;
+  for (auto& kv : st->units)
+    if (kv.second.live) {
+      set_error("run_schedule with units still in flight");
+      return PO_E_STATE;
+    }
+  int rc = stage_synchronize(st);
+  if (rc) return rc;
+  st->sync_events.reset();
+  reset_run_stats(st);
+  st->collect_timing = true;
+  auto t0 = std::chrono::steady_clock::now();
+  for (const po_op& op : ops) {
+    size_t i = (size_t)op.chunk * m + op.mb;
+    switch (op.kind) {
+      case 0: rc = stage_forward(st, op.mb, op.chunk, x_in[i], y_out[i]); break;
+      case 1: rc = stage_backward(st, op.mb, op.chunk, dy[i], dx[i]); break;
+      case 2: rc = stage_offload(st, op.mb, op.chunk, op.ratio); break;
+      default: rc = stage_reload(st, op.mb, op.chunk); break;
+    }
+    if (rc) break;
+  }
+  int rc2 = stage_synchronize(st);
+  auto t1 = std::chrono::steady_clock::now();
+  st->collect_timing = false;
+  if (rc) return rc;
+  if (rc2) return rc2;
+  st->stats.wall_s = std::chrono::duration<double>(t1 - t0).count();
+  st->stats.tokens_per_s = (double)m * c.seq / st->stats.wall_s;
+  st->stats.pool_bytes_allocated = st->dev_pool.allocated();
+  st->stats.host_bytes_allocated = st->host_pool.allocated();
+  rc = collect_spans(st);
+  if (rc) return rc;
+  if (out) *out = st->stats;
+  return PO_OK;
+}
+
+// ------------------------------------------------------------------------------
+// Create / destroy
+// ------------------------------------------------------------------------------
+int stage_create(const po_config* cfg, void* compute_stream, po_stage** out) {
+  int rc = validate_config(cfg);
+  if (rc) return rc;
+  if (!out) {
+    set_error("stage_create: out is NULL");
+    return PO_E_INVAL;
+  }
+  po_stage* st = new po_stage();
+  st->cfg = *cfg;
+  build_param_layout(st->cfg, st->pl);
+  build_slab_layout(st->cfg, st->sl);
+  st->Lu = cfg->n_layers / cfg->n_chunks;
+  st->E = cfg->dtype == PO_BF16 ? 2 : 4;
+  st->compute = (hipStream_t)compute_stream;
+  memset(&st->stats, 0, sizeof(st->stats));
+  st->sync_events.flags = hipEventDisableTiming;
+  st->time_events.flags = hipEventDefault;
+  st->dev_pool.host = false;
+  st->dev_pool.buf_bytes = st->sl.bytes;
+  st->dev_pool.cap = cfg->device_pool_cap_bytes;
+  st->host_pool.host = true;
+  st->host_pool.buf_bytes = st->sl.bytes;
+  st->host_pool.cap = cfg->host_pool_cap_bytes;
+  auto fail = [&](int code) {
+    po_stage_destroy(st);
+    return code;
+  };
+  // Copy streams at the default priority.
+  if (hipStreamCreateWithFlags(&st->offload, hipStreamNonBlocking) != hipSuccess) {
+    set_error("creating the offload stream failed");
+    st->offload = nullptr;
+    return fail(PO_E_HIP);
+  }
+  if (cfg->copy_streams == 2) {
+    if (hipStreamCreateWithFlags(&st->reload, hipStreamNonBlocking) != hipSuccess) {
+      set_error("creating the reload stream failed");
+      st->reload = nullptr;
+      return fail(PO_E_HIP);
+    }
+    st->own_reload_stream = true;
+  } else {
+    st->reload = st->offload;
+  }
+  // Workspaces: one allocation, carved up.
+  size_t s = cfg->seq, h = cfg->hidden, f = cfg->ffn, E = st->E;
+  size_t sh = align_up(s * h * E, 256), sf = align_up(s * f * E, 256), s3h = align_up(s * 3 * h * E, 256);
+  size_t delta = align_up((size_t)cfg->n_heads * s * 4, 256);
+  size_t lnws = align_up(layernorm_backward_workspace((int)s, (int)h), 256);
+  size_t maxn = std::max((size_t)3 * h, f);
+  size_t colws = align_up(colsum_workspace((int)s, (int)maxn), 256);
+  size_t total = 7 * sh + 2 * sf + s3h + delta + lnws + colws;
+  if (hipMalloc((void**)&st->ws, total) != hipSuccess) {
+    (void)hipGetLastError();
+    set_error("workspace allocation of %zu bytes failed", total);
+    st->ws = nullptr;
+    return fail(PO_E_DEVICE_OOM);
+  }
+  st->ws_bytes = total;
+  char* p = st->ws;
+  auto take = [&](size_t n) {
+    char* r = p;
+    p += n;
+    return r;
+  };
+  st->w_n = take(sh);
+  st->w_do = take(sh);
+  st->w_dx1 = take(sh);
+  st->w_dn = take(sh);
+  st->w_dy[0] = take(sh);
+  st->w_dy[1] = take(sh);
+  st->w_x0 = take(sh);
+  st->w_g = take(sf);
+  st->w_du = take(sf);
+  st->w_dqkv = take(s3h);
+  st->w_delta = (float*)take(delta);
+  st->w_lnws = (float*)take(lnws);
+  st->w_colws = (float*)take(colws);
+  reset_run_stats(st);
+  *out = st;
+  return PO_OK;
+}
+
+}  // namespace po
+
+// ------------------------------------------------------------------------------
+// C ABI
+// ------------------------------------------------------------------------------
+extern "C" {
+
+void po_config_default(po_config* c) {
+  if (!c) return;
+  memset(c, 0, sizeof(*c));
+  c->n_layers = 1;
+  c->n_chunks = 1;
+  c->hidden = 64;
+  c->n_heads = 1;
+  c->ffn = 256;
+  c->seq = 1;
+  c->dtype = PO_F32;
+  c->pipeline_degree = 1;
+  c->prefetch_passes = 1;
+  c->copy_streams = 2;
+  c->ln_eps = 1e-5f;
+}
+
+const char* po_last_error(void) { return po::get_error(); }
+
+int po_param_count(const po_config* cfg, int64_t* n) {
+  int rc = validate_config(cfg);
+  if (rc) return rc;
+  if (!n) {
+    set_error("po_param_count: n is NULL");
+    return PO_E_INVAL;
+  }
+  ParamLayout pl;
+  build_param_layout(*cfg, pl);
+  *n = pl.total;
+  return PO_OK;
+}
+
+int po_param_layout(const po_config* cfg, po_param_desc* out, int32_t* n) {
+  int rc = validate_config(cfg);
+  if (rc) return rc;
+  if (!n) {
+    set_error("po_param_layout: n is NULL");
+    return PO_E_INVAL;
+  }
+  ParamLayout pl;
+  build_param_layout(*cfg, pl);
+  int32_t have = (int32_t)pl.descs.size();
+  if (out) {
+    int32_t k = *n < have ? *n : have;
+    for (int32_t i = 0; i < k; ++i) out[i] = pl.descs[i];
+  }
+  *n = have;
+  return PO_OK;
+}
+
+int po_saved_bytes_per_layer(const po_config* cfg, uint64_t* bytes) {
+  int rc = validate_config(cfg);
+  if (rc) return rc;
+  if (!bytes) {
+    set_error("po_saved_bytes_per_layer: bytes is NULL");
+    return PO_E_INVAL;
+  }
+  SlabLayout sl;
+  build_slab_layout(*cfg, sl);
+  *bytes = sl.bytes;
+  return PO_OK;
+}
+
+int po_schedule_ops(int32_t schedule, int32_t d, int32_t rank, int32_t v, int32_t m, float ratio, int32_t policy,
+                    int32_t prefetch, po_op* out, int32_t* n) {
+  if (!n) {
+    set_error("po_schedule_ops: n is NULL");
+    return PO_E_INVAL;
+  }
+  std::vector<po_op> ops;
+  if (!build_schedule(schedule, d, rank, v, m, ratio, policy, prefetch, ops)) return PO_E_INVAL;
+  int32_t have = (int32_t)ops.size();
+  if (out) {
+    int32_t k = *n < have ? *n : have;
+    for (int32_t i = 0; i < k; ++i) out[i] = ops[i];
+  }
+  *n = have;
+  return PO_OK;
+}
+
+double po_offload_k(int32_t h, int32_t s, double bc, double bo) {
+  return 10.0 / (3.0 * (6.0 * (double)h + (double)s)) * bc / bo;
+}
+
+int po_stage_create(const po_config* cfg, void* compute_stream, po_stage** out) {
+  return stage_create(cfg, compute_stream, out);
+}
+
+void po_stage_destroy(po_stage* st) {
+  if (!st) return;
+  if (st->compute || st->offload) (void)stage_synchronize(st);
+  st->dev_pool.destroy();
+  st->host_pool.destroy();
+  st->sync_events.destroy();
+  st->time_events.destroy();
+  if (st->ws) (void)hipFree(st->ws);
+  if (st->own_reload_stream && st->reload) (void)hipStreamDestroy(st->reload);
+  if (st->offload) (void)hipStreamDestroy(st->offload);
+  delete st;
+}
+
+int po_bind_params(po_stage* st, const void* params, float* grads) {
+  if (!st || !params || !grads) {
+    set_error("po_bind_params: NULL argument");
+    return PO_E_INVAL;
+  }
+  if (((uintptr_t)params | (uintptr_t)grads) % 16 != 0) {
+    set_error("po_bind_params: buffers must be 16-byte aligned");
+    return PO_E_INVAL;
+  }
+  st->params = (const char*)params;
+  st->grads = grads;
+  return PO_OK;
+}
+
+#define PO_NEED_STAGE(st)             \
+  if (!(st)) {                        \
+    set_error("stage is NULL");       \
+    return PO_E_INVAL;                \
+  }
+
+int po_stage_forward(po_stage* st, int32_t mb, int32_t chunk, const void* x_in, void* y_out) {
+  PO_NEED_STAGE(st);
+  return stage_forward(st, mb, chunk, x_in, y_out);
+}
+int po_stage_backward(po_stage* st, int32_t mb, int32_t chunk, const void* dy, void* dx) {
+  PO_NEED_STAGE(st);
+  return stage_backward(st, mb, chunk, dy, dx);
+}
+int po_offload(po_stage* st, int32_t mb, int32_t chunk, float ratio) {
+  PO_NEED_STAGE(st);
+  return stage_offload(st, mb, chunk, ratio);
+}
+int po_reload(po_stage* st, int32_t mb, int32_t chunk) {
+  PO_NEED_STAGE(st);
+  return stage_reload(st, mb, chunk);
+}
+int po_run_schedule(po_stage* st, int32_t schedule, int32_t m, float ratio, const void* const* x_in,
+                    void* const* y_out, const void* const* dy, void* const* dx, po_stats* stats) {
+  PO_NEED_STAGE(st);
+  return stage_run_schedule(st, schedule, m, ratio, x_in, y_out, dy, dx, stats);
+}
+int po_synchronize(po_stage* st) {
+  PO_NEED_STAGE(st);
+  int rc = stage_synchronize(st);
+  if (rc == PO_OK && st->in_flight_units == 0) st->sync_events.reset();  // nothing refers to them any more
+  return rc;
+}
+int po_get_stats(const po_stage* st, po_stats* out) {
+  PO_NEED_STAGE(st);
+  if (!out) {
+    set_error("po_get_stats: out is NULL");
+    return PO_E_INVAL;
+  }
+  *out = st->stats;
+  out->pool_bytes_allocated = st->dev_pool.allocated();
+  out->host_bytes_allocated = st->host_pool.allocated();
+  return PO_OK;
+}
+
+// ---- single operations -----------------------------------------------------------
+static int ok(bool b) { return b ? PO_OK : PO_E_INVAL; }
+static bool dtype_ok(int32_t dtype) {
+  if (dtype == PO_F32 || dtype == PO_BF16) return true;
+  set_error("unknown dtype %d", dtype);
+  return false;
+}
+
+int po_op_layernorm_forward(int32_t dtype, const void* x, const void* gain, const void* shift, void* y, int32_t rows,
+                            int32_t h, float eps, void* stream) {
+  if (!dtype_ok(dtype)) return PO_E_INVAL;
+  return ok(layernorm_forward(dtype, x, gain, shift, y, rows, h, eps, (hipStream_t)stream));
+}
+uint64_t po_op_layernorm_backward_workspace(int32_t rows, int32_t h) {
+  return rows > 0 && h > 0 ? layernorm_backward_workspace(rows, h) : 0;
+}
+int po_op_layernorm_backward(int32_t dtype, const void* dn, const void* x, const void* gain, const void* dres,
+                             void* dx, float* dgain, float* dshift, float* partials, int32_t rows, int32_t h,
+                             float eps, void* stream) {
+  if (!dtype_ok(dtype)) return PO_E_INVAL;
+  return ok(layernorm_backward(dtype, dn, x, gain, dres, dx, dgain, dshift, partials, rows, h, eps,
+                               (hipStream_t)stream));
+}
+int po_op_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32_t N, int32_t K, const void* A,
+               int32_t lda, const void* B, int32_t ldb, const void* bias, const void* residual, void* out,
+               void* gelu_out, const void* gelu_u, float* acc_f32, int32_t force_generic, void* stream) {
+  if (!dtype_ok(dtype)) return PO_E_INVAL;
+  Epilogue e;
+  e.bias = bias;
+  e.residual = residual;
+  e.out = out;
+  e.gelu_out = gelu_out;
+  e.gelu_u = gelu_u;
+  e.acc_f32 = acc_f32;
+  e.ldc = N;
+  return ok(gemm(dtype, trans_a != 0, trans_b != 0, M, N, K, A, lda, B, ldb, e, force_generic != 0,
+                 (hipStream_t)stream));
+}
+int po_op_attention_forward(int32_t dtype, const void* qkv, void* o, float* lse, int32_t s, int32_t h,
+                            int32_t n_heads, int32_t force_generic, void* stream) {
+  if (!dtype_ok(dtype)) return PO_E_INVAL;
+  return ok(attention_forward(dtype, qkv, o, lse, s, h, n_heads, force_generic != 0, (hipStream_t)stream));
+}
+int po_op_attention_backward(int32_t dtype, const void* qkv, const void* o, const float* lse, const void* d_o,
+                             void* dqkv, float* delta, int32_t s, int32_t h, int32_t n_heads, int32_t force_generic,
+                             void* stream) {
+  if (!dtype_ok(dtype)) return PO_E_INVAL;
+  return ok(attention_backward(dtype, qkv, o, lse, d_o, dqkv, delta, s, h, n_heads, force_generic != 0,
+                               (hipStream_t)stream));
+}
+uint64_t po_op_colsum_workspace(int32_t rows, int32_t n) { return rows > 0 && n > 0 ? colsum_workspace(rows, n) : 0; }
+int po_op_colsum_accumulate(int32_t dtype, const void* x, float* acc, float* workspace, int32_t rows, int32_t n,
+                            void* stream) {
+  if (!dtype_ok(dtype)) return PO_E_INVAL;
+  return ok(colsum_accumulate(dtype, x, acc, workspace, rows, n, (hipStream_t)stream));
+}
+int po_op_pack(const void* const* seg_ptrs, const uint64_t* seg_bytes, int32_t n_seg, void* packed, void* stream) {
+  return ok(pack_segments(seg_ptrs, seg_bytes, n_seg, packed, (hipStream_t)stream));
+}
+int po_op_unpack(void* const* seg_ptrs, const uint64_t* seg_bytes, int32_t n_seg, const void* packed, void* stream) {
+  return ok(unpack_segments(seg_ptrs, seg_bytes, n_seg, packed, (hipStream_t)stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,107 @@
+"""Host-only checks of the C ABI: the library loads, exports every declared
+symbol, and its pure-host entry points (schedule, parameter layout, Eq. 1, config
+validation) agree with the independent oracle models.  No GPU work is issued."""
+import os
+import re
+
+import pytest
+
+from oracle import schedule_oracle as sch
+from paper_2503_01328_amd import binding as po
+from paper_2503_01328_amd import inputs as syn
+from paper_2503_01328_amd import harness
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    header = open(os.path.join(ROOT, "include", "pipeoffload.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(po_[a-z0-9_]+)\s*\(", header))
+    assert len(declared) >= 25
+    for name in declared:
+        assert hasattr(po.lib, name), f"{name} declared in the header but not exported"
+        assert name in po.EXPORTS, f"{name} has no binding"
+        assert hasattr(po, name), f"binding lacks a Python function {name}"
+    assert set(po.EXPORTS) == declared
+
+
+SCHEDS = {"1f1b": po.PO_SCHED_1F1B, "1f1b-interleaved": po.PO_SCHED_1F1B_INTERLEAVED}
+
+
+@pytest.mark.parametrize("name,d,v,m", [("1f1b", 2, 1, 4), ("1f1b", 4, 1, 8), ("1f1b", 8, 1, 16), ("1f1b", 16, 1, 16),
+                                        ("1f1b", 4, 1, 3), ("1f1b-interleaved", 8, 2, 32),
+                                        ("1f1b-interleaved", 4, 3, 8), ("1f1b-interleaved", 2, 2, 2)])
+@pytest.mark.parametrize("ratio", [0.0, 0.25, 0.5, 1.0])
+@pytest.mark.parametrize("prefetch", [0, 1, 3])
+def test_schedule_ops_match_the_oracle_model(name, d, v, m, ratio, prefetch):
+    for rank in sorted({0, d // 2, d - 1}):
+        for policy, pname in ((po.PO_SEL_ALTERNATE_MB, "alternate-mb"), (po.PO_SEL_LONGEST_LIFESPAN, "longest-lifespan")):
+            got = po.po_schedule_ops(SCHEDS[name], d, rank, v, m, ratio, policy, prefetch)
+            passes = sch.compute_passes(name, d, rank, v, m)
+            want = sch.with_offload(passes, sch.selected_units(m, v, ratio, pname), prefetch)
+            assert got == want
+            assert sch.simulate(got)["errors"] == []
+
+
+def test_schedule_ops_reject_bad_arguments():
+    for args in [(0, 4, 4, 1, 8, 0.5), (0, 4, 0, 2, 8, 0.5), (1, 4, 0, 2, 6, 0.5), (0, 4, 0, 1, 8, 1.5), (7, 4, 0, 1, 8, 0.5)]:
+        with pytest.raises(po.PipeOffloadError) as e:
+            po.po_schedule_ops(*args)
+        assert e.value.code == po.PO_E_INVAL
+        assert "schedule" in po.po_last_error()
+
+
+def test_offload_k_is_eq1():
+    for h, s in [(8192, 4096), (4096, 4096), (5120, 16384), (2048, 2048)]:
+        assert abs(po.po_offload_k(h, s, 220e12, 15e9) - sch.offload_ratio_k(h, s, 220e12, 15e9)) < 1e-12
+    assert abs(po.po_offload_k(8192, 4096, 220e12, 15e9) - 0.918) < 1e-3
+
+
+@pytest.mark.parametrize("key", ["C1", "C2", "C3", "C5"])
+def test_param_layout_and_saved_bytes(key):
+    shape = syn.CONFIGS[key]
+    cfg = harness.make_config(shape)
+    layout = po.po_param_layout(cfg)
+    h, f = shape.hidden, shape.ffn
+    per_layer = 12 * h * h + 13 * h if f == 4 * h else None
+    total = po.po_param_count(cfg)
+    emb = (shape.vocab + shape.seq) * h if shape.vocab else 0
+    assert total == emb + shape.n_layers * per_layer
+    # tensors tile the buffer without gaps, in the documented order, 16-byte aligned for bf16
+    off = 0
+    for d in layout:
+        assert d["offset"] == off and d["offset"] % 8 == 0
+        off += d["rows"] * d["cols"]
+    assert off == total
+    names = [d["name"] for d in layout if d["layer"] == 0]
+    assert names == [n for n, _ in syn.LAYER_PARAMS]
+    # Appendix C: 20 s h bytes per layer at two bytes per element (+ fp32 log-sum-exp, + alignment)
+    E = 2 if shape.dtype == "bf16" else 4
+    want = sch.saved_bytes_per_layer(shape.seq, h, shape.n_heads, E)
+    got = po.po_saved_bytes_per_layer(cfg)
+    assert want <= got < want + 6 * 256
+
+
+def test_invalid_configs_are_rejected_without_touching_the_gpu():
+    good = harness.make_config(syn.CONFIGS["C1"])
+    assert po.po_param_count(good) > 0
+    for field, value in [("n_layers", 0), ("n_chunks", 3), ("hidden", 100), ("n_heads", 7), ("seq", 0),
+                         ("dtype", 5), ("rank", 2), ("copy_streams", 3), ("ln_eps", 0.0)]:
+        cfg = harness.make_config(syn.CONFIGS["C1"])
+        setattr(cfg, field, value)
+        with pytest.raises(po.PipeOffloadError) as e:
+            po.po_param_count(cfg)
+        assert e.value.code == po.PO_E_INVAL
+
+
+def test_flatten_unflatten_roundtrip():
+    shape = syn.StageShape(2, 1, 64, 2, 256, 8, vocab=16, dtype="f32")
+    cfg = harness.make_config(shape)
+    params = syn.stage_params(shape, 3)
+    flat = harness.flatten_params(cfg, params)
+    back = harness.unflatten(cfg, flat)
+    for l in range(2):
+        for k, a in params["layers"][l].items():
+            assert (back["layers"][l][k] == a).all()
+    assert (back["wte"] == params["wte"]).all() and (back["wpe"] == params["wpe"]).all()

@@ -1,0 +1,215 @@
+"""Parity of the single HIP operations against the CPU oracle, through the C ABI.
+
+Tolerances (max |got - ref| / max |ref| per tensor): 1e-4 in fp32, 2e-2 in bf16.
+The oracle is fed the values the kernel is fed (bf16-rounded where bf16)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import stage_oracle as so
+from paper_2503_01328_amd import binding as po
+from paper_2503_01328_amd import inputs as syn
+from paper_2503_01328_amd.harness import max_rel_err
+
+pytestmark = pytest.mark.gpu
+
+DT = {"f32": (po.PO_F32, torch.float32, 1e-4), "bf16": (po.PO_BF16, torch.bfloat16, 2e-2)}
+
+
+def _dev(a, tdt, dev):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev).to(tdt).contiguous()
+
+
+def _rand(rng, shape, dtype, scale=1.0, shift=0.0):
+    a = (rng.standard_normal(shape) * scale + shift).astype(np.float32)
+    return syn.round_to_bf16(a) if dtype == "bf16" else a
+
+
+def _np(t):
+    return t.to(torch.float32).cpu().numpy()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("rows,h", [(1, 64), (7, 256), (130, 1024), (33, 5120)])
+def test_layernorm_forward_and_backward(gpu_device, dtype, rows, h):
+    code, tdt, tol = DT[dtype]
+    rng = np.random.default_rng(rows * 1000 + h)
+    x = _rand(rng, (rows, h), dtype, 2.0, 0.5)
+    g = _rand(rng, (h,), dtype, 0.1, 1.0)
+    b = _rand(rng, (h,), dtype, 0.1)
+    dn = _rand(rng, (rows, h), dtype)
+    dres = _rand(rng, (rows, h), dtype)
+    xd, gd, bd, dnd, dresd = (_dev(a, tdt, gpu_device) for a in (x, g, b, dn, dres))
+    y = torch.empty_like(xd)
+    po.po_op_layernorm_forward(code, xd, gd, bd, y, rows, h, 1e-5)
+    ref, cache = so.layernorm_forward(x.astype(np.float64), g.astype(np.float64), b.astype(np.float64), 1e-5)
+    assert max_rel_err(_np(y), ref) < tol
+    ws = torch.empty(po.po_op_layernorm_backward_workspace(rows, h) // 4, dtype=torch.float32, device=gpu_device)
+    dx = torch.empty_like(xd)
+    dg0 = rng.standard_normal(h).astype(np.float32)
+    db0 = rng.standard_normal(h).astype(np.float32)
+    dg, db = torch.from_numpy(dg0).to(gpu_device), torch.from_numpy(db0).to(gpu_device)
+    po.po_op_layernorm_backward(code, dnd, xd, gd, dresd, dx, dg, db, ws, rows, h, 1e-5)
+    rdx, rdg, rdb = so.layernorm_backward(dn.astype(np.float64), cache, g.astype(np.float64))
+    assert max_rel_err(_np(dx), rdx + dres) < tol
+    assert max_rel_err(_np(dg) - dg0, rdg) < max(tol, 1e-4)  # fp32 accumulators added into existing values
+    assert max_rel_err(_np(db) - db0, rdb) < max(tol, 1e-4)
+    # without a residual
+    po.po_op_layernorm_backward(code, dnd, xd, gd, None, dx, dg, db, ws, rows, h, 1e-5)
+    assert max_rel_err(_np(dx), rdx) < tol
+
+
+GEMM_SHAPES_GENERIC = [(1, 1, 1), (5, 7, 3), (64, 64, 16), (70, 130, 45), (128, 256, 256)]
+
+
+def _gemm_case(gpu_device, dtype, ta, tb, M, N, K, epilogue, force_generic):
+    code, tdt, tol = DT[dtype]
+    rng = np.random.default_rng(M * 7 + N * 3 + K + ta * 2 + tb)
+    A = _rand(rng, (K, M) if ta else (M, K), dtype)
+    B = _rand(rng, (N, K) if tb else (K, N), dtype, 0.05)
+    Ad, Bd = _dev(A, tdt, gpu_device), _dev(B, tdt, gpu_device)
+    a64 = (A.T if ta else A).astype(np.float64)
+    b64 = (B.T if tb else B).astype(np.float64)
+    ref = a64 @ b64
+    lda, ldb = A.shape[1], B.shape[1]
+    kw = dict(force_generic=force_generic)
+    if epilogue == "plain":
+        out = torch.empty(M, N, dtype=tdt, device=gpu_device)
+        po.po_op_gemm(code, ta, tb, M, N, K, Ad, lda, Bd, ldb, out=out, **kw)
+        assert max_rel_err(_np(out), ref) < tol
+    elif epilogue == "bias_residual":
+        bias = _rand(rng, (N,), dtype)
+        res = _rand(rng, (M, N), dtype)
+        out = torch.empty(M, N, dtype=tdt, device=gpu_device)
+        po.po_op_gemm(code, ta, tb, M, N, K, Ad, lda, Bd, ldb, bias=_dev(bias, tdt, gpu_device),
+                      residual=_dev(res, tdt, gpu_device), out=out, **kw)
+        assert max_rel_err(_np(out), ref + bias + res) < tol
+    elif epilogue == "bias_gelu":
+        bias = _rand(rng, (N,), dtype)
+        out = torch.empty(M, N, dtype=tdt, device=gpu_device)
+        g = torch.empty(M, N, dtype=tdt, device=gpu_device)
+        po.po_op_gemm(code, ta, tb, M, N, K, Ad, lda, Bd, ldb, bias=_dev(bias, tdt, gpu_device), out=out,
+                      gelu_out=g, **kw)
+        assert max_rel_err(_np(out), ref + bias) < tol
+        assert max_rel_err(_np(g), so.gelu(_np(out).astype(np.float64))) < tol  # gelu of the stored (rounded) u
+    elif epilogue == "gelu_backward":
+        u = _rand(rng, (M, N), dtype, 1.5)
+        out = torch.empty(M, N, dtype=tdt, device=gpu_device)
+        g = torch.empty(M, N, dtype=tdt, device=gpu_device)
+        po.po_op_gemm(code, ta, tb, M, N, K, Ad, lda, Bd, ldb, out=out, gelu_out=g,
+                      gelu_u=_dev(u, tdt, gpu_device), **kw)
+        assert max_rel_err(_np(out), ref * so.gelu_derivative(u.astype(np.float64))) < tol
+        assert max_rel_err(_np(g), so.gelu(u.astype(np.float64))) < tol
+    elif epilogue == "accumulate":
+        acc0 = rng.standard_normal((M, N)).astype(np.float32)
+        acc = torch.from_numpy(acc0).to(gpu_device)
+        po.po_op_gemm(code, ta, tb, M, N, K, Ad, lda, Bd, ldb, acc_f32=acc, **kw)
+        assert max_rel_err(_np(acc) - acc0, ref) < max(tol, 2e-4)
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("shape", GEMM_SHAPES_GENERIC)
+def test_gemm_generic_all_forms(gpu_device, dtype, ta, tb, shape):
+    _gemm_case(gpu_device, dtype, ta, tb, *shape, "plain", 1)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("epilogue", ["bias_residual", "bias_gelu", "gelu_backward", "accumulate"])
+def test_gemm_generic_epilogues(gpu_device, dtype, epilogue):
+    _gemm_case(gpu_device, dtype, 0, 0, 70, 130, 45, epilogue, 1)
+
+
+# MFMA path: 128-tiles (M, N multiples of 128) and 256-tiles (>= 200 tiles of 256 x 256), K multiple of 64
+MFMA_SHAPES = [(128, 128, 64), (256, 384, 192), (384, 128, 1024), (4096, 3328, 128)]
+
+
+@pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("shape", MFMA_SHAPES)
+def test_gemm_mfma_all_forms(gpu_device, ta, tb, shape):
+    _gemm_case(gpu_device, "bf16", ta, tb, *shape, "plain", 0)
+
+
+@pytest.mark.parametrize("epilogue", ["bias_residual", "bias_gelu", "gelu_backward", "accumulate"])
+@pytest.mark.parametrize("shape", [(256, 384, 192), (4096, 3328, 128)])
+def test_gemm_mfma_epilogues(gpu_device, epilogue, shape):
+    form = {"accumulate": (1, 0), "gelu_backward": (0, 1)}.get(epilogue, (0, 0))
+    _gemm_case(gpu_device, "bf16", *form, *shape, epilogue, 0)
+
+
+def test_gemm_rejects_bad_arguments(gpu_device):
+    a = torch.zeros(64, 64, device=gpu_device)
+    with pytest.raises(po.PipeOffloadError):
+        po.po_op_gemm(po.PO_F32, 0, 0, 64, 64, 64, a, 32, a, 64, out=a)  # lda too small
+    with pytest.raises(po.PipeOffloadError):
+        po.po_op_gemm(po.PO_F32, 0, 0, 64, 64, 64, a, 64, a, 64)  # no output
+    with pytest.raises(po.PipeOffloadError):
+        po.po_op_gemm(9, 0, 0, 64, 64, 64, a, 64, a, 64, out=a)  # bad dtype
+    with pytest.raises(po.PipeOffloadError):
+        po.po_op_gemm(po.PO_F32, 0, 0, 0, 64, 64, a, 64, a, 64, out=a)  # empty
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("s,h,a", [(1, 64, 1), (5, 64, 2), (64, 128, 2), (65, 256, 4), (200, 256, 2), (130, 512, 2)])
+@pytest.mark.parametrize("force_generic", [1, 0])
+def test_attention_forward_and_backward(gpu_device, dtype, s, h, a, force_generic):
+    code, tdt, tol = DT[dtype]
+    rng = np.random.default_rng(s * 31 + h + a)
+    qkv = _rand(rng, (s, 3 * h), dtype)
+    d_o = _rand(rng, (s, h), dtype)
+    qd, dod = _dev(qkv, tdt, gpu_device), _dev(d_o, tdt, gpu_device)
+    o = torch.empty(s, h, dtype=tdt, device=gpu_device)
+    lse = torch.empty(a, s, dtype=torch.float32, device=gpu_device)
+    po.po_op_attention_forward(code, qd, o, lse, s, h, a, force_generic)
+    q64 = qkv.astype(np.float64)
+    q, k, v = q64[:, :h], q64[:, h:2 * h], q64[:, 2 * h:]
+    ro, probs = so.attention_forward(q, k, v, a)
+    assert max_rel_err(_np(o), ro) < tol
+    # log-sum-exp of the scaled, masked scores: a plain definition
+    dh = h // a
+    for t in range(a):
+        sc = (q[:, t * dh:(t + 1) * dh] @ k[:, t * dh:(t + 1) * dh].T) / np.sqrt(dh)
+        sc = np.where(np.triu(np.ones((s, s), dtype=bool), 1), -np.inf, sc)
+        ref_lse = np.log(np.exp(sc - sc.max(1, keepdims=True)).sum(1)) + sc.max(1)
+        assert np.abs(_np(lse[t]) - ref_lse).max() < 1e-3 * max(1.0, np.abs(ref_lse).max())
+    dqkv = torch.empty(s, 3 * h, dtype=tdt, device=gpu_device)
+    delta = torch.empty(a, s, dtype=torch.float32, device=gpu_device)
+    po.po_op_attention_backward(code, qd, o, lse, dod, dqkv, delta, s, h, a, force_generic)
+    rdq, rdk, rdv = so.attention_backward(d_o.astype(np.float64), q, k, v, probs, a)
+    got = _np(dqkv)
+    btol = tol if dtype == "f32" else 3e-2  # o is rounded to bf16 before delta = rowsum(dO * O) is formed
+    assert max_rel_err(got[:, :h], rdq) < btol
+    assert max_rel_err(got[:, h:2 * h], rdk) < btol
+    assert max_rel_err(got[:, 2 * h:], rdv) < btol
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("rows,n", [(1, 2), (37, 130), (300, 1024)])
+def test_colsum_accumulate(gpu_device, dtype, rows, n):
+    code, tdt, tol = DT[dtype]
+    rng = np.random.default_rng(rows + n)
+    x = _rand(rng, (rows, n), dtype)
+    acc0 = rng.standard_normal(n).astype(np.float32)
+    acc = torch.from_numpy(acc0).to(gpu_device)
+    ws = torch.empty(po.po_op_colsum_workspace(rows, n) // 4, dtype=torch.float32, device=gpu_device)
+    po.po_op_colsum_accumulate(code, _dev(x, tdt, gpu_device), acc, ws, rows, n)
+    assert max_rel_err(_np(acc) - acc0, x.astype(np.float64).sum(0)) < 1e-4
+
+
+def test_pack_unpack_roundtrip_is_bit_exact(gpu_device):
+    rng = np.random.default_rng(0)
+    sizes = [16, 4096 + 16, 0, 1 << 20, 48, 3 * 16384 + 32]  # bytes, multiples of 16, one empty
+    segs = [torch.from_numpy(rng.integers(0, 256, size=n, dtype=np.uint8)).to(gpu_device) for n in sizes]
+    total = sum(sizes)
+    packed = torch.zeros(total, dtype=torch.uint8, device=gpu_device)
+    po.po_op_pack([(t if t.numel() else 0, n) for t, n in zip(segs, sizes)], packed)
+    want = np.concatenate([t.cpu().numpy() for t in segs])
+    assert np.array_equal(packed.cpu().numpy(), want)  # byte-exact: oracle = concatenation
+    outs = [torch.zeros_like(t) for t in segs]
+    po.po_op_unpack([(t if t.numel() else 0, n) for t, n in zip(outs, sizes)], packed)
+    for a, b in zip(outs, segs):
+        assert torch.equal(a, b)
+    with pytest.raises(po.PipeOffloadError):
+        po.po_op_pack([(segs[0], 8)], packed)  # not a multiple of 16
+    po.po_op_pack([], packed)  # empty is a no-op

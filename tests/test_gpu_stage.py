@@ -1,0 +1,204 @@
+"""Stage-level parity against the CPU oracle and the offload exactness checks.
+
+Gradients, outputs and input gradients of the HIP path are compared per tensor
+with max |got - ref| / max |ref|: 1e-4 in fp32, 2e-2 in bf16.  With offload the
+HIP path must reproduce its own no-offload results bit for bit (offload is a copy)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import schedule_oracle as sch
+from oracle import stage_oracle as so
+from paper_2503_01328_amd import binding as po
+from paper_2503_01328_amd import inputs as syn
+from paper_2503_01328_amd.harness import StageRunner, max_rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle(shape, runner, m):
+    x = {(j, c): syn.unit_input(shape, j, c, runner.seed) for j in range(m) for c in range(shape.n_chunks)}
+    dy = {(j, c): syn.unit_upstream_grad(shape, j, c, runner.seed) for j in range(m) for c in range(shape.n_chunks)}
+    return so.run_stage(runner.params_np, shape.n_layers, shape.n_chunks, shape.n_heads, x, dy, vocab=shape.vocab)
+
+
+def _compare(shape, got, ref, tol):
+    y, dx, g = got
+    ry, rdx, rg = ref
+    worst = 0.0
+    for u in ry:
+        e = max_rel_err(y[u], ry[u])
+        assert e < tol, ("y", u, e)
+        if rdx[u] is not None:
+            e = max_rel_err(dx[u], rdx[u])
+            assert e < tol, ("dx", u, e)
+    for l in range(shape.n_layers):
+        for k, a in rg["layers"][l].items():
+            e = max_rel_err(g["layers"][l][k], a)
+            worst = max(worst, e)
+            assert e < tol, (l, k, e)
+    for k in ("wte", "wpe"):
+        if k in rg:
+            e = max_rel_err(g[k], rg[k])
+            assert e < tol, (k, e)
+    return worst
+
+
+def _snapshot(r):
+    torch.cuda.synchronize()
+    return ([t.clone() for t in r.y], [None if t is None else t.clone() for t in r.dx], r.grads.clone())
+
+
+def _assert_bit_identical(a, b):
+    for ta, tb in zip(a[0], b[0]):
+        assert torch.equal(ta, tb)
+    for ta, tb in zip(a[1], b[1]):
+        assert (ta is None and tb is None) or torch.equal(ta, tb)
+    assert torch.equal(a[2], b[2])
+
+
+def test_config1_tiny_gpt_fp32_against_oracle_with_full_offload(gpu_device):
+    shape = syn.CONFIGS["C1"]
+    with StageRunner(shape) as r:
+        r.make_inputs()
+        stats = r.run(po.PO_SCHED_1F1B, 1.0)
+        assert stats["n_offloads"] == 4 * 2 and stats["n_reloads"] == 4 * 2
+        assert stats["peak_in_flight_units"] == 2
+        got = r.results()
+        _compare(shape, got, _oracle(shape, r, 4), 1e-4)
+        with_offload = _snapshot(r)
+        r.zero_grads()
+        r.run(po.PO_SCHED_1F1B, 0.0)
+        _assert_bit_identical(with_offload, _snapshot(r))
+
+
+SMALL_BF16 = syn.StageShape(2, 1, 256, 2, 1024, 384, dtype="bf16", pipeline_degree=3, n_microbatches=5)
+SMALL_BF16_RAGGED = syn.StageShape(1, 1, 192, 3, 320, 200, dtype="bf16", pipeline_degree=2, n_microbatches=3)
+
+
+@pytest.mark.parametrize("shape", [SMALL_BF16, SMALL_BF16_RAGGED], ids=["mfma-tiles", "ragged-generic"])
+def test_bf16_stage_against_oracle(gpu_device, shape):
+    with StageRunner(shape) as r:
+        r.make_inputs()
+        r.run(po.PO_SCHED_1F1B, 0.5)
+        _compare(shape, r.results(), _oracle(shape, r, shape.n_microbatches), 2e-2)
+
+
+@pytest.mark.parametrize("shape", [SMALL_BF16, syn.StageShape(2, 1, 128, 2, 512, 96, vocab=50, dtype="f32",
+                                                             pipeline_degree=4, n_microbatches=6)],
+                         ids=["bf16", "f32-embed"])
+def test_offload_is_bit_identical_in_every_mode(gpu_device, shape):
+    base = None
+    for kw in [dict(ratio=0.0), dict(ratio=0.5), dict(ratio=1.0), dict(ratio=1.0, copy_streams=1),
+               dict(ratio=1.0, staged_copies=1), dict(ratio=0.5, staged_copies=1, copy_streams=1),
+               dict(ratio=1.0, prefetch_passes=0), dict(ratio=1.0, prefetch_passes=3),
+               dict(ratio=1.0, debug_poison=1), dict(ratio=1.0, debug_poison=1, staged_copies=1)]:
+        ratio = kw.pop("ratio")
+        with StageRunner(shape, **kw) as r:
+            r.make_inputs()
+            stats = r.run(po.PO_SCHED_1F1B, ratio)
+            snap = _snapshot(r)
+            # second run on the same stage (pools warm, slabs reused) must agree as well
+            r.zero_grads()
+            stats2 = r.run(po.PO_SCHED_1F1B, ratio)
+            _assert_bit_identical(snap, _snapshot(r))
+            assert stats2["pool_bytes_allocated"] == stats["pool_bytes_allocated"]
+        if base is None:
+            base = snap
+        else:
+            _assert_bit_identical(base, snap)
+
+
+def test_interleaved_schedule_chunks_and_residency(gpu_device):
+    shape = syn.StageShape(4, 2, 128, 2, 512, 64, dtype="bf16", pipeline_degree=2, n_microbatches=4)
+    results = {}
+    for ratio, policy in [(0.0, 0), (0.5, 0), (0.5, 1), (1.0, 0)]:
+        with StageRunner(shape, select_policy=policy) as r:
+            r.make_inputs()
+            stats = r.run(po.PO_SCHED_1F1B_INTERLEAVED, ratio)
+            results[(ratio, policy)] = _snapshot(r)
+            ops = sch.with_offload(sch.interleaved_one_f_one_b(2, 0, 2, 4),
+                                   sch.selected_units(4, 2, ratio, "longest-lifespan" if policy else "alternate-mb"), 1)
+            model = sch.simulate(ops)
+            assert stats["peak_in_flight_units"] == model["peak_in_flight"]
+            assert stats["peak_resident_units"] == model["peak_resident"]
+            assert stats["n_offloads"] == sum(o[0] == "OFFLOAD" for o in ops) * 2  # two layers per unit
+            if ratio == 0.0:
+                _compare(shape, r.results(), _oracle(shape, r, 4), 2e-2)
+    base = results[(0.0, 0)]
+    for k, v in results.items():
+        _assert_bit_identical(base, v)
+
+
+def test_manual_calls_partial_ratio_and_state_errors(gpu_device):
+    shape = syn.StageShape(4, 1, 128, 2, 512, 64, dtype="f32", pipeline_degree=2, n_microbatches=2)
+    with StageRunner(shape) as r:
+        r.make_inputs()
+        st = r.stage
+        layer_bytes = po.po_saved_bytes_per_layer(r.cfg)
+        po.po_stage_forward(st, 0, 0, r.x[0], r.y[0])
+        with pytest.raises(po.PipeOffloadError) as e:
+            po.po_stage_forward(st, 0, 0, r.x[0], r.y[0])  # still in flight
+        assert e.value.code == po.PO_E_STATE
+        with pytest.raises(po.PipeOffloadError) as e:
+            po.po_stage_backward(st, 1, 0, r.dy[1], r.dx[1])  # never forwarded
+        assert e.value.code == po.PO_E_STATE
+        with pytest.raises(po.PipeOffloadError) as e:
+            po.po_offload(st, 0, 0, 1.5)
+        assert e.value.code == po.PO_E_INVAL
+        po.po_offload(st, 0, 0, 0.3)  # ceil(0.3 * 4) = 2 layers, lowest first
+        po.po_synchronize(st)
+        s = po.po_get_stats(st)
+        assert s["n_offloads"] == 2 and s["bytes_d2h"] == 2 * layer_bytes
+        with pytest.raises(po.PipeOffloadError) as e:
+            po.po_stage_backward(st, 0, 0, r.dy[0], r.dx[0])  # two layers are on the host
+        assert e.value.code == po.PO_E_STATE
+        assert "reload" in po.po_last_error()
+        with pytest.raises(po.PipeOffloadError) as e:
+            po.po_offload(st, 0, 0, 0.5)  # those layers are not resident any more
+        assert e.value.code == po.PO_E_STATE
+        po.po_reload(st, 0, 0)
+        po.po_reload(st, 0, 0)  # nothing left on the host: no-op
+        po.po_stage_backward(st, 0, 0, r.dy[0], r.dx[0])
+        po.po_synchronize(st)
+        assert po.po_get_stats(st)["n_reloads"] == 2
+        partial = (r.dx[0].clone(), r.grads.clone(), r.y[0].clone())
+        r.zero_grads()
+        po.po_stage_forward(st, 0, 0, r.x[0], r.y[0])
+        po.po_stage_backward(st, 0, 0, r.dy[0], r.dx[0])
+        po.po_synchronize(st)
+        assert torch.equal(partial[0], r.dx[0]) and torch.equal(partial[1], r.grads) and torch.equal(partial[2], r.y[0])
+
+
+def test_pool_caps_give_oom_codes(gpu_device):
+    shape = syn.StageShape(2, 1, 128, 2, 512, 64, dtype="f32", pipeline_degree=4, n_microbatches=4)
+    layer_bytes = po.po_saved_bytes_per_layer(po.po_config_default(
+        n_layers=2, hidden=128, n_heads=2, ffn=512, seq=64))
+    with StageRunner(shape, device_pool_cap_bytes=3 * layer_bytes) as r:
+        r.make_inputs()
+        with pytest.raises(po.PipeOffloadError) as e:
+            r.run(po.PO_SCHED_1F1B, 0.0)  # four units of two layers in flight do not fit three slabs
+        assert e.value.code == po.PO_E_DEVICE_OOM
+    with StageRunner(shape, host_pool_cap_bytes=1 * layer_bytes) as r:
+        r.make_inputs()
+        with pytest.raises(po.PipeOffloadError) as e:
+            r.run(po.PO_SCHED_1F1B, 1.0)
+        assert e.value.code == po.PO_E_HOST_OOM
+
+
+def test_peak_slab_bytes_follow_the_schedule_model(gpu_device):
+    shape = syn.StageShape(1, 1, 128, 2, 512, 64, dtype="bf16", pipeline_degree=6, n_microbatches=12)
+    layer_bytes = None
+    peaks = {}
+    for ratio in (0.0, 0.5, 1.0):
+        with StageRunner(shape) as r:
+            layer_bytes = po.po_saved_bytes_per_layer(r.cfg)
+            r.make_inputs()
+            stats = r.run(po.PO_SCHED_1F1B, ratio)
+            ops = sch.with_offload(sch.one_f_one_b(6, 0, 12), sch.selected_units(12, 1, ratio), 1)
+            model = sch.simulate(ops)
+            assert stats["peak_in_flight_units"] == model["peak_in_flight"] == 6
+            assert stats["peak_resident_units"] == model["peak_resident"]
+            assert stats["peak_slab_bytes"] == model["peak_resident"] * layer_bytes
+            peaks[ratio] = stats["peak_slab_bytes"]
+    assert peaks[1.0] < peaks[0.5] < peaks[0.0]
