@@ -1,0 +1,161 @@
+#!/usr/bin/env python3
+"""Benchmark of the stage + activation-offload hot path on one MI355X.
+
+A step is one po_run_schedule over all microbatches of the workload (every
+forward, offload, reload and backward of the rank-local 1F1B schedule).  Inputs,
+parameters and outputs are resident in HBM before the timed region; slab and
+pinned-buffer pools are warm.  Prints ONE JSON line.
+
+  value            stage tokens/s at offload ratio 1 (full offload), m*s / step time
+  ratios           tokens/s, ms/step, peak activation GB, overlap, host-link GB/s at ratios 0, 0.5, 1
+  roofline         bf16 MFMA GEMM launches of the timed steps (HIP events on the compute stream,
+                   recorded by the library around every GEMM launch) against 2.5 PFLOP/s
+  cpu_baseline     the numpy oracle timed on a bounded sample of the same workload
+"""
+import argparse
+import dataclasses
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0
+
+
+def model_flops_per_run(shape):
+    """72 h^2 + 6 s h per token and layer (GEMMs forward + backward, causal attention), Eq. 1's T_c with the
+    causal half of its attention term."""
+    h, s = shape.hidden, shape.seq
+    per_token_layer = 72.0 * h * h + 6.0 * s * h
+    return per_token_layer * s * shape.n_layers * shape.n_microbatches
+
+
+def cpu_baseline(shape):
+    """Times the oracle (float32 instantiation, as it stands) on one microbatch of one layer of the workload."""
+    import numpy as np
+
+    from oracle import stage_oracle as so
+    from paper_2503_01328_amd import inputs as syn
+
+    one = dataclasses.replace(shape, n_layers=1, n_chunks=1, vocab=0)
+    params = syn.stage_params(one, 1234)
+    x = {(0, 0): syn.unit_input(one, 0, 0)}
+    dy = {(0, 0): syn.unit_upstream_grad(one, 0, 0)}
+    t0 = time.perf_counter()
+    so.run_stage(params, 1, 1, one.n_heads, x, dy, dtype=np.float32)
+    dt = time.perf_counter() - t0
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count()
+    omp = os.environ.get("OMP_NUM_THREADS")
+    if omp and omp.isdigit():
+        cores = min(cores, int(omp))
+    tokens_per_s = shape.seq / (dt * shape.n_layers)
+    return {"value": tokens_per_s, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"1 microbatch x 1 layer of {shape.n_layers} (fp32 numpy oracle, forward+backward, {dt:.2f} s), "
+                      f"scaled by the layer count"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="C2", help="workload: C1..C5 (default C2, the configuration the metric is quoted on)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-streams", type=int, default=2)
+    ap.add_argument("--prefetch", type=int, default=1)
+    ap.add_argument("--staged", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs one pipeline rank on one GPU; --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2503_01328_amd import binding as po
+    from paper_2503_01328_amd import inputs as syn
+    from paper_2503_01328_amd.harness import StageRunner
+
+    shape = syn.CONFIGS[args.config]
+    sched = po.PO_SCHED_1F1B_INTERLEAVED if shape.n_chunks > 1 else po.PO_SCHED_1F1B
+    tokens = shape.n_microbatches * shape.seq
+    ratios = {}
+    headline = None
+    with StageRunner(shape, device_params=True, copy_streams=args.copy_streams, prefetch_passes=args.prefetch,
+                     staged_copies=args.staged, profile_kernels=1) as r:
+        r.make_inputs_on_device()
+        for ratio in (0.0, 0.5, 1.0):
+            for _ in range(args.warmup):
+                r.run(sched, ratio)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            per = []
+            for _ in range(args.steps):
+                per.append(r.run(sched, ratio))
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / args.steps
+            agg = {k: sum(p[k] for p in per) / len(per) for k in
+                   ("compute_busy_s", "d2h_busy_s", "h2d_busy_s", "gemm_busy_s", "gemm_flops", "attn_busy_s",
+                    "attn_flops", "pack_busy_s")}
+            last = per[-1]
+            ratios[ratio] = dict(
+                tokens_per_s=tokens / dt, ms_per_step=dt * 1e3,
+                peak_activation_gb=last["peak_slab_bytes"] / 1e9,
+                peak_resident_units=last["peak_resident_units"], peak_in_flight_units=last["peak_in_flight_units"],
+                d2h_gb_per_s=(last["bytes_d2h"] / agg["d2h_busy_s"] / 1e9) if agg["d2h_busy_s"] else None,
+                h2d_gb_per_s=(last["bytes_h2d"] / agg["h2d_busy_s"] / 1e9) if agg["h2d_busy_s"] else None,
+                copy_busy_ms=(agg["d2h_busy_s"] + agg["h2d_busy_s"]) * 1e3,
+                compute_busy_ms=agg["compute_busy_s"] * 1e3,
+                gemm_tflops=agg["gemm_flops"] / agg["gemm_busy_s"] / 1e12 if agg["gemm_busy_s"] else None,
+                gemm_busy_ms=agg["gemm_busy_s"] * 1e3, n_gemm_launches=last["n_gemm_launches"],
+                attn_tflops=agg["attn_flops"] / agg["attn_busy_s"] / 1e12 if agg["attn_busy_s"] else None,
+                attn_busy_ms=agg["attn_busy_s"] * 1e3,
+                mfu=model_flops_per_run(shape) / dt / (PEAK_BF16_TFLOPS * 1e12),
+            )
+        base = ratios[0.0]["ms_per_step"]
+        for ratio, d in ratios.items():
+            if ratio > 0 and d["copy_busy_ms"] > 0:
+                d["overlap"] = max(0.0, min(1.0, 1.0 - (d["ms_per_step"] - base) / d["copy_busy_ms"]))
+            else:
+                d["overlap"] = None
+            d["throughput_vs_no_offload"] = base / d["ms_per_step"]
+        headline = ratios[1.0]
+        # Eq. 1 with measured rates: compute rate = model flops / compute time at ratio 0, link rate = measured D2H
+        bc = model_flops_per_run(shape) / (ratios[0.0]["ms_per_step"] * 1e-3)
+        bo = (headline["d2h_gb_per_s"] or 0) * 1e9
+        k_meas = po.po_offload_k(shape.hidden, shape.seq, bc, bo) if bo else None
+        gemm = ratios[0.0]
+        dtype = "bf16" if shape.dtype == "bf16" else "f32"
+
+    out = {
+        "metric": "stage tokens/sec at offload ratio 0/0.5/1; peak activation HBM GB; overlap %",
+        "value": headline["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": headline["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": f"{args.config}: GPT stage, {shape.n_layers} layers, hidden {shape.hidden}, "
+                               f"{shape.n_heads} heads, FFN {shape.ffn}, seq {shape.seq}, {shape.n_microbatches} "
+                               f"microbatches, simulated pipeline degree {shape.pipeline_degree}, "
+                               f"{'interleaved ' if shape.n_chunks > 1 else ''}1F1B rank 0; value is at offload ratio 1",
+                   "copy_streams": args.copy_streams, "prefetch_passes": args.prefetch, "staged_copies": args.staged},
+        "ratios": {str(k): v for k, v in ratios.items()},
+        "k_eq1_measured_serial": k_meas, "k_eq1_measured_duplex": (k_meas / 2 if k_meas else None),
+        "roofline": {"bound": "mfma", "achieved": gemm["gemm_tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": (gemm["gemm_tflops"] / PEAK_BF16_TFLOPS) if gemm["gemm_tflops"] else None,
+                     "traffic": None,
+                     "kernel": "gemm_mfma_kernel (all bf16 GEMM launches of a step at ratio 0: 2MNK flops / "
+                               "event-timed duration)",
+                     "launches_per_step": gemm["n_gemm_launches"], "busy_ms_per_step": gemm["gemm_busy_ms"]},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(shape)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

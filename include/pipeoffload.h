@@ -70,6 +70,7 @@ typedef struct po_config {
   int32_t select_policy;   /* po_select */
   int32_t staged_copies;   /* 0: copy slabs in place; 1: pack into a staging buffer before D2H, unpack after H2D */
   int32_t debug_poison;    /* 1: fill a slab with a NaN pattern whenever it is released */
+  int32_t profile_kernels; /* 1: po_run_schedule brackets every GEMM and attention launch with HIP events */
   float ln_eps;            /* LayerNorm epsilon */
   uint64_t host_pool_cap_bytes;   /* 0 = unlimited; else PO_E_HOST_OOM beyond it */
   uint64_t device_pool_cap_bytes; /* 0 = unlimited; else PO_E_DEVICE_OOM beyond it */
@@ -98,6 +99,10 @@ typedef struct po_stats {
   double h2d_busy_s;        /* sum of reload copy durations */
   double pack_busy_s;       /* sum of pack + unpack kernel durations (staged copies only) */
   double compute_span_s;    /* first compute pass start to last compute pass end */
+  double gemm_busy_s;       /* profile_kernels: sum of GEMM launch durations on the compute stream */
+  double gemm_flops;        /* profile_kernels: 2 M N K summed over those launches */
+  double attn_busy_s;       /* profile_kernels: sum of attention forward/backward launch durations */
+  double attn_flops;        /* profile_kernels: causal model flops, 2 s^2 h forward, 4 s^2 h backward */
   uint64_t bytes_d2h, bytes_h2d;
   uint64_t peak_slab_bytes;      /* high-water mark of activation slab bytes in use (incl. staging) */
   uint64_t pool_bytes_allocated; /* device bytes the slab pool holds */
@@ -105,7 +110,7 @@ typedef struct po_stats {
   uint64_t workspace_bytes;      /* temporaries: recompute buffers, gradient workspaces */
   int32_t peak_resident_units;   /* high-water mark of units with at least one layer resident */
   int32_t peak_in_flight_units;  /* forwarded and not yet backwarded */
-  int32_t n_compute_passes, n_offloads, n_reloads, reserved;
+  int32_t n_compute_passes, n_offloads, n_reloads, n_gemm_launches;
 } po_stats;
 
 /* Fills *cfg with defaults (1 chunk, fp32, d = 1, prefetch 1, two copy streams, eps 1e-5). HOST. */

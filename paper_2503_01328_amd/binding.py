@@ -28,7 +28,7 @@ OP_KINDS = ("F", "B", "OFFLOAD", "RELOAD")
 class po_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "n_chunks", "hidden", "n_heads", "ffn", "seq", "vocab", "dtype", "pipeline_degree", "rank",
-        "prefetch_passes", "copy_streams", "select_policy", "staged_copies", "debug_poison")] + [
+        "prefetch_passes", "copy_streams", "select_policy", "staged_copies", "debug_poison", "profile_kernels")] + [
         ("ln_eps", C.c_float), ("host_pool_cap_bytes", C.c_uint64), ("device_pool_cap_bytes", C.c_uint64)]
 
 
@@ -43,14 +43,15 @@ class po_op(C.Structure):
 
 class po_stats(C.Structure):
     _fields_ = [(n, C.c_double) for n in ("wall_s", "tokens_per_s", "compute_busy_s", "d2h_busy_s", "h2d_busy_s",
-                                           "pack_busy_s", "compute_span_s")] + \
+                                           "pack_busy_s", "compute_span_s", "gemm_busy_s", "gemm_flops",
+                                           "attn_busy_s", "attn_flops")] + \
                [(n, C.c_uint64) for n in ("bytes_d2h", "bytes_h2d", "peak_slab_bytes", "pool_bytes_allocated",
                                           "host_bytes_allocated", "workspace_bytes")] + \
                [(n, C.c_int32) for n in ("peak_resident_units", "peak_in_flight_units", "n_compute_passes",
-                                         "n_offloads", "n_reloads", "reserved")]
+                                         "n_offloads", "n_reloads", "n_gemm_launches")]
 
     def as_dict(self):
-        return {n: getattr(self, n) for n, _ in self._fields_ if n != "reserved"}
+        return {n: getattr(self, n) for n, _ in self._fields_}
 
 
 EXPORTS = {

@@ -273,7 +273,8 @@ struct Unit {
 
 struct TimedSpan {
   hipEvent_t start, stop;
-  int kind;  // 0 compute, 1 d2h, 2 h2d, 3 pack/unpack
+  int kind;  // 0 compute pass, 1 d2h, 2 h2d, 3 pack/unpack, 4 gemm, 5 attention
+  double flops;
 };
 
 }  // namespace po
@@ -327,6 +328,7 @@ static int span_begin(po_stage* st, hipStream_t stream, int kind, size_t* idx) {
   }
   TimedSpan sp;
   sp.kind = kind;
+  sp.flops = 0.0;
   int rc = st->time_events.get(&sp.start);
   if (rc) return rc;
   rc = st->time_events.get(&sp.stop);
@@ -358,6 +360,44 @@ static Epilogue make_ep(int ldc) {
   return e;
 }
 
+// GEMM / attention launches of the stage; bracketed by events when profile_kernels is set.
+static int st_gemm(po_stage* st, int ta, int tb, int M, int N, int K, const void* A, int lda, const void* B, int ldb,
+                   const Epilogue& e) {
+  bool prof = st->collect_timing && st->cfg.profile_kernels;
+  size_t span = (size_t)-1;
+  if (prof) {
+    int rc = span_begin(st, st->compute, 4, &span);
+    if (rc) return rc;
+    st->spans[span].flops = 2.0 * M * N * K;
+  }
+  PO_K(gemm(st->cfg.dtype, ta, tb, M, N, K, A, lda, B, ldb, e, false, st->compute));
+  return span_end(st, st->compute, span);
+}
+
+static int st_attention(po_stage* st, bool backward, const void* qkv, void* o, float* lse, const void* d_o,
+                        void* dqkv) {
+  const po_config& c = st->cfg;
+  bool prof = st->collect_timing && c.profile_kernels;
+  size_t span = (size_t)-1;
+  if (prof) {
+    int rc = span_begin(st, st->compute, 5, &span);
+    if (rc) return rc;
+    st->spans[span].flops = (backward ? 4.0 : 2.0) * c.seq * (double)c.seq * c.hidden;
+  }
+  if (backward)
+    PO_K(attention_backward(c.dtype, qkv, o, lse, d_o, dqkv, st->w_delta, c.seq, c.hidden, c.n_heads, false,
+                            st->compute));
+  else
+    PO_K(attention_forward(c.dtype, qkv, o, lse, c.seq, c.hidden, c.n_heads, false, st->compute));
+  return span_end(st, st->compute, span);
+}
+
+#define PO_RC(call)          \
+  do {                       \
+    int rc__ = (call);       \
+    if (rc__) return rc__;   \
+  } while (0)
+
 static int layer_forward(po_stage* st, int layer, char* slab, void* y_out) {
   const po_config& c = st->cfg;
   const ParamLayout& pl = st->pl;
@@ -375,24 +415,24 @@ static int layer_forward(po_stage* st, int layer, char* slab, void* y_out) {
   Epilogue e = make_ep(3 * h);
   e.bias = st->P(layer, pl.b_qkv);
   e.out = qkv;
-  PO_K(gemm(dt, 0, 0, s, 3 * h, h, st->w_n, h, st->P(layer, pl.w_qkv), 3 * h, e, false, q));
-  PO_K(attention_forward(dt, qkv, o, lse, s, h, c.n_heads, false, q));
+  PO_RC(st_gemm(st, 0, 0, s, 3 * h, h, st->w_n, h, st->P(layer, pl.w_qkv), 3 * h, e));
+  PO_RC(st_attention(st, false, qkv, o, lse, nullptr, nullptr));
   e = make_ep(h);
   e.bias = st->P(layer, pl.b_o);
   e.residual = x;
   e.out = x1;
-  PO_K(gemm(dt, 0, 0, s, h, h, o, h, st->P(layer, pl.w_o), h, e, false, q));
+  PO_RC(st_gemm(st, 0, 0, s, h, h, o, h, st->P(layer, pl.w_o), h, e));
   PO_K(layernorm_forward(dt, x1, st->P(layer, pl.ln2_g), st->P(layer, pl.ln2_b), st->w_n, s, h, c.ln_eps, q));
   e = make_ep(f);
   e.bias = st->P(layer, pl.b_fc1);
   e.out = u;
   e.gelu_out = st->w_g;
-  PO_K(gemm(dt, 0, 0, s, f, h, st->w_n, h, st->P(layer, pl.w_fc1), f, e, false, q));
+  PO_RC(st_gemm(st, 0, 0, s, f, h, st->w_n, h, st->P(layer, pl.w_fc1), f, e));
   e = make_ep(h);
   e.bias = st->P(layer, pl.b_fc2);
   e.residual = x1;
   e.out = y_out;
-  PO_K(gemm(dt, 0, 0, s, h, f, st->w_g, f, st->P(layer, pl.w_fc2), h, e, false, q));
+  PO_RC(st_gemm(st, 0, 0, s, h, f, st->w_g, f, st->P(layer, pl.w_fc2), h, e));
   return PO_OK;
 }
 
@@ -415,42 +455,42 @@ static int layer_backward(po_stage* st, int layer, const char* slab, const void*
   e.out = st->w_du;
   e.gelu_u = u;
   e.gelu_out = st->w_g;
-  PO_K(gemm(dt, 0, 1, s, f, h, dy, h, st->P(layer, pl.w_fc2), h, e, false, q));
+  PO_RC(st_gemm(st, 0, 1, s, f, h, dy, h, st->P(layer, pl.w_fc2), h, e));
   e = make_ep(h);
   e.acc_f32 = st->G(layer, pl.w_fc2);
-  PO_K(gemm(dt, 1, 0, f, h, s, st->w_g, f, dy, h, e, false, q));
+  PO_RC(st_gemm(st, 1, 0, f, h, s, st->w_g, f, dy, h, e));
   PO_K(colsum_accumulate(dt, dy, st->G(layer, pl.b_fc2), st->w_colws, s, h, q));
   // FC1: n2 recomputed; dW1 += n2^T du; db1 += colsum(du); dn2 = du W1^T
   PO_K(layernorm_forward(dt, x1, st->P(layer, pl.ln2_g), st->P(layer, pl.ln2_b), st->w_n, s, h, c.ln_eps, q));
   e = make_ep(f);
   e.acc_f32 = st->G(layer, pl.w_fc1);
-  PO_K(gemm(dt, 1, 0, h, f, s, st->w_n, h, st->w_du, f, e, false, q));
+  PO_RC(st_gemm(st, 1, 0, h, f, s, st->w_n, h, st->w_du, f, e));
   PO_K(colsum_accumulate(dt, st->w_du, st->G(layer, pl.b_fc1), st->w_colws, s, f, q));
   e = make_ep(h);
   e.out = st->w_dn;
-  PO_K(gemm(dt, 0, 1, s, h, f, st->w_du, f, st->P(layer, pl.w_fc1), f, e, false, q));
+  PO_RC(st_gemm(st, 0, 1, s, h, f, st->w_du, f, st->P(layer, pl.w_fc1), f, e));
   // LN2 backward + residual: dx1 = dy + LNbwd(dn2)
   PO_K(layernorm_backward(dt, st->w_dn, x1, st->P(layer, pl.ln2_g), dy, st->w_dx1, st->G(layer, pl.ln2_g),
                           st->G(layer, pl.ln2_b), st->w_lnws, s, h, c.ln_eps, q));
   // Out-proj: dWo += O^T dx1; dbo += colsum(dx1); dO = dx1 Wo^T
   e = make_ep(h);
   e.acc_f32 = st->G(layer, pl.w_o);
-  PO_K(gemm(dt, 1, 0, h, h, s, o, h, st->w_dx1, h, e, false, q));
+  PO_RC(st_gemm(st, 1, 0, h, h, s, o, h, st->w_dx1, h, e));
   PO_K(colsum_accumulate(dt, st->w_dx1, st->G(layer, pl.b_o), st->w_colws, s, h, q));
   e = make_ep(h);
   e.out = st->w_do;
-  PO_K(gemm(dt, 0, 1, s, h, h, st->w_dx1, h, st->P(layer, pl.w_o), h, e, false, q));
+  PO_RC(st_gemm(st, 0, 1, s, h, h, st->w_dx1, h, st->P(layer, pl.w_o), h, e));
   // Attention backward
-  PO_K(attention_backward(dt, qkv, o, lse, st->w_do, st->w_dqkv, st->w_delta, s, h, c.n_heads, false, q));
+  PO_RC(st_attention(st, true, qkv, const_cast<char*>(o), const_cast<float*>(lse), st->w_do, st->w_dqkv));
   // QKV: n1 recomputed; dWqkv += n1^T dqkv; dbqkv += colsum(dqkv); dn1 = dqkv Wqkv^T
   PO_K(layernorm_forward(dt, x, st->P(layer, pl.ln1_g), st->P(layer, pl.ln1_b), st->w_n, s, h, c.ln_eps, q));
   e = make_ep(3 * h);
   e.acc_f32 = st->G(layer, pl.w_qkv);
-  PO_K(gemm(dt, 1, 0, h, 3 * h, s, st->w_n, h, st->w_dqkv, 3 * h, e, false, q));
+  PO_RC(st_gemm(st, 1, 0, h, 3 * h, s, st->w_n, h, st->w_dqkv, 3 * h, e));
   PO_K(colsum_accumulate(dt, st->w_dqkv, st->G(layer, pl.b_qkv), st->w_colws, s, 3 * h, q));
   e = make_ep(h);
   e.out = st->w_dn;
-  PO_K(gemm(dt, 0, 1, s, h, 3 * h, st->w_dqkv, 3 * h, st->P(layer, pl.w_qkv), 3 * h, e, false, q));
+  PO_RC(st_gemm(st, 0, 1, s, h, 3 * h, st->w_dqkv, 3 * h, st->P(layer, pl.w_qkv), 3 * h, e));
   // LN1 backward + residual: dx = dx1 + LNbwd(dn1)
   PO_K(layernorm_backward(dt, st->w_dn, x, st->P(layer, pl.ln1_g), st->w_dx1, dx_out, st->G(layer, pl.ln1_g),
                           st->G(layer, pl.ln1_b), st->w_lnws, s, h, c.ln_eps, q));
@@ -744,12 +784,15 @@ int stage_synchronize(po_stage* st) {
 
 // Folds the recorded spans into the stats (all streams must be drained).
 static int collect_spans(po_stage* st) {
-  double busy[4] = {0, 0, 0, 0};
+  double busy[6] = {0, 0, 0, 0, 0, 0};
+  double flops[6] = {0, 0, 0, 0, 0, 0};
   hipEvent_t first = nullptr, last = nullptr;
   for (const TimedSpan& sp : st->spans) {
     float ms = 0.f;
     PO_HIP(hipEventElapsedTime(&ms, sp.start, sp.stop));
     busy[sp.kind] += ms * 1e-3;
+    flops[sp.kind] += sp.flops;
+    if (sp.kind == 4) ++st->stats.n_gemm_launches;
     if (sp.kind == 0) {
       if (!first) first = sp.start;
       last = sp.stop;
@@ -759,6 +802,10 @@ static int collect_spans(po_stage* st) {
   st->stats.d2h_busy_s = busy[1];
   st->stats.h2d_busy_s = busy[2];
   st->stats.pack_busy_s = busy[3];
+  st->stats.gemm_busy_s = busy[4];
+  st->stats.gemm_flops = flops[4];
+  st->stats.attn_busy_s = busy[5];
+  st->stats.attn_flops = flops[5];
   if (first && last) {
     float ms = 0.f;
     PO_HIP(hipEventElapsedTime(&ms, first, last));

@@ -66,17 +66,21 @@ class StageRunner:
     """Owns a stage plus the caller-side buffers (parameters, gradients, unit inputs and outputs)."""
 
     def __init__(self, shape: syn.StageShape, seed: int = 1234, device="cuda:0", params: dict | None = None,
-                 n_microbatches: int | None = None, **cfg_overrides):
+                 n_microbatches: int | None = None, device_params: bool = False, **cfg_overrides):
         self.shape = shape
         self.seed = seed
         self.device = torch.device(device)
         self.cfg = make_config(shape, **cfg_overrides)
         self.m = n_microbatches if n_microbatches is not None else shape.n_microbatches
         self.v = shape.n_chunks
-        self.params_np = params if params is not None else syn.stage_params(shape, seed)
-        flat = flatten_params(self.cfg, self.params_np)
-        self.params = torch.from_numpy(flat).to(self.device).to(torch_dtype(self.cfg)).contiguous()
-        self.grads = torch.zeros(flat.shape[0], dtype=torch.float32, device=self.device)
+        if device_params:  # large configurations: draw the parameters on the device
+            self.params_np = None
+            self.params = random_device_params(self.cfg, self.device, seed)
+        else:
+            self.params_np = params if params is not None else syn.stage_params(shape, seed)
+            flat = flatten_params(self.cfg, self.params_np)
+            self.params = torch.from_numpy(flat).to(self.device).to(torch_dtype(self.cfg)).contiguous()
+        self.grads = torch.zeros(self.params.shape[0], dtype=torch.float32, device=self.device)
         torch.cuda.synchronize()
         self.stage = po.po_stage_create(self.cfg, torch.cuda.current_stream(self.device))
         po.po_bind_params(self.stage, self.params, self.grads)
