@@ -1,24 +1,701 @@
-// bf16 causal attention on the matrix cores (placeholder: not yet enabled).
+// bf16 causal attention on the CDNA4 matrix cores, forward and backward, with
+// online softmax (no s x s matrix is ever stored; the forward keeps the
+// per-row log-sum-exp, the backward recomputes the probabilities from it).
+//
+// Layout idea shared by all three kernels.  A 32 x 32 MFMA leaves lane L with
+// column (L % 32) of the result and 16 of its rows.  The kernels always put the
+// index a wave OWNS (its query rows in forward and dQ, its key rows in dK/dV)
+// on the MFMA column, so that
+//   * softmax statistics of a query row live in one lane (plus its partner
+//     L ^ 32): row max / row sum need no cross-lane tree,
+//   * a probability tile converted to bf16 is already laid out as the B operand
+//     of the next MFMA (k index = the 8 rows a lane holds per 16-deep step), so
+//     P and dS never travel through LDS,
+//   * the other operand of that next MFMA (V, dO, Q or K as [row][dh], i.e. with
+//     the contraction index as the slow dimension) is fetched with the gfx950
+//     transposing LDS read (ds_read_b64_tr_b16), two per fragment.
+//
+// Forward: block = 4 waves, a wave owns QT x 32 query rows; K/V tiles of 64 keys
+// are staged through LDS (register-prefetched, double-buffered).  Blocks with the
+// most key tiles are launched first (causal work is triangular).
+//
+// Backward, deterministic without atomics: one kernel per key block accumulates
+// dK and dV over the query tiles at or below the diagonal; one kernel per query
+// block accumulates dQ over the key tiles up to the diagonal.  Both recompute
+// S = Q K^T and dP = dO V^T.
+#include <math.h>
+
 #include "kernels.h"
 
 namespace po {
 
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+#define LDS_AS3(p) ((s16x4 __attribute__((address_space(3)))*)(p))
+
+constexpr int kKeysPerTile = 64;
+
+// ---- LDS tiles -------------------------------------------------------------------
+// "Row" tile: [rows][DH] bf16, 16-byte chunks XOR-swizzled by the row index; read with
+// ds_read_b128 as an MFMA operand whose contraction index is the head dimension.
+template <int DH>
+__device__ __forceinline__ int row_tile_offset(int row, int chunk) {
+  constexpr int CPR = DH / 8;
+  return row * (DH * 2) + ((chunk ^ (row & (CPR - 1))) << 4);
+}
+// "Transposable" tile: [rows][DH + 16] bf16 (32 bytes of padding per row so that the four
+// rows touched by a 16-lane transposing read fall into different banks).
+template <int DH>
+__device__ __forceinline__ int tr_tile_offset(int row, int col) {
+  return row * ((DH + 16) * 2) + col * 2;
+}
+template <int DH> constexpr int row_tile_bytes(int rows) { return rows * DH * 2; }
+template <int DH> constexpr int tr_tile_bytes(int rows) { return rows * (DH + 16) * 2; }
+
+// Fragment whose contraction index is the tile's row: lane (column c = lane % 32 of the
+// 32-wide block starting at col0, half = lane / 32) receives rows
+// {row0 + 4 half + 0..3} and {row0 + 4 half + 8 + 0..3} of column col0 + c.
+// Within a group of 16 lanes, the transposing read hands lane i element (i % 4) of the
+// four addresses supplied by lanes i / 4, 4 + i / 4, 8 + i / 4, 12 + i / 4 of the group.
+template <int DH>
+__device__ __forceinline__ bf16x8 read_tr_fragment(const char* tile, int row0, int col0, int lane) {
+  int i = lane & 15;
+  int grp = lane >> 4;
+  int half = grp >> 1;
+  int c0 = col0 + 16 * (grp & 1);
+  int r = row0 + 4 * half + (i >> 2);
+  int c = c0 + 4 * (i & 3);
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_AS3(tile + tr_tile_offset<DH>(r, c)));
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_AS3(tile + tr_tile_offset<DH>(r + 8, c)));
+  union {
+    struct {
+      s16x4 a, b;
+    } s;
+    bf16x8 v;
+  } u;
+  u.s.a = lo;
+  u.s.b = hi;
+  return u.v;
+}
+
+template <int DH>
+__device__ __forceinline__ bf16x8 read_row_fragment(const char* tile, int row, int chunk) {
+  return *reinterpret_cast<const bf16x8*>(tile + row_tile_offset<DH>(row, chunk));
+}
+
+// Eight consecutive accumulator values -> bf16 operand fragment.
+__device__ __forceinline__ bf16x8 pack_bf16x8(const f32x16& a, int first) {
+  bf16x8 r;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) r[e] = (bf16)a[first + e];
+  return r;
+}
+
+// Global -> register staging of a [64][DH] tile (rows of the qkv / dO matrices), 256 threads.
+template <int DH>
+struct TileLoader {
+  static constexpr int CPR = DH / 8;                 // 16-byte chunks per row
+  static constexpr int N = kKeysPerTile * CPR / 256;  // chunks per thread
+  uint4 reg[N];
+  __device__ __forceinline__ void load(const bf16* base, int ld, int row0, int tid) {
+#pragma unroll
+    for (int u = 0; u < N; ++u) {
+      int e = tid + 256 * u;
+      int row = e / CPR, c = e % CPR;
+      reg[u] = *reinterpret_cast<const uint4*>(base + (size_t)(row0 + row) * ld + c * 8);
+    }
+  }
+  __device__ __forceinline__ void store_row_tile(char* tile, int tid) const {
+#pragma unroll
+    for (int u = 0; u < N; ++u) {
+      int e = tid + 256 * u;
+      int row = e / CPR, c = e % CPR;
+      *reinterpret_cast<uint4*>(tile + row_tile_offset<DH>(row, c)) = reg[u];
+    }
+  }
+  __device__ __forceinline__ void store_tr_tile(char* tile, int tid) const {
+#pragma unroll
+    for (int u = 0; u < N; ++u) {
+      int e = tid + 256 * u;
+      int row = e / CPR, c = e % CPR;
+      *reinterpret_cast<uint4*>(tile + tr_tile_offset<DH>(row, c * 8)) = reg[u];
+    }
+  }
+};
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// ==================================================================================
+// Forward
+// ==================================================================================
+template <int DH, int QT>
+__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ o,
+                                                            float* __restrict__ lse, int s, int h, float scale) {
+  constexpr int KS = DH / 16;   // 16-deep MFMA steps over the head dimension
+  constexpr int DT = DH / 32;   // 32-wide output tiles over the head dimension
+  constexpr int BQ = 128 * QT;  // query rows per block
+  constexpr int KBYTES = row_tile_bytes<DH>(kKeysPerTile);
+  constexpr int VBYTES = tr_tile_bytes<DH>(kKeysPerTile);
+  constexpr int STAGE = KBYTES + VBYTES;
+  extern __shared__ __align__(16) char smem[];
+
+  int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int half = lane >> 5, col = lane & 31;
+  int head = blockIdx.y;
+  int qblock = gridDim.x - 1 - blockIdx.x;  // heaviest blocks first
+  int q0 = qblock * BQ;
+  int qw0 = q0 + wave * (32 * QT);  // first query row of this wave
+  int ld = 3 * h;
+  const bf16* qbase = qkv + head * DH;
+  const bf16* kbase = qkv + h + head * DH;
+  const bf16* vbase = qkv + 2 * h + head * DH;
+  const float c = scale * 1.4426950408889634f;  // scores are kept raw; exp(x * scale) = exp2(x * c)
+
+  // Q fragments stay in registers: B operand, column = query row.
+  bf16x8 qf[QT][KS];
+#pragma unroll
+  for (int t = 0; t < QT; ++t)
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk)
+      qf[t][kk] = *reinterpret_cast<const bf16x8*>(qbase + (size_t)(qw0 + 32 * t + col) * ld + 16 * kk + 8 * half);
+
+  f32x16 oacc[QT][DT];
+  float m_run[QT], l_run[QT];
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    m_run[t] = -INFINITY;
+    l_run[t] = 0.f;
+#pragma unroll
+    for (int d = 0; d < DT; ++d)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) oacc[t][d][e] = 0.f;
+  }
+
+  int nkv = (q0 + BQ) / kKeysPerTile;
+  TileLoader<DH> lk, lv;
+  lk.load(kbase, ld, 0, tid);
+  lv.load(vbase, ld, 0, tid);
+  lk.store_row_tile(smem, tid);
+  lv.store_tr_tile(smem + KBYTES, tid);
+  __syncthreads();
+
+  for (int kt = 0; kt < nkv; ++kt) {
+    const char* ktile = smem + (kt & 1) * STAGE;
+    const char* vtile = ktile + KBYTES;
+    char* nxt = smem + ((kt + 1) & 1) * STAGE;
+    bool more = kt + 1 < nkv;
+    if (more) {
+      lk.load(kbase, ld, (kt + 1) * kKeysPerTile, tid);
+      lv.load(vbase, ld, (kt + 1) * kKeysPerTile, tid);
+    }
+    int key0 = kt * kKeysPerTile;
+    if (key0 <= qw0 + 32 * QT - 1) {  // some key of the tile is visible to some row of this wave
+      // S^T = K Q^T : rows = keys, columns = query rows
+      f32x16 sacc[QT][2];
+#pragma unroll
+      for (int t = 0; t < QT; ++t)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) sacc[t][j][e] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk) {
+        bf16x8 kf[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) kf[j] = read_row_fragment<DH>(ktile, 32 * j + col, 2 * kk + half);
+#pragma unroll
+        for (int t = 0; t < QT; ++t)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            sacc[t][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j], qf[t][kk], sacc[t][j], 0, 0, 0);
+      }
+      bf16x8 pf[QT][2][2];  // [q tile][key sub-tile][16-key step]
+#pragma unroll
+      for (int t = 0; t < QT; ++t) {
+        int q = qw0 + 32 * t + col;
+        bool need_mask = key0 + kKeysPerTile - 1 > qw0 + 32 * t;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            if (need_mask) {
+              int key = key0 + 32 * j + 8 * (e >> 2) + 4 * half + (e & 3);
+              if (key > q) sacc[t][j][e] = -INFINITY;
+            }
+            mx = fmaxf(mx, sacc[t][j][e]);
+          }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        float m_new = fmaxf(m_run[t], mx);
+        float alpha = fast_exp2((m_run[t] - m_new) * c);
+        float mc = m_new * c;
+        float sum = 0.f;
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            float p = fast_exp2(sacc[t][j][e] * c - mc);
+            sacc[t][j][e] = p;
+            sum += p;
+          }
+        l_run[t] = l_run[t] * alpha + sum;
+        m_run[t] = m_new;
+#pragma unroll
+        for (int d = 0; d < DT; ++d)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) oacc[t][d][e] *= alpha;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          pf[t][j][0] = pack_bf16x8(sacc[t][j], 0);
+          pf[t][j][1] = pack_bf16x8(sacc[t][j], 8);
+        }
+      }
+      // O^T += V^T P^T : rows = head dimension, columns = query rows, contraction over keys
+#pragma unroll
+      for (int d = 0; d < DT; ++d)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int st = 0; st < 2; ++st) {
+            bf16x8 vf = read_tr_fragment<DH>(vtile, 32 * j + 16 * st, 32 * d, lane);
+#pragma unroll
+            for (int t = 0; t < QT; ++t)
+              oacc[t][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[t][j][st], oacc[t][d], 0, 0, 0);
+          }
+    }
+    if (more) {
+      lk.store_row_tile(nxt, tid);
+      lv.store_tr_tile(nxt + KBYTES, tid);
+    }
+    __syncthreads();
+  }
+
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    int q = qw0 + 32 * t + col;
+    float l = l_run[t] + __shfl_xor(l_run[t], 32, 64);
+    float inv = 1.0f / l;
+#pragma unroll
+    for (int d = 0; d < DT; ++d)
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        bf16x4 v;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] = (bf16)(oacc[t][d][4 * b + r] * inv);
+        *reinterpret_cast<bf16x4*>(o + (size_t)q * h + head * DH + 32 * d + 8 * b + 4 * half) = v;
+      }
+    if (half == 0) lse[(size_t)head * s + q] = m_run[t] * scale + __logf(l);
+  }
+}
+
+// ==================================================================================
+// Backward, part 1: dK and dV.  Block = 128 keys (a wave owns 32), loop over the
+// 64-row query tiles at or below the diagonal.  Q and dO tiles are staged in LDS in
+// the padded [row][DH + 16] form, which serves both kinds of reads: ds_read_b128
+// fragments (contraction over the head dimension, for S and dP) and transposing
+// fragments (contraction over the query rows, for dV and dK).
+//   S[q][key]  = Q K^T          P = exp(S scale - lse[q])
+//   dP[q][key] = dO V^T         dS = P (dP - delta[q])
+//   dV[key]   += P^T dO         dK[key] += dS^T Q   (times scale at the end)
+// ==================================================================================
+template <int DH>
+__device__ __forceinline__ bf16x8 read_padded_row_fragment(const char* tile, int row, int chunk) {
+  return *reinterpret_cast<const bf16x8*>(tile + tr_tile_offset<DH>(row, chunk * 8));
+}
+
+template <int DH>
+__global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __restrict__ qkv,
+                                                                const bf16* __restrict__ d_o,
+                                                                const float* __restrict__ lse,
+                                                                const float* __restrict__ delta,
+                                                                bf16* __restrict__ dqkv, int s, int h, float scale) {
+  constexpr int KS = DH / 16, DT = DH / 32;
+  constexpr int TBYTES = tr_tile_bytes<DH>(kKeysPerTile);
+  constexpr int STAGE = 2 * TBYTES + 512;  // Q tile, dO tile, lse[64], delta[64]
+  extern __shared__ __align__(16) char smem[];
+
+  int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int half = lane >> 5, col = lane & 31;
+  int head = blockIdx.y;
+  int kb0 = blockIdx.x * 128;   // first key of the block (the earliest blocks have the most query tiles)
+  int kw0 = kb0 + wave * 32;    // first key of this wave
+  int ld = 3 * h;
+  const bf16* qbase = qkv + head * DH;
+  const bf16* dobase = d_o + head * DH;
+  const float* lse_h = lse + (size_t)head * s;
+  const float* delta_h = delta + (size_t)head * s;
+  const float LOG2E = 1.4426950408889634f;
+  const float c = scale * LOG2E;
+
+  // K and V fragments of this wave's keys: B operands, column = key, contraction over the head dimension.
+  bf16x8 kf[KS], vf[KS];
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk) {
+    const bf16* row = qkv + (size_t)(kw0 + col) * ld + head * DH + 16 * kk + 8 * half;
+    kf[kk] = *reinterpret_cast<const bf16x8*>(row + h);
+    vf[kk] = *reinterpret_cast<const bf16x8*>(row + 2 * h);
+  }
+  f32x16 dk[DT], dv[DT];
+#pragma unroll
+  for (int d = 0; d < DT; ++d)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) dk[d][e] = dv[d][e] = 0.f;
+
+  int q_first = kb0 / kKeysPerTile, q_last = s / kKeysPerTile;  // query tiles [q_first, q_last)
+  TileLoader<DH> lq, ldo;
+  float stat = 0.f;  // threads 0..63: lse * log2(e) of a row, threads 64..127: delta of a row
+  auto load_stats = [&](int q0) {
+    if (tid < 64)
+      stat = lse_h[q0 + tid] * LOG2E;
+    else if (tid < 128)
+      stat = delta_h[q0 + tid - 64];
+  };
+  auto store_stats = [&](char* stage) {
+    if (tid < 128) reinterpret_cast<float*>(stage + 2 * TBYTES)[tid] = stat;
+  };
+  lq.load(qbase, ld, q_first * kKeysPerTile, tid);
+  ldo.load(dobase, h, q_first * kKeysPerTile, tid);
+  load_stats(q_first * kKeysPerTile);
+  lq.store_tr_tile(smem, tid);
+  ldo.store_tr_tile(smem + TBYTES, tid);
+  store_stats(smem);
+  __syncthreads();
+
+  for (int qt = q_first; qt < q_last; ++qt) {
+    int it = qt - q_first;
+    const char* qtile = smem + (it & 1) * STAGE;
+    const char* dotile = qtile + TBYTES;
+    const float* st_lse = reinterpret_cast<const float*>(qtile + 2 * TBYTES);
+    const float* st_delta = st_lse + 64;
+    char* nxt = smem + ((it + 1) & 1) * STAGE;
+    bool more = qt + 1 < q_last;
+    if (more) {
+      lq.load(qbase, ld, (qt + 1) * kKeysPerTile, tid);
+      ldo.load(dobase, h, (qt + 1) * kKeysPerTile, tid);
+      load_stats((qt + 1) * kKeysPerTile);
+    }
+    int q0 = qt * kKeysPerTile;
+    if (q0 + kKeysPerTile - 1 >= kw0) {  // some row of the tile sees some key of this wave
+      f32x16 sacc[2], pacc[2];
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) sacc[j][e] = pacc[j][e] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          bf16x8 qa = read_padded_row_fragment<DH>(qtile, 32 * j + col, 2 * kk + half);
+          bf16x8 da = read_padded_row_fragment<DH>(dotile, 32 * j + col, 2 * kk + half);
+          sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[kk], sacc[j], 0, 0, 0);
+          pacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vf[kk], pacc[j], 0, 0, 0);
+        }
+      bool need_mask = q0 < kw0 + 31;
+      int key = kw0 + col;
+      bf16x8 pf[2][2], dsf[2][2];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          float4 l4 = *reinterpret_cast<const float4*>(st_lse + 32 * j + 8 * b + 4 * half);
+          float4 d4 = *reinterpret_cast<const float4*>(st_delta + 32 * j + 8 * b + 4 * half);
+          float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            int e = 4 * b + r;
+            float p = fast_exp2(sacc[j][e] * c - lv[r]);
+            if (need_mask && key > q0 + 32 * j + 8 * b + 4 * half + r) p = 0.f;
+            sacc[j][e] = p;
+            pacc[j][e] = p * (pacc[j][e] - dl[r]);
+          }
+        }
+        pf[j][0] = pack_bf16x8(sacc[j], 0);
+        pf[j][1] = pack_bf16x8(sacc[j], 8);
+        dsf[j][0] = pack_bf16x8(pacc[j], 0);
+        dsf[j][1] = pack_bf16x8(pacc[j], 8);
+      }
+#pragma unroll
+      for (int d = 0; d < DT; ++d)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int st = 0; st < 2; ++st) {
+            bf16x8 dot = read_tr_fragment<DH>(dotile, 32 * j + 16 * st, 32 * d, lane);
+            bf16x8 qtr = read_tr_fragment<DH>(qtile, 32 * j + 16 * st, 32 * d, lane);
+            dv[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dot, pf[j][st], dv[d], 0, 0, 0);
+            dk[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qtr, dsf[j][st], dk[d], 0, 0, 0);
+          }
+    }
+    if (more) {
+      lq.store_tr_tile(nxt, tid);
+      ldo.store_tr_tile(nxt + TBYTES, tid);
+      store_stats(nxt);
+    }
+    __syncthreads();
+  }
+
+  int key = kw0 + col;
+#pragma unroll
+  for (int d = 0; d < DT; ++d)
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      bf16x4 vk, vv;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        vk[r] = (bf16)(dk[d][4 * b + r] * scale);
+        vv[r] = (bf16)dv[d][4 * b + r];
+      }
+      size_t off = (size_t)key * ld + head * DH + 32 * d + 8 * b + 4 * half;
+      *reinterpret_cast<bf16x4*>(dqkv + off + h) = vk;
+      *reinterpret_cast<bf16x4*>(dqkv + off + 2 * h) = vv;
+    }
+}
+
+// ==================================================================================
+// Backward, part 2: dQ.  Block = 128 QT query rows (a wave owns 32 QT), loop over the
+// key tiles up to the diagonal.  K is staged in the padded form (row fragments for
+// S^T = K Q^T, transposing fragments for dQ^T = K^T dS^T), V in the swizzled row form.
+// ==================================================================================
+template <int DH, int QT>
+__global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv,
+                                                               const bf16* __restrict__ d_o,
+                                                               const float* __restrict__ lse,
+                                                               const float* __restrict__ delta,
+                                                               bf16* __restrict__ dqkv, int s, int h, float scale) {
+  constexpr int KS = DH / 16, DT = DH / 32;
+  constexpr int BQ = 128 * QT;
+  constexpr int KBYTES = tr_tile_bytes<DH>(kKeysPerTile);
+  constexpr int VBYTES = row_tile_bytes<DH>(kKeysPerTile);
+  constexpr int STAGE = KBYTES + VBYTES;
+  extern __shared__ __align__(16) char smem[];
+
+  int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int half = lane >> 5, col = lane & 31;
+  int head = blockIdx.y;
+  int qblock = gridDim.x - 1 - blockIdx.x;
+  int q0 = qblock * BQ;
+  int qw0 = q0 + wave * (32 * QT);
+  int ld = 3 * h;
+  const bf16* kbase = qkv + h + head * DH;
+  const bf16* vbase = qkv + 2 * h + head * DH;
+  const float LOG2E = 1.4426950408889634f;
+  const float c = scale * LOG2E;
+
+  bf16x8 qf[QT][KS], dof[QT][KS];
+  float lse_q[QT], delta_q[QT];
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    int q = qw0 + 32 * t + col;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+      qf[t][kk] = *reinterpret_cast<const bf16x8*>(qkv + (size_t)q * ld + head * DH + 16 * kk + 8 * half);
+      dof[t][kk] = *reinterpret_cast<const bf16x8*>(d_o + (size_t)q * h + head * DH + 16 * kk + 8 * half);
+    }
+    lse_q[t] = lse[(size_t)head * s + q] * LOG2E;
+    delta_q[t] = delta[(size_t)head * s + q];
+  }
+  f32x16 dq[QT][DT];
+#pragma unroll
+  for (int t = 0; t < QT; ++t)
+#pragma unroll
+    for (int d = 0; d < DT; ++d)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) dq[t][d][e] = 0.f;
+
+  int nkv = (q0 + BQ) / kKeysPerTile;
+  TileLoader<DH> lk, lv;
+  lk.load(kbase, ld, 0, tid);
+  lv.load(vbase, ld, 0, tid);
+  lk.store_tr_tile(smem, tid);
+  lv.store_row_tile(smem + KBYTES, tid);
+  __syncthreads();
+
+  for (int kt = 0; kt < nkv; ++kt) {
+    const char* ktile = smem + (kt & 1) * STAGE;
+    const char* vtile = ktile + KBYTES;
+    char* nxt = smem + ((kt + 1) & 1) * STAGE;
+    bool more = kt + 1 < nkv;
+    if (more) {
+      lk.load(kbase, ld, (kt + 1) * kKeysPerTile, tid);
+      lv.load(vbase, ld, (kt + 1) * kKeysPerTile, tid);
+    }
+    int key0 = kt * kKeysPerTile;
+    if (key0 <= qw0 + 32 * QT - 1) {
+      f32x16 sacc[QT][2], pacc[QT][2];
+#pragma unroll
+      for (int t = 0; t < QT; ++t)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) sacc[t][j][e] = pacc[t][j][e] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          bf16x8 ka = read_padded_row_fragment<DH>(ktile, 32 * j + col, 2 * kk + half);
+          bf16x8 va = read_row_fragment<DH>(vtile, 32 * j + col, 2 * kk + half);
+#pragma unroll
+          for (int t = 0; t < QT; ++t) {
+            sacc[t][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[t][kk], sacc[t][j], 0, 0, 0);
+            pacc[t][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, dof[t][kk], pacc[t][j], 0, 0, 0);
+          }
+        }
+      bf16x8 dsf[QT][2][2];
+#pragma unroll
+      for (int t = 0; t < QT; ++t) {
+        int q = qw0 + 32 * t + col;
+        bool need_mask = key0 + kKeysPerTile - 1 > qw0 + 32 * t;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            float p = fast_exp2(sacc[t][j][e] * c - lse_q[t]);
+            if (need_mask && key0 + 32 * j + 8 * (e >> 2) + 4 * half + (e & 3) > q) p = 0.f;
+            pacc[t][j][e] = p * (pacc[t][j][e] - delta_q[t]);
+          }
+          dsf[t][j][0] = pack_bf16x8(pacc[t][j], 0);
+          dsf[t][j][1] = pack_bf16x8(pacc[t][j], 8);
+        }
+      }
+#pragma unroll
+      for (int d = 0; d < DT; ++d)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int st = 0; st < 2; ++st) {
+            bf16x8 ktr = read_tr_fragment<DH>(ktile, 32 * j + 16 * st, 32 * d, lane);
+#pragma unroll
+            for (int t = 0; t < QT; ++t)
+              dq[t][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktr, dsf[t][j][st], dq[t][d], 0, 0, 0);
+          }
+    }
+    if (more) {
+      lk.store_tr_tile(nxt, tid);
+      lv.store_row_tile(nxt + KBYTES, tid);
+    }
+    __syncthreads();
+  }
+
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    int q = qw0 + 32 * t + col;
+#pragma unroll
+    for (int d = 0; d < DT; ++d)
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        bf16x4 v;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] = (bf16)(dq[t][d][4 * b + r] * scale);
+        *reinterpret_cast<bf16x4*>(dqkv + (size_t)q * ld + head * DH + 32 * d + 8 * b + 4 * half) = v;
+      }
+  }
+}
+
+// delta[head][i] = sum_e dO[i, head, e] * O[i, head, e]: one wave per (head, row).
+template <int DH>
+__global__ __launch_bounds__(256) void attn_delta_mfma_path_kernel(const bf16* __restrict__ o,
+                                                                   const bf16* __restrict__ d_o,
+                                                                   float* __restrict__ delta, int s, int h) {
+  int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  int head = blockIdx.y;
+  int i = blockIdx.x * 4 + wave;
+  if (i >= s) return;
+  float d = 0.f;
+  if (lane * 2 < DH) {
+    size_t idx = (size_t)i * h + head * DH + lane * 2;
+    d = (float)o[idx] * (float)d_o[idx] + (float)o[idx + 1] * (float)d_o[idx + 1];
+  }
+  d = wave_sum(d);
+  if (lane == 0) delta[(size_t)head * s + i] = d;
+}
+
+// ==================================================================================
+// Host side
+// ==================================================================================
 bool attention_mfma_supported(int s, int h, int n_heads) {
-  (void)s;
-  (void)h;
-  (void)n_heads;
-  return false;
+  if (n_heads <= 0 || h % n_heads != 0) return false;
+  int dh = h / n_heads;
+  return (dh == 64 || dh == 128) && s >= 128 && s % 128 == 0;
 }
 
-bool attention_forward_mfma(const void*, void*, float*, int, int, int, hipStream_t) {
-  set_error("attention_forward_mfma: not available");
-  return false;
+template <int DH, int QT>
+static bool launch_fwd(const bf16* qkv, bf16* o, float* lse, int s, int h, int n_heads, hipStream_t stream) {
+  constexpr int smem = 2 * (row_tile_bytes<DH>(kKeysPerTile) + tr_tile_bytes<DH>(kKeysPerTile));
+  auto kern = attn_fwd_mfma_kernel<DH, QT>;
+  static bool configured = false;
+  if (!configured) {
+    PO_HIP_OK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  smem));
+    configured = true;
+  }
+  dim3 grid(s / (128 * QT), n_heads);
+  kern<<<grid, 256, smem, stream>>>(qkv, o, lse, s, h, 1.0f / sqrtf((float)DH));
+  return launch_ok("attn_fwd_mfma_kernel");
 }
 
-bool attention_backward_mfma(const void*, const void*, const float*, const void*, void*, float*, int, int, int,
-                             hipStream_t) {
-  set_error("attention_backward_mfma: not available");
-  return false;
+bool attention_forward_mfma(const void* qkv, void* o, float* lse, int s, int h, int n_heads, hipStream_t stream) {
+  if (!attention_mfma_supported(s, h, n_heads) || !qkv || !o || !lse ||
+      ((uintptr_t)qkv | (uintptr_t)o) % 16 != 0) {
+    set_error("attention_forward_mfma: unsupported s=%d h=%d heads=%d or bad pointers", s, h, n_heads);
+    return false;
+  }
+  int dh = h / n_heads;
+  const bf16* q = (const bf16*)qkv;
+  bf16* out = (bf16*)o;
+  // two query tiles per wave once that still fills the chip
+  bool big = s % 256 == 0 && (int64_t)(s / 256) * n_heads >= 512;
+  if (dh == 128) {
+    if (big) return launch_fwd<128, 2>(q, out, lse, s, h, n_heads, stream);
+    return launch_fwd<128, 1>(q, out, lse, s, h, n_heads, stream);
+  }
+  if (big) return launch_fwd<64, 2>(q, out, lse, s, h, n_heads, stream);
+  return launch_fwd<64, 1>(q, out, lse, s, h, n_heads, stream);
+}
+
+template <int DH>
+static bool launch_bwd(const bf16* qkv, const bf16* o, const float* lse, const bf16* d_o, bf16* dqkv, float* delta,
+                       int s, int h, int n_heads, hipStream_t stream) {
+  constexpr int smem_kv = 2 * (2 * tr_tile_bytes<DH>(kKeysPerTile) + 512);
+  constexpr int smem_q = 2 * (tr_tile_bytes<DH>(kKeysPerTile) + row_tile_bytes<DH>(kKeysPerTile));
+  auto kkv = attn_bwd_dkv_mfma_kernel<DH>;
+  auto kq1 = attn_bwd_dq_mfma_kernel<DH, 1>;
+  auto kq2 = attn_bwd_dq_mfma_kernel<DH, 2>;
+  static bool configured = false;
+  if (!configured) {
+    PO_HIP_OK(hipFuncSetAttribute(reinterpret_cast<const void*>(kkv), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  smem_kv));
+    PO_HIP_OK(hipFuncSetAttribute(reinterpret_cast<const void*>(kq1), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  smem_q));
+    PO_HIP_OK(hipFuncSetAttribute(reinterpret_cast<const void*>(kq2), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  smem_q));
+    configured = true;
+  }
+  float scale = 1.0f / sqrtf((float)DH);
+  attn_delta_mfma_path_kernel<DH><<<dim3(ceil_div(s, 4), n_heads), 256, 0, stream>>>(o, d_o, delta, s, h);
+  kkv<<<dim3(s / 128, n_heads), 256, smem_kv, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, scale);
+  bool big = s % 256 == 0 && (int64_t)(s / 256) * n_heads >= 512;
+  if (big)
+    kq2<<<dim3(s / 256, n_heads), 256, smem_q, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, scale);
+  else
+    kq1<<<dim3(s / 128, n_heads), 256, smem_q, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, scale);
+  return launch_ok("attention backward MFMA kernels");
+}
+
+bool attention_backward_mfma(const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv,
+                             float* delta, int s, int h, int n_heads, hipStream_t stream) {
+  if (!attention_mfma_supported(s, h, n_heads) || !qkv || !o || !lse || !d_o || !dqkv || !delta ||
+      ((uintptr_t)qkv | (uintptr_t)o | (uintptr_t)d_o | (uintptr_t)dqkv) % 16 != 0) {
+    set_error("attention_backward_mfma: unsupported s=%d h=%d heads=%d or bad pointers", s, h, n_heads);
+    return false;
+  }
+  if (h / n_heads == 128)
+    return launch_bwd<128>((const bf16*)qkv, (const bf16*)o, lse, (const bf16*)d_o, (bf16*)dqkv, delta, s, h,
+                           n_heads, stream);
+  return launch_bwd<64>((const bf16*)qkv, (const bf16*)o, lse, (const bf16*)d_o, (bf16*)dqkv, delta, s, h, n_heads,
+                        stream);
 }
 
 }  // namespace po

@@ -154,6 +154,18 @@ def test_gemm_rejects_bad_arguments(gpu_device):
 @pytest.mark.parametrize("s,h,a", [(1, 64, 1), (5, 64, 2), (64, 128, 2), (65, 256, 4), (200, 256, 2), (130, 512, 2)])
 @pytest.mark.parametrize("force_generic", [1, 0])
 def test_attention_forward_and_backward(gpu_device, dtype, s, h, a, force_generic):
+    _attention_case(gpu_device, dtype, s, h, a, force_generic)
+
+
+# shapes the matrix-core kernels take: head size 64 / 128, s a multiple of 128; the last two
+# are large enough in (s / 256) * heads to select two query tiles per wave
+@pytest.mark.parametrize("s,h,a", [(128, 128, 2), (256, 256, 2), (384, 128, 1), (640, 192, 3), (512, 16384, 256),
+                                   (512, 32768, 256)])
+def test_attention_mfma(gpu_device, s, h, a):
+    _attention_case(gpu_device, "bf16", s, h, a, 0)
+
+
+def _attention_case(gpu_device, dtype, s, h, a, force_generic):
     code, tdt, tol = DT[dtype]
     rng = np.random.default_rng(s * 31 + h + a)
     qkv = _rand(rng, (s, 3 * h), dtype)
