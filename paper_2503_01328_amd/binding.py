@@ -11,6 +11,10 @@ from __future__ import annotations
 import ctypes as C
 import os
 
+# PyTorch ships its own HIP runtime.  It has to be loaded before this library, so that both
+# resolve to ONE runtime in the process: with two, kernel launches from here see no device.
+import torch  # noqa: F401  (device memory and streams come from torch anyway)
+
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libpipeoffload.so")
 if not os.path.exists(_LIB_PATH):
     raise ImportError(
@@ -122,7 +126,6 @@ def _ptr(t):
 
 def _stream(stream):
     if stream is None:
-        import torch
         stream = torch.cuda.current_stream()
     if isinstance(stream, int):
         return C.c_void_p(stream)

@@ -32,6 +32,7 @@ namespace po {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 #define LDS_AS3(p) ((s16x4 __attribute__((address_space(3)))*)(p))
@@ -99,13 +100,13 @@ template <int DH>
 struct TileLoader {
   static constexpr int CPR = DH / 8;                 // 16-byte chunks per row
   static constexpr int N = kKeysPerTile * CPR / 256;  // chunks per thread
-  uint4 reg[N];
+  u32x4 reg[N];
   __device__ __forceinline__ void load(const bf16* base, int ld, int row0, int tid) {
 #pragma unroll
     for (int u = 0; u < N; ++u) {
       int e = tid + 256 * u;
       int row = e / CPR, c = e % CPR;
-      reg[u] = *reinterpret_cast<const uint4*>(base + (size_t)(row0 + row) * ld + c * 8);
+      reg[u] = *reinterpret_cast<const u32x4*>(base + (size_t)(row0 + row) * ld + c * 8);
     }
   }
   __device__ __forceinline__ void store_row_tile(char* tile, int tid) const {
@@ -113,7 +114,7 @@ struct TileLoader {
     for (int u = 0; u < N; ++u) {
       int e = tid + 256 * u;
       int row = e / CPR, c = e % CPR;
-      *reinterpret_cast<uint4*>(tile + row_tile_offset<DH>(row, c)) = reg[u];
+      *reinterpret_cast<u32x4*>(tile + row_tile_offset<DH>(row, c)) = reg[u];
     }
   }
   __device__ __forceinline__ void store_tr_tile(char* tile, int tid) const {
@@ -121,7 +122,7 @@ struct TileLoader {
     for (int u = 0; u < N; ++u) {
       int e = tid + 256 * u;
       int row = e / CPR, c = e % CPR;
-      *reinterpret_cast<uint4*>(tile + tr_tile_offset<DH>(row, c * 8)) = reg[u];
+      *reinterpret_cast<u32x4*>(tile + tr_tile_offset<DH>(row, c * 8)) = reg[u];
     }
   }
 };

@@ -29,6 +29,7 @@ namespace po {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBK = 64;
 
@@ -39,7 +40,7 @@ template <int R, bool TRANS>
 struct Stager {
   // k-contiguous: R*8 chunks of 16 B, R/32 per thread.  Transposed: R blocks of 8x8, at most one per thread.
   static constexpr int NREG = TRANS ? 8 : R / 32;
-  uint4 reg[NREG];
+  u32x4 reg[NREG];
 
   // base points at element (row 0 of the tile, k = 0 of the matrix); k0 = slice start.
   __device__ __forceinline__ void load(const bf16* __restrict__ base, int ld, int k0, int tid) {
@@ -48,14 +49,14 @@ struct Stager {
         int rb = tid % (R / 8), kb = tid / (R / 8);
         const bf16* p = base + (size_t)(k0 + 8 * kb) * ld + 8 * rb;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) reg[i] = *reinterpret_cast<const uint4*>(p + (size_t)i * ld);
+        for (int i = 0; i < 8; ++i) reg[i] = *reinterpret_cast<const u32x4*>(p + (size_t)i * ld);
       }
     } else {
 #pragma unroll
       for (int u = 0; u < NREG; ++u) {
         int e = tid + 256 * u;
         int row = e >> 3, c = e & 7;
-        reg[u] = *reinterpret_cast<const uint4*>(base + (size_t)row * ld + k0 + c * 8);
+        reg[u] = *reinterpret_cast<const u32x4*>(base + (size_t)row * ld + k0 + c * 8);
       }
     }
   }
@@ -67,7 +68,7 @@ struct Stager {
         const uint32_t* in = reinterpret_cast<const uint32_t*>(reg);  // in[i*4 + d]: k = i, m = 2d, 2d+1
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-          uint4 o;
+          u32x4 o;
           uint32_t* od = reinterpret_cast<uint32_t*>(&o);
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
@@ -75,7 +76,7 @@ struct Stager {
             od[q] = (j & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
           }
           int row = 8 * rb + j;
-          *reinterpret_cast<uint4*>(lds + row * 128 + (swizzle_chunk(kb, row) << 4)) = o;
+          *reinterpret_cast<u32x4*>(lds + row * 128 + (swizzle_chunk(kb, row) << 4)) = o;
         }
       }
     } else {
@@ -83,7 +84,7 @@ struct Stager {
       for (int u = 0; u < NREG; ++u) {
         int e = tid + 256 * u;
         int row = e >> 3, c = e & 7;
-        *reinterpret_cast<uint4*>(lds + row * 128 + (swizzle_chunk(c, row) << 4)) = reg[u];
+        *reinterpret_cast<u32x4*>(lds + row * 128 + (swizzle_chunk(c, row) << 4)) = reg[u];
       }
     }
   }
@@ -98,11 +99,15 @@ struct __attribute__((aligned(8))) bf16x4_t {
   bf16 v[4];
 };
 
+// Epilogue kinds are compile-time so that the fully unrolled accumulator walk stays small.
+enum EpiKind : int { kEpiStore = 0, kEpiStoreGelu = 1, kEpiGeluBackward = 2, kEpiAccumulate = 3 };
+
+template <int EPI>
 __device__ __forceinline__ void epilogue_store4(const Epilogue& e, int m, int n, float a0, float a1, float a2,
                                                 float a3) {
   size_t idx = (size_t)m * e.ldc + n;
   float a[4] = {a0, a1, a2, a3};
-  if (e.acc_f32) {
+  if (EPI == kEpiAccumulate) {
     float4* p = reinterpret_cast<float4*>(e.acc_f32 + idx);
     float4 o = *p;
     o.x += a[0];
@@ -112,17 +117,7 @@ __device__ __forceinline__ void epilogue_store4(const Epilogue& e, int m, int n,
     *p = o;
     return;
   }
-  if (e.bias) {
-    bf16x4_t b = *reinterpret_cast<const bf16x4_t*>(static_cast<const bf16*>(e.bias) + n);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) a[i] += (float)b.v[i];
-  }
-  if (e.residual) {
-    bf16x4_t r = *reinterpret_cast<const bf16x4_t*>(static_cast<const bf16*>(e.residual) + idx);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) a[i] += (float)r.v[i];
-  }
-  if (e.gelu_u) {
+  if (EPI == kEpiGeluBackward) {
     bf16x4_t u = *reinterpret_cast<const bf16x4_t*>(static_cast<const bf16*>(e.gelu_u) + idx);
     bf16x4_t o, g;
 #pragma unroll
@@ -135,11 +130,21 @@ __device__ __forceinline__ void epilogue_store4(const Epilogue& e, int m, int n,
     *reinterpret_cast<bf16x4_t*>(static_cast<bf16*>(e.out) + idx) = o;
     return;
   }
+  if (e.bias) {
+    bf16x4_t b = *reinterpret_cast<const bf16x4_t*>(static_cast<const bf16*>(e.bias) + n);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a[i] += (float)b.v[i];
+  }
+  if (e.residual) {
+    bf16x4_t r = *reinterpret_cast<const bf16x4_t*>(static_cast<const bf16*>(e.residual) + idx);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a[i] += (float)r.v[i];
+  }
   bf16x4_t o;
 #pragma unroll
   for (int i = 0; i < 4; ++i) o.v[i] = (bf16)a[i];
-  if (e.out) *reinterpret_cast<bf16x4_t*>(static_cast<bf16*>(e.out) + idx) = o;
-  if (e.gelu_out) {
+  *reinterpret_cast<bf16x4_t*>(static_cast<bf16*>(e.out) + idx) = o;
+  if (EPI == kEpiStoreGelu) {
     bf16x4_t g;
 #pragma unroll
     for (int i = 0; i < 4; ++i) g.v[i] = (bf16)gelu_f((float)o.v[i]);
@@ -148,7 +153,7 @@ __device__ __forceinline__ void epilogue_store4(const Epilogue& e, int m, int n,
 }
 
 // ---- the kernel ---------------------------------------------------------------
-template <int WTM, int WTN, bool TA, bool TB>
+template <int WTM, int WTN, bool TA, bool TB, int EPI>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(int K, const bf16* __restrict__ A, int lda,
                                                         const bf16* __restrict__ B, int ldb, Epilogue ep,
                                                         int tiles_m, int tiles_n) {
@@ -236,7 +241,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int K, const bf16* __res
       int nb = n0 + wn * (WTN * 32) + j * 32 + 4 * (lane >> 5);
 #pragma unroll
       for (int q = 0; q < 4; ++q)
-        epilogue_store4(ep, m, nb + 8 * q, acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
+        epilogue_store4<EPI>(ep, m, nb + 8 * q, acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
                         acc[i][j][4 * q + 3]);
     }
   }
@@ -260,12 +265,12 @@ bool gemm_mfma_supported(int trans_a, int trans_b, int M, int N, int K, int lda,
   return wtm != 0 && K > 0 && K % kBK == 0 && lda % 8 == 0 && ldb % 8 == 0 && ldc % 4 == 0;
 }
 
-template <int WTM, int WTN, bool TA, bool TB>
-static bool launch_mfma(int M, int N, int K, const bf16* A, int lda, const bf16* B, int ldb, const Epilogue& ep,
-                        hipStream_t stream) {
+template <int WTM, int WTN, bool TA, bool TB, int EPI>
+static bool launch_mfma_epi(int M, int N, int K, const bf16* A, int lda, const bf16* B, int ldb, const Epilogue& ep,
+                            hipStream_t stream) {
   constexpr int BM = 64 * WTM, BN = 64 * WTN;
   constexpr int smem = 2 * (BM + BN) * 128;
-  auto kern = gemm_mfma_kernel<WTM, WTN, TA, TB>;
+  auto kern = gemm_mfma_kernel<WTM, WTN, TA, TB, EPI>;
   static bool configured = false;  // per instantiation
   if (!configured) {
     PO_HIP_OK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -275,6 +280,15 @@ static bool launch_mfma(int M, int N, int K, const bf16* A, int lda, const bf16*
   int tiles_m = M / BM, tiles_n = N / BN;
   kern<<<tiles_m * tiles_n, 256, smem, stream>>>(K, A, lda, B, ldb, ep, tiles_m, tiles_n);
   return launch_ok("gemm_mfma_kernel");
+}
+
+template <int WTM, int WTN, bool TA, bool TB>
+static bool launch_mfma(int M, int N, int K, const bf16* A, int lda, const bf16* B, int ldb, const Epilogue& ep,
+                        hipStream_t stream) {
+  if (ep.acc_f32) return launch_mfma_epi<WTM, WTN, TA, TB, kEpiAccumulate>(M, N, K, A, lda, B, ldb, ep, stream);
+  if (ep.gelu_u) return launch_mfma_epi<WTM, WTN, TA, TB, kEpiGeluBackward>(M, N, K, A, lda, B, ldb, ep, stream);
+  if (ep.gelu_out) return launch_mfma_epi<WTM, WTN, TA, TB, kEpiStoreGelu>(M, N, K, A, lda, B, ldb, ep, stream);
+  return launch_mfma_epi<WTM, WTN, TA, TB, kEpiStore>(M, N, K, A, lda, B, ldb, ep, stream);
 }
 
 template <int WTM, int WTN>

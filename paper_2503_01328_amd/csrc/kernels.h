@@ -68,6 +68,10 @@ bool attention_backward(int dtype, const void* qkv, const void* o, const float* 
     }                                                                                    \
   } while (0)
 
+// hipGetLastError is sticky per thread: an error left behind by an earlier, unrelated HIP call
+// (of this library or of the host program) must not be blamed on the next launch.
+inline void begin_launch() { (void)hipGetLastError(); }
+
 inline bool launch_ok(const char* what) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) {

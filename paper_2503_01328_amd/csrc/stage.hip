@@ -1084,23 +1084,28 @@ int po_bind_params(po_stage* st, const void* params, float* grads) {
   }
 
 int po_stage_forward(po_stage* st, int32_t mb, int32_t chunk, const void* x_in, void* y_out) {
+  begin_launch();
   PO_NEED_STAGE(st);
   return stage_forward(st, mb, chunk, x_in, y_out);
 }
 int po_stage_backward(po_stage* st, int32_t mb, int32_t chunk, const void* dy, void* dx) {
+  begin_launch();
   PO_NEED_STAGE(st);
   return stage_backward(st, mb, chunk, dy, dx);
 }
 int po_offload(po_stage* st, int32_t mb, int32_t chunk, float ratio) {
+  begin_launch();
   PO_NEED_STAGE(st);
   return stage_offload(st, mb, chunk, ratio);
 }
 int po_reload(po_stage* st, int32_t mb, int32_t chunk) {
+  begin_launch();
   PO_NEED_STAGE(st);
   return stage_reload(st, mb, chunk);
 }
 int po_run_schedule(po_stage* st, int32_t schedule, int32_t m, float ratio, const void* const* x_in,
                     void* const* y_out, const void* const* dy, void* const* dx, po_stats* stats) {
+  begin_launch();
   PO_NEED_STAGE(st);
   return stage_run_schedule(st, schedule, m, ratio, x_in, y_out, dy, dx, stats);
 }
@@ -1132,6 +1137,7 @@ static bool dtype_ok(int32_t dtype) {
 
 int po_op_layernorm_forward(int32_t dtype, const void* x, const void* gain, const void* shift, void* y, int32_t rows,
                             int32_t h, float eps, void* stream) {
+  begin_launch();
   if (!dtype_ok(dtype)) return PO_E_INVAL;
   return ok(layernorm_forward(dtype, x, gain, shift, y, rows, h, eps, (hipStream_t)stream));
 }
@@ -1141,6 +1147,7 @@ uint64_t po_op_layernorm_backward_workspace(int32_t rows, int32_t h) {
 int po_op_layernorm_backward(int32_t dtype, const void* dn, const void* x, const void* gain, const void* dres,
                              void* dx, float* dgain, float* dshift, float* partials, int32_t rows, int32_t h,
                              float eps, void* stream) {
+  begin_launch();
   if (!dtype_ok(dtype)) return PO_E_INVAL;
   return ok(layernorm_backward(dtype, dn, x, gain, dres, dx, dgain, dshift, partials, rows, h, eps,
                                (hipStream_t)stream));
@@ -1148,6 +1155,7 @@ int po_op_layernorm_backward(int32_t dtype, const void* dn, const void* x, const
 int po_op_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32_t N, int32_t K, const void* A,
                int32_t lda, const void* B, int32_t ldb, const void* bias, const void* residual, void* out,
                void* gelu_out, const void* gelu_u, float* acc_f32, int32_t force_generic, void* stream) {
+  begin_launch();
   if (!dtype_ok(dtype)) return PO_E_INVAL;
   Epilogue e;
   e.bias = bias;
@@ -1162,12 +1170,14 @@ int po_op_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32
 }
 int po_op_attention_forward(int32_t dtype, const void* qkv, void* o, float* lse, int32_t s, int32_t h,
                             int32_t n_heads, int32_t force_generic, void* stream) {
+  begin_launch();
   if (!dtype_ok(dtype)) return PO_E_INVAL;
   return ok(attention_forward(dtype, qkv, o, lse, s, h, n_heads, force_generic != 0, (hipStream_t)stream));
 }
 int po_op_attention_backward(int32_t dtype, const void* qkv, const void* o, const float* lse, const void* d_o,
                              void* dqkv, float* delta, int32_t s, int32_t h, int32_t n_heads, int32_t force_generic,
                              void* stream) {
+  begin_launch();
   if (!dtype_ok(dtype)) return PO_E_INVAL;
   return ok(attention_backward(dtype, qkv, o, lse, d_o, dqkv, delta, s, h, n_heads, force_generic != 0,
                                (hipStream_t)stream));
@@ -1175,13 +1185,16 @@ int po_op_attention_backward(int32_t dtype, const void* qkv, const void* o, cons
 uint64_t po_op_colsum_workspace(int32_t rows, int32_t n) { return rows > 0 && n > 0 ? colsum_workspace(rows, n) : 0; }
 int po_op_colsum_accumulate(int32_t dtype, const void* x, float* acc, float* workspace, int32_t rows, int32_t n,
                             void* stream) {
+  begin_launch();
   if (!dtype_ok(dtype)) return PO_E_INVAL;
   return ok(colsum_accumulate(dtype, x, acc, workspace, rows, n, (hipStream_t)stream));
 }
 int po_op_pack(const void* const* seg_ptrs, const uint64_t* seg_bytes, int32_t n_seg, void* packed, void* stream) {
+  begin_launch();
   return ok(pack_segments(seg_ptrs, seg_bytes, n_seg, packed, (hipStream_t)stream));
 }
 int po_op_unpack(void* const* seg_ptrs, const uint64_t* seg_bytes, int32_t n_seg, const void* packed, void* stream) {
+  begin_launch();
   return ok(unpack_segments(seg_ptrs, seg_bytes, n_seg, packed, (hipStream_t)stream));
 }
 
