@@ -69,7 +69,7 @@ def main():
     ap.add_argument("--config", default="C2", help="workload: C1..C5 (default C2, the configuration the metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-streams", type=int, default=2)
-    ap.add_argument("--prefetch", type=int, default=1)
+    ap.add_argument("--prefetch", type=int, default=2)
     ap.add_argument("--staged", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:

@@ -113,7 +113,7 @@ typedef struct po_stats {
   int32_t n_compute_passes, n_offloads, n_reloads, n_gemm_launches;
 } po_stats;
 
-/* Fills *cfg with defaults (1 chunk, fp32, d = 1, prefetch 1, two copy streams, eps 1e-5). HOST. */
+/* Fills *cfg with defaults (1 chunk, fp32, d = 1, prefetch 2, two copy streams, eps 1e-5). HOST. */
 void po_config_default(po_config* cfg);
 
 /* Thread-local text of the last error. */

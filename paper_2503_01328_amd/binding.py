@@ -162,7 +162,7 @@ def po_saved_bytes_per_layer(cfg) -> int:
     return b.value
 
 
-def po_schedule_ops(schedule, d, rank, v, m, ratio, policy=0, prefetch=1):
+def po_schedule_ops(schedule, d, rank, v, m, ratio, policy=0, prefetch=2):
     n = C.c_int32(0)
     _check(lib.po_schedule_ops(schedule, d, rank, v, m, ratio, policy, prefetch, None, C.byref(n)))
     arr = (po_op * n.value)()

@@ -974,7 +974,7 @@ void po_config_default(po_config* c) {
   c->seq = 1;
   c->dtype = PO_F32;
   c->pipeline_degree = 1;
-  c->prefetch_passes = 1;
+  c->prefetch_passes = 2;
   c->copy_streams = 2;
   c->ln_eps = 1e-5f;
 }

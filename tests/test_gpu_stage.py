@@ -118,7 +118,8 @@ def test_interleaved_schedule_chunks_and_residency(gpu_device):
             stats = r.run(po.PO_SCHED_1F1B_INTERLEAVED, ratio)
             results[(ratio, policy)] = _snapshot(r)
             ops = sch.with_offload(sch.interleaved_one_f_one_b(2, 0, 2, 4),
-                                   sch.selected_units(4, 2, ratio, "longest-lifespan" if policy else "alternate-mb"), 1)
+                                   sch.selected_units(4, 2, ratio, "longest-lifespan" if policy else "alternate-mb"),
+                                   r.cfg.prefetch_passes)
             model = sch.simulate(ops)
             assert stats["peak_in_flight_units"] == model["peak_in_flight"]
             assert stats["peak_resident_units"] == model["peak_resident"]
@@ -195,7 +196,7 @@ def test_peak_slab_bytes_follow_the_schedule_model(gpu_device):
             layer_bytes = po.po_saved_bytes_per_layer(r.cfg)
             r.make_inputs()
             stats = r.run(po.PO_SCHED_1F1B, ratio)
-            ops = sch.with_offload(sch.one_f_one_b(6, 0, 12), sch.selected_units(12, 1, ratio), 1)
+            ops = sch.with_offload(sch.one_f_one_b(6, 0, 12), sch.selected_units(12, 1, ratio), r.cfg.prefetch_passes)
             model = sch.simulate(ops)
             assert stats["peak_in_flight_units"] == model["peak_in_flight"] == 6
             assert stats["peak_resident_units"] == model["peak_resident"]
