@@ -200,6 +200,19 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int K, const bf16* __res
   sb.store(smem + BM * 128, tid);
   __syncthreads();
 
+  // Fragments of k-step 0 of the first slice.
+  bf16x8 fa[2][WTM], fb[2][WTN];
+  auto load_fragments = [&](const char* stage, int kk, int buf) {
+    int chunk = 2 * kk + (lane >> 5);
+    const char* la = stage;
+    const char* lb = stage + BM * 128;
+#pragma unroll
+    for (int i = 0; i < WTM; ++i) fa[buf][i] = read_fragment(la, wm * (WTM * 32) + i * 32 + (lane & 31), chunk);
+#pragma unroll
+    for (int j = 0; j < WTN; ++j) fb[buf][j] = read_fragment(lb, wn * (WTN * 32) + j * 32 + (lane & 31), chunk);
+  };
+  load_fragments(smem, 0, 0);
+
   for (int kt = 0; kt < nk; ++kt) {
     char* cur = smem + (kt & 1) * STAGE;
     char* nxt = smem + ((kt + 1) & 1) * STAGE;
@@ -208,27 +221,23 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int K, const bf16* __res
       sa.load(a_base, lda, (kt + 1) * kBK, tid);
       sb.load(b_base, ldb, (kt + 1) * kBK, tid);
     }
-    const char* la = cur;
-    const char* lb = cur + BM * 128;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      int chunk = 2 * kk + (lane >> 5);
-      bf16x8 fa[WTM], fb[WTN];
-#pragma unroll
-      for (int i = 0; i < WTM; ++i) fa[i] = read_fragment(la, wm * (WTM * 32) + i * 32 + (lane & 31), chunk);
-#pragma unroll
-      for (int j = 0; j < WTN; ++j) fb[j] = read_fragment(lb, wn * (WTN * 32) + j * 32 + (lane & 31), chunk);
+      // fragments of the next k-step are fetched while the matrix cores work on this one
+      if (kk < 3) load_fragments(cur, kk + 1, (kk + 1) & 1);
+      // the next slice goes to the other LDS buffer under the last k-step's MFMAs
+      if (kk == 3 && more) {
+        sa.store(nxt, tid);
+        sb.store(nxt + BM * 128, tid);
+      }
 #pragma unroll
       for (int i = 0; i < WTM; ++i)
 #pragma unroll
         for (int j = 0; j < WTN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
-    }
-    if (more) {
-      sa.store(nxt, tid);
-      sb.store(nxt + BM * 128, tid);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][j], fa[kk & 1][i], acc[i][j], 0, 0, 0);
     }
     __syncthreads();
+    if (more) load_fragments(nxt, 0, 0);
   }
 
   // Accumulator layout: acc[i][j][4q + r] = C[m][n] with m = ... + (lane & 31),

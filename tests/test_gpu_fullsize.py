@@ -1,0 +1,138 @@
+"""Parity at the benchmark's full sizes, in the launch configurations bench.py times.
+
+The oracle cannot run whole C3 / C5 jobs in test time, so outputs are sampled: GEMM entries are
+checked one by one against fp64 dot products, attention is checked on whole heads (every row and
+column of the sampled head, fp64 oracle on that head's slices), and one C2-shaped layer is checked
+in full through the stage.  Tolerance as everywhere in bf16: max |got - ref| / max |ref| < 2e-2."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import stage_oracle as so
+from paper_2503_01328_amd import binding as po
+from paper_2503_01328_amd import inputs as syn
+from paper_2503_01328_amd.harness import StageRunner, max_rel_err
+
+pytestmark = pytest.mark.gpu
+BF = torch.bfloat16
+
+
+def _bf16_normal(rng, shape, scale=1.0):
+    return syn.round_to_bf16(rng.standard_normal(shape, dtype=np.float32) * np.float32(scale))
+
+
+def _dev(a, dev):
+    return torch.from_numpy(a).to(dev).to(BF).contiguous()
+
+
+def _np(t):
+    return t.to(torch.float32).cpu().numpy()
+
+
+# (name, trans_a, trans_b, M, N, K, epilogue): the stage's GEMM shapes at C2 / C3 / C5
+FULL_GEMMS = [
+    ("C2 qkv forward", 0, 0, 2048, 6144, 2048, "bias"),
+    ("C2 fc2 wgrad", 1, 0, 8192, 2048, 2048, "accumulate"),
+    ("C3 fc1 forward", 0, 0, 4096, 16384, 4096, "bias_gelu"),
+    ("C3 fc2 dgrad", 0, 1, 4096, 16384, 4096, "gelu_backward"),
+    ("C3 fc1 wgrad", 1, 0, 4096, 16384, 4096, "accumulate"),
+    ("C3 out-proj forward", 0, 0, 4096, 4096, 4096, "bias_residual"),
+    ("C5 qkv forward", 0, 0, 16384, 15360, 5120, "bias"),
+    ("C5 fc1 dgrad", 0, 1, 16384, 5120, 20480, "plain"),
+    ("C5 fc2 wgrad", 1, 0, 20480, 5120, 16384, "accumulate"),
+]
+
+
+@pytest.mark.parametrize("name,ta,tb,M,N,K,epilogue", FULL_GEMMS, ids=[g[0] for g in FULL_GEMMS])
+def test_gemm_full_size_sampled_entries(gpu_device, name, ta, tb, M, N, K, epilogue):
+    rng = np.random.default_rng(M + 3 * N + 7 * K)
+    A = _bf16_normal(rng, (K, M) if ta else (M, K))
+    B = _bf16_normal(rng, (N, K) if tb else (K, N), 0.05)
+    Ad, Bd = _dev(A, gpu_device), _dev(B, gpu_device)
+    n_samples = 384
+    ms = np.concatenate([rng.integers(0, M, n_samples - 4), [0, M - 1, 0, M - 1]])
+    ns = np.concatenate([rng.integers(0, N, n_samples - 4), [0, N - 1, N - 1, 0]])
+    a_rows = (A[:, ms].T if ta else A[ms, :]).astype(np.float64)
+    b_cols = (B[ns, :] if tb else B[:, ns].T).astype(np.float64)
+    ref = np.einsum("ik,ik->i", a_rows, b_cols)
+    kw = {}
+    out = torch.empty(M, N, dtype=BF, device=gpu_device)
+    if epilogue == "accumulate":
+        acc = torch.zeros(M, N, dtype=torch.float32, device=gpu_device)
+        po.po_op_gemm(po.PO_BF16, ta, tb, M, N, K, Ad, A.shape[1], Bd, B.shape[1], acc_f32=acc)
+        got = acc[torch.from_numpy(ms).to(gpu_device), torch.from_numpy(ns).to(gpu_device)].cpu().numpy()
+    else:
+        if epilogue in ("bias", "bias_gelu", "bias_residual"):
+            bias = _bf16_normal(rng, (N,))
+            kw["bias"] = _dev(bias, gpu_device)
+            ref = ref + bias[ns]
+        if epilogue == "bias_residual":
+            res = _bf16_normal(rng, (M, N))
+            kw["residual"] = _dev(res, gpu_device)
+            ref = ref + res[ms, ns]
+        if epilogue == "bias_gelu":
+            kw["gelu_out"] = torch.empty(M, N, dtype=BF, device=gpu_device)
+        if epilogue == "gelu_backward":
+            u = _bf16_normal(rng, (M, N), 1.5)
+            kw["gelu_u"] = _dev(u, gpu_device)
+            kw["gelu_out"] = torch.empty(M, N, dtype=BF, device=gpu_device)
+            ref = ref * so.gelu_derivative(u[ms, ns].astype(np.float64))
+        po.po_op_gemm(po.PO_BF16, ta, tb, M, N, K, Ad, A.shape[1], Bd, B.shape[1], out=out, **kw)
+        mi, ni = torch.from_numpy(ms).to(gpu_device), torch.from_numpy(ns).to(gpu_device)
+        got = _np(out[mi, ni])
+        if epilogue == "bias_gelu":
+            assert max_rel_err(_np(kw["gelu_out"][mi, ni]), so.gelu(got.astype(np.float64))) < 2e-2
+        if epilogue == "gelu_backward":
+            assert max_rel_err(_np(kw["gelu_out"][mi, ni]), so.gelu(u[ms, ns].astype(np.float64))) < 2e-2
+    assert max_rel_err(got, ref) < 2e-2, name
+
+
+@pytest.mark.parametrize("s,h,a,heads", [(2048, 2048, 16, (0, 15)), (4096, 4096, 32, (0, 17)), (16384, 5120, 40, (39,))],
+                         ids=["C2", "C3", "C5"])
+def test_attention_full_size_sampled_heads(gpu_device, s, h, a, heads):
+    rng = np.random.default_rng(s + h)
+    dh = h // a
+    qkv = _bf16_normal(rng, (s, 3 * h))
+    d_o = _bf16_normal(rng, (s, h))
+    qd, dod = _dev(qkv, gpu_device), _dev(d_o, gpu_device)
+    o = torch.empty(s, h, dtype=BF, device=gpu_device)
+    lse = torch.empty(a, s, dtype=torch.float32, device=gpu_device)
+    dqkv = torch.empty(s, 3 * h, dtype=BF, device=gpu_device)
+    delta = torch.empty(a, s, dtype=torch.float32, device=gpu_device)
+    po.po_op_attention_forward(po.PO_BF16, qd, o, lse, s, h, a)
+    po.po_op_attention_backward(po.PO_BF16, qd, o, lse, dod, dqkv, delta, s, h, a)
+    torch.cuda.synchronize()
+    for t in heads:
+        c = slice(t * dh, (t + 1) * dh)
+        q = qkv[:, c].astype(np.float64)
+        k = qkv[:, h + t * dh: h + (t + 1) * dh].astype(np.float64)
+        v = qkv[:, 2 * h + t * dh: 2 * h + (t + 1) * dh].astype(np.float64)
+        ro, probs = so.attention_forward(q, k, v, 1)
+        assert max_rel_err(_np(o[:, c]), ro) < 2e-2
+        rdq, rdk, rdv = so.attention_backward(d_o[:, c].astype(np.float64), q, k, v, probs, 1)
+        del probs
+        got = _np(dqkv[:, c]), _np(dqkv[:, h + t * dh: h + (t + 1) * dh]), _np(dqkv[:, 2 * h + t * dh: 2 * h + (t + 1) * dh])
+        assert max_rel_err(got[0], rdq) < 3e-2
+        assert max_rel_err(got[1], rdk) < 3e-2
+        assert max_rel_err(got[2], rdv) < 3e-2
+
+
+def test_one_c2_shaped_layer_through_the_stage(gpu_device):
+    """Every kernel of the stage at C2's shapes (h 2048, 16 heads, FFN 8192, s 2048), two microbatches of one
+    layer under 1F1B with full offload; all outputs and gradients against the fp64 oracle."""
+    shape = dataclasses.replace(syn.CONFIGS["C2"], n_layers=1, n_microbatches=2)
+    with StageRunner(shape, seed=77) as r:
+        r.make_inputs()
+        stats = r.run(po.PO_SCHED_1F1B, 1.0)
+        y, dx, g = r.results()
+        assert stats["n_offloads"] == 2
+    x = {(j, 0): syn.unit_input(shape, j, 0, 77) for j in range(2)}
+    dy = {(j, 0): syn.unit_upstream_grad(shape, j, 0, 77) for j in range(2)}
+    ry, rdx, rg = so.run_stage(r.params_np, 1, 1, shape.n_heads, x, dy)
+    for u in ry:
+        assert max_rel_err(y[u], ry[u]) < 2e-2
+        assert max_rel_err(dx[u], rdx[u]) < 2e-2
+    for k, a in rg["layers"][0].items():
+        assert max_rel_err(g["layers"][0][k], a) < 2e-2, k
