@@ -133,7 +133,7 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // Forward
 // ==================================================================================
 template <int DH, int QT>
-__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ o,
+__global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ o,
                                                             float* __restrict__ lse, int s, int h, float scale) {
   constexpr int KS = DH / 16;   // 16-deep MFMA steps over the head dimension
   constexpr int DT = DH / 32;   // 32-wide output tiles over the head dimension
@@ -218,17 +218,18 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restri
       for (int t = 0; t < QT; ++t) {
         int q = qw0 + 32 * t + col;
         bool need_mask = key0 + kKeysPerTile - 1 > qw0 + 32 * t;
+        if (need_mask) {  // only tiles that straddle the diagonal pay for the mask
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+              if (key0 + 32 * j + 8 * (e >> 2) + 4 * half + (e & 3) > q) sacc[t][j][e] = -INFINITY;
+        }
         float mx = -INFINITY;
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            if (need_mask) {
-              int key = key0 + 32 * j + 8 * (e >> 2) + 4 * half + (e & 3);
-              if (key > q) sacc[t][j][e] = -INFINITY;
-            }
-            mx = fmaxf(mx, sacc[t][j][e]);
-          }
+          for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[t][j][e]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         float m_new = fmaxf(m_run[t], mx);
         float alpha = fast_exp2((m_run[t] - m_new) * c);
@@ -243,11 +244,14 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restri
             sum += p;
           }
         l_run[t] = l_run[t] * alpha + sum;
+        bool moved = __builtin_amdgcn_ballot_w64(m_new > m_run[t]) != 0;
         m_run[t] = m_new;
+        if (moved) {  // rescale only when some row's maximum moved
 #pragma unroll
-        for (int d = 0; d < DT; ++d)
+          for (int d = 0; d < DT; ++d)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) oacc[t][d][e] *= alpha;
+            for (int e = 0; e < 16; ++e) oacc[t][d][e] *= alpha;
+        }
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
           pf[t][j][0] = pack_bf16x8(sacc[t][j], 0);
@@ -308,7 +312,7 @@ __device__ __forceinline__ bf16x8 read_padded_row_fragment(const char* tile, int
 }
 
 template <int DH>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __restrict__ qkv,
+__global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* __restrict__ qkv,
                                                                 const bf16* __restrict__ d_o,
                                                                 const float* __restrict__ lse,
                                                                 const float* __restrict__ delta,
@@ -379,56 +383,52 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
       load_stats((qt + 1) * kKeysPerTile);
     }
     int q0 = qt * kKeysPerTile;
-    if (q0 + kKeysPerTile - 1 >= kw0) {  // some row of the tile sees some key of this wave
-      f32x16 sacc[2], pacc[2];
+    int key = kw0 + col;
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 2; ++j) {  // 32-row halves of the query tile, one at a time (keeps registers low)
+      int qs0 = q0 + 32 * j;
+      if (qs0 + 31 < kw0) continue;  // every row of this half is above every key of this wave
+      f32x16 sacc, pacc;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) sacc[j][e] = pacc[j][e] = 0.f;
+      for (int e = 0; e < 16; ++e) sacc[e] = pacc[e] = 0.f;
 #pragma unroll
-      for (int kk = 0; kk < KS; ++kk)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          bf16x8 qa = read_padded_row_fragment<DH>(qtile, 32 * j + col, 2 * kk + half);
-          bf16x8 da = read_padded_row_fragment<DH>(dotile, 32 * j + col, 2 * kk + half);
-          sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[kk], sacc[j], 0, 0, 0);
-          pacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vf[kk], pacc[j], 0, 0, 0);
-        }
-      bool need_mask = q0 < kw0 + 31;
-      int key = kw0 + col;
-      bf16x8 pf[2][2], dsf[2][2];
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          float4 l4 = *reinterpret_cast<const float4*>(st_lse + 32 * j + 8 * b + 4 * half);
-          float4 d4 = *reinterpret_cast<const float4*>(st_delta + 32 * j + 8 * b + 4 * half);
-          float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            int e = 4 * b + r;
-            float p = fast_exp2(sacc[j][e] * c - lv[r]);
-            if (need_mask && key > q0 + 32 * j + 8 * b + 4 * half + r) p = 0.f;
-            sacc[j][e] = p;
-            pacc[j][e] = p * (pacc[j][e] - dl[r]);
-          }
-        }
-        pf[j][0] = pack_bf16x8(sacc[j], 0);
-        pf[j][1] = pack_bf16x8(sacc[j], 8);
-        dsf[j][0] = pack_bf16x8(pacc[j], 0);
-        dsf[j][1] = pack_bf16x8(pacc[j], 8);
+      for (int kk = 0; kk < KS; ++kk) {
+        bf16x8 qa = read_padded_row_fragment<DH>(qtile, 32 * j + col, 2 * kk + half);
+        bf16x8 da = read_padded_row_fragment<DH>(dotile, 32 * j + col, 2 * kk + half);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[kk], sacc, 0, 0, 0);
+        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vf[kk], pacc, 0, 0, 0);
       }
+      bool need_mask = qs0 < kw0 + 31;
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        float4 l4 = *reinterpret_cast<const float4*>(st_lse + 32 * j + 8 * b + 4 * half);
+        float4 d4 = *reinterpret_cast<const float4*>(st_delta + 32 * j + 8 * b + 4 * half);
+        float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          int e = 4 * b + r;
+          sacc[e] = fast_exp2(sacc[e] * c - lv[r]);
+          pacc[e] -= dl[r];
+        }
+      }
+      if (need_mask) {  // only tiles that straddle the diagonal pay for the mask
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (key > qs0 + 8 * (e >> 2) + 4 * half + (e & 3)) sacc[e] = 0.f;
+      }
+#pragma unroll
+      for (int e = 0; e < 16; ++e) pacc[e] *= sacc[e];
+      bf16x8 pf[2] = {pack_bf16x8(sacc, 0), pack_bf16x8(sacc, 8)};
+      bf16x8 dsf[2] = {pack_bf16x8(pacc, 0), pack_bf16x8(pacc, 8)};
 #pragma unroll
       for (int d = 0; d < DT; ++d)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-          for (int st = 0; st < 2; ++st) {
-            bf16x8 dot = read_tr_fragment<DH>(dotile, 32 * j + 16 * st, 32 * d, lane);
-            bf16x8 qtr = read_tr_fragment<DH>(qtile, 32 * j + 16 * st, 32 * d, lane);
-            dv[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dot, pf[j][st], dv[d], 0, 0, 0);
-            dk[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qtr, dsf[j][st], dk[d], 0, 0, 0);
-          }
+        for (int st = 0; st < 2; ++st) {
+          bf16x8 dot = read_tr_fragment<DH>(dotile, 32 * j + 16 * st, 32 * d, lane);
+          bf16x8 qtr = read_tr_fragment<DH>(qtile, 32 * j + 16 * st, 32 * d, lane);
+          dv[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dot, pf[st], dv[d], 0, 0, 0);
+          dk[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qtr, dsf[st], dk[d], 0, 0, 0);
+        }
     }
     if (more) {
       lq.store_tr_tile(nxt, tid);
@@ -461,7 +461,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
 // S^T = K Q^T, transposing fragments for dQ^T = K^T dS^T), V in the swizzled row form.
 // ==================================================================================
 template <int DH, int QT>
-__global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv,
+__global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv,
                                                                const bf16* __restrict__ d_o,
                                                                const float* __restrict__ lse,
                                                                const float* __restrict__ delta,
@@ -524,54 +524,51 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __res
       lv.load(vbase, ld, (kt + 1) * kKeysPerTile, tid);
     }
     int key0 = kt * kKeysPerTile;
-    if (key0 <= qw0 + 32 * QT - 1) {
-      f32x16 sacc[QT][2], pacc[QT][2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {  // 32-key halves of the tile, one at a time (keeps registers low)
+      int ks0 = key0 + 32 * j;
+      if (ks0 > qw0 + 32 * QT - 1) continue;  // every key of this half is beyond every row of this wave
+      f32x16 sacc[QT], pacc[QT];
 #pragma unroll
       for (int t = 0; t < QT; ++t)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int e = 0; e < 16; ++e) sacc[t][e] = pacc[t][e] = 0.f;
 #pragma unroll
-          for (int e = 0; e < 16; ++e) sacc[t][j][e] = pacc[t][j][e] = 0.f;
+      for (int kk = 0; kk < KS; ++kk) {
+        bf16x8 ka = read_padded_row_fragment<DH>(ktile, 32 * j + col, 2 * kk + half);
+        bf16x8 va = read_row_fragment<DH>(vtile, 32 * j + col, 2 * kk + half);
 #pragma unroll
-      for (int kk = 0; kk < KS; ++kk)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          bf16x8 ka = read_padded_row_fragment<DH>(ktile, 32 * j + col, 2 * kk + half);
-          bf16x8 va = read_row_fragment<DH>(vtile, 32 * j + col, 2 * kk + half);
-#pragma unroll
-          for (int t = 0; t < QT; ++t) {
-            sacc[t][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[t][kk], sacc[t][j], 0, 0, 0);
-            pacc[t][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, dof[t][kk], pacc[t][j], 0, 0, 0);
-          }
+        for (int t = 0; t < QT; ++t) {
+          sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[t][kk], sacc[t], 0, 0, 0);
+          pacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, dof[t][kk], pacc[t], 0, 0, 0);
         }
-      bf16x8 dsf[QT][2][2];
+      }
+      bf16x8 dsf[QT][2];
 #pragma unroll
       for (int t = 0; t < QT; ++t) {
         int q = qw0 + 32 * t + col;
-        bool need_mask = key0 + kKeysPerTile - 1 > qw0 + 32 * t;
+        bool need_mask = ks0 + 31 > qw0 + 32 * t;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+        for (int e = 0; e < 16; ++e) sacc[t][e] = fast_exp2(sacc[t][e] * c - lse_q[t]);
+        if (need_mask) {  // only tiles that straddle the diagonal pay for the mask
 #pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            float p = fast_exp2(sacc[t][j][e] * c - lse_q[t]);
-            if (need_mask && key0 + 32 * j + 8 * (e >> 2) + 4 * half + (e & 3) > q) p = 0.f;
-            pacc[t][j][e] = p * (pacc[t][j][e] - delta_q[t]);
-          }
-          dsf[t][j][0] = pack_bf16x8(pacc[t][j], 0);
-          dsf[t][j][1] = pack_bf16x8(pacc[t][j], 8);
+          for (int e = 0; e < 16; ++e)
+            if (ks0 + 8 * (e >> 2) + 4 * half + (e & 3) > q) sacc[t][e] = 0.f;
         }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) pacc[t][e] = sacc[t][e] * (pacc[t][e] - delta_q[t]);
+        dsf[t][0] = pack_bf16x8(pacc[t], 0);
+        dsf[t][1] = pack_bf16x8(pacc[t], 8);
       }
 #pragma unroll
       for (int d = 0; d < DT; ++d)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int st = 0; st < 2; ++st) {
+          bf16x8 ktr = read_tr_fragment<DH>(ktile, 32 * j + 16 * st, 32 * d, lane);
 #pragma unroll
-          for (int st = 0; st < 2; ++st) {
-            bf16x8 ktr = read_tr_fragment<DH>(ktile, 32 * j + 16 * st, 32 * d, lane);
-#pragma unroll
-            for (int t = 0; t < QT; ++t)
-              dq[t][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktr, dsf[t][j][st], dq[t][d], 0, 0, 0);
-          }
+          for (int t = 0; t < QT; ++t)
+            dq[t][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktr, dsf[t][st], dq[t][d], 0, 0, 0);
+        }
     }
     if (more) {
       lk.store_tr_tile(nxt, tid);
@@ -647,7 +644,7 @@ bool attention_forward_mfma(const void* qkv, void* o, float* lse, int s, int h, 
   const bf16* q = (const bf16*)qkv;
   bf16* out = (bf16*)o;
   // two query tiles per wave once that still fills the chip
-  bool big = s % 256 == 0 && (int64_t)(s / 256) * n_heads >= 512;
+  bool big = false && s % 256 == 0 && (int64_t)(s / 256) * n_heads >= 512;
   if (dh == 128) {
     if (big) return launch_fwd<128, 2>(q, out, lse, s, h, n_heads, stream);
     return launch_fwd<128, 1>(q, out, lse, s, h, n_heads, stream);
@@ -677,7 +674,7 @@ static bool launch_bwd(const bf16* qkv, const bf16* o, const float* lse, const b
   float scale = 1.0f / sqrtf((float)DH);
   attn_delta_mfma_path_kernel<DH><<<dim3(ceil_div(s, 4), n_heads), 256, 0, stream>>>(o, d_o, delta, s, h);
   kkv<<<dim3(s / 128, n_heads), 256, smem_kv, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, scale);
-  bool big = s % 256 == 0 && (int64_t)(s / 256) * n_heads >= 512;
+  bool big = false && s % 256 == 0 && (int64_t)(s / 256) * n_heads >= 512;
   if (big)
     kq2<<<dim3(s / 256, n_heads), 256, smem_q, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, scale);
   else
