@@ -24,6 +24,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0
+# HBM bytes per GEMM launch (average over all bf16 GEMM launches of a step) from the rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE passes summarised in profiles/hbm_traffic_c2.md, scaled by the copy-kernel calibration given there.
+# Counters cannot be read inside this script, so the figure is carried here per workload; None = not collected.
+MEASURED_GEMM_TRAFFIC_BYTES = {"C2": 182041897}
 
 
 def model_flops_per_run(shape):
@@ -147,7 +151,7 @@ def main():
         "k_eq1_measured_serial": k_meas, "k_eq1_measured_duplex": (k_meas / 2 if k_meas else None),
         "roofline": {"bound": "mfma", "achieved": gemm["gemm_tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": (gemm["gemm_tflops"] / PEAK_BF16_TFLOPS) if gemm["gemm_tflops"] else None,
-                     "traffic": None,
+                     "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(args.config),
                      "kernel": "gemm_mfma_kernel (all bf16 GEMM launches of a step at ratio 0: 2MNK flops / "
                                "event-timed duration)",
                      "launches_per_step": gemm["n_gemm_launches"], "busy_ms_per_step": gemm["gemm_busy_ms"]},
