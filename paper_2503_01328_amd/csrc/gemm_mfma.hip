@@ -2,24 +2,30 @@
 //
 // One 256-thread block (4 waves, 2 x 2) owns a (64*WTM) x (64*WTN) tile of C; a
 // wave owns WTM x WTN MFMA tiles of 32 x 32, i.e. up to 128 x 128 with 256 fp32
-// accumulators per lane.  K is walked in slices of 64.  A slice of an operand is
-// held in LDS as [rows][64] bf16 (128 bytes per row, eight 16-byte chunks whose
-// position is XOR-swizzled with the row index so that fragment reads and slice
-// writes spread over the banks).  Slices are double-buffered: while the matrix
-// cores work on slice t from LDS, the global loads of slice t+1 are in flight
-// into registers and are written to the other LDS buffer before one barrier.
+// accumulators per lane.  K is walked in slices of 64, double-buffered in LDS.
 //
-// Operand forms (all three are needed by the stage):
-//   forward   C = A[M,K]   B[K,N]      (B is n-contiguous -> transposed on the way to LDS)
-//   dgrad     C = A[M,K]   B^T, B[N,K] (both k-contiguous -> straight copies)
-//   wgrad     C = A^T B, A[K,M] B[K,N] (both transposed on the way to LDS)
-// A transposed operand is read from HBM in 8 x 8 blocks along its contiguous
-// dimension (still 16-byte coalesced loads) and transposed in registers, so that
-// LDS always holds k-contiguous rows and every MFMA fragment is one ds_read_b128.
+// Operand slices travel HBM -> LDS directly (global_load_lds_dwordx4: lane L of
+// a wave deposits its 16 bytes at LDS base + 16 L), so no registers and no
+// ds_write instructions are spent on staging.  Because the LDS side of such a
+// load is fixed, the bank-conflict swizzle is applied on the global side: each
+// lane fetches the 16-byte chunk that belongs at its LDS position.
 //
-// The MFMA is issued with the B fragment in the first operand slot: a lane then
-// holds four consecutive n of one row m per accumulator quad, which gives 8-byte
-// (bf16) or 16-byte (fp32) vector accesses in the epilogue.
+// Two LDS layouts, chosen by how the operand lies in memory:
+//   k-contiguous operand (A of forward/dgrad, B of dgrad): "row tile"
+//     [rows][64] bf16, 128 bytes per row, 16-byte chunk c stored at c ^ (row & 7);
+//     an MFMA fragment is one ds_read_b128.
+//   operand whose contiguous index is m or n (B of forward, both of wgrad):
+//     "k-major tile" [64][rows] bf16, 32-byte unit u of a row stored at
+//     u ^ (k & 7); an MFMA fragment is two transposing reads (ds_read_b64_tr_b16),
+//     arranged so that a lane receives k = 16 kk + 8 half + 0..7 exactly as the
+//     ds_read_b128 path does, which lets the two kinds be mixed in one MFMA.
+// Nothing is transposed in registers.
+//
+// The MFMA is issued with the B fragment in the first operand slot, so a lane holds
+// four consecutive n of one row m per accumulator quad.  The epilogue moves each
+// 32-row strip of a wave through LDS and then touches global memory row-wise, 16
+// bytes per lane, whole 128-byte lines per row: bias, residual, GeLU, GeLU-backward
+// and the fp32 accumulate all happen on that coalesced side.
 //
 // Workgroup ids are remapped so that the blocks that land on one XCD (ids equal
 // modulo 8) work on neighbouring tiles and share operand slices in that XCD's L2.
@@ -29,136 +35,152 @@ namespace po {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+#define PO_LDS3(p) ((void __attribute__((address_space(3)))*)(p))
+#define PO_GLB1(p) ((const void __attribute__((address_space(1)))*)(p))
+#define PO_LDS_S16X4(p) ((s16x4 __attribute__((address_space(3)))*)(p))
 
 constexpr int kBK = 64;
 
-__device__ __forceinline__ int swizzle_chunk(int chunk, int row) { return chunk ^ (row & 7) ^ ((row >> 3) & 7); }
-
-// ---- global -> registers -> LDS staging of one operand slice ----------------
-template <int R, bool TRANS>
-struct Stager {
-  // k-contiguous: R*8 chunks of 16 B, R/32 per thread.  Transposed: R blocks of 8x8, at most one per thread.
-  static constexpr int NREG = TRANS ? 8 : R / 32;
-  u32x4 reg[NREG];
-
-  // base points at element (row 0 of the tile, k = 0 of the matrix); k0 = slice start.
-  __device__ __forceinline__ void load(const bf16* __restrict__ base, int ld, int k0, int tid) {
-    if (TRANS) {
-      if (tid < R) {
-        int rb = tid % (R / 8), kb = tid / (R / 8);
-        const bf16* p = base + (size_t)(k0 + 8 * kb) * ld + 8 * rb;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) reg[i] = *reinterpret_cast<const u32x4*>(p + (size_t)i * ld);
-      }
-    } else {
-#pragma unroll
-      for (int u = 0; u < NREG; ++u) {
-        int e = tid + 256 * u;
-        int row = e >> 3, c = e & 7;
-        reg[u] = *reinterpret_cast<const u32x4*>(base + (size_t)row * ld + k0 + c * 8);
-      }
-    }
-  }
-
-  __device__ __forceinline__ void store(char* lds, int tid) const {
-    if (TRANS) {
-      if (tid < R) {
-        int rb = tid % (R / 8), kb = tid / (R / 8);
-        const uint32_t* in = reinterpret_cast<const uint32_t*>(reg);  // in[i*4 + d]: k = i, m = 2d, 2d+1
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          u32x4 o;
-          uint32_t* od = reinterpret_cast<uint32_t*>(&o);
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            uint32_t a = in[(2 * q) * 4 + (j >> 1)], b = in[(2 * q + 1) * 4 + (j >> 1)];
-            od[q] = (j & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
-          }
-          int row = 8 * rb + j;
-          *reinterpret_cast<u32x4*>(lds + row * 128 + (swizzle_chunk(kb, row) << 4)) = o;
-        }
-      }
-    } else {
-#pragma unroll
-      for (int u = 0; u < NREG; ++u) {
-        int e = tid + 256 * u;
-        int row = e >> 3, c = e & 7;
-        *reinterpret_cast<u32x4*>(lds + row * 128 + (swizzle_chunk(c, row) << 4)) = reg[u];
-      }
-    }
-  }
-};
-
-__device__ __forceinline__ bf16x8 read_fragment(const char* lds, int row, int chunk) {
-  return *reinterpret_cast<const bf16x8*>(lds + row * 128 + (swizzle_chunk(chunk, row) << 4));
-}
-
-// ---- epilogue on four consecutive n of one row --------------------------------
-struct __attribute__((aligned(8))) bf16x4_t {
-  bf16 v[4];
-};
-
-// Epilogue kinds are compile-time so that the fully unrolled accumulator walk stays small.
 enum EpiKind : int { kEpiStore = 0, kEpiStoreGelu = 1, kEpiGeluBackward = 2, kEpiAccumulate = 3 };
 
+// ---- HBM -> LDS, one operand slice -----------------------------------------------
+// KMAJOR == false: operand is [R rows][K], slice = R rows x 64 k, row tile in LDS.
+// KMAJOR == true : operand is [K][R], slice = 64 k x R, k-major tile in LDS.
+// `base` points at (first row of the tile, k = 0); the slice starts at k0.
+template <int R, bool KMAJOR>
+__device__ __forceinline__ void load_slice(const bf16* __restrict__ base, int ld, int k0, char* lds, int wave,
+                                           int lane) {
+  constexpr int N_INST = R * 128 / 1024;  // wave-level 1 KiB loads in the slice
+#pragma unroll
+  for (int u = 0; u < N_INST / 4; ++u) {
+    int g = u * 4 + wave;  // which 1 KiB piece of the tile this wave fills now
+    const bf16* src;
+    if (!KMAJOR) {
+      int row = 8 * g + (lane >> 3);
+      int c = (lane & 7) ^ (row & 7);
+      src = base + (size_t)row * ld + k0 + c * 8;
+    } else {
+      constexpr int ROW_BYTES = 2 * R;
+      int byte = g * 1024 + lane * 16;
+      int k = byte / ROW_BYTES;
+      int pos16 = (byte % ROW_BYTES) >> 4;
+      int unit = (pos16 >> 1) ^ (k & 7);
+      src = base + (size_t)(k0 + k) * ld + (unit * 2 + (pos16 & 1)) * 8;
+    }
+    // Issued as inline assembly on purpose: through the builtin the compiler treats every later
+    // LDS read as dependent on the load and waits for it at once, which would undo the double
+    // buffering.  The caller waits (wait_slice_loads) before the barrier that publishes the slice.
+    unsigned lds_addr = (unsigned)(size_t)PO_LDS3(lds + g * 1024);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(src)
+                 : "memory");
+  }
+}
+
+__device__ __forceinline__ void wait_slice_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// ---- LDS -> MFMA fragment: 32 rows (row0 + lane % 32), k = 16 kk + 8 (lane / 32) + 0..7 ----
+template <int R, bool KMAJOR>
+__device__ __forceinline__ bf16x8 read_fragment(const char* lds, int row0, int kk, int lane) {
+  if (!KMAJOR) {
+    int row = row0 + (lane & 31);
+    int c = (2 * kk + (lane >> 5)) ^ (row & 7);
+    return *reinterpret_cast<const bf16x8*>(lds + row * 128 + (c << 4));
+  } else {
+    // Transposing read: within a group of 16 lanes, lane i receives element (i % 4) of the
+    // addresses supplied by lanes i / 4, 4 + i / 4, 8 + i / 4, 12 + i / 4.  Lane r of the group
+    // supplies row k = kbase + r / 4, columns m0 + 4 (r % 4) .. + 3; lane i then holds
+    // k = kbase .. kbase + 3 of column m0 + i.
+    constexpr int ROW_BYTES = 2 * R;
+    int i = lane & 15, grp = lane >> 4;
+    int m = row0 + 16 * (grp & 1) + 4 * (i & 3);
+    int k = 16 * kk + 8 * (grp >> 1) + (i >> 2);
+    int unit = m >> 4;
+    int inner = (m & 15) * 2;
+    const char* p0 = lds + k * ROW_BYTES + ((unit ^ (k & 7)) << 5) + inner;
+    const char* p1 = lds + (k + 4) * ROW_BYTES + ((unit ^ ((k + 4) & 7)) << 5) + inner;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PO_LDS_S16X4(p0));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PO_LDS_S16X4(p1));
+    union {
+      struct {
+        s16x4 a, b;
+      } s;
+      bf16x8 v;
+    } u;
+    u.s.a = lo;
+    u.s.b = hi;
+    return u.v;
+  }
+}
+
+// ---- epilogue on one row-contiguous piece ----------------------------------------
+// v[0..N) are consecutive n of row m starting at n.  bf16 kinds use N = 8 (16-byte accesses),
+// the fp32 accumulate uses N = 4.
+struct __attribute__((aligned(16))) bf16x8_t {
+  bf16 v[8];
+};
+
 template <int EPI>
-__device__ __forceinline__ void epilogue_store4(const Epilogue& e, int m, int n, float a0, float a1, float a2,
-                                                float a3) {
+__device__ __forceinline__ void epilogue_row_piece(const Epilogue& e, int m, int n, const float* v) {
   size_t idx = (size_t)m * e.ldc + n;
-  float a[4] = {a0, a1, a2, a3};
   if (EPI == kEpiAccumulate) {
-    float4* p = reinterpret_cast<float4*>(e.acc_f32 + idx);
-    float4 o = *p;
-    o.x += a[0];
-    o.y += a[1];
-    o.z += a[2];
-    o.w += a[3];
+    f32x4* p = reinterpret_cast<f32x4*>(e.acc_f32 + idx);
+    f32x4 o = *p;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] += v[i];
     *p = o;
     return;
   }
-  if (EPI == kEpiGeluBackward) {
-    bf16x4_t u = *reinterpret_cast<const bf16x4_t*>(static_cast<const bf16*>(e.gelu_u) + idx);
-    bf16x4_t o, g;
+  float a[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < 8; ++i) a[i] = v[i];
+  if (EPI == kEpiGeluBackward) {
+    bf16x8_t u = *reinterpret_cast<const bf16x8_t*>(static_cast<const bf16*>(e.gelu_u) + idx);
+    bf16x8_t o, g;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
       float uf = (float)u.v[i];
       g.v[i] = (bf16)gelu_f(uf);
       o.v[i] = (bf16)(a[i] * gelu_grad_f(uf));
     }
-    if (e.gelu_out) *reinterpret_cast<bf16x4_t*>(static_cast<bf16*>(e.gelu_out) + idx) = g;
-    *reinterpret_cast<bf16x4_t*>(static_cast<bf16*>(e.out) + idx) = o;
+    if (e.gelu_out) *reinterpret_cast<bf16x8_t*>(static_cast<bf16*>(e.gelu_out) + idx) = g;
+    *reinterpret_cast<bf16x8_t*>(static_cast<bf16*>(e.out) + idx) = o;
     return;
   }
   if (e.bias) {
-    bf16x4_t b = *reinterpret_cast<const bf16x4_t*>(static_cast<const bf16*>(e.bias) + n);
+    bf16x8_t b = *reinterpret_cast<const bf16x8_t*>(static_cast<const bf16*>(e.bias) + n);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) a[i] += (float)b.v[i];
+    for (int i = 0; i < 8; ++i) a[i] += (float)b.v[i];
   }
   if (e.residual) {
-    bf16x4_t r = *reinterpret_cast<const bf16x4_t*>(static_cast<const bf16*>(e.residual) + idx);
+    bf16x8_t r = *reinterpret_cast<const bf16x8_t*>(static_cast<const bf16*>(e.residual) + idx);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) a[i] += (float)r.v[i];
+    for (int i = 0; i < 8; ++i) a[i] += (float)r.v[i];
   }
-  bf16x4_t o;
+  bf16x8_t o;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) o.v[i] = (bf16)a[i];
-  *reinterpret_cast<bf16x4_t*>(static_cast<bf16*>(e.out) + idx) = o;
+  for (int i = 0; i < 8; ++i) o.v[i] = (bf16)a[i];
+  *reinterpret_cast<bf16x8_t*>(static_cast<bf16*>(e.out) + idx) = o;
   if (EPI == kEpiStoreGelu) {
-    bf16x4_t g;
+    bf16x8_t g;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) g.v[i] = (bf16)gelu_f((float)o.v[i]);
-    *reinterpret_cast<bf16x4_t*>(static_cast<bf16*>(e.gelu_out) + idx) = g;
+    for (int i = 0; i < 8; ++i) g.v[i] = (bf16)gelu_f((float)o.v[i]);
+    *reinterpret_cast<bf16x8_t*>(static_cast<bf16*>(e.gelu_out) + idx) = g;
   }
 }
 
 // ---- the kernel ---------------------------------------------------------------
+// TA: A is [K, M] (m-contiguous).  TB: B is [K, N] (n-contiguous).
 template <int WTM, int WTN, bool TA, bool TB, int EPI>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(int K, const bf16* __restrict__ A, int lda,
                                                         const bf16* __restrict__ B, int ldb, Epilogue ep,
                                                         int tiles_m, int tiles_n) {
   constexpr int BM = 64 * WTM, BN = 64 * WTN;
-  constexpr int STAGE = (BM + BN) * 128;
+  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128;
+  constexpr int STAGE = A_BYTES + B_BYTES;
   extern __shared__ __align__(16) char smem[];
 
   // XCD-aware remap: ids equal modulo 8 share an XCD; give each XCD a contiguous run of tiles,
@@ -174,16 +196,13 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int K, const bf16* __res
   int tile_m = first_m + (lin % width) % gsize;
   int tile_n = (lin % width) / gsize;
 
-  int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int tid = threadIdx.x, lane = tid & 63;
+  int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   int wm = wave >> 1, wn = wave & 1;
   int m0 = tile_m * BM, n0 = tile_n * BN;
 
-  // Operand bases at (first row of the tile, k = 0).
-  const bf16* a_base = TA ? A + m0 : A + (size_t)m0 * lda;  // TA: A is [K, M]
-  const bf16* b_base = TB ? B + n0 : B + (size_t)n0 * ldb;  // TB: B is [K, N] (n-contiguous)
-
-  Stager<BM, TA> sa;
-  Stager<BN, TB> sb;
+  const bf16* a_base = TA ? A + m0 : A + (size_t)m0 * lda;
+  const bf16* b_base = TB ? B + n0 : B + (size_t)n0 * ldb;
 
   f32x16 acc[WTM][WTN];
 #pragma unroll
@@ -194,22 +213,18 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int K, const bf16* __res
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   int nk = K / kBK;
-  sa.load(a_base, lda, 0, tid);
-  sb.load(b_base, ldb, 0, tid);
-  sa.store(smem, tid);
-  sb.store(smem + BM * 128, tid);
+  load_slice<BM, TA>(a_base, lda, 0, smem, wave, lane);
+  load_slice<BN, TB>(b_base, ldb, 0, smem + A_BYTES, wave, lane);
+  wait_slice_loads();
   __syncthreads();
 
-  // Fragments of k-step 0 of the first slice.
   bf16x8 fa[2][WTM], fb[2][WTN];
   auto load_fragments = [&](const char* stage, int kk, int buf) {
-    int chunk = 2 * kk + (lane >> 5);
-    const char* la = stage;
-    const char* lb = stage + BM * 128;
 #pragma unroll
-    for (int i = 0; i < WTM; ++i) fa[buf][i] = read_fragment(la, wm * (WTM * 32) + i * 32 + (lane & 31), chunk);
+    for (int i = 0; i < WTM; ++i) fa[buf][i] = read_fragment<BM, TA>(stage, wm * (WTM * 32) + i * 32, kk, lane);
 #pragma unroll
-    for (int j = 0; j < WTN; ++j) fb[buf][j] = read_fragment(lb, wn * (WTN * 32) + j * 32 + (lane & 31), chunk);
+    for (int j = 0; j < WTN; ++j)
+      fb[buf][j] = read_fragment<BN, TB>(stage + A_BYTES, wn * (WTN * 32) + j * 32, kk, lane);
   };
   load_fragments(smem, 0, 0);
 
@@ -217,41 +232,65 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int K, const bf16* __res
     char* cur = smem + (kt & 1) * STAGE;
     char* nxt = smem + ((kt + 1) & 1) * STAGE;
     bool more = kt + 1 < nk;
-    if (more) {
-      sa.load(a_base, lda, (kt + 1) * kBK, tid);
-      sb.load(b_base, ldb, (kt + 1) * kBK, tid);
+    if (more) {  // the next slice flows into the other buffer while this one is consumed
+      load_slice<BM, TA>(a_base, lda, (kt + 1) * kBK, nxt, wave, lane);
+      load_slice<BN, TB>(b_base, ldb, (kt + 1) * kBK, nxt + A_BYTES, wave, lane);
     }
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      // fragments of the next k-step are fetched while the matrix cores work on this one
       if (kk < 3) load_fragments(cur, kk + 1, (kk + 1) & 1);
-      // the next slice goes to the other LDS buffer under the last k-step's MFMAs
-      if (kk == 3 && more) {
-        sa.store(nxt, tid);
-        sb.store(nxt + BM * 128, tid);
-      }
 #pragma unroll
       for (int i = 0; i < WTM; ++i)
 #pragma unroll
         for (int j = 0; j < WTN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][j], fa[kk & 1][i], acc[i][j], 0, 0, 0);
     }
+    wait_slice_loads();
     __syncthreads();
     if (more) load_fragments(nxt, 0, 0);
   }
 
-  // Accumulator layout: acc[i][j][4q + r] = C[m][n] with m = ... + (lane & 31),
-  // n = ... + 8q + 4 (lane >> 5) + r.
+  // Epilogue.  acc[i][j][4q + r] = C[m][n], m = strip row (lane & 31), n = 32 j + 8 q + 4 (lane >> 5) + r.
+  // Each wave owns a private [32][WTN*32 + 4] fp32 strip in LDS (the operand buffers are free now).
+  constexpr int STRIP_N = WTN * 32;
+  constexpr int STRIP_LD = STRIP_N + 4;  // floats; the 16-byte pad staggers rows over the banks
+  float* strip = reinterpret_cast<float*>(smem) + wave * (32 * STRIP_LD);
+  int col = lane & 31, half = lane >> 5;
 #pragma unroll
   for (int i = 0; i < WTM; ++i) {
-    int m = m0 + wm * (WTM * 32) + i * 32 + (lane & 31);
 #pragma unroll
-    for (int j = 0; j < WTN; ++j) {
-      int nb = n0 + wn * (WTN * 32) + j * 32 + 4 * (lane >> 5);
+    for (int j = 0; j < WTN; ++j)
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
-        epilogue_store4<EPI>(ep, m, nb + 8 * q, acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
-                        acc[i][j][4 * q + 3]);
+      for (int q = 0; q < 4; ++q) {
+        f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+        *reinterpret_cast<f32x4*>(strip + col * STRIP_LD + 32 * j + 8 * q + 4 * half) = v;
+      }
+    // (a wave reads back only what it wrote itself: program order is enough, no barrier)
+    int mrow0 = m0 + wm * (WTM * 32) + i * 32;
+    int ncol0 = n0 + wn * STRIP_N;
+    if (EPI == kEpiAccumulate) {
+      constexpr int LPR = STRIP_N / 4;  // lanes per row, 4 floats each
+      constexpr int RPI = 64 / LPR;     // rows per wave-wide access
+#pragma unroll
+      for (int it = 0; it < 32 / RPI; ++it) {
+        int r = it * RPI + lane / LPR;
+        int c = (lane % LPR) * 4;
+        f32x4 v = *reinterpret_cast<const f32x4*>(strip + r * STRIP_LD + c);
+        float vv[4] = {v[0], v[1], v[2], v[3]};
+        epilogue_row_piece<EPI>(ep, mrow0 + r, ncol0 + c, vv);
+      }
+    } else {
+      constexpr int LPR = STRIP_N / 8;  // lanes per row, 8 values each
+      constexpr int RPI = 64 / LPR;
+#pragma unroll
+      for (int it = 0; it < 32 / RPI; ++it) {
+        int r = it * RPI + lane / LPR;
+        int c = (lane % LPR) * 8;
+        f32x4 v0 = *reinterpret_cast<const f32x4*>(strip + r * STRIP_LD + c);
+        f32x4 v1 = *reinterpret_cast<const f32x4*>(strip + r * STRIP_LD + c + 4);
+        float vv[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+        epilogue_row_piece<EPI>(ep, mrow0 + r, ncol0 + c, vv);
+      }
     }
   }
 }
@@ -271,14 +310,16 @@ bool gemm_mfma_supported(int trans_a, int trans_b, int M, int N, int K, int lda,
   (void)trans_b;
   int wtm, wtn;
   pick_tile(M, N, wtm, wtn);
-  return wtm != 0 && K > 0 && K % kBK == 0 && lda % 8 == 0 && ldb % 8 == 0 && ldc % 4 == 0;
+  return wtm != 0 && K > 0 && K % kBK == 0 && lda % 8 == 0 && ldb % 8 == 0 && ldc % 8 == 0;
 }
 
 template <int WTM, int WTN, bool TA, bool TB, int EPI>
 static bool launch_mfma_epi(int M, int N, int K, const bf16* A, int lda, const bf16* B, int ldb, const Epilogue& ep,
                             hipStream_t stream) {
   constexpr int BM = 64 * WTM, BN = 64 * WTN;
-  constexpr int smem = 2 * (BM + BN) * 128;
+  constexpr int smem_ops = 2 * (BM + BN) * 128;
+  constexpr int smem_epi = 4 * 32 * (WTN * 32 + 4) * 4;
+  constexpr int smem = smem_ops > smem_epi ? smem_ops : smem_epi;
   auto kern = gemm_mfma_kernel<WTM, WTN, TA, TB, EPI>;
   static bool configured = false;  // per instantiation
   if (!configured) {
@@ -323,8 +364,8 @@ bool gemm_mfma_bf16(int trans_a, int trans_b, int M, int N, int K, const void* A
     return false;
   }
   uintptr_t al = (uintptr_t)A | (uintptr_t)B | (uintptr_t)ep.out | (uintptr_t)ep.gelu_out | (uintptr_t)ep.gelu_u |
-                 (uintptr_t)ep.residual | (uintptr_t)ep.acc_f32;
-  if (al % 16 != 0 || (uintptr_t)ep.bias % 8 != 0) {
+                 (uintptr_t)ep.residual | (uintptr_t)ep.acc_f32 | (uintptr_t)ep.bias;
+  if (al % 16 != 0) {
     set_error("gemm_mfma: operands must be 16-byte aligned");
     return false;
   }
