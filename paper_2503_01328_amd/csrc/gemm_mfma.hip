@@ -29,6 +29,8 @@
 //
 // Workgroup ids are remapped so that the blocks that land on one XCD (ids equal
 // modulo 8) work on neighbouring tiles and share operand slices in that XCD's L2.
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace po {
@@ -51,12 +53,18 @@ enum EpiKind : int { kEpiStore = 0, kEpiStoreGelu = 1, kEpiGeluBackward = 2, kEp
 // KMAJOR == false: operand is [R rows][K], slice = R rows x 64 k, row tile in LDS.
 // KMAJOR == true : operand is [K][R], slice = 64 k x R, k-major tile in LDS.
 // `base` points at (first row of the tile, k = 0); the slice starts at k0.
+// The slice is issued in four quarters (part = 0..3) so that the issue can be spread between the MFMAs
+// of the four k-steps of the slice being consumed; part < 0 issues everything.
 template <int R, bool KMAJOR>
 __device__ __forceinline__ void load_slice(const bf16* __restrict__ base, int ld, int k0, char* lds, int wave,
-                                           int lane) {
+                                           int lane, int part = -1) {
   constexpr int N_INST = R * 128 / 1024;  // wave-level 1 KiB loads in the slice
+  constexpr int PER_WAVE = N_INST / 4;
+  constexpr int PER_PART = PER_WAVE / 4;
+  static_assert(PER_PART >= 1, "tile too small to split the slice in four");
 #pragma unroll
-  for (int u = 0; u < N_INST / 4; ++u) {
+  for (int u = 0; u < PER_WAVE; ++u) {
+    if (part >= 0 && u / PER_PART != part) continue;
     int g = u * 4 + wave;  // which 1 KiB piece of the tile this wave fills now
     const bf16* src;
     if (!KMAJOR) {
@@ -219,36 +227,63 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int K, const bf16* __res
   __syncthreads();
 
   bf16x8 fa[2][WTM], fb[2][WTN];
+  // Fragments are fetched in the order a0 b0 a1 b1 ... and the MFMAs of a k-step walk the
+  // (i, j) grid as a growing square, so the first MFMAs need only the first fragments fetched
+  // and the fragment fetched last is needed last.
   auto load_fragments = [&](const char* stage, int kk, int buf) {
 #pragma unroll
-    for (int i = 0; i < WTM; ++i) fa[buf][i] = read_fragment<BM, TA>(stage, wm * (WTM * 32) + i * 32, kk, lane);
-#pragma unroll
-    for (int j = 0; j < WTN; ++j)
-      fb[buf][j] = read_fragment<BN, TB>(stage + A_BYTES, wn * (WTN * 32) + j * 32, kk, lane);
+    for (int t = 0; t < (WTM > WTN ? WTM : WTN); ++t) {
+      if (t < WTM) fa[buf][t] = read_fragment<BM, TA>(stage, wm * (WTM * 32) + t * 32, kk, lane);
+      if (t < WTN) fb[buf][t] = read_fragment<BN, TB>(stage + A_BYTES, wn * (WTN * 32) + t * 32, kk, lane);
+    }
   };
   load_fragments(smem, 0, 0);
 
-  for (int kt = 0; kt < nk; ++kt) {
+  // One slice: MFMAs on `cur`; with MORE, the next slice streams into `nxt` meanwhile.  The last
+  // slice is peeled off so that the steady-state loop body has no branches.
+  auto slice = [&](int kt, auto more_tag) {
+    constexpr bool MORE = decltype(more_tag)::value;
     char* cur = smem + (kt & 1) * STAGE;
     char* nxt = smem + ((kt + 1) & 1) * STAGE;
-    bool more = kt + 1 < nk;
-    if (more) {  // the next slice flows into the other buffer while this one is consumed
-      load_slice<BM, TA>(a_base, lda, (kt + 1) * kBK, nxt, wave, lane);
-      load_slice<BN, TB>(b_base, ldb, (kt + 1) * kBK, nxt + A_BYTES, wave, lane);
-    }
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       if (kk < 3) load_fragments(cur, kk + 1, (kk + 1) & 1);
+      if (MORE && kk < 2) {  // the next slice is issued under the first two k-steps (half each): early
+                             // enough to land before the barrier, spread enough not to stall the issue
 #pragma unroll
-      for (int i = 0; i < WTM; ++i)
+        for (int q = 2 * kk; q < 2 * kk + 2; ++q) {
+          load_slice<BM, TA>(a_base, lda, (kt + 1) * kBK, nxt, wave, lane, q);
+          load_slice<BN, TB>(b_base, ldb, (kt + 1) * kBK, nxt + A_BYTES, wave, lane, q);
+        }
+      }
 #pragma unroll
-        for (int j = 0; j < WTN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][j], fa[kk & 1][i], acc[i][j], 0, 0, 0);
+      for (int t = 0; t < (WTM > WTN ? WTM : WTN); ++t) {  // ring t of the growing square
+#pragma unroll
+        for (int j = 0; j < t && j < WTN; ++j)
+          if (t < WTM)
+            acc[t][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][j], fa[kk & 1][t], acc[t][j], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i <= t && i < WTM; ++i)
+          if (t < WTN)
+            acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][t], fa[kk & 1][i], acc[i][t], 0, 0, 0);
+      }
+      // Pin the order inside the k-step: the LDS reads of the next k-step's fragments are spread
+      // between this k-step's MFMAs (which do not depend on them), so their latency is hidden.
+      if (kk < 3) {
+#pragma unroll
+        for (int r = 0; r < WTM + WTN; ++r) {
+          __builtin_amdgcn_sched_group_barrier(0x100, TA || TB ? 2 : 1, 0);  // LDS reads
+          __builtin_amdgcn_sched_group_barrier(0x008, (WTM * WTN) / (WTM + WTN), 0);  // MFMAs
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
-    wait_slice_loads();
+    if (MORE) wait_slice_loads();
     __syncthreads();
-    if (more) load_fragments(nxt, 0, 0);
-  }
+    if (MORE) load_fragments(nxt, 0, 0);
+  };
+  for (int kt = 0; kt + 1 < nk; ++kt) slice(kt, std::true_type{});
+  slice(nk - 1, std::false_type{});
 
   // Epilogue.  acc[i][j][4q + r] = C[m][n], m = strip row (lane & 31), n = 32 j + 8 q + 4 (lane >> 5) + r.
   // Each wave owns a private [32][WTN*32 + 4] fp32 strip in LDS (the operand buffers are free now).
