@@ -91,7 +91,7 @@ bool layernorm_forward(int dtype, const void* x, const void* gain, const void* s
 //   dx = dres + rstd (dxhat - mean(dxhat) - xhat mean(dxhat xhat))
 //   dgain += colsum(dn * xhat) ; dshift += colsum(dn)
 // Kernel 1 (wave per row) writes dx and the row statistics; kernel 2 builds
-// per-row-chunk column partials; kernel 3 adds them in chunk order.
+// per-row-chunk column partials; kernel 3 adds them in a fixed tree.
 // --------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void ln_backward_rows_kernel(const T* __restrict__ dn, const T* __restrict__ x,
@@ -181,17 +181,44 @@ __global__ __launch_bounds__(256) void ln_backward_cols_kernel(const T* __restri
   }
 }
 
-__global__ void ln_backward_final_kernel(const float* __restrict__ partials, float* __restrict__ dgain,
-                                         float* __restrict__ dshift, int h, int n_chunks) {
-  int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= h) return;
-  float sg = 0.f, sb = 0.f;
-  for (int k = 0; k < n_chunks; ++k) {
-    sg += partials[((size_t)k * 2 + 0) * h + c];
-    sb += partials[((size_t)k * 2 + 1) * h + c];
+// Sums up to 64 chunk partials per column in a fixed tree: a block owns 64 columns, thread (part, c) adds the
+// chunks part, part + 4, ... in that order (its loads are independent, so they are all in flight together), and
+// thread c of part 0 adds the four parts in order.  Partials are laid out [chunk][N_OUT][n]; plane o is added
+// into out0 (o = 0) or out1 (o = 1).
+template <int N_OUT>
+__global__ __launch_bounds__(256) void chunk_partials_final_kernel(const float* __restrict__ partials,
+                                                                   float* __restrict__ out0,
+                                                                   float* __restrict__ out1, int n, int n_chunks) {
+  __shared__ float red[N_OUT][4][64];
+  int part = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  int c = blockIdx.x * 64 + lane;
+  float acc[N_OUT];
+#pragma unroll
+  for (int o = 0; o < N_OUT; ++o) acc[o] = 0.f;
+  if (c < n) {
+    float v[N_OUT][16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      int k = part + 4 * i;
+#pragma unroll
+      for (int o = 0; o < N_OUT; ++o) v[o][i] = k < n_chunks ? partials[((size_t)k * N_OUT + o) * n + c] : 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+      for (int o = 0; o < N_OUT; ++o) acc[o] += v[o][i];
   }
-  dgain[c] += sg;
-  dshift[c] += sb;
+#pragma unroll
+  for (int o = 0; o < N_OUT; ++o) red[o][part][lane] = acc[o];
+  __syncthreads();
+  if (part == 0 && c < n) {
+#pragma unroll
+    for (int o = 0; o < N_OUT; ++o) {
+      float s = ((red[o][0][lane] + red[o][1][lane]) + red[o][2][lane]) + red[o][3][lane];
+      float* out = o == 0 ? out0 : out1;
+      out[c] += s;
+    }
+  }
 }
 
 static int reduce_chunks(int rows) { return max(1, min(64, ceil_div(rows, 32))); }
@@ -211,7 +238,7 @@ bool layernorm_backward(int dtype, const void* dn, const void* x, const void* ga
   float* partials = workspace + (size_t)rows * 2;
   int n_chunks = reduce_chunks(rows);
   int rows_per_chunk = ceil_div(rows, n_chunks);
-  dim3 g1(ceil_div(rows, 4)), g2(ceil_div(h, 128), n_chunks), g3(ceil_div(h, 256));
+  dim3 g1(ceil_div(rows, 4)), g2(ceil_div(h, 128), n_chunks), g3(ceil_div(h, 64));
   if (dtype == kF32) {
     ln_backward_rows_kernel<float><<<g1, 256, 0, stream>>>((const float*)dn, (const float*)x, (const float*)gain,
                                                            (const float*)dres, (float*)dx, stats, rows, h, eps);
@@ -223,7 +250,7 @@ bool layernorm_backward(int dtype, const void* dn, const void* x, const void* ga
     ln_backward_cols_kernel<bf16><<<g2, 256, 0, stream>>>((const bf16*)dn, (const bf16*)x, stats, partials, rows,
                                                           h, rows_per_chunk);
   }
-  ln_backward_final_kernel<<<g3, 256, 0, stream>>>(partials, dgain, dshift, h, n_chunks);
+  chunk_partials_final_kernel<2><<<g3, 256, 0, stream>>>(partials, dgain, dshift, h, n_chunks);
   return launch_ok("layernorm_backward kernels");
 }
 
@@ -256,15 +283,6 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict
   }
 }
 
-__global__ void colsum_final_kernel(const float* __restrict__ partials, float* __restrict__ acc, int n,
-                                    int n_chunks) {
-  int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= n) return;
-  float s = 0.f;
-  for (int k = 0; k < n_chunks; ++k) s += partials[(size_t)k * n + c];
-  acc[c] += s;
-}
-
 size_t colsum_workspace(int rows, int n) { return (size_t)reduce_chunks(rows) * n * sizeof(float); }
 
 bool colsum_accumulate(int dtype, const void* x, float* acc, float* workspace, int rows, int n,
@@ -280,7 +298,7 @@ bool colsum_accumulate(int dtype, const void* x, float* acc, float* workspace, i
     colsum_partial_kernel<float><<<g, 256, 0, stream>>>((const float*)x, workspace, rows, n, rows_per_chunk);
   else
     colsum_partial_kernel<bf16><<<g, 256, 0, stream>>>((const bf16*)x, workspace, rows, n, rows_per_chunk);
-  colsum_final_kernel<<<ceil_div(n, 256), 256, 0, stream>>>(workspace, acc, n, n_chunks);
+  chunk_partials_final_kernel<1><<<ceil_div(n, 64), 256, 0, stream>>>(workspace, acc, nullptr, n, n_chunks);
   return launch_ok("colsum kernels");
 }
 
