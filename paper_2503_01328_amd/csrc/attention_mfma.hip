@@ -16,8 +16,8 @@
 //     transposing LDS read (ds_read_b64_tr_b16), two per fragment.
 //
 // Forward: block = 4 waves, a wave owns QT x 32 query rows; K/V tiles of 64 keys
-// are staged through LDS (register-prefetched, double-buffered).  Blocks with the
-// most key tiles are launched first (causal work is triangular).
+// are staged through LDS (loaded HBM -> LDS directly, double-buffered).  Blocks with the
+// most key tiles are launched first, over all heads (causal work is triangular).
 //
 // Backward, deterministic without atomics: one kernel per key block accumulates
 // dK and dV over the query tiles at or below the diagonal; one kernel per query
@@ -39,22 +39,50 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kKeysPerTile = 64;
 
-// ---- LDS tiles -------------------------------------------------------------------
-// "Row" tile: [rows][DH] bf16, 16-byte chunks XOR-swizzled by the row index; read with
-// ds_read_b128 as an MFMA operand whose contraction index is the head dimension.
+// ---- LDS tile --------------------------------------------------------------------
+// [64 rows][DH] bf16, unpadded: the 16-byte chunk c of row r sits at chunk position c ^ swz(r).
+// One tile serves both kinds of MFMA operand reads without bank conflicts:
+//  * ds_read_b128 "row" fragments (contraction over the head dimension): 16 lanes read the same
+//    chunk of 16 consecutive rows; swz is a bijection of those rows onto the 16 chunk positions
+//    of a 256-byte bank line (for DH = 64 two rows share a line and the row parity picks the half);
+//  * transposing reads (contraction over the tile's rows): a half-wave reads 64 contiguous bytes
+//    of four consecutive rows; swz sends them to the four different 64-byte quarters of a line.
 template <int DH>
-__device__ __forceinline__ int row_tile_offset(int row, int chunk) {
-  constexpr int CPR = DH / 8;
-  return row * (DH * 2) + ((chunk ^ (row & (CPR - 1))) << 4);
+__device__ __forceinline__ int swz(int r) {
+  if (DH == 128) return ((r & 3) << 2) | ((r >> 2) & 3);
+  return (((r >> 1) & 1) << 2) | ((r >> 2) & 3);
 }
-// "Transposable" tile: [rows][DH + 16] bf16 (32 bytes of padding per row so that the four
-// rows touched by a 16-lane transposing read fall into different banks).
 template <int DH>
-__device__ __forceinline__ int tr_tile_offset(int row, int col) {
-  return row * ((DH + 16) * 2) + col * 2;
+__device__ __forceinline__ int tile_offset(int row, int chunk) {
+  return row * (DH * 2) + ((chunk ^ swz<DH>(row)) << 4);
 }
-template <int DH> constexpr int row_tile_bytes(int rows) { return rows * DH * 2; }
-template <int DH> constexpr int tr_tile_bytes(int rows) { return rows * (DH + 16) * 2; }
+template <int DH> constexpr int tile_bytes() { return kKeysPerTile * DH * 2; }
+
+// HBM -> LDS without a register stop: a wave-level global_load_lds_dwordx4 writes 1 KiB of the tile
+// (lane L fills bytes 16 L ..), so each lane fetches the chunk that belongs at its position.  256
+// threads; `base` points at (row 0, first element of the head), rows are `ld` elements apart.
+// Inline assembly on purpose: through the builtin the compiler waits for the load before every
+// later LDS read, which would undo the double buffering.  Callers wait (wait_tile_loads) before
+// the barrier that publishes the tile.
+template <int DH>
+__device__ __forceinline__ void load_tile_async(const bf16* __restrict__ base, int ld, int row0, char* tile,
+                                                int wave, int lane) {
+  constexpr int ROW_BYTES = DH * 2;
+  constexpr int PER_WAVE = tile_bytes<DH>() / 1024 / 4;
+#pragma unroll
+  for (int u = 0; u < PER_WAVE; ++u) {
+    int n = u * 4 + wave;
+    int byte = n * 1024 + lane * 16;
+    int row = byte / ROW_BYTES;
+    int c = ((byte % ROW_BYTES) >> 4) ^ swz<DH>(row);
+    const bf16* src = base + (size_t)(row0 + row) * ld + c * 8;
+    unsigned lds_addr = __builtin_amdgcn_readfirstlane(
+        (unsigned)(size_t)((void __attribute__((address_space(3)))*)(tile + n * 1024)));  // wave-uniform
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(src)
+                 : "memory");
+  }
+}
+__device__ __forceinline__ void wait_tile_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // Fragment whose contraction index is the tile's row: lane (column c = lane % 32 of the
 // 32-wide block starting at col0, half = lane / 32) receives rows
@@ -66,11 +94,11 @@ __device__ __forceinline__ bf16x8 read_tr_fragment(const char* tile, int row0, i
   int i = lane & 15;
   int grp = lane >> 4;
   int half = grp >> 1;
-  int c0 = col0 + 16 * (grp & 1);
   int r = row0 + 4 * half + (i >> 2);
-  int c = c0 + 4 * (i & 3);
-  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_AS3(tile + tr_tile_offset<DH>(r, c)));
-  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_AS3(tile + tr_tile_offset<DH>(r + 8, c)));
+  int c = col0 + 16 * (grp & 1) + 4 * (i & 3);
+  int inner = (c & 7) * 2;
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_AS3(tile + tile_offset<DH>(r, c >> 3) + inner));
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_AS3(tile + tile_offset<DH>(r + 8, c >> 3) + inner));
   union {
     struct {
       s16x4 a, b;
@@ -84,7 +112,7 @@ __device__ __forceinline__ bf16x8 read_tr_fragment(const char* tile, int row0, i
 
 template <int DH>
 __device__ __forceinline__ bf16x8 read_row_fragment(const char* tile, int row, int chunk) {
-  return *reinterpret_cast<const bf16x8*>(tile + row_tile_offset<DH>(row, chunk));
+  return *reinterpret_cast<const bf16x8*>(tile + tile_offset<DH>(row, chunk));
 }
 
 // Eight consecutive accumulator values -> bf16 operand fragment.
@@ -94,38 +122,6 @@ __device__ __forceinline__ bf16x8 pack_bf16x8(const f32x16& a, int first) {
   for (int e = 0; e < 8; ++e) r[e] = (bf16)a[first + e];
   return r;
 }
-
-// Global -> register staging of a [64][DH] tile (rows of the qkv / dO matrices), 256 threads.
-template <int DH>
-struct TileLoader {
-  static constexpr int CPR = DH / 8;                 // 16-byte chunks per row
-  static constexpr int N = kKeysPerTile * CPR / 256;  // chunks per thread
-  u32x4 reg[N];
-  __device__ __forceinline__ void load(const bf16* base, int ld, int row0, int tid) {
-#pragma unroll
-    for (int u = 0; u < N; ++u) {
-      int e = tid + 256 * u;
-      int row = e / CPR, c = e % CPR;
-      reg[u] = *reinterpret_cast<const u32x4*>(base + (size_t)(row0 + row) * ld + c * 8);
-    }
-  }
-  __device__ __forceinline__ void store_row_tile(char* tile, int tid) const {
-#pragma unroll
-    for (int u = 0; u < N; ++u) {
-      int e = tid + 256 * u;
-      int row = e / CPR, c = e % CPR;
-      *reinterpret_cast<u32x4*>(tile + row_tile_offset<DH>(row, c)) = reg[u];
-    }
-  }
-  __device__ __forceinline__ void store_tr_tile(char* tile, int tid) const {
-#pragma unroll
-    for (int u = 0; u < N; ++u) {
-      int e = tid + 256 * u;
-      int row = e / CPR, c = e % CPR;
-      *reinterpret_cast<u32x4*>(tile + tr_tile_offset<DH>(row, c * 8)) = reg[u];
-    }
-  }
-};
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -138,15 +134,16 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_fwd_mfma_kernel(con
   constexpr int KS = DH / 16;   // 16-deep MFMA steps over the head dimension
   constexpr int DT = DH / 32;   // 32-wide output tiles over the head dimension
   constexpr int BQ = 128 * QT;  // query rows per block
-  constexpr int KBYTES = row_tile_bytes<DH>(kKeysPerTile);
-  constexpr int VBYTES = tr_tile_bytes<DH>(kKeysPerTile);
-  constexpr int STAGE = KBYTES + VBYTES;
+  constexpr int KBYTES = tile_bytes<DH>();
+  constexpr int STAGE = 2 * KBYTES;  // K tile, V tile
   extern __shared__ __align__(16) char smem[];
 
   int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int half = lane >> 5, col = lane & 31;
-  int head = blockIdx.y;
-  int qblock = gridDim.x - 1 - blockIdx.x;  // heaviest blocks first
+  // Heads vary fastest in dispatch order and the query blocks with the most key tiles come first, over all
+  // heads: causal work is triangular, and a heavy block that starts late would run on alone at the end.
+  int head = blockIdx.x;
+  int qblock = gridDim.y - 1 - blockIdx.y;
   int q0 = qblock * BQ;
   int qw0 = q0 + wave * (32 * QT);  // first query row of this wave
   int ld = 3 * h;
@@ -176,11 +173,9 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_fwd_mfma_kernel(con
   }
 
   int nkv = (q0 + BQ) / kKeysPerTile;
-  TileLoader<DH> lk, lv;
-  lk.load(kbase, ld, 0, tid);
-  lv.load(vbase, ld, 0, tid);
-  lk.store_row_tile(smem, tid);
-  lv.store_tr_tile(smem + KBYTES, tid);
+  load_tile_async<DH>(kbase, ld, 0, smem, wave, lane);
+  load_tile_async<DH>(vbase, ld, 0, smem + KBYTES, wave, lane);
+  wait_tile_loads();
   __syncthreads();
 
   for (int kt = 0; kt < nkv; ++kt) {
@@ -188,9 +183,9 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_fwd_mfma_kernel(con
     const char* vtile = ktile + KBYTES;
     char* nxt = smem + ((kt + 1) & 1) * STAGE;
     bool more = kt + 1 < nkv;
-    if (more) {
-      lk.load(kbase, ld, (kt + 1) * kKeysPerTile, tid);
-      lv.load(vbase, ld, (kt + 1) * kKeysPerTile, tid);
+    if (more) {  // the other stage was last read before the barrier that ended the previous iteration
+      load_tile_async<DH>(kbase, ld, (kt + 1) * kKeysPerTile, nxt, wave, lane);
+      load_tile_async<DH>(vbase, ld, (kt + 1) * kKeysPerTile, nxt + KBYTES, wave, lane);
     }
     int key0 = kt * kKeysPerTile;
     if (key0 <= qw0 + 32 * QT - 1) {  // some key of the tile is visible to some row of this wave
@@ -271,10 +266,7 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_fwd_mfma_kernel(con
               oacc[t][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[t][j][st], oacc[t][d], 0, 0, 0);
           }
     }
-    if (more) {
-      lk.store_row_tile(nxt, tid);
-      lv.store_tr_tile(nxt + KBYTES, tid);
-    }
+    wait_tile_loads();
     __syncthreads();
   }
 
@@ -298,19 +290,13 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_fwd_mfma_kernel(con
 
 // ==================================================================================
 // Backward, part 1: dK and dV.  Block = 128 keys (a wave owns 32), loop over the
-// 64-row query tiles at or below the diagonal.  Q and dO tiles are staged in LDS in
-// the padded [row][DH + 16] form, which serves both kinds of reads: ds_read_b128
-// fragments (contraction over the head dimension, for S and dP) and transposing
-// fragments (contraction over the query rows, for dV and dK).
+// 64-row query tiles at or below the diagonal.  The Q and dO tiles in LDS serve both
+// kinds of reads: ds_read_b128 fragments (contraction over the head dimension, for S
+// and dP) and transposing fragments (contraction over the query rows, for dV and dK).
 //   S[q][key]  = Q K^T          P = exp(S scale - lse[q])
 //   dP[q][key] = dO V^T         dS = P (dP - delta[q])
 //   dV[key]   += P^T dO         dK[key] += dS^T Q   (times scale at the end)
 // ==================================================================================
-template <int DH>
-__device__ __forceinline__ bf16x8 read_padded_row_fragment(const char* tile, int row, int chunk) {
-  return *reinterpret_cast<const bf16x8*>(tile + tr_tile_offset<DH>(row, chunk * 8));
-}
-
 template <int DH>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* __restrict__ qkv,
                                                                 const bf16* __restrict__ d_o,
@@ -318,14 +304,14 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
                                                                 const float* __restrict__ delta,
                                                                 bf16* __restrict__ dqkv, int s, int h, float scale) {
   constexpr int KS = DH / 16, DT = DH / 32;
-  constexpr int TBYTES = tr_tile_bytes<DH>(kKeysPerTile);
+  constexpr int TBYTES = tile_bytes<DH>();
   constexpr int STAGE = 2 * TBYTES + 512;  // Q tile, dO tile, lse[64], delta[64]
   extern __shared__ __align__(16) char smem[];
 
   int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int half = lane >> 5, col = lane & 31;
-  int head = blockIdx.y;
-  int kb0 = blockIdx.x * 128;   // first key of the block (the earliest blocks have the most query tiles)
+  int head = blockIdx.x;        // heads vary fastest in dispatch order: heaviest blocks of all heads first
+  int kb0 = blockIdx.y * 128;   // first key of the block (the earliest blocks have the most query tiles)
   int kw0 = kb0 + wave * 32;    // first key of this wave
   int ld = 3 * h;
   const bf16* qbase = qkv + head * DH;
@@ -350,7 +336,6 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
     for (int e = 0; e < 16; ++e) dk[d][e] = dv[d][e] = 0.f;
 
   int q_first = kb0 / kKeysPerTile, q_last = s / kKeysPerTile;  // query tiles [q_first, q_last)
-  TileLoader<DH> lq, ldo;
   float stat = 0.f;  // threads 0..63: lse * log2(e) of a row, threads 64..127: delta of a row
   auto load_stats = [&](int q0) {
     if (tid < 64)
@@ -361,12 +346,11 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
   auto store_stats = [&](char* stage) {
     if (tid < 128) reinterpret_cast<float*>(stage + 2 * TBYTES)[tid] = stat;
   };
-  lq.load(qbase, ld, q_first * kKeysPerTile, tid);
-  ldo.load(dobase, h, q_first * kKeysPerTile, tid);
+  load_tile_async<DH>(qbase, ld, q_first * kKeysPerTile, smem, wave, lane);
+  load_tile_async<DH>(dobase, h, q_first * kKeysPerTile, smem + TBYTES, wave, lane);
   load_stats(q_first * kKeysPerTile);
-  lq.store_tr_tile(smem, tid);
-  ldo.store_tr_tile(smem + TBYTES, tid);
   store_stats(smem);
+  wait_tile_loads();
   __syncthreads();
 
   for (int qt = q_first; qt < q_last; ++qt) {
@@ -377,9 +361,15 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
     const float* st_delta = st_lse + 64;
     char* nxt = smem + ((it + 1) & 1) * STAGE;
     bool more = qt + 1 < q_last;
-    if (more) {
-      lq.load(qbase, ld, (qt + 1) * kKeysPerTile, tid);
-      ldo.load(dobase, h, (qt + 1) * kKeysPerTile, tid);
+    // The swizzled LDS addresses and the per-lane global addresses are cheap to rebuild (a few XORs and
+    // multiply-adds); hiding the lane id from the optimiser here keeps it from carrying some thirty address
+    // registers across iterations and spilling accumulators instead.
+    int lane_l = lane;
+    asm volatile("" : "+v"(lane_l));
+    int col_l = lane_l & 31, half_l = lane_l >> 5;
+    if (more) {  // the other stage was last read before the barrier that ended the previous iteration
+      load_tile_async<DH>(qbase, ld, (qt + 1) * kKeysPerTile, nxt, wave, lane_l);
+      load_tile_async<DH>(dobase, h, (qt + 1) * kKeysPerTile, nxt + TBYTES, wave, lane_l);
       load_stats((qt + 1) * kKeysPerTile);
     }
     int q0 = qt * kKeysPerTile;
@@ -393,8 +383,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
       for (int e = 0; e < 16; ++e) sacc[e] = pacc[e] = 0.f;
 #pragma unroll
       for (int kk = 0; kk < KS; ++kk) {
-        bf16x8 qa = read_padded_row_fragment<DH>(qtile, 32 * j + col, 2 * kk + half);
-        bf16x8 da = read_padded_row_fragment<DH>(dotile, 32 * j + col, 2 * kk + half);
+        bf16x8 qa = read_row_fragment<DH>(qtile, 32 * j + col_l, 2 * kk + half_l);
+        bf16x8 da = read_row_fragment<DH>(dotile, 32 * j + col_l, 2 * kk + half_l);
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[kk], sacc, 0, 0, 0);
         pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vf[kk], pacc, 0, 0, 0);
       }
@@ -424,17 +414,14 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
       for (int d = 0; d < DT; ++d)
 #pragma unroll
         for (int st = 0; st < 2; ++st) {
-          bf16x8 dot = read_tr_fragment<DH>(dotile, 32 * j + 16 * st, 32 * d, lane);
-          bf16x8 qtr = read_tr_fragment<DH>(qtile, 32 * j + 16 * st, 32 * d, lane);
+          bf16x8 dot = read_tr_fragment<DH>(dotile, 32 * j + 16 * st, 32 * d, lane_l);
+          bf16x8 qtr = read_tr_fragment<DH>(qtile, 32 * j + 16 * st, 32 * d, lane_l);
           dv[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dot, pf[st], dv[d], 0, 0, 0);
           dk[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qtr, dsf[st], dk[d], 0, 0, 0);
         }
     }
-    if (more) {
-      lq.store_tr_tile(nxt, tid);
-      ldo.store_tr_tile(nxt + TBYTES, tid);
-      store_stats(nxt);
-    }
+    if (more) store_stats(nxt);
+    wait_tile_loads();
     __syncthreads();
   }
 
@@ -457,8 +444,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
 
 // ==================================================================================
 // Backward, part 2: dQ.  Block = 128 QT query rows (a wave owns 32 QT), loop over the
-// key tiles up to the diagonal.  K is staged in the padded form (row fragments for
-// S^T = K Q^T, transposing fragments for dQ^T = K^T dS^T), V in the swizzled row form.
+// key tiles up to the diagonal.  The K tile is read both ways (row fragments for
+// S^T = K Q^T, transposing fragments for dQ^T = K^T dS^T), the V tile as row fragments.
 // ==================================================================================
 template <int DH, int QT>
 __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv,
@@ -468,15 +455,14 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_bwd_dq_mfma_kernel(
                                                                bf16* __restrict__ dqkv, int s, int h, float scale) {
   constexpr int KS = DH / 16, DT = DH / 32;
   constexpr int BQ = 128 * QT;
-  constexpr int KBYTES = tr_tile_bytes<DH>(kKeysPerTile);
-  constexpr int VBYTES = row_tile_bytes<DH>(kKeysPerTile);
-  constexpr int STAGE = KBYTES + VBYTES;
+  constexpr int KBYTES = tile_bytes<DH>();
+  constexpr int STAGE = 2 * KBYTES;  // K tile, V tile
   extern __shared__ __align__(16) char smem[];
 
   int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int half = lane >> 5, col = lane & 31;
-  int head = blockIdx.y;
-  int qblock = gridDim.x - 1 - blockIdx.x;
+  int head = blockIdx.x;  // dispatch order as in the forward kernel
+  int qblock = gridDim.y - 1 - blockIdx.y;
   int q0 = qblock * BQ;
   int qw0 = q0 + wave * (32 * QT);
   int ld = 3 * h;
@@ -507,11 +493,9 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_bwd_dq_mfma_kernel(
       for (int e = 0; e < 16; ++e) dq[t][d][e] = 0.f;
 
   int nkv = (q0 + BQ) / kKeysPerTile;
-  TileLoader<DH> lk, lv;
-  lk.load(kbase, ld, 0, tid);
-  lv.load(vbase, ld, 0, tid);
-  lk.store_tr_tile(smem, tid);
-  lv.store_row_tile(smem + KBYTES, tid);
+  load_tile_async<DH>(kbase, ld, 0, smem, wave, lane);
+  load_tile_async<DH>(vbase, ld, 0, smem + KBYTES, wave, lane);
+  wait_tile_loads();
   __syncthreads();
 
   for (int kt = 0; kt < nkv; ++kt) {
@@ -519,9 +503,9 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_bwd_dq_mfma_kernel(
     const char* vtile = ktile + KBYTES;
     char* nxt = smem + ((kt + 1) & 1) * STAGE;
     bool more = kt + 1 < nkv;
-    if (more) {
-      lk.load(kbase, ld, (kt + 1) * kKeysPerTile, tid);
-      lv.load(vbase, ld, (kt + 1) * kKeysPerTile, tid);
+    if (more) {  // the other stage was last read before the barrier that ended the previous iteration
+      load_tile_async<DH>(kbase, ld, (kt + 1) * kKeysPerTile, nxt, wave, lane);
+      load_tile_async<DH>(vbase, ld, (kt + 1) * kKeysPerTile, nxt + KBYTES, wave, lane);
     }
     int key0 = kt * kKeysPerTile;
 #pragma unroll
@@ -535,7 +519,7 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_bwd_dq_mfma_kernel(
         for (int e = 0; e < 16; ++e) sacc[t][e] = pacc[t][e] = 0.f;
 #pragma unroll
       for (int kk = 0; kk < KS; ++kk) {
-        bf16x8 ka = read_padded_row_fragment<DH>(ktile, 32 * j + col, 2 * kk + half);
+        bf16x8 ka = read_row_fragment<DH>(ktile, 32 * j + col, 2 * kk + half);
         bf16x8 va = read_row_fragment<DH>(vtile, 32 * j + col, 2 * kk + half);
 #pragma unroll
         for (int t = 0; t < QT; ++t) {
@@ -570,10 +554,7 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_bwd_dq_mfma_kernel(
             dq[t][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktr, dsf[t][st], dq[t][d], 0, 0, 0);
         }
     }
-    if (more) {
-      lk.store_tr_tile(nxt, tid);
-      lv.store_row_tile(nxt + KBYTES, tid);
-    }
+    wait_tile_loads();
     __syncthreads();
   }
 
@@ -621,7 +602,7 @@ bool attention_mfma_supported(int s, int h, int n_heads) {
 
 template <int DH, int QT>
 static bool launch_fwd(const bf16* qkv, bf16* o, float* lse, int s, int h, int n_heads, hipStream_t stream) {
-  constexpr int smem = 2 * (row_tile_bytes<DH>(kKeysPerTile) + tr_tile_bytes<DH>(kKeysPerTile));
+  constexpr int smem = 4 * tile_bytes<DH>();
   auto kern = attn_fwd_mfma_kernel<DH, QT>;
   static bool configured = false;
   if (!configured) {
@@ -629,7 +610,7 @@ static bool launch_fwd(const bf16* qkv, bf16* o, float* lse, int s, int h, int n
                                   smem));
     configured = true;
   }
-  dim3 grid(s / (128 * QT), n_heads);
+  dim3 grid(n_heads, s / (128 * QT));
   kern<<<grid, 256, smem, stream>>>(qkv, o, lse, s, h, 1.0f / sqrtf((float)DH));
   return launch_ok("attn_fwd_mfma_kernel");
 }
@@ -656,8 +637,8 @@ bool attention_forward_mfma(const void* qkv, void* o, float* lse, int s, int h, 
 template <int DH>
 static bool launch_bwd(const bf16* qkv, const bf16* o, const float* lse, const bf16* d_o, bf16* dqkv, float* delta,
                        int s, int h, int n_heads, hipStream_t stream) {
-  constexpr int smem_kv = 2 * (2 * tr_tile_bytes<DH>(kKeysPerTile) + 512);
-  constexpr int smem_q = 2 * (tr_tile_bytes<DH>(kKeysPerTile) + row_tile_bytes<DH>(kKeysPerTile));
+  constexpr int smem_kv = 2 * (2 * tile_bytes<DH>() + 512);
+  constexpr int smem_q = 4 * tile_bytes<DH>();
   auto kkv = attn_bwd_dkv_mfma_kernel<DH>;
   auto kq1 = attn_bwd_dq_mfma_kernel<DH, 1>;
   auto kq2 = attn_bwd_dq_mfma_kernel<DH, 2>;
@@ -673,12 +654,12 @@ static bool launch_bwd(const bf16* qkv, const bf16* o, const float* lse, const b
   }
   float scale = 1.0f / sqrtf((float)DH);
   attn_delta_mfma_path_kernel<DH><<<dim3(ceil_div(s, 4), n_heads), 256, 0, stream>>>(o, d_o, delta, s, h);
-  kkv<<<dim3(s / 128, n_heads), 256, smem_kv, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, scale);
+  kkv<<<dim3(n_heads, s / 128), 256, smem_kv, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, scale);
   bool big = false && s % 256 == 0 && (int64_t)(s / 256) * n_heads >= 512;
   if (big)
-    kq2<<<dim3(s / 256, n_heads), 256, smem_q, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, scale);
+    kq2<<<dim3(n_heads, s / 256), 256, smem_q, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, scale);
   else
-    kq1<<<dim3(s / 128, n_heads), 256, smem_q, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, scale);
+    kq1<<<dim3(n_heads, s / 128), 256, smem_q, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, scale);
   return launch_ok("attention backward MFMA kernels");
 }
 
