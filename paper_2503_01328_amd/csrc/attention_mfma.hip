@@ -32,6 +32,7 @@ namespace po {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
@@ -60,25 +61,34 @@ template <int DH> constexpr int tile_bytes() { return kKeysPerTile * DH * 2; }
 
 // HBM -> LDS without a register stop: a wave-level global_load_lds_dwordx4 writes 1 KiB of the tile
 // (lane L fills bytes 16 L ..), so each lane fetches the chunk that belongs at its position.  256
-// threads; `base` points at (row 0, first element of the head), rows are `ld` elements apart.
+// threads issue tile_bytes / 4096 loads each; between two loads of a wave the source advances by a
+// whole number of rows that is a multiple of 16, which leaves swz unchanged: the per-lane part of the
+// address is one 32-bit byte offset (tile_lane_offset, computed once per kernel) and everything else
+// is wave-uniform scalar arithmetic.  `base` points at (row 0, first element of the head), rows are
+// `ld` elements apart; base, row0 and wave must be wave-uniform.
 // Inline assembly on purpose: through the builtin the compiler waits for the load before every
 // later LDS read, which would undo the double buffering.  Callers wait (wait_tile_loads) before
 // the barrier that publishes the tile.
 template <int DH>
-__device__ __forceinline__ void load_tile_async(const bf16* __restrict__ base, int ld, int row0, char* tile,
-                                                int wave, int lane) {
+__device__ __forceinline__ unsigned tile_lane_offset(int ld, int wave, int lane) {
   constexpr int ROW_BYTES = DH * 2;
-  constexpr int PER_WAVE = tile_bytes<DH>() / 1024 / 4;
+  int byte = wave * 1024 + lane * 16;
+  int row = byte / ROW_BYTES;
+  int c = ((byte % ROW_BYTES) >> 4) ^ swz<DH>(row);
+  return (unsigned)((row * ld + c * 8) * 2);
+}
+template <int DH>
+__device__ __forceinline__ void load_tile_async(const bf16* __restrict__ base, int ld, int row0, char* tile,
+                                                int wave, unsigned lane_offset) {
+  constexpr int PER_WAVE = tile_bytes<DH>() / 4096;
+  constexpr int ROWS_PER_LOAD = 4096 / (DH * 2);  // rows the four waves cover with one load each
+  static_assert(ROWS_PER_LOAD % 16 == 0, "swz must not change between the loads of a lane");
 #pragma unroll
   for (int u = 0; u < PER_WAVE; ++u) {
-    int n = u * 4 + wave;
-    int byte = n * 1024 + lane * 16;
-    int row = byte / ROW_BYTES;
-    int c = ((byte % ROW_BYTES) >> 4) ^ swz<DH>(row);
-    const bf16* src = base + (size_t)(row0 + row) * ld + c * 8;
-    unsigned lds_addr = __builtin_amdgcn_readfirstlane(
-        (unsigned)(size_t)((void __attribute__((address_space(3)))*)(tile + n * 1024)));  // wave-uniform
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(src)
+    const bf16* src = base + (size_t)(row0 + u * ROWS_PER_LOAD) * ld;
+    unsigned lds_addr = (unsigned)(size_t)((void __attribute__((address_space(3)))*)(tile + (u * 4 + wave) * 1024));
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr),
+                 "v"(lane_offset), "s"(src)
                  : "memory");
   }
 }
@@ -138,7 +148,7 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_fwd_mfma_kernel(con
   constexpr int STAGE = 2 * KBYTES;  // K tile, V tile
   extern __shared__ __align__(16) char smem[];
 
-  int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   int half = lane >> 5, col = lane & 31;
   // Heads vary fastest in dispatch order and the query blocks with the most key tiles come first, over all
   // heads: causal work is triangular, and a heavy block that starts late would run on alone at the end.
@@ -173,8 +183,9 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_fwd_mfma_kernel(con
   }
 
   int nkv = (q0 + BQ) / kKeysPerTile;
-  load_tile_async<DH>(kbase, ld, 0, smem, wave, lane);
-  load_tile_async<DH>(vbase, ld, 0, smem + KBYTES, wave, lane);
+  const unsigned lane_off = tile_lane_offset<DH>(ld, wave, lane);
+  load_tile_async<DH>(kbase, ld, 0, smem, wave, lane_off);
+  load_tile_async<DH>(vbase, ld, 0, smem + KBYTES, wave, lane_off);
   wait_tile_loads();
   __syncthreads();
 
@@ -184,8 +195,8 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_fwd_mfma_kernel(con
     char* nxt = smem + ((kt + 1) & 1) * STAGE;
     bool more = kt + 1 < nkv;
     if (more) {  // the other stage was last read before the barrier that ended the previous iteration
-      load_tile_async<DH>(kbase, ld, (kt + 1) * kKeysPerTile, nxt, wave, lane);
-      load_tile_async<DH>(vbase, ld, (kt + 1) * kKeysPerTile, nxt + KBYTES, wave, lane);
+      load_tile_async<DH>(kbase, ld, (kt + 1) * kKeysPerTile, nxt, wave, lane_off);
+      load_tile_async<DH>(vbase, ld, (kt + 1) * kKeysPerTile, nxt + KBYTES, wave, lane_off);
     }
     int key0 = kt * kKeysPerTile;
     if (key0 <= qw0 + 32 * QT - 1) {  // some key of the tile is visible to some row of this wave
@@ -294,7 +305,8 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_fwd_mfma_kernel(con
 // kinds of reads: ds_read_b128 fragments (contraction over the head dimension, for S
 // and dP) and transposing fragments (contraction over the query rows, for dV and dK).
 //   S[q][key]  = Q K^T          P = exp(S scale - lse[q])
-//   dP[q][key] = dO V^T         dS = P (dP - delta[q])
+//   dP[q][key] = dO V^T         dS = P (dP - delta[q])      (lse and delta are folded into the
+//                                                            initial value of the two accumulators)
 //   dV[key]   += P^T dO         dK[key] += dS^T Q   (times scale at the end)
 // ==================================================================================
 template <int DH>
@@ -308,7 +320,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
   constexpr int STAGE = 2 * TBYTES + 512;  // Q tile, dO tile, lse[64], delta[64]
   extern __shared__ __align__(16) char smem[];
 
-  int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   int half = lane >> 5, col = lane & 31;
   int head = blockIdx.x;        // heads vary fastest in dispatch order: heaviest blocks of all heads first
   int kb0 = blockIdx.y * 128;   // first key of the block (the earliest blocks have the most query tiles)
@@ -322,12 +334,21 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
   const float c = scale * LOG2E;
 
   // K and V fragments of this wave's keys: B operands, column = key, contraction over the head dimension.
-  bf16x8 kf[KS], vf[KS];
+  // With DH = 128 the last two V fragments live in LDS (a private 16-byte slot per lane and fragment)
+  // instead of registers: at two waves per SIMD the register file cannot hold them without spilling.
+  constexpr int V_IN_LDS = DH == 128 ? 2 : 0;
+  constexpr int V_IN_REG = KS - V_IN_LDS;
+  char* vslot = smem + 2 * STAGE + (wave * V_IN_LDS * 64 + lane) * 16;
+  bf16x8 kf[KS], vf[V_IN_REG > 0 ? V_IN_REG : 1];
 #pragma unroll
   for (int kk = 0; kk < KS; ++kk) {
     const bf16* row = qkv + (size_t)(kw0 + col) * ld + head * DH + 16 * kk + 8 * half;
     kf[kk] = *reinterpret_cast<const bf16x8*>(row + h);
-    vf[kk] = *reinterpret_cast<const bf16x8*>(row + 2 * h);
+    bf16x8 v = *reinterpret_cast<const bf16x8*>(row + 2 * h);
+    if (kk < V_IN_REG)
+      vf[kk] = v;
+    else
+      *reinterpret_cast<bf16x8*>(vslot + (kk - V_IN_REG) * 1024) = v;
   }
   f32x16 dk[DT], dv[DT];
 #pragma unroll
@@ -336,18 +357,22 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
     for (int e = 0; e < 16; ++e) dk[d][e] = dv[d][e] = 0.f;
 
   int q_first = kb0 / kKeysPerTile, q_last = s / kKeysPerTile;  // query tiles [q_first, q_last)
-  float stat = 0.f;  // threads 0..63: lse * log2(e) of a row, threads 64..127: delta of a row
-  auto load_stats = [&](int q0) {
-    if (tid < 64)
-      stat = lse_h[q0 + tid] * LOG2E;
-    else if (tid < 128)
-      stat = delta_h[q0 + tid - 64];
-  };
+  // Row statistics enter as the initial value of the accumulators: S starts at -lse / scale, so that
+  // exp2((S - lse / scale) * scale * log2 e) = P, and dP starts at -delta, so that dS = P * acc.
+  // Threads 0..63 carry lse of a row, 64..127 delta of a row (128..255 repeat them and store nothing).  The
+  // load is unconditional and its value is not touched until store_stats, after the tile's arithmetic:
+  // any earlier use would wait for this load and with it for the tile loads issued just before it.
+  const float* stat_src = ((tid & 64) ? delta_h - 64 : lse_h) + (tid & 127);
+  const float stat_mul = (tid & 64) ? -1.0f : __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(
+                                                   __builtin_bit_cast(int, -1.0f / scale)));
+  float stat = 0.f;
+  auto load_stats = [&](int q0) { stat = stat_src[q0]; };
   auto store_stats = [&](char* stage) {
-    if (tid < 128) reinterpret_cast<float*>(stage + 2 * TBYTES)[tid] = stat;
+    if (tid < 128) reinterpret_cast<float*>(stage + 2 * TBYTES)[tid] = stat * stat_mul;
   };
-  load_tile_async<DH>(qbase, ld, q_first * kKeysPerTile, smem, wave, lane);
-  load_tile_async<DH>(dobase, h, q_first * kKeysPerTile, smem + TBYTES, wave, lane);
+  const unsigned q_lane_off = tile_lane_offset<DH>(ld, wave, lane), do_lane_off = tile_lane_offset<DH>(h, wave, lane);
+  load_tile_async<DH>(qbase, ld, q_first * kKeysPerTile, smem, wave, q_lane_off);
+  load_tile_async<DH>(dobase, h, q_first * kKeysPerTile, smem + TBYTES, wave, do_lane_off);
   load_stats(q_first * kKeysPerTile);
   store_stats(smem);
   wait_tile_loads();
@@ -361,15 +386,16 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
     const float* st_delta = st_lse + 64;
     char* nxt = smem + ((it + 1) & 1) * STAGE;
     bool more = qt + 1 < q_last;
-    // The swizzled LDS addresses and the per-lane global addresses are cheap to rebuild (a few XORs and
-    // multiply-adds); hiding the lane id from the optimiser here keeps it from carrying some thirty address
-    // registers across iterations and spilling accumulators instead.
+    // The swizzled LDS addresses are cheap to rebuild (a few XORs); hiding the lane id from the optimiser
+    // here keeps it from carrying some twenty address registers across iterations and spilling
+    // accumulators instead.
     int lane_l = lane;
     asm volatile("" : "+v"(lane_l));
     int col_l = lane_l & 31, half_l = lane_l >> 5;
+    const char* vslot_l = smem + 2 * STAGE + (wave * V_IN_LDS * 64 + lane_l) * 16;
     if (more) {  // the other stage was last read before the barrier that ended the previous iteration
-      load_tile_async<DH>(qbase, ld, (qt + 1) * kKeysPerTile, nxt, wave, lane_l);
-      load_tile_async<DH>(dobase, h, (qt + 1) * kKeysPerTile, nxt + TBYTES, wave, lane_l);
+      load_tile_async<DH>(qbase, ld, (qt + 1) * kKeysPerTile, nxt, wave, q_lane_off);
+      load_tile_async<DH>(dobase, h, (qt + 1) * kKeysPerTile, nxt + TBYTES, wave, do_lane_off);
       load_stats((qt + 1) * kKeysPerTile);
     }
     int q0 = qt * kKeysPerTile;
@@ -380,27 +406,30 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
       if (qs0 + 31 < kw0) continue;  // every row of this half is above every key of this wave
       f32x16 sacc, pacc;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) sacc[e] = pacc[e] = 0.f;
+      for (int b = 0; b < 4; ++b) {  // accumulator row 8 b + 4 half + r is query row 32 j + that
+        f32x4 l4 = *reinterpret_cast<const f32x4*>(st_lse + 32 * j + 8 * b + 4 * half_l);
+        f32x4 d4 = *reinterpret_cast<const f32x4*>(st_delta + 32 * j + 8 * b + 4 * half_l);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          sacc[4 * b + r] = l4[r];
+          pacc[4 * b + r] = d4[r];
+        }
+      }
 #pragma unroll
       for (int kk = 0; kk < KS; ++kk) {
         bf16x8 qa = read_row_fragment<DH>(qtile, 32 * j + col_l, 2 * kk + half_l);
         bf16x8 da = read_row_fragment<DH>(dotile, 32 * j + col_l, 2 * kk + half_l);
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[kk], sacc, 0, 0, 0);
-        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vf[kk], pacc, 0, 0, 0);
+        bf16x8 vb;
+        if (kk < V_IN_REG)
+          vb = vf[kk];
+        else
+          vb = *reinterpret_cast<const bf16x8*>(vslot_l + (kk - V_IN_REG) * 1024);
+        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vb, pacc, 0, 0, 0);
       }
       bool need_mask = qs0 < kw0 + 31;
 #pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        float4 l4 = *reinterpret_cast<const float4*>(st_lse + 32 * j + 8 * b + 4 * half);
-        float4 d4 = *reinterpret_cast<const float4*>(st_delta + 32 * j + 8 * b + 4 * half);
-        float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          int e = 4 * b + r;
-          sacc[e] = fast_exp2(sacc[e] * c - lv[r]);
-          pacc[e] -= dl[r];
-        }
-      }
+      for (int e = 0; e < 16; ++e) sacc[e] = fast_exp2(sacc[e] * c);
       if (need_mask) {  // only tiles that straddle the diagonal pay for the mask
 #pragma unroll
         for (int e = 0; e < 16; ++e)
@@ -459,7 +488,7 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_bwd_dq_mfma_kernel(
   constexpr int STAGE = 2 * KBYTES;  // K tile, V tile
   extern __shared__ __align__(16) char smem[];
 
-  int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   int half = lane >> 5, col = lane & 31;
   int head = blockIdx.x;  // dispatch order as in the forward kernel
   int qblock = gridDim.y - 1 - blockIdx.y;
@@ -493,8 +522,9 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_bwd_dq_mfma_kernel(
       for (int e = 0; e < 16; ++e) dq[t][d][e] = 0.f;
 
   int nkv = (q0 + BQ) / kKeysPerTile;
-  load_tile_async<DH>(kbase, ld, 0, smem, wave, lane);
-  load_tile_async<DH>(vbase, ld, 0, smem + KBYTES, wave, lane);
+  const unsigned lane_off = tile_lane_offset<DH>(ld, wave, lane);
+  load_tile_async<DH>(kbase, ld, 0, smem, wave, lane_off);
+  load_tile_async<DH>(vbase, ld, 0, smem + KBYTES, wave, lane_off);
   wait_tile_loads();
   __syncthreads();
 
@@ -504,8 +534,8 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_bwd_dq_mfma_kernel(
     char* nxt = smem + ((kt + 1) & 1) * STAGE;
     bool more = kt + 1 < nkv;
     if (more) {  // the other stage was last read before the barrier that ended the previous iteration
-      load_tile_async<DH>(kbase, ld, (kt + 1) * kKeysPerTile, nxt, wave, lane);
-      load_tile_async<DH>(vbase, ld, (kt + 1) * kKeysPerTile, nxt + KBYTES, wave, lane);
+      load_tile_async<DH>(kbase, ld, (kt + 1) * kKeysPerTile, nxt, wave, lane_off);
+      load_tile_async<DH>(vbase, ld, (kt + 1) * kKeysPerTile, nxt + KBYTES, wave, lane_off);
     }
     int key0 = kt * kKeysPerTile;
 #pragma unroll
@@ -637,7 +667,7 @@ bool attention_forward_mfma(const void* qkv, void* o, float* lse, int s, int h, 
 template <int DH>
 static bool launch_bwd(const bf16* qkv, const bf16* o, const float* lse, const bf16* d_o, bf16* dqkv, float* delta,
                        int s, int h, int n_heads, hipStream_t stream) {
-  constexpr int smem_kv = 2 * (2 * tile_bytes<DH>() + 512);
+  constexpr int smem_kv = 2 * (2 * tile_bytes<DH>() + 512) + (DH == 128 ? 8192 : 0);  // + V fragments kept in LDS
   constexpr int smem_q = 4 * tile_bytes<DH>();
   auto kkv = attn_bwd_dkv_mfma_kernel<DH>;
   auto kq1 = attn_bwd_dq_mfma_kernel<DH, 1>;
