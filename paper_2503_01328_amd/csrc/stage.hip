@@ -23,6 +23,8 @@
 #include <chrono>
 #include <deque>
 #include <map>
+#include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 #include <vector>
 
@@ -168,6 +170,7 @@ void build_slab_layout(const po_config& c, SlabLayout& sl) {
 struct PoolBuf {
   char* ptr = nullptr;
   hipEvent_t free_event = nullptr;  // work after which the buffer may be overwritten
+  hipStream_t guard_stream = nullptr;  // stream that event was recorded on
   bool guarded = false;
 };
 
@@ -185,9 +188,18 @@ struct Pool {
   int acquire(hipStream_t stream, int* out) {
     int idx;
     if (!free_list.empty()) {
-      idx = free_list.front();
-      free_list.pop_front();
-      if (bufs[idx].guarded) PO_HIP(hipStreamWaitEvent(stream, bufs[idx].free_event, 0));
+      // Oldest buffer that needs no wait (never used, or handed back on the taker's own stream, where stream
+      // order already protects it); else the oldest of all, whose guard event the taker's stream waits for.
+      auto pick = free_list.begin();
+      for (auto it = free_list.begin(); it != free_list.end(); ++it)
+        if (!bufs[*it].guarded || bufs[*it].guard_stream == stream) {
+          pick = it;
+          break;
+        }
+      idx = *pick;
+      free_list.erase(pick);
+      if (bufs[idx].guarded && bufs[idx].guard_stream != stream)
+        PO_HIP(hipStreamWaitEvent(stream, bufs[idx].free_event, 0));
     } else {
       if (cap && allocated() + buf_bytes > cap) {
         set_error("%s pool cap of %llu bytes reached (%zu buffers of %zu bytes in use)", host ? "host" : "device",
@@ -215,6 +227,7 @@ struct Pool {
   // Hands a buffer back; it may be overwritten once the work enqueued on `stream` so far is done.
   int release(int idx, hipStream_t stream) {
     PO_HIP(hipEventRecord(bufs[idx].free_event, stream));
+    bufs[idx].guard_stream = stream;
     bufs[idx].guarded = true;
     free_list.push_back(idx);
     --in_use;
@@ -796,6 +809,23 @@ static int collect_spans(po_stage* st) {
     if (sp.kind == 0) {
       if (!first) first = sp.start;
       last = sp.stop;
+    }
+  }
+  // PIPEOFFLOAD_TRACE=<file>: one line per span of the run, "kind start_ms stop_ms" from the first span's start
+  // (kind as in TimedSpan), appended; a run separator line "# run" first.
+  if (const char* path = getenv("PIPEOFFLOAD_TRACE")) {
+    if (!st->spans.empty()) {
+      if (FILE* f = fopen(path, "a")) {
+        fprintf(f, "# run\n");
+        hipEvent_t origin = st->spans[0].start;
+        for (const TimedSpan& sp : st->spans) {
+          float a = 0.f, b = 0.f;
+          PO_HIP(hipEventElapsedTime(&a, origin, sp.start));
+          PO_HIP(hipEventElapsedTime(&b, origin, sp.stop));
+          fprintf(f, "%d %.4f %.4f\n", sp.kind, a, b);
+        }
+        fclose(f);
+      }
     }
   }
   st->stats.compute_busy_s = busy[0];
