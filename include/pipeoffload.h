@@ -172,7 +172,11 @@ int po_reload(po_stage* st, int32_t mb, int32_t chunk);
 /* Runs a whole rank-local schedule: po_schedule_ops(schedule, d, rank, v, m, ratio, ...)
  * executed with the four calls above.  Arrays are HOST arrays of DEVICE pointers,
  * indexed [chunk * m + mb], length m * v.  dx entries may be NULL for embedding
- * units.  stats (HOST) may be NULL.  Returns after everything has drained. */
+ * units.  stats (HOST) may be NULL.  Returns after everything has drained.
+ * If the environment variable PIPEOFFLOAD_TRACE names a file, every run appends
+ * "# run" and one line per timed span, "kind start_ms stop_ms" measured from the
+ * first span (kind 0 compute pass, 1 D2H copy, 2 H2D copy, 3 pack/unpack, 4 GEMM
+ * launch, 5 attention launch; 4 and 5 only with profile_kernels). */
 int po_run_schedule(po_stage* st, int32_t schedule, int32_t n_microbatches, float offload_ratio,
                     const void* const* x_in, void* const* y_out, const void* const* dy, void* const* dx,
                     po_stats* stats);
