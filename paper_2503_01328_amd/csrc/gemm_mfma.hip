@@ -131,22 +131,17 @@ struct __attribute__((aligned(16))) bf16x8_t {
   bf16 v[8];
 };
 
+// `aux` is the piece of the auxiliary operand at the same place, loaded by the caller ahead of time:
+// u for the GeLU backward kind, the residual (if any) for the store kinds.
 template <int EPI>
-__device__ __forceinline__ void epilogue_row_piece(const Epilogue& e, int m, int n, const float* v) {
+__device__ __forceinline__ void epilogue_row_piece(const Epilogue& e, int m, int n, const float* v,
+                                                   const bf16x8_t& aux) {
   size_t idx = (size_t)m * e.ldc + n;
-  if (EPI == kEpiAccumulate) {
-    f32x4* p = reinterpret_cast<f32x4*>(e.acc_f32 + idx);
-    f32x4 o = *p;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) o[i] += v[i];
-    *p = o;
-    return;
-  }
   float a[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) a[i] = v[i];
   if (EPI == kEpiGeluBackward) {
-    bf16x8_t u = *reinterpret_cast<const bf16x8_t*>(static_cast<const bf16*>(e.gelu_u) + idx);
+    const bf16x8_t& u = aux;
     bf16x8_t o, g;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -164,9 +159,8 @@ __device__ __forceinline__ void epilogue_row_piece(const Epilogue& e, int m, int
     for (int i = 0; i < 8; ++i) a[i] += (float)b.v[i];
   }
   if (e.residual) {
-    bf16x8_t r = *reinterpret_cast<const bf16x8_t*>(static_cast<const bf16*>(e.residual) + idx);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) a[i] += (float)r.v[i];
+    for (int i = 0; i < 8; ++i) a[i] += (float)aux.v[i];
   }
   bf16x8_t o;
 #pragma unroll
@@ -304,27 +298,45 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int K, const bf16* __res
     int mrow0 = m0 + wm * (WTM * 32) + i * 32;
     int ncol0 = n0 + wn * STRIP_N;
     if (EPI == kEpiAccumulate) {
+      // fp32 read-modify-write of the strip: all loads of the old values are issued before the first
+      // add, so that a wave keeps 16 KiB in flight instead of one access at a time.
       constexpr int LPR = STRIP_N / 4;  // lanes per row, 4 floats each
       constexpr int RPI = 64 / LPR;     // rows per wave-wide access
+      constexpr int NIT = 32 / RPI;
+      f32x4 old[NIT];
+      float* cbase = ep.acc_f32 + (size_t)(mrow0 + lane / LPR) * ep.ldc + ncol0 + (lane % LPR) * 4;
 #pragma unroll
-      for (int it = 0; it < 32 / RPI; ++it) {
+      for (int it = 0; it < NIT; ++it)
+        old[it] = *reinterpret_cast<const f32x4*>(cbase + (size_t)(it * RPI) * ep.ldc);
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) {
         int r = it * RPI + lane / LPR;
         int c = (lane % LPR) * 4;
         f32x4 v = *reinterpret_cast<const f32x4*>(strip + r * STRIP_LD + c);
-        float vv[4] = {v[0], v[1], v[2], v[3]};
-        epilogue_row_piece<EPI>(ep, mrow0 + r, ncol0 + c, vv);
+        *reinterpret_cast<f32x4*>(cbase + (size_t)(it * RPI) * ep.ldc) = old[it] + v;
       }
     } else {
       constexpr int LPR = STRIP_N / 8;  // lanes per row, 8 values each
       constexpr int RPI = 64 / LPR;
+      constexpr int NIT = 32 / RPI;
+      // the strip's pieces of u (GeLU backward) or of the residual are all requested before the first use
+      bf16x8_t aux[NIT];
+      const bf16* aux_src = EPI == kEpiGeluBackward ? static_cast<const bf16*>(ep.gelu_u)
+                                                    : static_cast<const bf16*>(ep.residual);
+      if (aux_src) {
+        const bf16* abase = aux_src + (size_t)(mrow0 + lane / LPR) * ep.ldc + ncol0 + (lane % LPR) * 8;
 #pragma unroll
-      for (int it = 0; it < 32 / RPI; ++it) {
+        for (int it = 0; it < NIT; ++it)
+          aux[it] = *reinterpret_cast<const bf16x8_t*>(abase + (size_t)(it * RPI) * ep.ldc);
+      }
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) {
         int r = it * RPI + lane / LPR;
         int c = (lane % LPR) * 8;
         f32x4 v0 = *reinterpret_cast<const f32x4*>(strip + r * STRIP_LD + c);
         f32x4 v1 = *reinterpret_cast<const f32x4*>(strip + r * STRIP_LD + c + 4);
         float vv[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
-        epilogue_row_piece<EPI>(ep, mrow0 + r, ncol0 + c, vv);
+        epilogue_row_piece<EPI>(ep, mrow0 + r, ncol0 + c, vv, aux[it]);
       }
     }
   }
