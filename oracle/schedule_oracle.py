@@ -15,7 +15,17 @@ independent model, in plain Python integers, of what one pipeline rank executes:
   slot after the forward, latest slot before the backward; on a single rank
   with a dedicated copy queue these collapse to these two rules).
 
-Op tuples are (kind, mb, chunk) with kind in {"F", "B", "OFFLOAD", "RELOAD"}.
+* Generalized interleaved schedule (Section 3.2 "free lunch" and Section 3.3):
+  the backward is split into an input-gradient pass B and a weight-gradient
+  pass W that directly follows it; the inner loop repeats g microbatches
+  (ceil(d/2) <= g <= d) instead of d; rank i forwards g(v-1) + d - i units
+  before its first backward.  g = d is the schedule the paper calls GIS
+  (warm-up d(v-1) + d - i, peak dv on rank 0), g = ceil(d/2) is GIS-H; in
+  general the rank-0 peak is g(v-1) + d.
+* pipeline_timeline runs the op lists of all d ranks against each other with
+  given pass durations, which yields the bubble sizes of Table 1.
+
+Op tuples are (kind, mb, chunk) with kind in {"F", "B", "W", "OFFLOAD", "RELOAD"}.
 """
 from __future__ import annotations
 
@@ -60,7 +70,85 @@ def interleaved_one_f_one_b(d, rank, v, m):
     return ops
 
 
-def compute_passes(schedule, d, rank, v, m):
+def _grouped_unit(k, g, v, backward):
+    group, within = divmod(k, g * v)
+    chunk = within // g
+    mb = group * g + within % g
+    return (mb, v - 1 - chunk) if backward else (mb, chunk)
+
+
+def generalized_interleaved(d, rank, v, m, g=None):
+    """Compute passes of the generalized interleaved schedule with split backward
+    on ``rank`` (Sections 3.2 and 3.3): the k-th forward handles microbatch group
+    k // (g v), chunk (k // g) % v; the backward passes walk the chunks in reverse
+    and each input-gradient pass B is directly followed by its weight-gradient
+    pass W.  g defaults to d (GIS)."""
+    g = d if g is None else g
+    if not (math.ceil(d / 2) <= g <= d):
+        raise ValueError("the group size must lie in [ceil(d/2), d]")
+    if m % g:
+        raise ValueError("the schedule needs m to be a multiple of the group size")
+    total = m * v
+    warm = min(g * (v - 1) + d - rank - 1, total)
+    ops = [("F",) + _grouped_unit(k, g, v, False) for k in range(warm)]
+    for j in range(total - warm):
+        ops.append(("F",) + _grouped_unit(warm + j, g, v, False))
+        ops.append(("B",) + _grouped_unit(j, g, v, True))
+        ops.append(("W",) + _grouped_unit(j, g, v, True))
+    for j in range(total - warm, total):
+        ops.append(("B",) + _grouped_unit(j, g, v, True))
+        ops.append(("W",) + _grouped_unit(j, g, v, True))
+    return ops
+
+
+def pipeline_timeline(rank_ops, d, v, t_f, t_b, t_w):
+    """Runs the op lists of all d ranks (compute passes only) against each other.
+
+    Model stage c d + i lives on rank i as chunk c.  F(mb, c) on rank i needs the
+    same forward on rank i-1, or on rank d-1 for chunk c-1 when i = 0.  B(mb, c)
+    needs its own forward and the same backward on rank i+1, or on rank 0 for chunk
+    c+1 when i = d-1.  W needs its own B.  A rank whose list has no W passes runs
+    fused backwards of duration t_b + t_w.  Returns (makespan, finished) where
+    finished is False when the lists deadlock."""
+    done = {}
+    ptr = [0] * d
+    free = [0.0] * d
+    split = [any(op[0] == "W" for op in ops) for ops in rank_ops]
+    progress = True
+    while progress:
+        progress = False
+        for i in range(d):
+            while ptr[i] < len(rank_ops[i]):
+                kind, mb, c = rank_ops[i][ptr[i]]
+                if kind == "F":
+                    deps = [(i - 1, "F", mb, c)] if i > 0 else ([(d - 1, "F", mb, c - 1)] if c > 0 else [])
+                    t = t_f
+                elif kind == "B":
+                    deps = [(i, "F", mb, c)]
+                    if i < d - 1:
+                        deps.append((i + 1, "B", mb, c))
+                    elif c < v - 1:
+                        deps.append((0, "B", mb, c + 1))
+                    t = t_b if split[i] else t_b + t_w
+                elif kind == "W":
+                    deps = [(i, "B", mb, c)]
+                    t = t_w
+                else:
+                    raise ValueError(kind)
+                if any(dep not in done for dep in deps):
+                    break
+                start = max([free[i]] + [done[dep] for dep in deps])
+                free[i] = start + t
+                done[(i, kind, mb, c)] = free[i]
+                ptr[i] += 1
+                progress = True
+    finished = all(ptr[i] == len(rank_ops[i]) for i in range(d))
+    return max(free), finished
+
+
+def compute_passes(schedule, d, rank, v, m, g=None):
+    if schedule == "gis":
+        return generalized_interleaved(d, rank, v, m, g)
     if schedule == "1f1b":
         if v != 1:
             raise ValueError("1F1B has one chunk per rank")
@@ -122,9 +210,12 @@ def simulate(ops):
     """Walk an op list with zero-time copies.  Returns a dict with the peak
     number of units in flight (forwarded, not yet backwarded), the peak number
     resident on the device, forwards before the first backward, and a list of
-    violated invariants (empty when the list is a valid schedule)."""
+    violated invariants (empty when the list is a valid schedule).  With split
+    backward passes a unit leaves the in-flight count at B (the paper's activation
+    count) and leaves the device at W."""
     state = {}
     errors = []
+    split = any(op[0] == "W" for op in ops)
     in_flight = resident = peak_in_flight = peak_resident = 0
     forwards_before_first_backward = None
     n_forward = 0
@@ -153,8 +244,16 @@ def simulate(ops):
                 errors.append(f"op {n}: backward of unit {u} in state {st}")
             if forwards_before_first_backward is None:
                 forwards_before_first_backward = n_forward
-            state[u] = "DONE"
             in_flight -= 1
+            if split:
+                state[u] = "WEIGHT-PENDING"  # its activations stay on the device until W
+            else:
+                state[u] = "DONE"
+                resident -= 1
+        elif kind == "W":
+            if st != "WEIGHT-PENDING":
+                errors.append(f"op {n}: weight-gradient pass of unit {u} in state {st}")
+            state[u] = "DONE"
             resident -= 1
         else:
             errors.append(f"op {n}: unknown kind {kind}")
@@ -169,7 +268,8 @@ def simulate(ops):
 
 def check_dependencies(passes, v):
     """Within one microbatch a rank must forward chunk c before chunk c+1 and
-    backward chunk c+1 before chunk c, and forward a unit before its backward."""
+    backward chunk c+1 before chunk c, forward a unit before its backward, and run
+    a weight-gradient pass after the unit's input-gradient pass."""
     pos = {(kind, mb, c): n for n, (kind, mb, c) in enumerate(passes)}
     bad = []
     for (kind, mb, c), n in pos.items():
@@ -179,6 +279,8 @@ def check_dependencies(passes, v):
             bad.append(("B-order", mb, c))
         if kind == "B" and pos[("F", mb, c)] > n:
             bad.append(("B-before-F", mb, c))
+        if kind == "W" and pos[("B", mb, c)] > n:
+            bad.append(("W-before-B", mb, c))
     return bad
 
 

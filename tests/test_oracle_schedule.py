@@ -111,3 +111,111 @@ def test_saved_bytes_is_20sh_plus_lse():
     # Appendix C: 20 b s h bytes per layer at two bytes per element
     assert sch.saved_bytes_per_layer(4096, 4096, 32, 2) == 20 * 4096 * 4096 + 4 * 32 * 4096
     assert sch.saved_bytes_per_layer(2048, 2048, 16, 2) - 4 * 16 * 2048 == 20 * 2048 * 2048
+
+
+# ---- generalized interleaved schedule with split backward (Sections 3.2, 3.3; Table 1) -------------------------
+GIS_CASES = [(4, 2, 8), (4, 2, 16), (8, 2, 32), (4, 3, 12), (8, 4, 32), (6, 2, 12)]
+TIMES = [(1.0, 1.0, 1.0), (1.0, 1.3, 0.7), (2.0, 2.5, 1.5)]
+
+
+def _bubble(rank_ops, d, v, m, t):
+    makespan, finished = sch.pipeline_timeline(rank_ops, d, v, *t)
+    assert finished  # the d op lists run against each other without deadlock
+    return makespan - m * v * sum(t)
+
+
+@pytest.mark.parametrize("d,v,m", GIS_CASES)
+@pytest.mark.parametrize("t", TIMES)
+def test_table1_bubbles(d, v, m, t):
+    tf, tb, tw = t
+    # 1F1B with the v stages of a device merged into one pass: v (d-1)(T_F + T_B + T_W)
+    ops = [sch.one_f_one_b(d, i, m) for i in range(d)]
+    merged = (v * tf, v * tb, v * tw)
+    makespan, finished = sch.pipeline_timeline(ops, d, 1, *merged)
+    assert finished and abs(makespan - m * sum(merged) - v * (d - 1) * (tf + tb + tw)) < 1e-9
+    # interleaved 1F1B: (d-1)(T_F + T_B + T_W)
+    ops = [sch.interleaved_one_f_one_b(d, i, v, m) for i in range(d)]
+    assert abs(_bubble(ops, d, v, m, t) - (d - 1) * (tf + tb + tw)) < 1e-9
+    # GIS (split backward, shorter warm-up): (d-1)(T_F + T_B)
+    ops = [sch.generalized_interleaved(d, i, v, m) for i in range(d)]
+    assert abs(_bubble(ops, d, v, m, t) - (d - 1) * (tf + tb)) < 1e-9
+    # GIS-H (g = d/2): (d-1)(T_F + T_B) + (v-1) d / 2 (T_F + T_B - T_W)
+    if d % 2 == 0 and m % (d // 2) == 0:
+        ops = [sch.generalized_interleaved(d, i, v, m, d // 2) for i in range(d)]
+        assert abs(_bubble(ops, d, v, m, t) - ((d - 1) * (tf + tb) + (v - 1) * d / 2 * (tf + tb - tw))) < 1e-9
+
+
+@pytest.mark.parametrize("d,v,m", GIS_CASES)
+def test_general_group_size_memory_and_extra_bubble(d, v, m):
+    for g in range(-(-d // 2), d + 1):
+        if m % g:
+            continue
+        rank_ops = [sch.generalized_interleaved(d, i, v, m, g) for i in range(d)]
+        for i, ops in enumerate(rank_ops):
+            r = sch.simulate(ops)
+            assert r["errors"] == []
+            assert sch.check_dependencies(ops, v) == []
+            assert r["forwards_before_first_backward"] == min(g * (v - 1) + d - i, m * v)  # Section 3.2 for g = d
+            if i == 0:
+                assert r["peak_in_flight"] == g * (v - 1) + d  # Section 3.3; dv for g = d
+            # W directly follows its B
+            for n, op in enumerate(ops):
+                if op[0] == "B":
+                    assert ops[n + 1] == ("W",) + op[1:]
+            assert sorted(o[1:] for o in ops if o[0] == "F") == sorted((mb, c) for mb in range(m) for c in range(v))
+        # Section 3.3: (d - g)(v - 1) extra bubbles over GIS (unit pass times)
+        assert abs(_bubble(rank_ops, d, v, m, (1.0, 1.0, 1.0)) - (2 * (d - 1) + (d - g) * (v - 1))) < 1e-9
+
+
+def test_gis_peak_is_below_interleaved_1f1b():
+    d, v, m = 8, 2, 32
+    assert sch.simulate(sch.interleaved_one_f_one_b(d, 0, v, m))["peak_in_flight"] == d * v + d - 1
+    assert sch.simulate(sch.generalized_interleaved(d, 0, v, m))["peak_in_flight"] == d * v
+    assert sch.simulate(sch.generalized_interleaved(d, 0, v, m, 4))["peak_in_flight"] == 4 * (v - 1) + d
+
+
+def test_gis_rejects_bad_group_sizes():
+    with pytest.raises(ValueError):
+        sch.generalized_interleaved(8, 0, 2, 32, 3)  # below ceil(d/2): stage dependencies cannot be met
+    with pytest.raises(ValueError):
+        sch.generalized_interleaved(8, 0, 2, 32, 9)
+    with pytest.raises(ValueError):
+        sch.generalized_interleaved(8, 0, 2, 30, 8)
+
+
+def test_group_size_below_half_the_depth_really_stalls():
+    # the lower bound ceil(d/2) is not arbitrary: built the same way with a smaller group the ranks wait on each
+    # other far beyond the Table 1 bubble (or never finish)
+    d, v, m, g = 8, 2, 24, 3
+    total = m * v
+
+    def ops_for(rank):
+        warm = min(g * (v - 1) + d - rank - 1, total)
+        ops = [("F",) + sch._grouped_unit(k, g, v, False) for k in range(warm)]
+        for j in range(total - warm):
+            ops += [("F",) + sch._grouped_unit(warm + j, g, v, False), ("B",) + sch._grouped_unit(j, g, v, True),
+                    ("W",) + sch._grouped_unit(j, g, v, True)]
+        for j in range(total - warm, total):
+            ops += [("B",) + sch._grouped_unit(j, g, v, True), ("W",) + sch._grouped_unit(j, g, v, True)]
+        return ops
+
+    makespan, finished = sch.pipeline_timeline([ops_for(i) for i in range(d)], d, v, 1.0, 1.0, 1.0)
+    assert (not finished) or makespan - 3 * total > 2 * (d - 1) + (d - g) * (v - 1)
+
+
+@pytest.mark.parametrize("ratio", [0.0, 0.5, 1.0])
+@pytest.mark.parametrize("prefetch", [1, 2, 3])
+@pytest.mark.parametrize("g", [4, 8])
+def test_offload_invariants_with_split_backward(ratio, prefetch, g):
+    d, v, m = 8, 2, 32
+    for rank in (0, d - 1):
+        passes = sch.compute_passes("gis", d, rank, v, m, g)
+        sel = sch.selected_units(m, v, ratio)
+        ops = sch.with_offload(passes, sel, prefetch)
+        r = sch.simulate(ops)
+        assert r["errors"] == []
+        assert [o for o in ops if o[0] in "FBW"] == passes
+        assert sum(o[0] == "OFFLOAD" for o in ops) == len(sel) == sum(o[0] == "RELOAD" for o in ops)
+        assert r["peak_in_flight"] == sch.simulate(passes)["peak_in_flight"]
+        if ratio == 1.0 and rank == 0:
+            assert r["peak_resident"] <= 1 + -(-(prefetch + 1) // 2)  # the unit in B/W plus the prefetched ones
