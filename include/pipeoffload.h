@@ -38,7 +38,10 @@ typedef enum { PO_F32 = 0, PO_BF16 = 1 } po_dtype;
 
 /* Rank-local op order.  1F1B: Table 1 first row / Appendix A.  Interleaved 1F1B:
  * Section 3.1 (warm-up d(v-1) + 2(d-i) - 1 forwards on rank i). */
-typedef enum { PO_SCHED_1F1B = 0, PO_SCHED_1F1B_INTERLEAVED = 1 } po_schedule;
+/* PO_SCHED_GIS: generalized interleaved schedule with split backward (Sections 3.2, 3.3): every input-gradient
+ * pass B is directly followed by the unit's weight-gradient pass W, warm-up g(v-1) + d-i-1 forwards, inner loop
+ * over g = po_config.group microbatches (g = d: the paper's GIS, g = ceil(d/2): GIS-H). */
+typedef enum { PO_SCHED_1F1B = 0, PO_SCHED_1F1B_INTERLEAVED = 1, PO_SCHED_GIS = 2 } po_schedule;
 
 /* How a whole-job offload ratio picks units.  ALTERNATE_MB: microbatch j is
  * offloaded iff floor((j+1) r) > floor(j r).  LONGEST_LIFESPAN (Section 2):
@@ -71,6 +74,7 @@ typedef struct po_config {
   int32_t staged_copies;   /* 0: copy slabs in place; 1: pack into a staging buffer before D2H, unpack after H2D */
   int32_t debug_poison;    /* 1: fill a slab with a NaN pattern whenever it is released */
   int32_t profile_kernels; /* 1: po_run_schedule brackets every GEMM and attention launch with HIP events */
+  int32_t group;           /* g of PO_SCHED_GIS, ceil(d/2) <= g <= d; 0 = d */
   float ln_eps;            /* LayerNorm epsilon */
   uint64_t host_pool_cap_bytes;   /* 0 = unlimited; else PO_E_HOST_OOM beyond it */
   uint64_t device_pool_cap_bytes; /* 0 = unlimited; else PO_E_DEVICE_OOM beyond it */
@@ -85,7 +89,8 @@ typedef struct po_param_desc {
   int64_t rows, cols;   /* vectors have rows == 1 */
 } po_param_desc;
 
-/* kind: 0 forward, 1 backward, 2 offload, 3 reload. */
+/* kind: 0 forward, 1 backward (input-gradient pass B in a schedule with W passes), 2 offload, 3 reload,
+ * 4 weight-gradient pass W. */
 typedef struct po_op {
   int32_t kind, mb, chunk;
   float ratio; /* offload: fraction of the unit's layers (rounded up, lowest layers first) */
@@ -132,7 +137,7 @@ int po_saved_bytes_per_layer(const po_config* cfg, uint64_t* bytes);
 /* The op list one rank executes, offload and reload ops included (Section 4.2 on a
  * single rank: offload right after the forward, reload `prefetch` compute passes
  * ahead of the backward).  out may be NULL to query *n. */
-int po_schedule_ops(int32_t schedule, int32_t d, int32_t rank, int32_t v, int32_t m, float ratio,
+int po_schedule_ops(int32_t schedule, int32_t d, int32_t rank, int32_t v, int32_t m, int32_t group, float ratio,
                     int32_t policy, int32_t prefetch, po_op* out, int32_t* n);
 
 /* Eq. 1: k = 10 / (3 (6h + s)) * B_c / B_o, with B_c in flop/s and B_o in byte/s. */
@@ -159,6 +164,15 @@ int po_stage_forward(po_stage* st, int32_t mb, int32_t chunk, const void* x_in, 
  * dx: DEVICE [s, h], may be NULL when the unit starts with the embedding.
  * LayerNorm and GeLU outputs are recomputed (Appendix C).  Frees the unit. */
 int po_stage_backward(po_stage* st, int32_t mb, int32_t chunk, const void* dy, void* dx);
+
+/* Split backward (Section 3.2, zero-bubble strategy).  po_stage_backward_input is the B pass: it computes the
+ * activation gradients only (dx as in po_stage_backward) and keeps, in a library-owned buffer, what the W pass
+ * needs; the unit keeps its activations.  po_stage_backward_weight is the W pass: it adds the unit's parameter
+ * gradients (the same values, bit for bit, as the fused po_stage_backward) and frees the unit.  dy must stay
+ * valid and unchanged until the W pass has run on the device.  A unit between its B and W pass can be neither
+ * offloaded nor reloaded (PO_E_STATE). */
+int po_stage_backward_input(po_stage* st, int32_t mb, int32_t chunk, const void* dy, void* dx);
+int po_stage_backward_weight(po_stage* st, int32_t mb, int32_t chunk);
 
 /* Asynchronously moves ceil(ratio * Lu) layers (lowest first) of a RESIDENT unit
  * to pinned host memory on the offload stream once its forward has finished, and

@@ -23,16 +23,17 @@ if not os.path.exists(_LIB_PATH):
 lib = C.CDLL(_LIB_PATH)
 
 PO_F32, PO_BF16 = 0, 1
-PO_SCHED_1F1B, PO_SCHED_1F1B_INTERLEAVED = 0, 1
+PO_SCHED_1F1B, PO_SCHED_1F1B_INTERLEAVED, PO_SCHED_GIS = 0, 1, 2
 PO_SEL_ALTERNATE_MB, PO_SEL_LONGEST_LIFESPAN = 0, 1
 PO_OK, PO_E_INVAL, PO_E_STATE, PO_E_DEVICE_OOM, PO_E_HOST_OOM, PO_E_HIP = 0, -1, -2, -3, -4, -5
-OP_KINDS = ("F", "B", "OFFLOAD", "RELOAD")
+OP_KINDS = ("F", "B", "OFFLOAD", "RELOAD", "W")
 
 
 class po_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "n_chunks", "hidden", "n_heads", "ffn", "seq", "vocab", "dtype", "pipeline_degree", "rank",
-        "prefetch_passes", "copy_streams", "select_policy", "staged_copies", "debug_poison", "profile_kernels")] + [
+        "prefetch_passes", "copy_streams", "select_policy", "staged_copies", "debug_poison", "profile_kernels",
+        "group")] + [
         ("ln_eps", C.c_float), ("host_pool_cap_bytes", C.c_uint64), ("device_pool_cap_bytes", C.c_uint64)]
 
 
@@ -64,7 +65,7 @@ EXPORTS = {
     "po_param_count": (C.c_int, [C.POINTER(po_config), C.POINTER(C.c_int64)]),
     "po_param_layout": (C.c_int, [C.POINTER(po_config), C.POINTER(po_param_desc), C.POINTER(C.c_int32)]),
     "po_saved_bytes_per_layer": (C.c_int, [C.POINTER(po_config), C.POINTER(C.c_uint64)]),
-    "po_schedule_ops": (C.c_int, [C.c_int32] * 5 + [C.c_float, C.c_int32, C.c_int32, C.POINTER(po_op),
+    "po_schedule_ops": (C.c_int, [C.c_int32] * 6 + [C.c_float, C.c_int32, C.c_int32, C.POINTER(po_op),
                                                     C.POINTER(C.c_int32)]),
     "po_offload_k": (C.c_double, [C.c_int32, C.c_int32, C.c_double, C.c_double]),
     "po_stage_create": (C.c_int, [C.POINTER(po_config), C.c_void_p, C.POINTER(C.c_void_p)]),
@@ -72,6 +73,8 @@ EXPORTS = {
     "po_bind_params": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "po_stage_forward": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
     "po_stage_backward": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
+    "po_stage_backward_input": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
+    "po_stage_backward_weight": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32]),
     "po_offload": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_float]),
     "po_reload": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32]),
     "po_run_schedule": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.POINTER(C.c_void_p),
@@ -162,11 +165,11 @@ def po_saved_bytes_per_layer(cfg) -> int:
     return b.value
 
 
-def po_schedule_ops(schedule, d, rank, v, m, ratio, policy=0, prefetch=2):
+def po_schedule_ops(schedule, d, rank, v, m, ratio, policy=0, prefetch=2, group=0):
     n = C.c_int32(0)
-    _check(lib.po_schedule_ops(schedule, d, rank, v, m, ratio, policy, prefetch, None, C.byref(n)))
+    _check(lib.po_schedule_ops(schedule, d, rank, v, m, group, ratio, policy, prefetch, None, C.byref(n)))
     arr = (po_op * n.value)()
-    _check(lib.po_schedule_ops(schedule, d, rank, v, m, ratio, policy, prefetch, arr, C.byref(n)))
+    _check(lib.po_schedule_ops(schedule, d, rank, v, m, group, ratio, policy, prefetch, arr, C.byref(n)))
     return [(OP_KINDS[o.kind], o.mb, o.chunk) for o in arr]
 
 
@@ -194,6 +197,14 @@ def po_stage_forward(stage, mb, chunk, x_in, y_out):
 
 def po_stage_backward(stage, mb, chunk, dy, dx):
     _check(lib.po_stage_backward(stage, mb, chunk, _ptr(dy), _ptr(dx)))
+
+
+def po_stage_backward_input(stage, mb, chunk, dy, dx):
+    _check(lib.po_stage_backward_input(stage, mb, chunk, _ptr(dy), _ptr(dx)))
+
+
+def po_stage_backward_weight(stage, mb, chunk):
+    _check(lib.po_stage_backward_weight(stage, mb, chunk))
 
 
 def po_offload(stage, mb, chunk, ratio):

@@ -228,10 +228,10 @@ size_t layernorm_backward_workspace(int rows, int h) {
 }
 
 bool layernorm_backward(int dtype, const void* dn, const void* x, const void* gain, const void* dres, void* dx,
-                        float* dgain, float* dshift, float* workspace, int rows, int h, float eps,
+                        float* dgain, float* dshift, float* workspace, int rows, int h, float eps, int parts,
                         hipStream_t stream) {
-  if (rows <= 0 || h <= 0 || h % 8 != 0 || !workspace) {
-    set_error("layernorm_backward: rows=%d h=%d workspace=%p", rows, h, (void*)workspace);
+  if (rows <= 0 || h <= 0 || h % 8 != 0 || !workspace || !(parts & (kLnInputGrad | kLnParamGrad))) {
+    set_error("layernorm_backward: rows=%d h=%d workspace=%p parts=%d", rows, h, (void*)workspace, parts);
     return false;
   }
   float* stats = workspace;
@@ -239,18 +239,23 @@ bool layernorm_backward(int dtype, const void* dn, const void* x, const void* ga
   int n_chunks = reduce_chunks(rows);
   int rows_per_chunk = ceil_div(rows, n_chunks);
   dim3 g1(ceil_div(rows, 4)), g2(ceil_div(h, 128), n_chunks), g3(ceil_div(h, 64));
-  if (dtype == kF32) {
-    ln_backward_rows_kernel<float><<<g1, 256, 0, stream>>>((const float*)dn, (const float*)x, (const float*)gain,
-                                                           (const float*)dres, (float*)dx, stats, rows, h, eps);
-    ln_backward_cols_kernel<float><<<g2, 256, 0, stream>>>((const float*)dn, (const float*)x, stats, partials,
-                                                           rows, h, rows_per_chunk);
-  } else {
-    ln_backward_rows_kernel<bf16><<<g1, 256, 0, stream>>>((const bf16*)dn, (const bf16*)x, (const bf16*)gain,
-                                                          (const bf16*)dres, (bf16*)dx, stats, rows, h, eps);
-    ln_backward_cols_kernel<bf16><<<g2, 256, 0, stream>>>((const bf16*)dn, (const bf16*)x, stats, partials, rows,
-                                                          h, rows_per_chunk);
+  if (parts & kLnInputGrad) {  // dx and the row statistics (kept in the workspace for the parameter part)
+    if (dtype == kF32)
+      ln_backward_rows_kernel<float><<<g1, 256, 0, stream>>>((const float*)dn, (const float*)x, (const float*)gain,
+                                                             (const float*)dres, (float*)dx, stats, rows, h, eps);
+    else
+      ln_backward_rows_kernel<bf16><<<g1, 256, 0, stream>>>((const bf16*)dn, (const bf16*)x, (const bf16*)gain,
+                                                            (const bf16*)dres, (bf16*)dx, stats, rows, h, eps);
   }
-  chunk_partials_final_kernel<2><<<g3, 256, 0, stream>>>(partials, dgain, dshift, h, n_chunks);
+  if (parts & kLnParamGrad) {  // dgain, dshift from (dn, x) and the statistics an input-gradient call left
+    if (dtype == kF32)
+      ln_backward_cols_kernel<float><<<g2, 256, 0, stream>>>((const float*)dn, (const float*)x, stats, partials,
+                                                             rows, h, rows_per_chunk);
+    else
+      ln_backward_cols_kernel<bf16><<<g2, 256, 0, stream>>>((const bf16*)dn, (const bf16*)x, stats, partials, rows,
+                                                            h, rows_per_chunk);
+    chunk_partials_final_kernel<2><<<g3, 256, 0, stream>>>(partials, dgain, dshift, h, n_chunks);
+  }
   return launch_ok("layernorm_backward kernels");
 }
 

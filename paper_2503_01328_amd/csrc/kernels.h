@@ -14,8 +14,11 @@ const char* get_error();
 bool layernorm_forward(int dtype, const void* x, const void* gain, const void* shift, void* y, int rows, int h,
                        float eps, hipStream_t stream);
 size_t layernorm_backward_workspace(int rows, int h);
+// parts: kLnInputGrad writes dx (= dres + LayerNorm input gradient) and the row statistics into the workspace;
+// kLnParamGrad adds the gain / shift gradients, reading the statistics an earlier or the same call left there.
+enum { kLnInputGrad = 1, kLnParamGrad = 2 };
 bool layernorm_backward(int dtype, const void* dn, const void* x, const void* gain, const void* dres, void* dx,
-                        float* dgain, float* dshift, float* workspace, int rows, int h, float eps,
+                        float* dgain, float* dshift, float* workspace, int rows, int h, float eps, int parts,
                         hipStream_t stream);
 size_t colsum_workspace(int rows, int n);
 bool colsum_accumulate(int dtype, const void* x, float* acc, float* workspace, int rows, int n, hipStream_t stream);

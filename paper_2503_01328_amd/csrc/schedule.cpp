@@ -8,6 +8,11 @@
 // group; backwards visit the chunks in reverse.  Warm-up is d(v-1) + 2(d-i-1)
 // forwards, which gives the paper's d(v-1) + 2(d-i) - 1 forwards before the
 // first backward and dv + d - 1 units in flight on rank 0.
+// Generalized interleaved schedule with split backward (Sections 3.2 and 3.3): the
+// inner loop repeats g microbatches (ceil(d/2) <= g <= d), rank i runs
+// g(v-1) + d-i-1 warm-up forwards, and every input-gradient pass B is directly
+// followed by the unit's weight-gradient pass W.  g = d is the paper's GIS (dv units
+// in flight on rank 0), g = ceil(d/2) its GIS-H; in general the peak is g(v-1) + d.
 // Offload placement (Section 4.2 collapsed to one rank with its own copy queues):
 // OFFLOAD directly after the unit's forward; RELOAD `prefetch` compute passes
 // before the unit's backward, never before its OFFLOAD.
@@ -24,14 +29,15 @@ struct Pass {
   int kind, mb, chunk;
 };
 
-static void unit_of(int n, int d, int v, bool backward, int& mb, int& chunk) {
-  int group = n / (d * v), within = n % (d * v);
-  chunk = within / d;
+// n-th forward (or backward) of a bi-level order whose inner loop repeats g microbatches
+static void unit_of(int n, int g, int v, bool backward, int& mb, int& chunk) {
+  int group = n / (g * v), within = n % (g * v);
+  chunk = within / g;
   if (backward) chunk = v - 1 - chunk;
-  mb = group * d + within % d;
+  mb = group * g + within % g;
 }
 
-static bool compute_passes(int schedule, int d, int rank, int v, int m, std::vector<Pass>& out) {
+static bool compute_passes(int schedule, int d, int rank, int v, int m, int g, std::vector<Pass>& out) {
   if (d < 1 || rank < 0 || rank >= d || v < 1 || m < 1) {
     set_error("schedule: d=%d rank=%d v=%d m=%d", d, rank, v, m);
     return false;
@@ -51,6 +57,19 @@ static bool compute_passes(int schedule, int d, int rank, int v, int m, std::vec
     }
     total = m * v;
     warm = (v - 1) * d + 2 * (d - rank - 1);
+    g = d;
+  } else if (schedule == PO_SCHED_GIS) {
+    if (g <= 0) g = d;
+    if (g > d || 2 * g < d) {
+      set_error("schedule: group size %d outside [ceil(d/2), d] for d=%d", g, d);
+      return false;
+    }
+    if (m % g != 0) {
+      set_error("schedule: m (%d) must be a multiple of the group size (%d)", m, g);
+      return false;
+    }
+    total = m * v;
+    warm = g * (v - 1) + d - rank - 1;
   } else {
     set_error("schedule: unknown schedule %d", schedule);
     return false;
@@ -63,16 +82,21 @@ static bool compute_passes(int schedule, int d, int rank, int v, int m, std::vec
       p.mb = n;
       p.chunk = 0;
     } else {
-      unit_of(n, d, v, kind == 1, p.mb, p.chunk);
+      unit_of(n, g, v, kind != 0, p.mb, p.chunk);
     }
     out.push_back(p);
   };
+  const bool split = schedule == PO_SCHED_GIS;
   for (int n = 0; n < warm; ++n) emit(0, n);
   for (int n = 0; n + warm < total; ++n) {
     emit(0, warm + n);
     emit(1, n);
+    if (split) emit(4, n);
   }
-  for (int n = total - warm; n < total; ++n) emit(1, n);
+  for (int n = total - warm; n < total; ++n) {
+    emit(1, n);
+    if (split) emit(4, n);
+  }
   return true;
 }
 
@@ -82,14 +106,14 @@ static bool unit_selected(int mb, int chunk, int v, float ratio, int policy) {
   return floor((mb + 1) * (double)ratio + eps) > floor(mb * (double)ratio + eps);
 }
 
-bool build_schedule(int schedule, int d, int rank, int v, int m, float ratio, int policy, int prefetch,
+bool build_schedule(int schedule, int d, int rank, int v, int m, int group, float ratio, int policy, int prefetch,
                     std::vector<po_op>& ops) {
   if (!(ratio >= 0.f && ratio <= 1.f) || prefetch < 0 || (policy != PO_SEL_ALTERNATE_MB && policy != PO_SEL_LONGEST_LIFESPAN)) {
     set_error("schedule: ratio=%g prefetch=%d policy=%d", ratio, prefetch, policy);
     return false;
   }
   std::vector<Pass> passes;
-  if (!compute_passes(schedule, d, rank, v, m, passes)) return false;
+  if (!compute_passes(schedule, d, rank, v, m, group, passes)) return false;
   int np = (int)passes.size();
   // position of each unit's forward
   std::vector<int> fpos((size_t)m * v, -1);

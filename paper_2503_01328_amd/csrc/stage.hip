@@ -33,7 +33,7 @@
 
 namespace po {
 
-bool build_schedule(int schedule, int d, int rank, int v, int m, float ratio, int policy, int prefetch,
+bool build_schedule(int schedule, int d, int rank, int v, int m, int group, float ratio, int policy, int prefetch,
                     std::vector<po_op>& ops);
 
 #define PO_HIP(expr)                                                                          \
@@ -74,10 +74,11 @@ int validate_config(const po_config* c) {
       c->seq < 1 || c->vocab < 0 || (c->dtype != PO_F32 && c->dtype != PO_BF16) || c->pipeline_degree < 1 ||
       c->rank < 0 || c->rank >= c->pipeline_degree || c->prefetch_passes < 0 ||
       (c->copy_streams != 1 && c->copy_streams != 2) || c->hidden / c->n_heads > 256 ||
-      (c->hidden / c->n_heads) % 8 != 0 || !(c->ln_eps > 0.f)) {
-    set_error("invalid config: L=%d v=%d h=%d a=%d f=%d s=%d vocab=%d dtype=%d d=%d rank=%d prefetch=%d copy_streams=%d",
+      (c->hidden / c->n_heads) % 8 != 0 || !(c->ln_eps > 0.f) || c->group < 0 || c->group > c->pipeline_degree ||
+      (c->group > 0 && 2 * c->group < c->pipeline_degree)) {
+    set_error("invalid config: L=%d v=%d h=%d a=%d f=%d s=%d vocab=%d dtype=%d d=%d rank=%d prefetch=%d copy_streams=%d group=%d",
               c->n_layers, c->n_chunks, c->hidden, c->n_heads, c->ffn, c->seq, c->vocab, c->dtype,
-              c->pipeline_degree, c->rank, c->prefetch_passes, c->copy_streams);
+              c->pipeline_degree, c->rank, c->prefetch_passes, c->copy_streams, c->group);
     return PO_E_INVAL;
   }
   return PO_OK;
@@ -282,6 +283,10 @@ struct Unit {
   std::vector<UnitLayer> layers;
   hipEvent_t fwd_done = nullptr;
   const void* x_in = nullptr;  // tokens pointer for embedding units (needed again in backward)
+  // split backward: set by the input-gradient pass, consumed by the weight-gradient pass
+  bool weight_pending = false;
+  int grad_buf = -1;            // buffer of the gradient pool holding this unit's BwdBufs tensors
+  const void* dy_top = nullptr;  // the caller's upstream gradient (read again by the weight-gradient pass)
 };
 
 struct TimedSpan {
@@ -305,14 +310,16 @@ struct po_stage {
   const char* params = nullptr;
   float* grads = nullptr;
   Pool dev_pool, host_pool;
+  Pool grad_pool;  // per-unit gradient tensors between a B pass and its W pass (split backward only)
+  size_t gl_sh = 0, gl_sf = 0, gl_s3h = 0, gl_lnws = 0, gl_layer = 0;  // layout of one such buffer
   EventBank sync_events, time_events;
   std::map<int64_t, Unit> units;
   std::vector<TimedSpan> spans;
   // workspaces
   char* ws = nullptr;
   size_t ws_bytes = 0;
-  char *w_n, *w_g, *w_du, *w_dqkv, *w_do, *w_dx1, *w_dn, *w_dy[2], *w_x0;
-  float *w_delta, *w_lnws, *w_colws;
+  char *w_n, *w_g, *w_du, *w_dqkv, *w_do, *w_dx1, *w_dn, *w_dn1, *w_dy[2], *w_x0;
+  float *w_delta, *w_lnws, *w_lnws1, *w_colws;
   // accounting
   int resident_units = 0, in_flight_units = 0;
   po_stats stats;
@@ -450,7 +457,19 @@ static int layer_forward(po_stage* st, int layer, char* slab, void* y_out) {
 }
 
 // dy: gradient of the layer output; dx_out: where the gradient of the layer input goes.
-static int layer_backward(po_stage* st, int layer, const char* slab, const void* dy, void* dx_out) {
+// Gradient tensors of one layer that the input-gradient half of the backward produces and the
+// weight-gradient half consumes.  The fused backward points them at the stage workspaces (one layer at a
+// time); the split backward (B pass, later W pass) points them into a per-unit buffer that lives from B to W.
+struct BwdBufs {
+  char *g, *du, *dn2, *dx1, *dqkv, *dn1;
+  float *lnws2, *lnws1;
+};
+
+// Input-gradient half of one layer (activation gradients only):
+//   du = (dy W2^T) * gelu'(u) with g = gelu(u) recomputed, dn2 = du W1^T, dx1 = dy + LNbwd(dn2; x1),
+//   dO = dx1 Wo^T, (dq, dk, dv) = attention backward, dn1 = dqkv Wqkv^T, dx = dx1 + LNbwd(dn1; x).
+static int layer_backward_input(po_stage* st, int layer, const char* slab, const void* dy, void* dx_out,
+                                const BwdBufs& b) {
   const po_config& c = st->cfg;
   const ParamLayout& pl = st->pl;
   const SlabLayout& sl = st->sl;
@@ -463,50 +482,64 @@ static int layer_backward(po_stage* st, int layer, const char* slab, const void*
   const char* u = slab + sl.off_u;
   const float* lse = (const float*)(slab + sl.off_lse);
 
-  // FC2: du = (dy W2^T) * gelu'(u), g = gelu(u) recomputed; dW2 += g^T dy; db2 += colsum(dy)
   Epilogue e = make_ep(f);
-  e.out = st->w_du;
+  e.out = b.du;
   e.gelu_u = u;
-  e.gelu_out = st->w_g;
+  e.gelu_out = b.g;
   PO_RC(st_gemm(st, 0, 1, s, f, h, dy, h, st->P(layer, pl.w_fc2), h, e));
   e = make_ep(h);
+  e.out = b.dn2;
+  PO_RC(st_gemm(st, 0, 1, s, h, f, b.du, f, st->P(layer, pl.w_fc1), f, e));
+  PO_K(layernorm_backward(dt, b.dn2, x1, st->P(layer, pl.ln2_g), dy, b.dx1, nullptr, nullptr, b.lnws2, s, h,
+                          c.ln_eps, kLnInputGrad, q));
+  e = make_ep(h);
+  e.out = st->w_do;
+  PO_RC(st_gemm(st, 0, 1, s, h, h, b.dx1, h, st->P(layer, pl.w_o), h, e));
+  PO_RC(st_attention(st, true, qkv, const_cast<char*>(o), const_cast<float*>(lse), st->w_do, b.dqkv));
+  e = make_ep(h);
+  e.out = b.dn1;
+  PO_RC(st_gemm(st, 0, 1, s, h, 3 * h, b.dqkv, 3 * h, st->P(layer, pl.w_qkv), 3 * h, e));
+  PO_K(layernorm_backward(dt, b.dn1, x, st->P(layer, pl.ln1_g), b.dx1, dx_out, nullptr, nullptr, b.lnws1, s, h,
+                          c.ln_eps, kLnInputGrad, q));
+  return PO_OK;
+}
+
+// Weight-gradient half of one layer (parameter gradients only, accumulated in fp32):
+//   dW2 += g^T dy, db2 += colsum(dy); dW1 += n2^T du, db1 += colsum(du) with n2 = LN2(x1) recomputed;
+//   dWo += O^T dx1, dbo += colsum(dx1); dWqkv += n1^T dqkv, dbqkv += colsum(dqkv) with n1 = LN1(x) recomputed;
+//   LayerNorm gains and shifts from (dn2, x1) and (dn1, x) with the row statistics the input half left.
+static int layer_backward_weight(po_stage* st, int layer, const char* slab, const void* dy, const BwdBufs& b) {
+  const po_config& c = st->cfg;
+  const ParamLayout& pl = st->pl;
+  const SlabLayout& sl = st->sl;
+  int s = c.seq, h = c.hidden, f = c.ffn, dt = c.dtype;
+  hipStream_t q = st->compute;
+  const char* x = slab + sl.off_x;
+  const char* o = slab + sl.off_o;
+  const char* x1 = slab + sl.off_x1;
+
+  Epilogue e = make_ep(h);
   e.acc_f32 = st->G(layer, pl.w_fc2);
-  PO_RC(st_gemm(st, 1, 0, f, h, s, st->w_g, f, dy, h, e));
+  PO_RC(st_gemm(st, 1, 0, f, h, s, b.g, f, dy, h, e));
   PO_K(colsum_accumulate(dt, dy, st->G(layer, pl.b_fc2), st->w_colws, s, h, q));
-  // FC1: n2 recomputed; dW1 += n2^T du; db1 += colsum(du); dn2 = du W1^T
   PO_K(layernorm_forward(dt, x1, st->P(layer, pl.ln2_g), st->P(layer, pl.ln2_b), st->w_n, s, h, c.ln_eps, q));
   e = make_ep(f);
   e.acc_f32 = st->G(layer, pl.w_fc1);
-  PO_RC(st_gemm(st, 1, 0, h, f, s, st->w_n, h, st->w_du, f, e));
-  PO_K(colsum_accumulate(dt, st->w_du, st->G(layer, pl.b_fc1), st->w_colws, s, f, q));
-  e = make_ep(h);
-  e.out = st->w_dn;
-  PO_RC(st_gemm(st, 0, 1, s, h, f, st->w_du, f, st->P(layer, pl.w_fc1), f, e));
-  // LN2 backward + residual: dx1 = dy + LNbwd(dn2)
-  PO_K(layernorm_backward(dt, st->w_dn, x1, st->P(layer, pl.ln2_g), dy, st->w_dx1, st->G(layer, pl.ln2_g),
-                          st->G(layer, pl.ln2_b), st->w_lnws, s, h, c.ln_eps, q));
-  // Out-proj: dWo += O^T dx1; dbo += colsum(dx1); dO = dx1 Wo^T
+  PO_RC(st_gemm(st, 1, 0, h, f, s, st->w_n, h, b.du, f, e));
+  PO_K(colsum_accumulate(dt, b.du, st->G(layer, pl.b_fc1), st->w_colws, s, f, q));
+  PO_K(layernorm_backward(dt, b.dn2, x1, st->P(layer, pl.ln2_g), nullptr, nullptr, st->G(layer, pl.ln2_g),
+                          st->G(layer, pl.ln2_b), b.lnws2, s, h, c.ln_eps, kLnParamGrad, q));
   e = make_ep(h);
   e.acc_f32 = st->G(layer, pl.w_o);
-  PO_RC(st_gemm(st, 1, 0, h, h, s, o, h, st->w_dx1, h, e));
-  PO_K(colsum_accumulate(dt, st->w_dx1, st->G(layer, pl.b_o), st->w_colws, s, h, q));
-  e = make_ep(h);
-  e.out = st->w_do;
-  PO_RC(st_gemm(st, 0, 1, s, h, h, st->w_dx1, h, st->P(layer, pl.w_o), h, e));
-  // Attention backward
-  PO_RC(st_attention(st, true, qkv, const_cast<char*>(o), const_cast<float*>(lse), st->w_do, st->w_dqkv));
-  // QKV: n1 recomputed; dWqkv += n1^T dqkv; dbqkv += colsum(dqkv); dn1 = dqkv Wqkv^T
+  PO_RC(st_gemm(st, 1, 0, h, h, s, o, h, b.dx1, h, e));
+  PO_K(colsum_accumulate(dt, b.dx1, st->G(layer, pl.b_o), st->w_colws, s, h, q));
   PO_K(layernorm_forward(dt, x, st->P(layer, pl.ln1_g), st->P(layer, pl.ln1_b), st->w_n, s, h, c.ln_eps, q));
   e = make_ep(3 * h);
   e.acc_f32 = st->G(layer, pl.w_qkv);
-  PO_RC(st_gemm(st, 1, 0, h, 3 * h, s, st->w_n, h, st->w_dqkv, 3 * h, e));
-  PO_K(colsum_accumulate(dt, st->w_dqkv, st->G(layer, pl.b_qkv), st->w_colws, s, 3 * h, q));
-  e = make_ep(h);
-  e.out = st->w_dn;
-  PO_RC(st_gemm(st, 0, 1, s, h, 3 * h, st->w_dqkv, 3 * h, st->P(layer, pl.w_qkv), 3 * h, e));
-  // LN1 backward + residual: dx = dx1 + LNbwd(dn1)
-  PO_K(layernorm_backward(dt, st->w_dn, x, st->P(layer, pl.ln1_g), st->w_dx1, dx_out, st->G(layer, pl.ln1_g),
-                          st->G(layer, pl.ln1_b), st->w_lnws, s, h, c.ln_eps, q));
+  PO_RC(st_gemm(st, 1, 0, h, 3 * h, s, st->w_n, h, b.dqkv, 3 * h, e));
+  PO_K(colsum_accumulate(dt, b.dqkv, st->G(layer, pl.b_qkv), st->w_colws, s, 3 * h, q));
+  PO_K(layernorm_backward(dt, b.dn1, x, st->P(layer, pl.ln1_g), nullptr, nullptr, st->G(layer, pl.ln1_g),
+                          st->G(layer, pl.ln1_b), b.lnws1, s, h, c.ln_eps, kLnParamGrad, q));
   return PO_OK;
 }
 
@@ -596,6 +629,10 @@ int stage_offload(po_stage* st, int mb, int chunk, float ratio) {
   }
   Unit* u = find_live_unit(st, mb, chunk, "offload");
   if (!u) return PO_E_STATE;
+  if (u->weight_pending) {
+    set_error("offload of unit (mb %d, chunk %d) between its input-gradient and weight-gradient pass", mb, chunk);
+    return PO_E_STATE;
+  }
   int n = (int)ceil((double)ratio * st->Lu - 1e-9);
   for (int l = 0; l < n; ++l)
     if (u->layers[l].state != L_RESIDENT) {
@@ -731,22 +768,32 @@ int stage_reload(po_stage* st, int mb, int chunk) {
   return PO_OK;
 }
 
-int stage_backward(po_stage* st, int mb, int chunk, const void* dy, void* dx) {
+// Checks shared by the three backward entry points; waits for pending reloads of the unit.
+static int backward_prologue(po_stage* st, int mb, int chunk, const void* dy, void* dx, const char* what,
+                             Unit** out) {
   const po_config& c = st->cfg;
-  if (!st->grads) {
-    set_error("backward before po_bind_params");
+  if (!st->params || !st->grads) {
+    set_error("%s before po_bind_params", what);
     return PO_E_STATE;
   }
-  Unit* u = find_live_unit(st, mb, chunk, "backward");
+  if (mb < 0 || chunk < 0 || chunk >= c.n_chunks) {
+    set_error("%s: mb=%d chunk=%d", what, mb, chunk);
+    return PO_E_INVAL;
+  }
+  Unit* u = find_live_unit(st, mb, chunk, what);
   if (!u) return PO_E_STATE;
+  if (u->weight_pending) {
+    set_error("%s of unit (mb %d, chunk %d) whose input-gradient pass already ran", what, mb, chunk);
+    return PO_E_STATE;
+  }
   bool embed = c.vocab > 0 && chunk == 0;
   if (!dy || (!dx && !embed)) {
-    set_error("backward: dy=%p dx=%p", dy, dx);
+    set_error("%s: dy=%p dx=%p", what, dy, dx);
     return PO_E_INVAL;
   }
   for (int l = 0; l < st->Lu; ++l)
     if (u->layers[l].state != L_RESIDENT) {
-      set_error("backward of unit (mb %d, chunk %d): layer %d is on the host and no reload was issued", mb, chunk,
+      set_error("%s of unit (mb %d, chunk %d): layer %d is on the host and no reload was issued", what, mb, chunk,
                 l);
       return PO_E_STATE;
     }
@@ -755,9 +802,66 @@ int stage_backward(po_stage* st, int mb, int chunk, const void* dy, void* dx) {
       PO_HIP(hipStreamWaitEvent(st->compute, L.h2d_done, 0));
       L.h2d_done = nullptr;
     }
-  size_t span;
-  int rc = span_begin(st, st->compute, 0, &span);
+  *out = u;
+  return PO_OK;
+}
+
+// Hands the unit's slabs back once its last pass has been enqueued.
+static int retire_unit(po_stage* st, Unit* u) {
+  for (UnitLayer& L : u->layers) {
+    if (st->cfg.debug_poison)
+      PO_K(fill_u32(st->dev_pool.bufs[L.dev].ptr, 0x7fc07fc0u, st->sl.bytes, st->compute));
+    int rc = st->dev_pool.release(L.dev, st->compute);
+    if (rc) return rc;
+    L = UnitLayer();
+  }
+  u->live = false;
+  u->weight_pending = false;
+  --st->resident_units;
+  return PO_OK;
+}
+
+static BwdBufs workspace_bufs(po_stage* st) {
+  BwdBufs b;
+  b.g = st->w_g;
+  b.du = st->w_du;
+  b.dn2 = st->w_dn;
+  b.dx1 = st->w_dx1;
+  b.dqkv = st->w_dqkv;
+  b.dn1 = st->w_dn1;
+  b.lnws2 = st->w_lnws;
+  b.lnws1 = st->w_lnws1;
+  return b;
+}
+
+// Layer l's tensors inside a unit's gradient buffer; *dy_in is where the gradient arriving at the layer's
+// output is kept (written by layer l+1's input-gradient half).
+static BwdBufs unit_bufs(const po_stage* st, char* buf, int l, char** dy_in) {
+  char* p = buf + (size_t)l * st->gl_layer;
+  BwdBufs b;
+  b.g = p;
+  b.du = b.g + st->gl_sf;
+  b.dn2 = b.du + st->gl_sf;
+  b.dx1 = b.dn2 + st->gl_sh;
+  b.dn1 = b.dx1 + st->gl_sh;
+  *dy_in = b.dn1 + st->gl_sh;
+  b.dqkv = *dy_in + st->gl_sh;
+  b.lnws2 = (float*)(b.dqkv + st->gl_s3h);
+  b.lnws1 = (float*)((char*)b.lnws2 + st->gl_lnws);
+  return b;
+}
+
+// Fused backward: per layer, the input-gradient half directly followed by the weight-gradient half.
+int stage_backward(po_stage* st, int mb, int chunk, const void* dy, void* dx) {
+  const po_config& c = st->cfg;
+  Unit* u;
+  int rc = backward_prologue(st, mb, chunk, dy, dx, "backward", &u);
   if (rc) return rc;
+  bool embed = c.vocab > 0 && chunk == 0;
+  size_t span;
+  rc = span_begin(st, st->compute, 0, &span);
+  if (rc) return rc;
+  BwdBufs bufs = workspace_bufs(st);
   const void* grad = dy;
   for (int l = st->Lu - 1; l >= 0; --l) {
     const char* slab = st->dev_pool.bufs[u->layers[l].dev].ptr;
@@ -766,7 +870,9 @@ int stage_backward(po_stage* st, int mb, int chunk, const void* dy, void* dx) {
       out = st->w_dy[l & 1];
     else
       out = embed ? (void*)st->w_dy[0] : dx;
-    rc = layer_backward(st, chunk * st->Lu + l, slab, grad, out);
+    rc = layer_backward_input(st, chunk * st->Lu + l, slab, grad, out, bufs);
+    if (rc) return rc;
+    rc = layer_backward_weight(st, chunk * st->Lu + l, slab, grad, bufs);
     if (rc) return rc;
     grad = out;
   }
@@ -775,15 +881,92 @@ int stage_backward(po_stage* st, int mb, int chunk, const void* dy, void* dx) {
                             st->grads + st->pl.emb_wpe, c.seq, c.hidden, c.vocab, st->compute));
   rc = span_end(st, st->compute, span);
   if (rc) return rc;
-  for (UnitLayer& L : u->layers) {
-    if (c.debug_poison) PO_K(fill_u32(st->dev_pool.bufs[L.dev].ptr, 0x7fc07fc0u, st->sl.bytes, st->compute));
-    rc = st->dev_pool.release(L.dev, st->compute);
-    if (rc) return rc;
-    L = UnitLayer();
-  }
-  u->live = false;
+  rc = retire_unit(st, u);
+  if (rc) return rc;
   --st->in_flight_units;
-  --st->resident_units;
+  ++st->stats.n_compute_passes;
+  return PO_OK;
+}
+
+// Split backward, B pass: activation gradients of every layer of the unit, top layer first; what the W pass
+// needs is left in a buffer of the gradient pool.  The unit keeps its slabs until the W pass.
+int stage_backward_input(po_stage* st, int mb, int chunk, const void* dy, void* dx) {
+  const po_config& c = st->cfg;
+  Unit* u;
+  int rc = backward_prologue(st, mb, chunk, dy, dx, "input-gradient pass", &u);
+  if (rc) return rc;
+  bool embed = c.vocab > 0 && chunk == 0;
+  rc = st->grad_pool.acquire(st->compute, &u->grad_buf);
+  if (rc) return rc;
+  char* buf = st->grad_pool.bufs[u->grad_buf].ptr;
+  size_t span;
+  rc = span_begin(st, st->compute, 0, &span);
+  if (rc) return rc;
+  const void* grad = dy;
+  for (int l = st->Lu - 1; l >= 0; --l) {
+    const char* slab = st->dev_pool.bufs[u->layers[l].dev].ptr;
+    char* dy_in;
+    BwdBufs bufs = unit_bufs(st, buf, l, &dy_in);
+    (void)dy_in;
+    void* out;
+    if (l > 0) {
+      char* below;  // layer l-1 keeps its incoming gradient for its own weight-gradient half
+      (void)unit_bufs(st, buf, l - 1, &below);
+      out = below;
+    } else {
+      out = embed ? (void*)(buf + (size_t)st->Lu * st->gl_layer) : dx;
+    }
+    rc = layer_backward_input(st, chunk * st->Lu + l, slab, grad, out, bufs);
+    if (rc) return rc;
+    grad = out;
+  }
+  rc = span_end(st, st->compute, span);
+  if (rc) return rc;
+  u->weight_pending = true;
+  u->dy_top = dy;
+  --st->in_flight_units;
+  ++st->stats.n_compute_passes;
+  return PO_OK;
+}
+
+// Split backward, W pass: parameter gradients of every layer of the unit; frees the unit.
+int stage_backward_weight(po_stage* st, int mb, int chunk) {
+  const po_config& c = st->cfg;
+  if (mb < 0 || chunk < 0 || chunk >= c.n_chunks) {
+    set_error("weight-gradient pass: mb=%d chunk=%d", mb, chunk);
+    return PO_E_INVAL;
+  }
+  Unit* u = find_live_unit(st, mb, chunk, "weight-gradient pass");
+  if (!u) return PO_E_STATE;
+  if (!u->weight_pending) {
+    set_error("weight-gradient pass of unit (mb %d, chunk %d) before its input-gradient pass", mb, chunk);
+    return PO_E_STATE;
+  }
+  bool embed = c.vocab > 0 && chunk == 0;
+  char* buf = st->grad_pool.bufs[u->grad_buf].ptr;
+  size_t span;
+  int rc = span_begin(st, st->compute, 0, &span);
+  if (rc) return rc;
+  for (int l = st->Lu - 1; l >= 0; --l) {
+    const char* slab = st->dev_pool.bufs[u->layers[l].dev].ptr;
+    char* dy_in;
+    BwdBufs bufs = unit_bufs(st, buf, l, &dy_in);
+    const void* grad = l == st->Lu - 1 ? u->dy_top : (const void*)dy_in;
+    rc = layer_backward_weight(st, chunk * st->Lu + l, slab, grad, bufs);
+    if (rc) return rc;
+  }
+  if (embed)
+    PO_K(embedding_backward(c.dtype, (const int32_t*)u->x_in, buf + (size_t)st->Lu * st->gl_layer,
+                            st->grads + st->pl.emb_wte, st->grads + st->pl.emb_wpe, c.seq, c.hidden, c.vocab,
+                            st->compute));
+  rc = span_end(st, st->compute, span);
+  if (rc) return rc;
+  rc = st->grad_pool.release(u->grad_buf, st->compute);
+  if (rc) return rc;
+  u->grad_buf = -1;
+  u->dy_top = nullptr;
+  rc = retire_unit(st, u);
+  if (rc) return rc;
   ++st->stats.n_compute_passes;
   return PO_OK;
 }
@@ -849,7 +1032,7 @@ static void reset_run_stats(po_stage* st) {
   memset(&st->stats, 0, sizeof(st->stats));
   st->stats.pool_bytes_allocated = pool;
   st->stats.host_bytes_allocated = host;
-  st->stats.workspace_bytes = st->ws_bytes;
+  st->stats.workspace_bytes = st->ws_bytes + st->grad_pool.allocated();
   st->spans.clear();
   st->time_events.reset();
 }
@@ -862,7 +1045,7 @@ int stage_run_schedule(po_stage* st, int schedule, int m, float ratio, const voi
     return PO_E_INVAL;
   }
   std::vector<po_op> ops;
-  if (!build_schedule(schedule, c.pipeline_degree, c.rank, c.n_chunks, m, ratio, c.select_policy,
+  if (!build_schedule(schedule, c.pipeline_degree, c.rank, c.n_chunks, m, c.group, ratio, c.select_policy,
                       c.prefetch_passes, ops))
     return PO_E_INVAL;
   for (auto& kv : st->units)
@@ -880,9 +1063,17 @@ int stage_run_schedule(po_stage* st, int schedule, int m, float ratio, const voi
     size_t i = (size_t)op.chunk * m + op.mb;
     switch (op.kind) {
       case 0: rc = stage_forward(st, op.mb, op.chunk, x_in[i], y_out[i]); break;
-      case 1: rc = stage_backward(st, op.mb, op.chunk, dy[i], dx[i]); break;
+      case 1:  // a schedule with W passes runs its B passes as input-gradient passes
+        rc = schedule == PO_SCHED_GIS ? stage_backward_input(st, op.mb, op.chunk, dy[i], dx[i])
+                                      : stage_backward(st, op.mb, op.chunk, dy[i], dx[i]);
+        break;
       case 2: rc = stage_offload(st, op.mb, op.chunk, op.ratio); break;
-      default: rc = stage_reload(st, op.mb, op.chunk); break;
+      case 3: rc = stage_reload(st, op.mb, op.chunk); break;
+      case 4: rc = stage_backward_weight(st, op.mb, op.chunk); break;
+      default:
+        set_error("run_schedule: op kind %d", op.kind);
+        rc = PO_E_INVAL;
+        break;
     }
     if (rc) break;
   }
@@ -895,6 +1086,7 @@ int stage_run_schedule(po_stage* st, int schedule, int m, float ratio, const voi
   st->stats.tokens_per_s = (double)m * c.seq / st->stats.wall_s;
   st->stats.pool_bytes_allocated = st->dev_pool.allocated();
   st->stats.host_bytes_allocated = st->host_pool.allocated();
+  st->stats.workspace_bytes = st->ws_bytes + st->grad_pool.allocated();
   rc = collect_spans(st);
   if (rc) return rc;
   if (out) *out = st->stats;
@@ -954,7 +1146,17 @@ int stage_create(const po_config* cfg, void* compute_stream, po_stage** out) {
   size_t lnws = align_up(layernorm_backward_workspace((int)s, (int)h), 256);
   size_t maxn = std::max((size_t)3 * h, f);
   size_t colws = align_up(colsum_workspace((int)s, (int)maxn), 256);
-  size_t total = 7 * sh + 2 * sf + s3h + delta + lnws + colws;
+  size_t total = 8 * sh + 2 * sf + s3h + delta + 2 * lnws + colws;
+  // one unit's gradient buffer for the split backward: per layer g, du [s,f]; dn2, dx1, dn1, incoming dy [s,h];
+  // dqkv [s,3h]; two LayerNorm workspaces; plus one [s,h] tensor per unit (gradient at the embedding output)
+  st->gl_sh = sh;
+  st->gl_sf = sf;
+  st->gl_s3h = s3h;
+  st->gl_lnws = lnws;
+  st->gl_layer = 2 * sf + 4 * sh + s3h + 2 * lnws;
+  st->grad_pool.host = false;
+  st->grad_pool.buf_bytes = (size_t)st->Lu * st->gl_layer + sh;
+  st->grad_pool.cap = 0;
   if (hipMalloc((void**)&st->ws, total) != hipSuccess) {
     (void)hipGetLastError();
     set_error("workspace allocation of %zu bytes failed", total);
@@ -972,6 +1174,7 @@ int stage_create(const po_config* cfg, void* compute_stream, po_stage** out) {
   st->w_do = take(sh);
   st->w_dx1 = take(sh);
   st->w_dn = take(sh);
+  st->w_dn1 = take(sh);
   st->w_dy[0] = take(sh);
   st->w_dy[1] = take(sh);
   st->w_x0 = take(sh);
@@ -980,6 +1183,7 @@ int stage_create(const po_config* cfg, void* compute_stream, po_stage** out) {
   st->w_dqkv = take(s3h);
   st->w_delta = (float*)take(delta);
   st->w_lnws = (float*)take(lnws);
+  st->w_lnws1 = (float*)take(lnws);
   st->w_colws = (float*)take(colws);
   reset_run_stats(st);
   *out = st;
@@ -1055,14 +1259,14 @@ int po_saved_bytes_per_layer(const po_config* cfg, uint64_t* bytes) {
   return PO_OK;
 }
 
-int po_schedule_ops(int32_t schedule, int32_t d, int32_t rank, int32_t v, int32_t m, float ratio, int32_t policy,
-                    int32_t prefetch, po_op* out, int32_t* n) {
+int po_schedule_ops(int32_t schedule, int32_t d, int32_t rank, int32_t v, int32_t m, int32_t group, float ratio,
+                    int32_t policy, int32_t prefetch, po_op* out, int32_t* n) {
   if (!n) {
     set_error("po_schedule_ops: n is NULL");
     return PO_E_INVAL;
   }
   std::vector<po_op> ops;
-  if (!build_schedule(schedule, d, rank, v, m, ratio, policy, prefetch, ops)) return PO_E_INVAL;
+  if (!build_schedule(schedule, d, rank, v, m, group, ratio, policy, prefetch, ops)) return PO_E_INVAL;
   int32_t have = (int32_t)ops.size();
   if (out) {
     int32_t k = *n < have ? *n : have;
@@ -1085,6 +1289,7 @@ void po_stage_destroy(po_stage* st) {
   if (st->compute || st->offload) (void)stage_synchronize(st);
   st->dev_pool.destroy();
   st->host_pool.destroy();
+  st->grad_pool.destroy();
   st->sync_events.destroy();
   st->time_events.destroy();
   if (st->ws) (void)hipFree(st->ws);
@@ -1122,6 +1327,16 @@ int po_stage_backward(po_stage* st, int32_t mb, int32_t chunk, const void* dy, v
   begin_launch();
   PO_NEED_STAGE(st);
   return stage_backward(st, mb, chunk, dy, dx);
+}
+int po_stage_backward_input(po_stage* st, int32_t mb, int32_t chunk, const void* dy, void* dx) {
+  begin_launch();
+  PO_NEED_STAGE(st);
+  return stage_backward_input(st, mb, chunk, dy, dx);
+}
+int po_stage_backward_weight(po_stage* st, int32_t mb, int32_t chunk) {
+  begin_launch();
+  PO_NEED_STAGE(st);
+  return stage_backward_weight(st, mb, chunk);
 }
 int po_offload(po_stage* st, int32_t mb, int32_t chunk, float ratio) {
   begin_launch();
@@ -1180,6 +1395,7 @@ int po_op_layernorm_backward(int32_t dtype, const void* dn, const void* x, const
   begin_launch();
   if (!dtype_ok(dtype)) return PO_E_INVAL;
   return ok(layernorm_backward(dtype, dn, x, gain, dres, dx, dgain, dshift, partials, rows, h, eps,
+                               kLnInputGrad | kLnParamGrad,
                                (hipStream_t)stream));
 }
 int po_op_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32_t N, int32_t K, const void* A,

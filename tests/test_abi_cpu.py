@@ -44,6 +44,27 @@ def test_schedule_ops_match_the_oracle_model(name, d, v, m, ratio, prefetch):
             assert sch.simulate(got)["errors"] == []
 
 
+@pytest.mark.parametrize("d,v,m,g", [(8, 2, 32, 8), (8, 2, 32, 4), (4, 3, 12, 2), (4, 3, 12, 3), (4, 2, 8, 0), (6, 2, 12, 3),
+                                     (2, 1, 4, 1)])
+@pytest.mark.parametrize("ratio", [0.0, 0.5, 1.0])
+@pytest.mark.parametrize("prefetch", [0, 2, 3])
+def test_gis_schedule_ops_match_the_oracle_model(d, v, m, g, ratio, prefetch):
+    for rank in sorted({0, d // 2, d - 1}):
+        for policy, pname in ((po.PO_SEL_ALTERNATE_MB, "alternate-mb"), (po.PO_SEL_LONGEST_LIFESPAN, "longest-lifespan")):
+            got = po.po_schedule_ops(po.PO_SCHED_GIS, d, rank, v, m, ratio, policy, prefetch, group=g)
+            passes = sch.compute_passes("gis", d, rank, v, m, g or None)
+            want = sch.with_offload(passes, sch.selected_units(m, v, ratio, pname), prefetch)
+            assert got == want
+            assert sch.simulate(got)["errors"] == []
+
+
+def test_gis_schedule_rejects_bad_groups():
+    for g, m in [(3, 32), (9, 32), (8, 30)]:
+        with pytest.raises(po.PipeOffloadError) as e:
+            po.po_schedule_ops(po.PO_SCHED_GIS, 8, 0, 2, m, 0.5, group=g)
+        assert e.value.code == po.PO_E_INVAL
+
+
 def test_schedule_ops_reject_bad_arguments():
     for args in [(0, 4, 4, 1, 8, 0.5), (0, 4, 0, 2, 8, 0.5), (1, 4, 0, 2, 6, 0.5), (0, 4, 0, 1, 8, 1.5), (7, 4, 0, 1, 8, 0.5)]:
         with pytest.raises(po.PipeOffloadError) as e:

@@ -203,3 +203,94 @@ def test_peak_slab_bytes_follow_the_schedule_model(gpu_device):
             assert stats["peak_slab_bytes"] == model["peak_resident"] * layer_bytes
             peaks[ratio] = stats["peak_slab_bytes"]
     assert peaks[1.0] < peaks[0.5] < peaks[0.0]
+
+
+# ---- split backward (B / W passes) and the generalized interleaved schedule (Sections 3.2, 3.3) ----------------
+@pytest.mark.parametrize("shape", [syn.StageShape(2, 1, 128, 2, 512, 96, vocab=50, dtype="f32", pipeline_degree=2,
+                                                  n_microbatches=3),
+                                   syn.StageShape(3, 1, 256, 2, 1024, 256, dtype="bf16", pipeline_degree=2,
+                                                  n_microbatches=3)], ids=["f32-embedding", "bf16-mfma"])
+def test_split_backward_is_bit_identical_to_the_fused_backward(gpu_device, shape):
+    m = shape.n_microbatches
+    with StageRunner(shape) as r:
+        r.make_inputs()
+        st = r.stage
+        for j in range(m):
+            po.po_stage_forward(st, j, 0, r.x[j], r.y[j])
+        for j in range(m):
+            po.po_stage_backward(st, j, 0, r.dy[j], r.dx[j])
+        fused = _snapshot(r)
+        _compare(shape, r.results(), _oracle(shape, r, m), 1e-4 if shape.dtype == "f32" else 2e-2)
+        # B directly followed by W
+        r.zero_grads()
+        for j in range(m):
+            po.po_stage_forward(st, j, 0, r.x[j], r.y[j])
+        for j in range(m):
+            po.po_stage_backward_input(st, j, 0, r.dy[j], r.dx[j])
+            po.po_stage_backward_weight(st, j, 0)
+        _assert_bit_identical(fused, _snapshot(r))
+        # all B passes first, W passes delayed (several units weight-pending at once)
+        r.zero_grads()
+        for j in range(m):
+            po.po_stage_forward(st, j, 0, r.x[j], r.y[j])
+        for j in range(m):
+            po.po_stage_backward_input(st, j, 0, r.dy[j], r.dx[j])
+        for j in range(m):
+            po.po_stage_backward_weight(st, j, 0)
+        _assert_bit_identical(fused, _snapshot(r))
+
+
+def test_split_backward_state_errors(gpu_device):
+    shape = syn.StageShape(2, 1, 128, 2, 512, 64, dtype="f32", pipeline_degree=2, n_microbatches=2)
+    with StageRunner(shape) as r:
+        r.make_inputs()
+        st = r.stage
+        po.po_stage_forward(st, 0, 0, r.x[0], r.y[0])
+        with pytest.raises(po.PipeOffloadError) as e:
+            po.po_stage_backward_weight(st, 0, 0)  # no input-gradient pass yet
+        assert e.value.code == po.PO_E_STATE
+        with pytest.raises(po.PipeOffloadError) as e:
+            po.po_stage_backward_weight(st, 1, 0)  # never forwarded
+        assert e.value.code == po.PO_E_STATE
+        po.po_stage_backward_input(st, 0, 0, r.dy[0], r.dx[0])
+        for call in (lambda: po.po_stage_backward_input(st, 0, 0, r.dy[0], r.dx[0]),
+                     lambda: po.po_stage_backward(st, 0, 0, r.dy[0], r.dx[0]),
+                     lambda: po.po_offload(st, 0, 0, 1.0),
+                     lambda: po.po_stage_forward(st, 0, 0, r.x[0], r.y[0])):
+            with pytest.raises(po.PipeOffloadError) as e:
+                call()
+            assert e.value.code == po.PO_E_STATE
+        po.po_stage_backward_weight(st, 0, 0)
+        with pytest.raises(po.PipeOffloadError) as e:
+            po.po_stage_backward_weight(st, 0, 0)  # the unit is gone
+        assert e.value.code == po.PO_E_STATE
+        po.po_synchronize(st)
+
+
+@pytest.mark.parametrize("group", [0, 2])
+def test_gis_schedule_against_oracle_and_schedule_model(gpu_device, group):
+    d, v, m = 4, 2, 8
+    shape = syn.StageShape(4, v, 128, 2, 512, 64, dtype="bf16", pipeline_degree=d, n_microbatches=m)
+    results = {}
+    for ratio in (0.0, 0.5, 1.0):
+        with StageRunner(shape, group=group) as r:
+            r.make_inputs()
+            stats = r.run(po.PO_SCHED_GIS, ratio)
+            results[ratio] = _snapshot(r)
+            ops = sch.with_offload(sch.generalized_interleaved(d, 0, v, m, group or None),
+                                   sch.selected_units(m, v, ratio), r.cfg.prefetch_passes)
+            model = sch.simulate(ops)
+            assert model["errors"] == []
+            assert stats["peak_in_flight_units"] == model["peak_in_flight"] == (group or d) * (v - 1) + d
+            assert stats["peak_resident_units"] == model["peak_resident"]
+            assert stats["n_compute_passes"] == 3 * m * v
+            if ratio == 0.0:
+                _compare(shape, r.results(), _oracle(shape, r, m), 2e-2)
+    for ratio in (0.5, 1.0):
+        _assert_bit_identical(results[0.0], results[ratio])
+    # every chunk sees its microbatches in ascending order in all these schedules, so the interleaved 1F1B run
+    # accumulates the same sums in the same order
+    with StageRunner(shape) as r:
+        r.make_inputs()
+        r.run(po.PO_SCHED_1F1B_INTERLEAVED, 0.0)
+        _assert_bit_identical(results[0.0], _snapshot(r))
