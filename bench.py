@@ -75,6 +75,10 @@ def main():
     ap.add_argument("--copy-streams", type=int, default=2)
     ap.add_argument("--prefetch", type=int, default=2)
     ap.add_argument("--staged", type=int, default=0)
+    ap.add_argument("--schedule", default="auto", choices=["auto", "1f1b", "1f1b-interleaved", "gis"],
+                    help="auto: 1F1B, or interleaved 1F1B for a workload with several chunks; gis: generalized "
+                         "interleaved schedule with split backward (Sections 3.2, 3.3)")
+    ap.add_argument("--group", type=int, default=0, help="group size g of --schedule gis (0 = pipeline degree)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs one pipeline rank on one GPU; --gpus must be 1", file=sys.stderr)
@@ -87,12 +91,16 @@ def main():
     from paper_2503_01328_amd.harness import StageRunner
 
     shape = syn.CONFIGS[args.config]
-    sched = po.PO_SCHED_1F1B_INTERLEAVED if shape.n_chunks > 1 else po.PO_SCHED_1F1B
+    sched_name = args.schedule
+    if sched_name == "auto":
+        sched_name = "1f1b-interleaved" if shape.n_chunks > 1 else "1f1b"
+    sched = {"1f1b": po.PO_SCHED_1F1B, "1f1b-interleaved": po.PO_SCHED_1F1B_INTERLEAVED,
+             "gis": po.PO_SCHED_GIS}[sched_name]
     tokens = shape.n_microbatches * shape.seq
     ratios = {}
     headline = None
     with StageRunner(shape, device_params=True, copy_streams=args.copy_streams, prefetch_passes=args.prefetch,
-                     staged_copies=args.staged, profile_kernels=1) as r:
+                     staged_copies=args.staged, profile_kernels=1, group=args.group) as r:
         r.make_inputs_on_device()
         for ratio in (0.0, 0.5, 1.0):
             for _ in range(args.warmup):
@@ -145,7 +153,8 @@ def main():
         "config": {"workload": f"{args.config}: GPT stage, {shape.n_layers} layers, hidden {shape.hidden}, "
                                f"{shape.n_heads} heads, FFN {shape.ffn}, seq {shape.seq}, {shape.n_microbatches} "
                                f"microbatches, simulated pipeline degree {shape.pipeline_degree}, "
-                               f"{'interleaved ' if shape.n_chunks > 1 else ''}1F1B rank 0; value is at offload ratio 1",
+                               f"schedule {sched_name}{' g=%d' % args.group if args.group else ''} rank 0; "
+                               f"value is at offload ratio 1",
                    "copy_streams": args.copy_streams, "prefetch_passes": args.prefetch, "staged_copies": args.staged},
         "ratios": {str(k): v for k, v in ratios.items()},
         "k_eq1_measured_serial": k_meas, "k_eq1_measured_duplex": (k_meas / 2 if k_meas else None),

@@ -68,7 +68,8 @@ typedef struct po_config {
   int32_t dtype;           /* po_dtype of parameters and activations; gradients are always fp32 */
   int32_t pipeline_degree; /* d of the simulated pipeline */
   int32_t rank;            /* i in [0, d): rank 0 holds the most units in flight */
-  int32_t prefetch_passes; /* run_schedule issues a unit's reload this many compute passes before its backward */
+  int32_t prefetch_passes; /* run_schedule issues a unit's reload this many forward / backward passes before its
+                              backward (weight-gradient passes in between are not counted) */
   int32_t copy_streams;    /* 2: separate offload and reload streams; 1: one shared copy stream (Section 4.2) */
   int32_t select_policy;   /* po_select */
   int32_t staged_copies;   /* 0: copy slabs in place; 1: pack into a staging buffer before D2H, unpack after H2D */

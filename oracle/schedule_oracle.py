@@ -188,13 +188,20 @@ def with_offload(passes, selected, prefetch=1):
 
     OFFLOAD(u) directly follows F(u).  RELOAD(u) is placed directly before the
     compute pass that runs ``prefetch`` passes ahead of B(u) (prefetch = 0:
-    directly before B(u) itself), but never before OFFLOAD(u).
+    directly before B(u) itself), but never before OFFLOAD(u).  Weight-gradient
+    passes are not counted: a (B, W) pair is one backward's worth of time, so the
+    same ``prefetch`` buys the same lead with fused and with split backwards.
     """
     pos_f = {(mb, c): n for n, (kind, mb, c) in enumerate(passes) if kind == "F"}
     reload_before = {}
     for n, (kind, mb, c) in enumerate(passes):
         if kind == "B" and (mb, c) in selected:
-            at = max(n - prefetch, pos_f[(mb, c)] + 1)
+            at, counted = n, 0
+            while counted < prefetch and at > 0:
+                at -= 1
+                if passes[at][0] != "W":
+                    counted += 1
+            at = max(at, pos_f[(mb, c)] + 1)
             reload_before.setdefault(at, []).append((mb, c))
     ops = []
     for n, (kind, mb, c) in enumerate(passes):

@@ -15,7 +15,8 @@
 // in flight on rank 0), g = ceil(d/2) its GIS-H; in general the peak is g(v-1) + d.
 // Offload placement (Section 4.2 collapsed to one rank with its own copy queues):
 // OFFLOAD directly after the unit's forward; RELOAD `prefetch` compute passes
-// before the unit's backward, never before its OFFLOAD.
+// before the unit's backward (W passes not counted: a B and its W together are one
+// backward's worth of time), never before its OFFLOAD.
 #include <math.h>
 
 #include <vector>
@@ -124,7 +125,11 @@ bool build_schedule(int schedule, int d, int rank, int v, int m, int group, floa
   for (int n = 0; n < np; ++n) {
     const Pass& p = passes[n];
     if (p.kind != 1 || !unit_selected(p.mb, p.chunk, v, ratio, policy)) continue;
-    int at = n - prefetch;
+    int at = n;  // walk back over `prefetch` forward / backward passes; W passes ride along uncounted
+    for (int counted = 0; counted < prefetch && at > 0;) {
+      --at;
+      if (passes[at].kind != 4) ++counted;
+    }
     int lo = fpos[(size_t)p.chunk * m + p.mb] + 1;
     if (at < lo) at = lo;
     before[at].push_back(p);
