@@ -74,7 +74,9 @@ typedef struct po_config {
   int32_t select_policy;   /* po_select */
   int32_t staged_copies;   /* 0: copy slabs in place; 1: pack into a staging buffer before D2H, unpack after H2D */
   int32_t debug_poison;    /* 1: fill a slab with a NaN pattern whenever it is released */
-  int32_t profile_kernels; /* 1: po_run_schedule brackets every GEMM and attention launch with HIP events */
+  int32_t profile_kernels; /* k > 0: po_run_schedule brackets every k-th GEMM launch and every k-th attention
+                              launch with HIP events (1 = all; an event pair idles the stream for a few
+                              microseconds, so benchmarks sample with an odd k) */
   int32_t group;           /* g of PO_SCHED_GIS, ceil(d/2) <= g <= d; 0 = d */
   float ln_eps;            /* LayerNorm epsilon */
   uint64_t host_pool_cap_bytes;   /* 0 = unlimited; else PO_E_HOST_OOM beyond it */
@@ -105,10 +107,10 @@ typedef struct po_stats {
   double h2d_busy_s;        /* sum of reload copy durations */
   double pack_busy_s;       /* sum of pack + unpack kernel durations (staged copies only) */
   double compute_span_s;    /* first compute pass start to last compute pass end */
-  double gemm_busy_s;       /* profile_kernels: sum of GEMM launch durations on the compute stream */
+  double gemm_busy_s;       /* profile_kernels: sum of the timed GEMM launches' durations on the compute stream */
   double gemm_flops;        /* profile_kernels: 2 M N K summed over those launches */
-  double attn_busy_s;       /* profile_kernels: sum of attention forward/backward launch durations */
-  double attn_flops;        /* profile_kernels: causal model flops, 2 s^2 h forward, 4 s^2 h backward */
+  double attn_busy_s;       /* profile_kernels: sum of the timed attention forward/backward launches' durations */
+  double attn_flops;        /* profile_kernels: causal model flops of those, 2 s^2 h forward, 4 s^2 h backward */
   uint64_t bytes_d2h, bytes_h2d;
   uint64_t peak_slab_bytes;      /* high-water mark of activation slab bytes in use (incl. staging) */
   uint64_t pool_bytes_allocated; /* device bytes the slab pool holds */

@@ -324,6 +324,7 @@ struct po_stage {
   int resident_units = 0, in_flight_units = 0;
   po_stats stats;
   bool collect_timing = false;
+  uint64_t gemm_launch_counter = 0, attn_launch_counter = 0;  // for profile_kernels sampling
 
   void note_usage() {
     uint64_t b = (uint64_t)dev_pool.in_use * sl.bytes;
@@ -380,10 +381,19 @@ static Epilogue make_ep(int ldc) {
   return e;
 }
 
-// GEMM / attention launches of the stage; bracketed by events when profile_kernels is set.
+// GEMM / attention launches of the stage.  profile_kernels = k > 0 brackets every k-th GEMM launch and every
+// k-th attention launch of a run with events (k = 1: all).  An event pair costs a few microseconds of idle
+// stream, so k > 1 samples; an odd k that is coprime to the 12 GEMMs and 2 attention launches of a layer walks
+// through all of their shapes.
+static bool sample_launch(po_stage* st, uint64_t& counter) {
+  int k = st->cfg.profile_kernels;
+  if (!st->collect_timing || k <= 0) return false;
+  return counter++ % (uint64_t)k == 0;
+}
+
 static int st_gemm(po_stage* st, int ta, int tb, int M, int N, int K, const void* A, int lda, const void* B, int ldb,
                    const Epilogue& e) {
-  bool prof = st->collect_timing && st->cfg.profile_kernels;
+  bool prof = sample_launch(st, st->gemm_launch_counter);
   size_t span = (size_t)-1;
   if (prof) {
     int rc = span_begin(st, st->compute, 4, &span);
@@ -397,7 +407,7 @@ static int st_gemm(po_stage* st, int ta, int tb, int M, int N, int K, const void
 static int st_attention(po_stage* st, bool backward, const void* qkv, void* o, float* lse, const void* d_o,
                         void* dqkv) {
   const po_config& c = st->cfg;
-  bool prof = st->collect_timing && c.profile_kernels;
+  bool prof = sample_launch(st, st->attn_launch_counter);
   size_t span = (size_t)-1;
   if (prof) {
     int rc = span_begin(st, st->compute, 5, &span);
