@@ -81,6 +81,7 @@ def main():
     ap.add_argument("--profile-every", type=int, default=5,
                     help="bracket every k-th GEMM / attention launch of the timed steps with HIP events (1 = all; an "
                          "event pair idles the stream for a few microseconds, which costs about 7 %% at C2 with k = 1)")
+    ap.add_argument("--weight-stream", type=int, default=0, help="1: weight-gradient work on its own stream")
     ap.add_argument("--group", type=int, default=0, help="group size g of --schedule gis (0 = pipeline degree)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -103,7 +104,8 @@ def main():
     ratios = {}
     headline = None
     with StageRunner(shape, device_params=True, copy_streams=args.copy_streams, prefetch_passes=args.prefetch,
-                     staged_copies=args.staged, profile_kernels=args.profile_every, group=args.group) as r:
+                     staged_copies=args.staged, profile_kernels=args.profile_every, group=args.group,
+                     weight_stream=args.weight_stream) as r:
         r.make_inputs_on_device()
         for ratio in (0.0, 0.5, 1.0):
             for _ in range(args.warmup):
@@ -159,7 +161,8 @@ def main():
                                f"microbatches, simulated pipeline degree {shape.pipeline_degree}, "
                                f"schedule {sched_name}{' g=%d' % args.group if args.group else ''} rank 0; "
                                f"value is at offload ratio 1",
-                   "copy_streams": args.copy_streams, "prefetch_passes": args.prefetch, "staged_copies": args.staged},
+                   "copy_streams": args.copy_streams, "prefetch_passes": args.prefetch, "staged_copies": args.staged,
+                   "weight_stream": args.weight_stream},
         "ratios": {str(k): v for k, v in ratios.items()},
         "k_eq1_measured_serial": k_meas, "k_eq1_measured_duplex": (k_meas / 2 if k_meas else None),
         "roofline": {"bound": "mfma", "achieved": gemm["gemm_tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",

@@ -78,6 +78,9 @@ typedef struct po_config {
                               launch with HIP events (1 = all; an event pair idles the stream for a few
                               microseconds, so benchmarks sample with an odd k) */
   int32_t group;           /* g of PO_SCHED_GIS, ceil(d/2) <= g <= d; 0 = d */
+  int32_t weight_stream;   /* 1: weight-gradient work (W passes, and the weight half of po_stage_backward) runs on a
+                              stream of its own after the unit's input-gradient work, beside the compute stream;
+                              results are bit-identical to 0; gradients are complete after po_synchronize */
   float ln_eps;            /* LayerNorm epsilon */
   uint64_t host_pool_cap_bytes;   /* 0 = unlimited; else PO_E_HOST_OOM beyond it */
   uint64_t device_pool_cap_bytes; /* 0 = unlimited; else PO_E_DEVICE_OOM beyond it */

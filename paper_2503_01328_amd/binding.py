@@ -33,7 +33,7 @@ class po_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "n_chunks", "hidden", "n_heads", "ffn", "seq", "vocab", "dtype", "pipeline_degree", "rank",
         "prefetch_passes", "copy_streams", "select_policy", "staged_copies", "debug_poison", "profile_kernels",
-        "group")] + [
+        "group", "weight_stream")] + [
         ("ln_eps", C.c_float), ("host_pool_cap_bytes", C.c_uint64), ("device_pool_cap_bytes", C.c_uint64)]
 
 

@@ -75,7 +75,7 @@ int validate_config(const po_config* c) {
       c->rank < 0 || c->rank >= c->pipeline_degree || c->prefetch_passes < 0 ||
       (c->copy_streams != 1 && c->copy_streams != 2) || c->hidden / c->n_heads > 256 ||
       (c->hidden / c->n_heads) % 8 != 0 || !(c->ln_eps > 0.f) || c->group < 0 || c->group > c->pipeline_degree ||
-      (c->group > 0 && 2 * c->group < c->pipeline_degree)) {
+      (c->group > 0 && 2 * c->group < c->pipeline_degree) || (c->weight_stream != 0 && c->weight_stream != 1)) {
     set_error("invalid config: L=%d v=%d h=%d a=%d f=%d s=%d vocab=%d dtype=%d d=%d rank=%d prefetch=%d copy_streams=%d group=%d",
               c->n_layers, c->n_chunks, c->hidden, c->n_heads, c->ffn, c->seq, c->vocab, c->dtype,
               c->pipeline_degree, c->rank, c->prefetch_passes, c->copy_streams, c->group);
@@ -287,6 +287,7 @@ struct Unit {
   bool weight_pending = false;
   int grad_buf = -1;            // buffer of the gradient pool holding this unit's BwdBufs tensors
   const void* dy_top = nullptr;  // the caller's upstream gradient (read again by the weight-gradient pass)
+  hipEvent_t b_done = nullptr;   // end of the input-gradient pass on the compute stream
 };
 
 struct TimedSpan {
@@ -306,6 +307,7 @@ struct po_stage {
   int Lu = 0;
   size_t E = 2;
   hipStream_t compute = nullptr, offload = nullptr, reload = nullptr;
+  hipStream_t wstream = nullptr;  // weight-gradient passes run here when cfg.weight_stream is set
   bool own_reload_stream = false;
   const char* params = nullptr;
   float* grads = nullptr;
@@ -319,7 +321,8 @@ struct po_stage {
   char* ws = nullptr;
   size_t ws_bytes = 0;
   char *w_n, *w_g, *w_du, *w_dqkv, *w_do, *w_dx1, *w_dn, *w_dn1, *w_dy[2], *w_x0;
-  float *w_delta, *w_lnws, *w_lnws1, *w_colws;
+  char* w_n_w;  // LayerNorm recompute output of the weight-gradient half (own buffer: it may run on its own stream)
+  float *w_delta, *w_lnws, *w_lnws1, *w_colws, *w_colws_w;
   // accounting
   int resident_units = 0, in_flight_units = 0;
   po_stats stats;
@@ -392,16 +395,17 @@ static bool sample_launch(po_stage* st, uint64_t& counter) {
 }
 
 static int st_gemm(po_stage* st, int ta, int tb, int M, int N, int K, const void* A, int lda, const void* B, int ldb,
-                   const Epilogue& e) {
+                   const Epilogue& e, hipStream_t q = nullptr) {
+  if (!q) q = st->compute;
   bool prof = sample_launch(st, st->gemm_launch_counter);
   size_t span = (size_t)-1;
   if (prof) {
-    int rc = span_begin(st, st->compute, 4, &span);
+    int rc = span_begin(st, q, 4, &span);
     if (rc) return rc;
     st->spans[span].flops = 2.0 * M * N * K;
   }
-  PO_K(gemm(st->cfg.dtype, ta, tb, M, N, K, A, lda, B, ldb, e, false, st->compute));
-  return span_end(st, st->compute, span);
+  PO_K(gemm(st->cfg.dtype, ta, tb, M, N, K, A, lda, B, ldb, e, false, q));
+  return span_end(st, q, span);
 }
 
 static int st_attention(po_stage* st, bool backward, const void* qkv, void* o, float* lse, const void* d_o,
@@ -518,36 +522,38 @@ static int layer_backward_input(po_stage* st, int layer, const char* slab, const
 //   dW2 += g^T dy, db2 += colsum(dy); dW1 += n2^T du, db1 += colsum(du) with n2 = LN2(x1) recomputed;
 //   dWo += O^T dx1, dbo += colsum(dx1); dWqkv += n1^T dqkv, dbqkv += colsum(dqkv) with n1 = LN1(x) recomputed;
 //   LayerNorm gains and shifts from (dn2, x1) and (dn1, x) with the row statistics the input half left.
-static int layer_backward_weight(po_stage* st, int layer, const char* slab, const void* dy, const BwdBufs& b) {
+// Runs on stream q with the LayerNorm-output and column-sum scratch buffers n_out / colws (the weight stream has
+// its own, so that it can run beside the compute stream).
+static int layer_backward_weight(po_stage* st, int layer, const char* slab, const void* dy, const BwdBufs& b,
+                                 hipStream_t q, char* n_out, float* colws) {
   const po_config& c = st->cfg;
   const ParamLayout& pl = st->pl;
   const SlabLayout& sl = st->sl;
   int s = c.seq, h = c.hidden, f = c.ffn, dt = c.dtype;
-  hipStream_t q = st->compute;
   const char* x = slab + sl.off_x;
   const char* o = slab + sl.off_o;
   const char* x1 = slab + sl.off_x1;
 
   Epilogue e = make_ep(h);
   e.acc_f32 = st->G(layer, pl.w_fc2);
-  PO_RC(st_gemm(st, 1, 0, f, h, s, b.g, f, dy, h, e));
-  PO_K(colsum_accumulate(dt, dy, st->G(layer, pl.b_fc2), st->w_colws, s, h, q));
-  PO_K(layernorm_forward(dt, x1, st->P(layer, pl.ln2_g), st->P(layer, pl.ln2_b), st->w_n, s, h, c.ln_eps, q));
+  PO_RC(st_gemm(st, 1, 0, f, h, s, b.g, f, dy, h, e, q));
+  PO_K(colsum_accumulate(dt, dy, st->G(layer, pl.b_fc2), colws, s, h, q));
+  PO_K(layernorm_forward(dt, x1, st->P(layer, pl.ln2_g), st->P(layer, pl.ln2_b), n_out, s, h, c.ln_eps, q));
   e = make_ep(f);
   e.acc_f32 = st->G(layer, pl.w_fc1);
-  PO_RC(st_gemm(st, 1, 0, h, f, s, st->w_n, h, b.du, f, e));
-  PO_K(colsum_accumulate(dt, b.du, st->G(layer, pl.b_fc1), st->w_colws, s, f, q));
+  PO_RC(st_gemm(st, 1, 0, h, f, s, n_out, h, b.du, f, e, q));
+  PO_K(colsum_accumulate(dt, b.du, st->G(layer, pl.b_fc1), colws, s, f, q));
   PO_K(layernorm_backward(dt, b.dn2, x1, st->P(layer, pl.ln2_g), nullptr, nullptr, st->G(layer, pl.ln2_g),
                           st->G(layer, pl.ln2_b), b.lnws2, s, h, c.ln_eps, kLnParamGrad, q));
   e = make_ep(h);
   e.acc_f32 = st->G(layer, pl.w_o);
-  PO_RC(st_gemm(st, 1, 0, h, h, s, o, h, b.dx1, h, e));
-  PO_K(colsum_accumulate(dt, b.dx1, st->G(layer, pl.b_o), st->w_colws, s, h, q));
-  PO_K(layernorm_forward(dt, x, st->P(layer, pl.ln1_g), st->P(layer, pl.ln1_b), st->w_n, s, h, c.ln_eps, q));
+  PO_RC(st_gemm(st, 1, 0, h, h, s, o, h, b.dx1, h, e, q));
+  PO_K(colsum_accumulate(dt, b.dx1, st->G(layer, pl.b_o), colws, s, h, q));
+  PO_K(layernorm_forward(dt, x, st->P(layer, pl.ln1_g), st->P(layer, pl.ln1_b), n_out, s, h, c.ln_eps, q));
   e = make_ep(3 * h);
   e.acc_f32 = st->G(layer, pl.w_qkv);
-  PO_RC(st_gemm(st, 1, 0, h, 3 * h, s, st->w_n, h, b.dqkv, 3 * h, e));
-  PO_K(colsum_accumulate(dt, b.dqkv, st->G(layer, pl.b_qkv), st->w_colws, s, 3 * h, q));
+  PO_RC(st_gemm(st, 1, 0, h, 3 * h, s, n_out, h, b.dqkv, 3 * h, e, q));
+  PO_K(colsum_accumulate(dt, b.dqkv, st->G(layer, pl.b_qkv), colws, s, 3 * h, q));
   PO_K(layernorm_backward(dt, b.dn1, x, st->P(layer, pl.ln1_g), nullptr, nullptr, st->G(layer, pl.ln1_g),
                           st->G(layer, pl.ln1_b), b.lnws1, s, h, c.ln_eps, kLnParamGrad, q));
   return PO_OK;
@@ -817,11 +823,10 @@ static int backward_prologue(po_stage* st, int mb, int chunk, const void* dy, vo
 }
 
 // Hands the unit's slabs back once its last pass has been enqueued.
-static int retire_unit(po_stage* st, Unit* u) {
+static int retire_unit(po_stage* st, Unit* u, hipStream_t q) {
   for (UnitLayer& L : u->layers) {
-    if (st->cfg.debug_poison)
-      PO_K(fill_u32(st->dev_pool.bufs[L.dev].ptr, 0x7fc07fc0u, st->sl.bytes, st->compute));
-    int rc = st->dev_pool.release(L.dev, st->compute);
+    if (st->cfg.debug_poison) PO_K(fill_u32(st->dev_pool.bufs[L.dev].ptr, 0x7fc07fc0u, st->sl.bytes, q));
+    int rc = st->dev_pool.release(L.dev, q);
     if (rc) return rc;
     L = UnitLayer();
   }
@@ -861,9 +866,19 @@ static BwdBufs unit_bufs(const po_stage* st, char* buf, int l, char** dy_in) {
   return b;
 }
 
-// Fused backward: per layer, the input-gradient half directly followed by the weight-gradient half.
+int stage_backward_input(po_stage* st, int mb, int chunk, const void* dy, void* dx);
+static int backward_weight_impl(po_stage* st, int mb, int chunk, bool count_pass);
+
+// Fused backward: per layer, the input-gradient half directly followed by the weight-gradient half on the stage
+// workspaces.  With a weight stream it is the B pass on the compute stream and the W pass on the weight stream
+// (same kernels, same inputs, same results), so that the next passes overlap the weight gradients.
 int stage_backward(po_stage* st, int mb, int chunk, const void* dy, void* dx) {
   const po_config& c = st->cfg;
+  if (st->wstream) {
+    int rc = stage_backward_input(st, mb, chunk, dy, dx);
+    if (rc) return rc;
+    return backward_weight_impl(st, mb, chunk, false);
+  }
   Unit* u;
   int rc = backward_prologue(st, mb, chunk, dy, dx, "backward", &u);
   if (rc) return rc;
@@ -882,7 +897,7 @@ int stage_backward(po_stage* st, int mb, int chunk, const void* dy, void* dx) {
       out = embed ? (void*)st->w_dy[0] : dx;
     rc = layer_backward_input(st, chunk * st->Lu + l, slab, grad, out, bufs);
     if (rc) return rc;
-    rc = layer_backward_weight(st, chunk * st->Lu + l, slab, grad, bufs);
+    rc = layer_backward_weight(st, chunk * st->Lu + l, slab, grad, bufs, st->compute, st->w_n_w, st->w_colws_w);
     if (rc) return rc;
     grad = out;
   }
@@ -891,7 +906,7 @@ int stage_backward(po_stage* st, int mb, int chunk, const void* dy, void* dx) {
                             st->grads + st->pl.emb_wpe, c.seq, c.hidden, c.vocab, st->compute));
   rc = span_end(st, st->compute, span);
   if (rc) return rc;
-  rc = retire_unit(st, u);
+  rc = retire_unit(st, u, st->compute);
   if (rc) return rc;
   --st->in_flight_units;
   ++st->stats.n_compute_passes;
@@ -932,6 +947,11 @@ int stage_backward_input(po_stage* st, int mb, int chunk, const void* dy, void* 
   }
   rc = span_end(st, st->compute, span);
   if (rc) return rc;
+  if (st->wstream) {
+    rc = st->sync_events.get(&u->b_done);
+    if (rc) return rc;
+    PO_HIP(hipEventRecord(u->b_done, st->compute));
+  }
   u->weight_pending = true;
   u->dy_top = dy;
   --st->in_flight_units;
@@ -939,8 +959,9 @@ int stage_backward_input(po_stage* st, int mb, int chunk, const void* dy, void* 
   return PO_OK;
 }
 
-// Split backward, W pass: parameter gradients of every layer of the unit; frees the unit.
-int stage_backward_weight(po_stage* st, int mb, int chunk) {
+// Split backward, W pass: parameter gradients of every layer of the unit; frees the unit.  Runs on the weight
+// stream when there is one (after the unit's B pass), else on the compute stream.
+static int backward_weight_impl(po_stage* st, int mb, int chunk, bool count_pass) {
   const po_config& c = st->cfg;
   if (mb < 0 || chunk < 0 || chunk >= c.n_chunks) {
     set_error("weight-gradient pass: mb=%d chunk=%d", mb, chunk);
@@ -953,36 +974,41 @@ int stage_backward_weight(po_stage* st, int mb, int chunk) {
     return PO_E_STATE;
   }
   bool embed = c.vocab > 0 && chunk == 0;
+  hipStream_t q = st->wstream ? st->wstream : st->compute;
+  if (st->wstream) PO_HIP(hipStreamWaitEvent(q, u->b_done, 0));
   char* buf = st->grad_pool.bufs[u->grad_buf].ptr;
   size_t span;
-  int rc = span_begin(st, st->compute, 0, &span);
+  int rc = span_begin(st, q, 0, &span);
   if (rc) return rc;
   for (int l = st->Lu - 1; l >= 0; --l) {
     const char* slab = st->dev_pool.bufs[u->layers[l].dev].ptr;
     char* dy_in;
     BwdBufs bufs = unit_bufs(st, buf, l, &dy_in);
     const void* grad = l == st->Lu - 1 ? u->dy_top : (const void*)dy_in;
-    rc = layer_backward_weight(st, chunk * st->Lu + l, slab, grad, bufs);
+    rc = layer_backward_weight(st, chunk * st->Lu + l, slab, grad, bufs, q, st->w_n_w, st->w_colws_w);
     if (rc) return rc;
   }
   if (embed)
     PO_K(embedding_backward(c.dtype, (const int32_t*)u->x_in, buf + (size_t)st->Lu * st->gl_layer,
-                            st->grads + st->pl.emb_wte, st->grads + st->pl.emb_wpe, c.seq, c.hidden, c.vocab,
-                            st->compute));
-  rc = span_end(st, st->compute, span);
+                            st->grads + st->pl.emb_wte, st->grads + st->pl.emb_wpe, c.seq, c.hidden, c.vocab, q));
+  rc = span_end(st, q, span);
   if (rc) return rc;
-  rc = st->grad_pool.release(u->grad_buf, st->compute);
+  rc = st->grad_pool.release(u->grad_buf, q);
   if (rc) return rc;
   u->grad_buf = -1;
   u->dy_top = nullptr;
-  rc = retire_unit(st, u);
+  u->b_done = nullptr;
+  rc = retire_unit(st, u, q);
   if (rc) return rc;
-  ++st->stats.n_compute_passes;
+  if (count_pass) ++st->stats.n_compute_passes;
   return PO_OK;
 }
 
+int stage_backward_weight(po_stage* st, int mb, int chunk) { return backward_weight_impl(st, mb, chunk, true); }
+
 int stage_synchronize(po_stage* st) {
   PO_HIP(hipStreamSynchronize(st->compute));
+  if (st->wstream) PO_HIP(hipStreamSynchronize(st->wstream));
   PO_HIP(hipStreamSynchronize(st->offload));
   if (st->reload != st->offload) PO_HIP(hipStreamSynchronize(st->reload));
   return PO_OK;
@@ -1149,6 +1175,13 @@ int stage_create(const po_config* cfg, void* compute_stream, po_stage** out) {
   } else {
     st->reload = st->offload;
   }
+  if (cfg->weight_stream) {
+    if (hipStreamCreateWithFlags(&st->wstream, hipStreamNonBlocking) != hipSuccess) {
+      set_error("creating the weight-gradient stream failed");
+      st->wstream = nullptr;
+      return fail(PO_E_HIP);
+    }
+  }
   // Workspaces: one allocation, carved up.
   size_t s = cfg->seq, h = cfg->hidden, f = cfg->ffn, E = st->E;
   size_t sh = align_up(s * h * E, 256), sf = align_up(s * f * E, 256), s3h = align_up(s * 3 * h * E, 256);
@@ -1156,7 +1189,7 @@ int stage_create(const po_config* cfg, void* compute_stream, po_stage** out) {
   size_t lnws = align_up(layernorm_backward_workspace((int)s, (int)h), 256);
   size_t maxn = std::max((size_t)3 * h, f);
   size_t colws = align_up(colsum_workspace((int)s, (int)maxn), 256);
-  size_t total = 8 * sh + 2 * sf + s3h + delta + 2 * lnws + colws;
+  size_t total = 9 * sh + 2 * sf + s3h + delta + 2 * lnws + 2 * colws;
   // one unit's gradient buffer for the split backward: per layer g, du [s,f]; dn2, dx1, dn1, incoming dy [s,h];
   // dqkv [s,3h]; two LayerNorm workspaces; plus one [s,h] tensor per unit (gradient at the embedding output)
   st->gl_sh = sh;
@@ -1185,6 +1218,7 @@ int stage_create(const po_config* cfg, void* compute_stream, po_stage** out) {
   st->w_dx1 = take(sh);
   st->w_dn = take(sh);
   st->w_dn1 = take(sh);
+  st->w_n_w = take(sh);
   st->w_dy[0] = take(sh);
   st->w_dy[1] = take(sh);
   st->w_x0 = take(sh);
@@ -1195,6 +1229,7 @@ int stage_create(const po_config* cfg, void* compute_stream, po_stage** out) {
   st->w_lnws = (float*)take(lnws);
   st->w_lnws1 = (float*)take(lnws);
   st->w_colws = (float*)take(colws);
+  st->w_colws_w = (float*)take(colws);
   reset_run_stats(st);
   *out = st;
   return PO_OK;
@@ -1305,6 +1340,7 @@ void po_stage_destroy(po_stage* st) {
   if (st->ws) (void)hipFree(st->ws);
   if (st->own_reload_stream && st->reload) (void)hipStreamDestroy(st->reload);
   if (st->offload) (void)hipStreamDestroy(st->offload);
+  if (st->wstream) (void)hipStreamDestroy(st->wstream);
   delete st;
 }
 

@@ -92,7 +92,9 @@ def test_offload_is_bit_identical_in_every_mode(gpu_device, shape):
     for kw in [dict(ratio=0.0), dict(ratio=0.5), dict(ratio=1.0), dict(ratio=1.0, copy_streams=1),
                dict(ratio=1.0, staged_copies=1), dict(ratio=0.5, staged_copies=1, copy_streams=1),
                dict(ratio=1.0, prefetch_passes=0), dict(ratio=1.0, prefetch_passes=3),
-               dict(ratio=1.0, debug_poison=1), dict(ratio=1.0, debug_poison=1, staged_copies=1)]:
+               dict(ratio=1.0, debug_poison=1), dict(ratio=1.0, debug_poison=1, staged_copies=1),
+               dict(ratio=0.0, weight_stream=1), dict(ratio=1.0, weight_stream=1),
+               dict(ratio=1.0, weight_stream=1, debug_poison=1, prefetch_passes=1)]:
         ratio = kw.pop("ratio")
         with StageRunner(shape, **kw) as r:
             r.make_inputs()
@@ -288,6 +290,10 @@ def test_gis_schedule_against_oracle_and_schedule_model(gpu_device, group):
                 _compare(shape, r.results(), _oracle(shape, r, m), 2e-2)
     for ratio in (0.5, 1.0):
         _assert_bit_identical(results[0.0], results[ratio])
+    with StageRunner(shape, group=group, weight_stream=1, debug_poison=1) as r:  # W passes on their own stream
+        r.make_inputs()
+        r.run(po.PO_SCHED_GIS, 1.0)
+        _assert_bit_identical(results[0.0], _snapshot(r))
     # every chunk sees its microbatches in ascending order in all these schedules, so the interleaved 1F1B run
     # accumulates the same sums in the same order
     with StageRunner(shape) as r:
