@@ -69,6 +69,69 @@ __global__ __launch_bounds__(256) void ln_forward_kernel(const T* __restrict__ x
   }
 }
 
+// Same arithmetic in the same order with the row held in registers: VPL 16-byte vectors per lane, one pass
+// over memory.  Used when h is VPL * 64 vectors exactly.
+template <typename T, int VPL>
+__global__ __launch_bounds__(256) void ln_forward_cached_kernel(const T* __restrict__ x, const T* __restrict__ gain,
+                                                                const T* __restrict__ shift, T* __restrict__ y,
+                                                                int rows, int h, float eps) {
+  constexpr int V = Vec16<T>::N;
+  int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  int lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const T* xr = x + (size_t)row * h;
+  T* yr = y + (size_t)row * h;
+  Vec16<T> xv[VPL];
+#pragma unroll
+  for (int j = 0; j < VPL; ++j) xv[j] = load16(xr + (j * kWave + lane) * V);
+  float sum = 0.f;
+#pragma unroll
+  for (int j = 0; j < VPL; ++j)
+#pragma unroll
+    for (int i = 0; i < V; ++i) sum += to_f32(xv[j].v[i]);
+  float mean = wave_sum(sum) / (float)h;
+  float sq = 0.f;
+#pragma unroll
+  for (int j = 0; j < VPL; ++j)
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      float d = to_f32(xv[j].v[i]) - mean;
+      sq += d * d;
+    }
+  float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)h + eps);
+#pragma unroll
+  for (int j = 0; j < VPL; ++j) {
+    int c = (j * kWave + lane) * V;
+    Vec16<T> g = load16(gain + c), b = load16(shift + c), o;
+#pragma unroll
+    for (int i = 0; i < V; ++i)
+      o.v[i] = from_f32<T>((to_f32(xv[j].v[i]) - mean) * rstd * to_f32(g.v[i]) + to_f32(b.v[i]));
+    store16(yr + c, o);
+  }
+}
+
+// Vectors per lane of a row that fits the register-cached kernels, else 0.
+template <typename T>
+static int cached_vpl(int h) {
+  int per_pass = kWave * Vec16<T>::N;
+  if (h % per_pass != 0) return 0;
+  int vpl = h / per_pass;
+  return (vpl <= 6 || vpl == 8 || vpl == 10 || vpl == 12 || vpl == 16) ? vpl : 0;
+}
+#define PO_VPL_SWITCH(vpl, CALL) \
+  switch (vpl) {                 \
+    case 1: CALL(1); break;      \
+    case 2: CALL(2); break;      \
+    case 3: CALL(3); break;      \
+    case 4: CALL(4); break;      \
+    case 5: CALL(5); break;      \
+    case 6: CALL(6); break;      \
+    case 8: CALL(8); break;      \
+    case 10: CALL(10); break;    \
+    case 12: CALL(12); break;    \
+    default: CALL(16); break;    \
+  }
+
 bool layernorm_forward(int dtype, const void* x, const void* gain, const void* shift, void* y, int rows, int h,
                        float eps, hipStream_t stream) {
   if (rows <= 0 || h <= 0 || h % 8 != 0) {
@@ -76,6 +139,21 @@ bool layernorm_forward(int dtype, const void* x, const void* gain, const void* s
     return false;
   }
   dim3 grid(ceil_div(rows, 4)), block(256);
+  int vpl = dtype == kF32 ? cached_vpl<float>(h) : cached_vpl<bf16>(h);
+  if (vpl) {
+#define PO_LNF_F32(N) ln_forward_cached_kernel<float, N><<<grid, block, 0, stream>>>( \
+      (const float*)x, (const float*)gain, (const float*)shift, (float*)y, rows, h, eps)
+#define PO_LNF_BF16(N) ln_forward_cached_kernel<bf16, N><<<grid, block, 0, stream>>>( \
+      (const bf16*)x, (const bf16*)gain, (const bf16*)shift, (bf16*)y, rows, h, eps)
+    if (dtype == kF32) {
+      PO_VPL_SWITCH(vpl, PO_LNF_F32)
+    } else {
+      PO_VPL_SWITCH(vpl, PO_LNF_BF16)
+    }
+#undef PO_LNF_F32
+#undef PO_LNF_BF16
+    return launch_ok("ln_forward_cached_kernel");
+  }
   if (dtype == kF32)
     ln_forward_kernel<float><<<grid, block, 0, stream>>>((const float*)x, (const float*)gain, (const float*)shift,
                                                          (float*)y, rows, h, eps);
@@ -125,6 +203,73 @@ __global__ __launch_bounds__(256) void ln_backward_rows_kernel(const T* __restri
     for (int i = 0; i < V; ++i) {
       float xh = (to_f32(v.v[i]) - mean) * rstd;
       float dxh = to_f32(d.v[i]) * to_f32(g.v[i]);
+      float val = rstd * (dxh - c1 - xh * c2);
+      if (dres) val += to_f32(r.v[i]);
+      o.v[i] = from_f32<T>(val);
+    }
+    store16(dx + (size_t)row * h + c, o);
+  }
+  if (lane == 0) {
+    stats[2 * row] = mean;
+    stats[2 * row + 1] = rstd;
+  }
+}
+
+// ln_backward_rows_kernel with x and dn of the row held in registers (same arithmetic, same order).
+template <typename T, int VPL>
+__global__ __launch_bounds__(256) void ln_backward_rows_cached_kernel(const T* __restrict__ dn, const T* __restrict__ x,
+                                                                      const T* __restrict__ gain,
+                                                                      const T* __restrict__ dres, T* __restrict__ dx,
+                                                                      float* __restrict__ stats, int rows, int h,
+                                                                      float eps) {
+  constexpr int V = Vec16<T>::N;
+  int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  int lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const T* xr = x + (size_t)row * h;
+  const T* dnr = dn + (size_t)row * h;
+  Vec16<T> xv[VPL], dv[VPL];
+#pragma unroll
+  for (int j = 0; j < VPL; ++j) {
+    xv[j] = load16(xr + (j * kWave + lane) * V);
+    dv[j] = load16(dnr + (j * kWave + lane) * V);
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int j = 0; j < VPL; ++j)
+#pragma unroll
+    for (int i = 0; i < V; ++i) sum += to_f32(xv[j].v[i]);
+  float mean = wave_sum(sum) / (float)h;
+  float sq = 0.f;
+#pragma unroll
+  for (int j = 0; j < VPL; ++j)
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      float d = to_f32(xv[j].v[i]) - mean;
+      sq += d * d;
+    }
+  float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)h + eps);
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int j = 0; j < VPL; ++j) {
+    Vec16<T> g = load16(gain + (j * kWave + lane) * V);
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      float dxh = to_f32(dv[j].v[i]) * to_f32(g.v[i]);
+      s1 += dxh;
+      s2 += dxh * (to_f32(xv[j].v[i]) - mean) * rstd;
+    }
+  }
+  float c1 = wave_sum(s1) / (float)h, c2 = wave_sum(s2) / (float)h;
+#pragma unroll
+  for (int j = 0; j < VPL; ++j) {
+    int c = (j * kWave + lane) * V;
+    Vec16<T> g = load16(gain + c), r, o;
+    if (dres) r = load16(dres + (size_t)row * h + c);
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      float xh = (to_f32(xv[j].v[i]) - mean) * rstd;
+      float dxh = to_f32(dv[j].v[i]) * to_f32(g.v[i]);
       float val = rstd * (dxh - c1 - xh * c2);
       if (dres) val += to_f32(r.v[i]);
       o.v[i] = from_f32<T>(val);
@@ -239,7 +384,20 @@ bool layernorm_backward(int dtype, const void* dn, const void* x, const void* ga
   int n_chunks = reduce_chunks(rows);
   int rows_per_chunk = ceil_div(rows, n_chunks);
   dim3 g1(ceil_div(rows, 4)), g2(ceil_div(h, 128), n_chunks), g3(ceil_div(h, 64));
-  if (parts & kLnInputGrad) {  // dx and the row statistics (kept in the workspace for the parameter part)
+  int vpl = dtype == kF32 ? cached_vpl<float>(h) : cached_vpl<bf16>(h);
+  if ((parts & kLnInputGrad) && vpl) {
+#define PO_LNB_F32(N) ln_backward_rows_cached_kernel<float, N><<<g1, 256, 0, stream>>>( \
+      (const float*)dn, (const float*)x, (const float*)gain, (const float*)dres, (float*)dx, stats, rows, h, eps)
+#define PO_LNB_BF16(N) ln_backward_rows_cached_kernel<bf16, N><<<g1, 256, 0, stream>>>( \
+      (const bf16*)dn, (const bf16*)x, (const bf16*)gain, (const bf16*)dres, (bf16*)dx, stats, rows, h, eps)
+    if (dtype == kF32) {
+      PO_VPL_SWITCH(vpl, PO_LNB_F32)
+    } else {
+      PO_VPL_SWITCH(vpl, PO_LNB_BF16)
+    }
+#undef PO_LNB_F32
+#undef PO_LNB_BF16
+  } else if (parts & kLnInputGrad) {  // dx and the row statistics (kept in the workspace for the parameter part)
     if (dtype == kF32)
       ln_backward_rows_kernel<float><<<g1, 256, 0, stream>>>((const float*)dn, (const float*)x, (const float*)gain,
                                                              (const float*)dres, (float*)dx, stats, rows, h, eps);

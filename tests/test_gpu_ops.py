@@ -30,7 +30,7 @@ def _np(t):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("rows,h", [(1, 64), (7, 256), (130, 1024), (33, 5120)])
+@pytest.mark.parametrize("rows,h", [(1, 64), (7, 256), (130, 1024), (33, 5120), (5, 2048), (3, 3584), (4, 8192)])
 def test_layernorm_forward_and_backward(gpu_device, dtype, rows, h):
     code, tdt, tol = DT[dtype]
     rng = np.random.default_rng(rows * 1000 + h)
