@@ -81,6 +81,8 @@ typedef struct po_config {
   int32_t weight_stream;   /* 1: weight-gradient work (W passes, and the weight half of po_stage_backward) runs on a
                               stream of its own after the unit's input-gradient work, beside the compute stream;
                               results are bit-identical to 0; gradients are complete after po_synchronize */
+  int32_t min_gap_passes;  /* run_schedule does not offload a unit with fewer than this many forward / backward
+                              passes between its forward and its backward (Section 4.4); 0 = offload all */
   float ln_eps;            /* LayerNorm epsilon */
   uint64_t host_pool_cap_bytes;   /* 0 = unlimited; else PO_E_HOST_OOM beyond it */
   uint64_t device_pool_cap_bytes; /* 0 = unlimited; else PO_E_DEVICE_OOM beyond it */
@@ -144,7 +146,7 @@ int po_saved_bytes_per_layer(const po_config* cfg, uint64_t* bytes);
  * single rank: offload right after the forward, reload `prefetch` compute passes
  * ahead of the backward).  out may be NULL to query *n. */
 int po_schedule_ops(int32_t schedule, int32_t d, int32_t rank, int32_t v, int32_t m, int32_t group, float ratio,
-                    int32_t policy, int32_t prefetch, po_op* out, int32_t* n);
+                    int32_t policy, int32_t prefetch, int32_t min_gap, po_op* out, int32_t* n);
 
 /* Eq. 1: k = 10 / (3 (6h + s)) * B_c / B_o, with B_c in flop/s and B_o in byte/s. */
 double po_offload_k(int32_t h, int32_t s, double compute_flops_per_s, double link_bytes_per_s);

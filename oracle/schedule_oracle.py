@@ -183,7 +183,23 @@ def selected_units(m, v, ratio, policy="alternate-mb"):
     return sel
 
 
-def with_offload(passes, selected, prefetch=1):
+def forward_backward_gaps(passes):
+    """For every unit, the number of forward / backward passes that run strictly
+    between its forward and its backward (weight-gradient passes not counted)."""
+    pos, gap = {}, {}
+    n = 0
+    for kind, mb, c in passes:
+        if kind == "W":
+            continue
+        if kind == "F":
+            pos[(mb, c)] = n
+        else:
+            gap[(mb, c)] = n - pos[(mb, c)] - 1
+        n += 1
+    return gap
+
+
+def with_offload(passes, selected, prefetch=1, min_gap=0):
     """Insert OFFLOAD / RELOAD ops into a list of compute passes.
 
     OFFLOAD(u) directly follows F(u).  RELOAD(u) is placed directly before the
@@ -191,7 +207,15 @@ def with_offload(passes, selected, prefetch=1):
     directly before B(u) itself), but never before OFFLOAD(u).  Weight-gradient
     passes are not counted: a (B, W) pair is one backward's worth of time, so the
     same ``prefetch`` buys the same lead with fused and with split backwards.
+
+    min_gap (Section 4.4, second caveat): a selected unit with fewer than min_gap
+    forward / backward passes between its forward and its backward is not
+    offloaded at all; its round trip could not be hidden and it adds next to
+    nothing to the peak.
     """
+    if min_gap > 0:
+        gap = forward_backward_gaps(passes)
+        selected = {u for u in selected if gap[u] >= min_gap}
     pos_f = {(mb, c): n for n, (kind, mb, c) in enumerate(passes) if kind == "F"}
     reload_before = {}
     for n, (kind, mb, c) in enumerate(passes):

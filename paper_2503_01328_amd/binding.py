@@ -33,7 +33,7 @@ class po_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "n_chunks", "hidden", "n_heads", "ffn", "seq", "vocab", "dtype", "pipeline_degree", "rank",
         "prefetch_passes", "copy_streams", "select_policy", "staged_copies", "debug_poison", "profile_kernels",
-        "group", "weight_stream")] + [
+        "group", "weight_stream", "min_gap_passes")] + [
         ("ln_eps", C.c_float), ("host_pool_cap_bytes", C.c_uint64), ("device_pool_cap_bytes", C.c_uint64)]
 
 
@@ -65,7 +65,7 @@ EXPORTS = {
     "po_param_count": (C.c_int, [C.POINTER(po_config), C.POINTER(C.c_int64)]),
     "po_param_layout": (C.c_int, [C.POINTER(po_config), C.POINTER(po_param_desc), C.POINTER(C.c_int32)]),
     "po_saved_bytes_per_layer": (C.c_int, [C.POINTER(po_config), C.POINTER(C.c_uint64)]),
-    "po_schedule_ops": (C.c_int, [C.c_int32] * 6 + [C.c_float, C.c_int32, C.c_int32, C.POINTER(po_op),
+    "po_schedule_ops": (C.c_int, [C.c_int32] * 6 + [C.c_float, C.c_int32, C.c_int32, C.c_int32, C.POINTER(po_op),
                                                     C.POINTER(C.c_int32)]),
     "po_offload_k": (C.c_double, [C.c_int32, C.c_int32, C.c_double, C.c_double]),
     "po_stage_create": (C.c_int, [C.POINTER(po_config), C.c_void_p, C.POINTER(C.c_void_p)]),
@@ -165,11 +165,11 @@ def po_saved_bytes_per_layer(cfg) -> int:
     return b.value
 
 
-def po_schedule_ops(schedule, d, rank, v, m, ratio, policy=0, prefetch=2, group=0):
+def po_schedule_ops(schedule, d, rank, v, m, ratio, policy=0, prefetch=2, group=0, min_gap=0):
     n = C.c_int32(0)
-    _check(lib.po_schedule_ops(schedule, d, rank, v, m, group, ratio, policy, prefetch, None, C.byref(n)))
+    _check(lib.po_schedule_ops(schedule, d, rank, v, m, group, ratio, policy, prefetch, min_gap, None, C.byref(n)))
     arr = (po_op * n.value)()
-    _check(lib.po_schedule_ops(schedule, d, rank, v, m, group, ratio, policy, prefetch, arr, C.byref(n)))
+    _check(lib.po_schedule_ops(schedule, d, rank, v, m, group, ratio, policy, prefetch, min_gap, arr, C.byref(n)))
     return [(OP_KINDS[o.kind], o.mb, o.chunk) for o in arr]
 
 

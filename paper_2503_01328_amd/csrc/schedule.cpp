@@ -16,7 +16,9 @@
 // Offload placement (Section 4.2 collapsed to one rank with its own copy queues):
 // OFFLOAD directly after the unit's forward; RELOAD `prefetch` compute passes
 // before the unit's backward (W passes not counted: a B and its W together are one
-// backward's worth of time), never before its OFFLOAD.
+// backward's worth of time), never before its OFFLOAD.  Units with fewer than min_gap
+// forward / backward passes between their forward and backward are not offloaded
+// (Section 4.4: their round trip cannot be hidden and they add nothing to the peak).
 #include <math.h>
 
 #include <vector>
@@ -108,9 +110,10 @@ static bool unit_selected(int mb, int chunk, int v, float ratio, int policy) {
 }
 
 bool build_schedule(int schedule, int d, int rank, int v, int m, int group, float ratio, int policy, int prefetch,
-                    std::vector<po_op>& ops) {
-  if (!(ratio >= 0.f && ratio <= 1.f) || prefetch < 0 || (policy != PO_SEL_ALTERNATE_MB && policy != PO_SEL_LONGEST_LIFESPAN)) {
-    set_error("schedule: ratio=%g prefetch=%d policy=%d", ratio, prefetch, policy);
+                    int min_gap, std::vector<po_op>& ops) {
+  if (!(ratio >= 0.f && ratio <= 1.f) || prefetch < 0 || min_gap < 0 ||
+      (policy != PO_SEL_ALTERNATE_MB && policy != PO_SEL_LONGEST_LIFESPAN)) {
+    set_error("schedule: ratio=%g prefetch=%d min_gap=%d policy=%d", ratio, prefetch, min_gap, policy);
     return false;
   }
   std::vector<Pass> passes;
@@ -120,11 +123,28 @@ bool build_schedule(int schedule, int d, int rank, int v, int m, int group, floa
   std::vector<int> fpos((size_t)m * v, -1);
   for (int n = 0; n < np; ++n)
     if (passes[n].kind == 0) fpos[(size_t)passes[n].chunk * m + passes[n].mb] = n;
+  // units that are offloaded: selected by the ratio, and (Section 4.4) with at least min_gap forward / backward
+  // passes between their forward and their backward
+  std::vector<char> offloaded((size_t)m * v, 0);
+  {
+    std::vector<int> fb_index((size_t)m * v, 0);
+    int count = 0;
+    for (int n = 0; n < np; ++n) {
+      const Pass& p = passes[n];
+      if (p.kind == 4) continue;
+      size_t u = (size_t)p.chunk * m + p.mb;
+      if (p.kind == 0)
+        fb_index[u] = count;
+      else
+        offloaded[u] = unit_selected(p.mb, p.chunk, v, ratio, policy) && count - fb_index[u] - 1 >= min_gap;
+      ++count;
+    }
+  }
   // reloads to emit before pass n
   std::vector<std::vector<Pass>> before(np);
   for (int n = 0; n < np; ++n) {
     const Pass& p = passes[n];
-    if (p.kind != 1 || !unit_selected(p.mb, p.chunk, v, ratio, policy)) continue;
+    if (p.kind != 1 || !offloaded[(size_t)p.chunk * m + p.mb]) continue;
     int at = n;  // walk back over `prefetch` forward / backward passes; W passes ride along uncounted
     for (int counted = 0; counted < prefetch && at > 0;) {
       --at;
@@ -138,7 +158,7 @@ bool build_schedule(int schedule, int d, int rank, int v, int m, int group, floa
   for (int n = 0; n < np; ++n) {
     for (const Pass& r : before[n]) ops.push_back(po_op{3, r.mb, r.chunk, 1.0f});
     ops.push_back(po_op{passes[n].kind, passes[n].mb, passes[n].chunk, 0.f});
-    if (passes[n].kind == 0 && unit_selected(passes[n].mb, passes[n].chunk, v, ratio, policy))
+    if (passes[n].kind == 0 && offloaded[(size_t)passes[n].chunk * m + passes[n].mb])
       ops.push_back(po_op{2, passes[n].mb, passes[n].chunk, 1.0f});
   }
   return true;

@@ -34,6 +34,7 @@
 namespace po {
 
 bool build_schedule(int schedule, int d, int rank, int v, int m, int group, float ratio, int policy, int prefetch,
+                    int min_gap,
                     std::vector<po_op>& ops);
 
 #define PO_HIP(expr)                                                                          \
@@ -75,7 +76,7 @@ int validate_config(const po_config* c) {
       c->rank < 0 || c->rank >= c->pipeline_degree || c->prefetch_passes < 0 ||
       (c->copy_streams != 1 && c->copy_streams != 2) || c->hidden / c->n_heads > 256 ||
       (c->hidden / c->n_heads) % 8 != 0 || !(c->ln_eps > 0.f) || c->group < 0 || c->group > c->pipeline_degree ||
-      (c->group > 0 && 2 * c->group < c->pipeline_degree) || (c->weight_stream != 0 && c->weight_stream != 1)) {
+      (c->group > 0 && 2 * c->group < c->pipeline_degree) || (c->weight_stream != 0 && c->weight_stream != 1) || c->min_gap_passes < 0) {
     set_error("invalid config: L=%d v=%d h=%d a=%d f=%d s=%d vocab=%d dtype=%d d=%d rank=%d prefetch=%d copy_streams=%d group=%d",
               c->n_layers, c->n_chunks, c->hidden, c->n_heads, c->ffn, c->seq, c->vocab, c->dtype,
               c->pipeline_degree, c->rank, c->prefetch_passes, c->copy_streams, c->group);
@@ -1082,7 +1083,7 @@ int stage_run_schedule(po_stage* st, int schedule, int m, float ratio, const voi
   }
   std::vector<po_op> ops;
   if (!build_schedule(schedule, c.pipeline_degree, c.rank, c.n_chunks, m, c.group, ratio, c.select_policy,
-                      c.prefetch_passes, ops))
+                      c.prefetch_passes, c.min_gap_passes, ops))
     return PO_E_INVAL;
   for (auto& kv : st->units)
     if (kv.second.live) {
@@ -1305,13 +1306,13 @@ int po_saved_bytes_per_layer(const po_config* cfg, uint64_t* bytes) {
 }
 
 int po_schedule_ops(int32_t schedule, int32_t d, int32_t rank, int32_t v, int32_t m, int32_t group, float ratio,
-                    int32_t policy, int32_t prefetch, po_op* out, int32_t* n) {
+                    int32_t policy, int32_t prefetch, int32_t min_gap, po_op* out, int32_t* n) {
   if (!n) {
     set_error("po_schedule_ops: n is NULL");
     return PO_E_INVAL;
   }
   std::vector<po_op> ops;
-  if (!build_schedule(schedule, d, rank, v, m, group, ratio, policy, prefetch, ops)) return PO_E_INVAL;
+  if (!build_schedule(schedule, d, rank, v, m, group, ratio, policy, prefetch, min_gap, ops)) return PO_E_INVAL;
   int32_t have = (int32_t)ops.size();
   if (out) {
     int32_t k = *n < have ? *n : have;

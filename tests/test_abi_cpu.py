@@ -58,6 +58,17 @@ def test_gis_schedule_ops_match_the_oracle_model(d, v, m, g, ratio, prefetch):
             assert sch.simulate(got)["errors"] == []
 
 
+@pytest.mark.parametrize("name,d,v,m", [("1f1b", 8, 1, 16), ("1f1b-interleaved", 8, 2, 32), ("gis", 8, 2, 32)])
+@pytest.mark.parametrize("min_gap", [1, 3, 9])
+def test_short_gap_units_are_skipped_like_in_the_oracle_model(name, d, v, m, min_gap):
+    code = {"gis": po.PO_SCHED_GIS, **SCHEDS}[name]
+    for rank in range(d):
+        for ratio in (0.5, 1.0):
+            got = po.po_schedule_ops(code, d, rank, v, m, ratio, 0, 2, min_gap=min_gap)
+            want = sch.with_offload(sch.compute_passes(name, d, rank, v, m), sch.selected_units(m, v, ratio), 2, min_gap)
+            assert got == want
+
+
 def test_gis_schedule_rejects_bad_groups():
     for g, m in [(3, 32), (9, 32), (8, 30)]:
         with pytest.raises(po.PipeOffloadError) as e:

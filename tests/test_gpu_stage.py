@@ -300,3 +300,17 @@ def test_gis_schedule_against_oracle_and_schedule_model(gpu_device, group):
         r.make_inputs()
         r.run(po.PO_SCHED_1F1B_INTERLEAVED, 0.0)
         _assert_bit_identical(results[0.0], _snapshot(r))
+
+
+def test_short_gap_units_are_not_offloaded(gpu_device):
+    # last rank of 1F1B: every backward directly follows its forward; with min_gap_passes = 1 nothing moves
+    shape = syn.StageShape(2, 1, 128, 2, 512, 64, dtype="bf16", pipeline_degree=4, rank=3, n_microbatches=6)
+    snaps = {}
+    for min_gap in (0, 1):
+        with StageRunner(shape, min_gap_passes=min_gap) as r:
+            r.make_inputs()
+            stats = r.run(po.PO_SCHED_1F1B, 1.0)
+            snaps[min_gap] = _snapshot(r)
+            assert stats["n_offloads"] == (12 if min_gap == 0 else 0)
+            assert stats["peak_resident_units"] == 1
+    _assert_bit_identical(snaps[0], snaps[1])

@@ -226,3 +226,37 @@ def test_offload_invariants_with_split_backward(ratio, prefetch, g):
                 between = [o for o in ops[n + 1:] if o[0] in "FB"]
                 gap = between.index(("B", mb, c))
                 assert gap == prefetch or all(o[0] in ("RELOAD", "OFFLOAD") for o in ops[ops.index(("OFFLOAD", mb, c)):n])
+
+
+# ---- short-gap units are not worth offloading (Section 4.4, second caveat) ------------------------------------
+@pytest.mark.parametrize("name,d,v,m", [("1f1b", 8, 1, 16), ("1f1b-interleaved", 8, 2, 32), ("gis", 8, 2, 32),
+                                        ("1f1b", 4, 1, 8)])
+@pytest.mark.parametrize("prefetch", [1, 2, 3])
+def test_skipping_short_gap_units_leaves_the_peak_alone(name, d, v, m, prefetch):
+    for rank in range(d):
+        passes = sch.compute_passes(name, d, rank, v, m)
+        gap = sch.forward_backward_gaps(passes)
+        sel = sch.selected_units(m, v, 1.0)
+        full = sch.simulate(sch.with_offload(passes, sel, prefetch))
+        for min_gap in range(0, prefetch + 2):
+            ops = sch.with_offload(passes, sel, prefetch, min_gap)
+            r = sch.simulate(ops)
+            assert r["errors"] == []
+            kept = {o[1:] for o in ops if o[0] == "OFFLOAD"}
+            assert kept == {u for u in sel if gap[u] >= min_gap}
+            # a unit whose reload would directly follow its offload contributes nothing: same peak without it
+            assert r["peak_resident"] == full["peak_resident"]
+    # the last rank of 1F1B runs every backward right after its forward: nothing is worth offloading there
+    last = sch.compute_passes(name, d, d - 1, v, m)
+    if name == "1f1b":
+        assert set(sch.forward_backward_gaps(last).values()) == {0}
+        assert not any(o[0] == "OFFLOAD" for o in sch.with_offload(last, sch.selected_units(m, v, 1.0), prefetch, 1))
+
+
+def test_forward_backward_gap_on_rank0_of_1f1b():
+    # d = 4, m = 8 on rank 0: F0 F1 F2 | F3 B0 F4 B1 F5 B2 F6 B3 F7 B4 | B5 B6 B7, counted by hand
+    gap = sch.forward_backward_gaps(sch.one_f_one_b(4, 0, 8))
+    assert [gap[(j, 0)] for j in range(8)] == [3, 4, 5, 6, 6, 5, 4, 3]
+    # weight-gradient passes are not counted
+    gis = sch.generalized_interleaved(4, 0, 1, 8)
+    assert sch.forward_backward_gaps(gis) == sch.forward_backward_gaps([o for o in gis if o[0] != "W"])
