@@ -7,7 +7,8 @@ parameters and outputs are resident in HBM before the timed region; slab and
 pinned-buffer pools are warm.  Prints ONE JSON line.
 
   value            stage tokens/s at offload ratio 1 (full offload), m*s / step time
-  ratios           tokens/s, ms/step, peak activation GB, overlap, host-link GB/s at ratios 0, 0.5, 1
+  ratios           tokens/s, ms/step, peak activation GB, overlap, host-link GB/s at ratios 0, 0.5, 1 and at
+                   "auto" = min(1, 1/k) with k from the measured transfer and compute times (Section 2)
   roofline         bf16 MFMA GEMM launches of the timed steps (HIP events on the compute stream,
                    recorded by the library around every k-th GEMM launch, k = --profile-every) against 2.5 PFLOP/s
   cpu_baseline     the numpy oracle timed on a bounded sample of the same workload
@@ -72,6 +73,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="C2", help="workload: C1..C5 (default C2, the configuration the metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-auto-ratio", action="store_true",
+                    help="skip the extra measurement at the ratio min(1, 1/k) derived from the measured transfer times")
     ap.add_argument("--copy-streams", type=int, default=2)
     ap.add_argument("--prefetch", type=int, default=2)
     ap.add_argument("--staged", type=int, default=0)
@@ -107,7 +110,7 @@ def main():
                      staged_copies=args.staged, profile_kernels=args.profile_every, group=args.group,
                      weight_stream=args.weight_stream) as r:
         r.make_inputs_on_device()
-        for ratio in (0.0, 0.5, 1.0):
+        def measure(ratio):
             for _ in range(args.warmup):
                 r.run(sched, ratio)
             torch.cuda.synchronize()
@@ -121,13 +124,14 @@ def main():
                    ("compute_busy_s", "d2h_busy_s", "h2d_busy_s", "gemm_busy_s", "gemm_flops", "attn_busy_s",
                     "attn_flops", "pack_busy_s")}
             last = per[-1]
-            ratios[ratio] = dict(
+            return dict(
                 tokens_per_s=tokens / dt, ms_per_step=dt * 1e3,
                 peak_activation_gb=last["peak_slab_bytes"] / 1e9,
                 peak_resident_units=last["peak_resident_units"], peak_in_flight_units=last["peak_in_flight_units"],
                 d2h_gb_per_s=(last["bytes_d2h"] / agg["d2h_busy_s"] / 1e9) if agg["d2h_busy_s"] else None,
                 h2d_gb_per_s=(last["bytes_h2d"] / agg["h2d_busy_s"] / 1e9) if agg["h2d_busy_s"] else None,
                 copy_busy_ms=(agg["d2h_busy_s"] + agg["h2d_busy_s"]) * 1e3,
+                d2h_busy_ms=agg["d2h_busy_s"] * 1e3, h2d_busy_ms=agg["h2d_busy_s"] * 1e3,
                 compute_busy_ms=agg["compute_busy_s"] * 1e3,
                 gemm_tflops=agg["gemm_flops"] / agg["gemm_busy_s"] / 1e12 if agg["gemm_busy_s"] else None,
                 gemm_busy_ms=agg["gemm_busy_s"] * 1e3 * args.profile_every,  # timed sample scaled to all launches
@@ -136,9 +140,21 @@ def main():
                 attn_busy_ms=agg["attn_busy_s"] * 1e3 * args.profile_every,
                 mfu=model_flops_per_run(shape) / dt / (PEAK_BF16_TFLOPS * 1e12),
             )
+        for ratio in (0.0, 0.5, 1.0):
+            ratios[ratio] = measure(ratio)
+        # Largest ratio whose transfers should still hide: k measured as the busier copy direction at ratio 1 over
+        # the step time at ratio 0 (both directions run at once on this machine), ratio = min(1, 1 / k).
+        one = ratios[1.0]
+        busy = [b for b in ((one["d2h_busy_ms"], one["h2d_busy_ms"])) if b]
+        k_transfer = (max(busy) / ratios[0.0]["ms_per_step"]) if busy else None
+        if k_transfer and not args.no_auto_ratio:
+            auto = po.po_offload_ratio_for_k(k_transfer)
+            ratios["auto"] = dict(ratios[1.0]) if auto >= 1.0 else measure(auto)
+            ratios["auto"]["ratio"] = auto
+            ratios["auto"]["k_transfer_measured"] = k_transfer
         base = ratios[0.0]["ms_per_step"]
         for ratio, d in ratios.items():
-            if ratio > 0 and d["copy_busy_ms"] > 0:
+            if ratio != 0.0 and d["copy_busy_ms"] > 0:
                 d["overlap"] = max(0.0, min(1.0, 1.0 - (d["ms_per_step"] - base) / d["copy_busy_ms"]))
             else:
                 d["overlap"] = None

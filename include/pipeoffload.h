@@ -151,6 +151,10 @@ int po_schedule_ops(int32_t schedule, int32_t d, int32_t rank, int32_t v, int32_
 /* Eq. 1: k = 10 / (3 (6h + s)) * B_c / B_o, with B_c in flop/s and B_o in byte/s. */
 double po_offload_k(int32_t h, int32_t s, double compute_flops_per_s, double link_bytes_per_s);
 
+/* Largest offload ratio whose transfers still hide behind compute for a given k (Section 2: k = T_o / T_c is the
+ * proportion indicator; everything can be offloaded when k <= 1, else a fraction 1 / k): min(1, 1 / k); 1 for k <= 0. */
+double po_offload_ratio_for_k(double k);
+
 /* ---- stage ---------------------------------------------------------------- */
 /* compute_stream: a hipStream_t (as void*) on the current device, NULL = default
  * stream.  Creates copy streams, events and workspaces; slabs and pinned buffers

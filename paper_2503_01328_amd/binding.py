@@ -68,6 +68,7 @@ EXPORTS = {
     "po_schedule_ops": (C.c_int, [C.c_int32] * 6 + [C.c_float, C.c_int32, C.c_int32, C.c_int32, C.POINTER(po_op),
                                                     C.POINTER(C.c_int32)]),
     "po_offload_k": (C.c_double, [C.c_int32, C.c_int32, C.c_double, C.c_double]),
+    "po_offload_ratio_for_k": (C.c_double, [C.c_double]),
     "po_stage_create": (C.c_int, [C.POINTER(po_config), C.c_void_p, C.POINTER(C.c_void_p)]),
     "po_stage_destroy": (None, [C.c_void_p]),
     "po_bind_params": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
@@ -171,6 +172,10 @@ def po_schedule_ops(schedule, d, rank, v, m, ratio, policy=0, prefetch=2, group=
     arr = (po_op * n.value)()
     _check(lib.po_schedule_ops(schedule, d, rank, v, m, group, ratio, policy, prefetch, min_gap, arr, C.byref(n)))
     return [(OP_KINDS[o.kind], o.mb, o.chunk) for o in arr]
+
+
+def po_offload_ratio_for_k(k) -> float:
+    return lib.po_offload_ratio_for_k(k)
 
 
 def po_offload_k(h, s, compute_flops_per_s, link_bytes_per_s) -> float:

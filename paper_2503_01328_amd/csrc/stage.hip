@@ -1322,6 +1322,8 @@ int po_schedule_ops(int32_t schedule, int32_t d, int32_t rank, int32_t v, int32_
   return PO_OK;
 }
 
+double po_offload_ratio_for_k(double k) { return k > 1.0 ? 1.0 / k : 1.0; }
+
 double po_offload_k(int32_t h, int32_t s, double bc, double bo) {
   return 10.0 / (3.0 * (6.0 * (double)h + (double)s)) * bc / bo;
 }

@@ -84,6 +84,12 @@ def test_schedule_ops_reject_bad_arguments():
         assert "schedule" in po.po_last_error()
 
 
+def test_offload_ratio_for_k():
+    assert po.po_offload_ratio_for_k(0.5) == 1.0 and po.po_offload_ratio_for_k(1.0) == 1.0
+    assert po.po_offload_ratio_for_k(2.0) == 0.5 and abs(po.po_offload_ratio_for_k(1.6) - 0.625) < 1e-12
+    assert po.po_offload_ratio_for_k(0.0) == 1.0 and po.po_offload_ratio_for_k(-1.0) == 1.0
+
+
 def test_offload_k_is_eq1():
     for h, s in [(8192, 4096), (4096, 4096), (5120, 16384), (2048, 2048)]:
         assert abs(po.po_offload_k(h, s, 220e12, 15e9) - sch.offload_ratio_k(h, s, 220e12, 15e9)) < 1e-12
