@@ -321,10 +321,12 @@ def offload_ratio_k(h, s, compute_flops_per_s, link_bytes_per_s):
     return 10.0 / (3.0 * (6.0 * h + s)) * compute_flops_per_s / link_bytes_per_s
 
 
-def saved_bytes_per_layer(s, h, n_heads, elem_bytes):
+def saved_bytes_per_layer(s, h, n_heads, elem_bytes, n_kv_heads=None):
     """Appendix C: 20 b s h bytes per layer at 2-byte elements once LayerNorm,
     GeLU and dropout outputs are recomputed, i.e. 10 s h elements: layer input,
     q, k, v, attention output, second LayerNorm's input and the 4h-wide MLP
-    pre-activation.  This build also keeps the softmax log-sum-exp per head and
-    row in fp32 (needed by a score-free attention backward)."""
-    return 10 * s * h * elem_bytes + 4 * n_heads * s
+    pre-activation.  With grouped-query attention k and v shrink to
+    n_kv_heads / n_heads of h each.  This build also keeps the softmax
+    log-sum-exp per head and row in fp32 (needed by a score-free attention backward)."""
+    kv = h if n_kv_heads is None else h // n_heads * n_kv_heads
+    return (8 * h + 2 * kv) * s * elem_bytes + 4 * n_heads * s

@@ -17,7 +17,8 @@ numpy array operations; matmul is used as a library primitive.
 Readings of points the paper leaves open (each is also listed in the design
 notes): pre-LN decoder layer; LayerNorm with gain and shift, biased variance,
 eps inside the square root; linear layers with bias; GeLU in its tanh form;
-causal softmax attention scaled by 1/sqrt(head_dim), plain multi-head; no
+causal softmax attention scaled by 1/sqrt(head_dim), multi-head, or grouped-query
+when the QKV projection is narrower than 3h (Table 2's query groups); no
 dropout; no final LayerNorm; learned token + position embedding when the stage
 is the first one.
 
@@ -75,22 +76,27 @@ def gelu_derivative(u):
 # Causal multi-head attention (the s-dependent term of Eq. 1's compute time)
 # --------------------------------------------------------------------------- #
 def attention_forward(q, k, v, n_heads):
-    """q, k, v: [s, h]; head t owns columns [t*dh, (t+1)*dh).  Returns O [s, h]
-    and the per-head probability matrices (kept only by the oracle)."""
+    """q: [s, h]; k, v: [s, h_kv] with h_kv = n_kv_heads * dh.  Query head t owns
+    columns [t*dh, (t+1)*dh) of q and reads key/value head t // (n_heads // n_kv_heads)
+    (grouped-query attention, Table 2's "query groups"; n_kv_heads = n_heads is plain
+    multi-head attention).  Returns O [s, h] and the per-head probability matrices
+    (kept only by the oracle)."""
     s, h = q.shape
     dh = h // n_heads
+    group = n_heads // (k.shape[1] // dh)
     scale = q.dtype.type(1.0 / math.sqrt(dh))
     o = np.empty_like(q)
     probs = []
     future = np.triu(np.ones((s, s), dtype=bool), k=1)  # j > i
     for t in range(n_heads):
         c = slice(t * dh, (t + 1) * dh)
-        sc = (q[:, c] @ k[:, c].T) * scale
+        ckv = slice((t // group) * dh, (t // group + 1) * dh)
+        sc = (q[:, c] @ k[:, ckv].T) * scale
         sc = np.where(future, -np.inf, sc)
         sc = sc - sc.max(axis=-1, keepdims=True)
         p = np.exp(sc)
         p = p / p.sum(axis=-1, keepdims=True)
-        o[:, c] = p @ v[:, c]
+        o[:, c] = p @ v[:, ckv]
         probs.append(p.astype(q.dtype))
     return o, probs
 
@@ -98,16 +104,18 @@ def attention_forward(q, k, v, n_heads):
 def attention_backward(do, q, k, v, probs, n_heads):
     s, h = q.shape
     dh = h // n_heads
+    group = n_heads // (k.shape[1] // dh)
     scale = q.dtype.type(1.0 / math.sqrt(dh))
-    dq, dk, dv = np.empty_like(q), np.empty_like(k), np.empty_like(v)
-    for t in range(n_heads):
+    dq, dk, dv = np.empty_like(q), np.zeros_like(k), np.zeros_like(v)
+    for t in range(n_heads):  # a key/value head collects the gradients of its query heads in head order
         c = slice(t * dh, (t + 1) * dh)
+        ckv = slice((t // group) * dh, (t // group + 1) * dh)
         p = probs[t]
-        dv[:, c] = p.T @ do[:, c]
-        dp = do[:, c] @ v[:, c].T
+        dv[:, ckv] += p.T @ do[:, c]
+        dp = do[:, c] @ v[:, ckv].T
         ds = p * (dp - (dp * p).sum(axis=-1, keepdims=True))
-        dq[:, c] = (ds @ k[:, c]) * scale
-        dk[:, c] = (ds.T @ q[:, c]) * scale
+        dq[:, c] = (ds @ k[:, ckv]) * scale
+        dk[:, ckv] += (ds.T @ q[:, c]) * scale
     return dq, dk, dv
 
 
@@ -118,7 +126,8 @@ def layer_forward(x, p, n_heads, eps):
     h = x.shape[1]
     n1, ln1 = layernorm_forward(x, p["ln1_g"], p["ln1_b"], eps)
     qkv = n1 @ p["w_qkv"] + p["b_qkv"]
-    q, k, v = qkv[:, :h], qkv[:, h:2 * h], qkv[:, 2 * h:]
+    h_kv = (qkv.shape[1] - h) // 2  # w_qkv is [h, h + 2 h_kv]: query block, key block, value block
+    q, k, v = qkv[:, :h], qkv[:, h:h + h_kv], qkv[:, h + h_kv:]
     o, probs = attention_forward(q, k, v, n_heads)
     x1 = x + o @ p["w_o"] + p["b_o"]
     n2, ln2 = layernorm_forward(x1, p["ln2_g"], p["ln2_b"], eps)

@@ -40,6 +40,16 @@ class StageShape:
     pipeline_degree: int = 1  # d
     rank: int = 0
     n_microbatches: int = 1   # m
+    n_kv_heads: int = 0       # key/value heads of grouped-query attention; 0 = n_heads (plain multi-head)
+
+    @property
+    def kv_heads(self) -> int:
+        return self.n_kv_heads or self.n_heads
+
+    @property
+    def kv_width(self) -> int:
+        """Columns of the key (and of the value) block of the QKV projection."""
+        return self.kv_heads * (self.hidden // self.n_heads)
 
     @property
     def layers_per_chunk(self) -> int:
@@ -60,20 +70,21 @@ CONFIGS = {
 }
 
 # Per-layer parameter tensors, in flat-buffer order: (name, rows, cols) as
-# functions of (h, f).  Vectors have rows == 1.
+# functions of (h, f, q) with q = h + 2 * kv_width, the width of the QKV projection
+# (3h for plain multi-head attention).  Vectors have rows == 1.
 LAYER_PARAMS = (
-    ("ln1_g", lambda h, f: (1, h)),
-    ("ln1_b", lambda h, f: (1, h)),
-    ("w_qkv", lambda h, f: (h, 3 * h)),
-    ("b_qkv", lambda h, f: (1, 3 * h)),
-    ("w_o", lambda h, f: (h, h)),
-    ("b_o", lambda h, f: (1, h)),
-    ("ln2_g", lambda h, f: (1, h)),
-    ("ln2_b", lambda h, f: (1, h)),
-    ("w_fc1", lambda h, f: (h, f)),
-    ("b_fc1", lambda h, f: (1, f)),
-    ("w_fc2", lambda h, f: (f, h)),
-    ("b_fc2", lambda h, f: (1, h)),
+    ("ln1_g", lambda h, f, q: (1, h)),
+    ("ln1_b", lambda h, f, q: (1, h)),
+    ("w_qkv", lambda h, f, q: (h, q)),
+    ("b_qkv", lambda h, f, q: (1, q)),
+    ("w_o", lambda h, f, q: (h, h)),
+    ("b_o", lambda h, f, q: (1, h)),
+    ("ln2_g", lambda h, f, q: (1, h)),
+    ("ln2_b", lambda h, f, q: (1, h)),
+    ("w_fc1", lambda h, f, q: (h, f)),
+    ("b_fc1", lambda h, f, q: (1, f)),
+    ("w_fc2", lambda h, f, q: (f, h)),
+    ("b_fc2", lambda h, f, q: (1, h)),
 )
 
 
@@ -110,7 +121,7 @@ def layer_params(shape: StageShape, layer: int, seed: int = 1234) -> dict:
     h, f = shape.hidden, shape.ffn
     out = {}
     for name, dims in LAYER_PARAMS:
-        r, c = dims(h, f)
+        r, c = dims(h, f, h + 2 * shape.kv_width)
         g = _rng(seed, f"L{layer}.{name}")
         a = g.standard_normal((r, c), dtype=np.float32) * np.float32(0.02)
         if name in ("ln1_g", "ln2_g"):

@@ -281,3 +281,93 @@ def test_bf16_rounding_helper_is_round_to_nearest_even():
     ref = torch.tensor(a).to(torch.bfloat16).to(torch.float32).numpy()
     np.testing.assert_array_equal(r, ref)
     np.testing.assert_array_equal(syn.bf16_bits_to_f32(syn.bf16_bits(r)), r)
+
+
+# ---- grouped-query attention (Table 2: query groups) ----------------------------------------------------------
+GQA_TINY = syn.StageShape(n_layers=2, n_chunks=1, hidden=16, n_heads=4, ffn=32, seq=6, dtype="f32", n_kv_heads=2)
+
+
+def _replicate_kv(params, shape):
+    """The multi-head model that computes the same function: every query head gets its own copy of its group's
+    key and value projection columns."""
+    h, dh, a, akv = shape.hidden, shape.head_dim, shape.n_heads, shape.kv_heads
+    group, hkv = a // akv, shape.kv_width
+    out = {"layers": []}
+    for p in params["layers"]:
+        q = dict(p)
+        w, b = p["w_qkv"], p["b_qkv"]
+        cols = list(range(h))
+        for block in (h, h + hkv):
+            for t in range(a):
+                cols += list(range(block + (t // group) * dh, block + (t // group + 1) * dh))
+        q["w_qkv"], q["b_qkv"] = w[:, cols].copy(), b[cols].copy()
+        out["layers"].append(q)
+    return out
+
+
+def test_grouped_query_attention_equals_multi_head_with_replicated_kv_weights():
+    shape = GQA_TINY
+    params, x, dy = _tiny_problem(shape, m=2, seed=11, scale=6.0)
+    assert params["layers"][0]["w_qkv"].shape == (16, 16 + 2 * 8)
+    y, dx, g = so.run_stage(params, shape.n_layers, 1, shape.n_heads, x, dy)
+    ym, dxm, gm = so.run_stage(_replicate_kv(params, shape), shape.n_layers, 1, shape.n_heads, x, dy)
+    h, dh, group, hkv = 16, 4, 2, 8
+    for u in y:
+        np.testing.assert_allclose(y[u], ym[u], rtol=1e-12, atol=1e-12)
+        np.testing.assert_allclose(dx[u], dxm[u], rtol=1e-11, atol=1e-12)
+    for l in range(shape.n_layers):
+        for k in g["layers"][l]:
+            if k in ("w_qkv", "b_qkv"):
+                continue
+            np.testing.assert_allclose(g["layers"][l][k], gm["layers"][l][k], rtol=1e-10, atol=1e-12, err_msg=k)
+        # a shared key/value column receives the sum of the gradients of its copies (chain rule through the copy)
+        for name in ("w_qkv", "b_qkv"):
+            full = gm["layers"][l][name]
+            got = g["layers"][l][name]
+            np.testing.assert_allclose(got[..., :h], full[..., :h], rtol=1e-10, atol=1e-12)
+            for blk in range(2):
+                for kvh in range(2):
+                    want = sum(full[..., h + blk * h + t * dh: h + blk * h + (t + 1) * dh]
+                               for t in range(kvh * group, (kvh + 1) * group))
+                    np.testing.assert_allclose(got[..., h + blk * hkv + kvh * dh: h + blk * hkv + (kvh + 1) * dh], want,
+                                               rtol=1e-10, atol=1e-12)
+
+
+def test_grouped_query_attention_finite_differences():
+    shape = GQA_TINY
+    params, x, dy = _tiny_problem(shape, m=1, seed=5, scale=6.0)
+    _, dx, grads = so.run_stage(params, shape.n_layers, 1, shape.n_heads, x, dy)
+    eps = 1e-6
+    rng = np.random.default_rng(1)
+    for l, p in enumerate(params["layers"]):
+        for name in ("w_qkv", "b_qkv", "w_o"):
+            flat = p[name].reshape(-1)
+            for idx in rng.choice(flat.size, size=10, replace=False):
+                old = flat[idx]
+                flat[idx] = old + eps
+                lp = _loss(params, shape, x, dy)
+                flat[idx] = old - eps
+                lm = _loss(params, shape, x, dy)
+                flat[idx] = old
+                an = grads["layers"][l][name].reshape(-1)[idx]
+                assert abs((lp - lm) / (2 * eps) - an) <= 1e-6 * max(1.0, abs(an)), (l, name, idx)
+
+
+def test_grouped_query_attention_against_torch_sdpa():
+    import torch.nn.functional as F
+
+    s, a, akv, dh = 7, 6, 2, 4
+    rng = np.random.default_rng(2)
+    q, k, v = rng.standard_normal((s, a * dh)), rng.standard_normal((s, akv * dh)), rng.standard_normal((s, akv * dh))
+    do = rng.standard_normal((s, a * dh))
+    o, probs = so.attention_forward(q, k, v, a)
+    dq, dk, dv = so.attention_backward(do, q, k, v, probs, a)
+    tq, tk, tv = (torch.tensor(t, requires_grad=True) for t in (q, k, v))
+    hd = lambda t, n: t.reshape(s, n, dh).transpose(0, 1)
+    to = F.scaled_dot_product_attention(hd(tq, a), hd(tk, akv).repeat_interleave(a // akv, dim=0),
+                                        hd(tv, akv).repeat_interleave(a // akv, dim=0), is_causal=True)
+    to = to.transpose(0, 1).reshape(s, a * dh)
+    np.testing.assert_allclose(to.detach().numpy(), o, rtol=1e-12, atol=1e-12)
+    (to * torch.tensor(do)).sum().backward()
+    for got, want in ((dq, tq.grad), (dk, tk.grad), (dv, tv.grad)):
+        np.testing.assert_allclose(got, want.numpy(), rtol=1e-11, atol=1e-12)
