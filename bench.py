@@ -35,7 +35,9 @@ def model_flops_per_run(shape):
     """72 h^2 + 6 s h per token and layer (GEMMs forward + backward, causal attention), Eq. 1's T_c with the
     causal half of its attention term."""
     h, s = shape.hidden, shape.seq
-    per_token_layer = 72.0 * h * h + 6.0 * s * h
+    # QKV projection is h x (h + 2 hkv): 6 (1 + 2 hkv / h) h^2 instead of 18 h^2 of the 72 h^2
+    qkv = 6.0 * h * (h + 2.0 * shape.kv_width)
+    per_token_layer = 54.0 * h * h + qkv + 6.0 * s * h
     return per_token_layer * s * shape.n_layers * shape.n_microbatches
 
 
@@ -85,6 +87,8 @@ def main():
                     help="bracket every k-th GEMM / attention launch of the timed steps with HIP events (1 = all; an "
                          "event pair idles the stream for a few microseconds, which costs about 7 %% at C2 with k = 1)")
     ap.add_argument("--weight-stream", type=int, default=0, help="1: weight-gradient work on its own stream")
+    ap.add_argument("--kv-heads", type=int, default=0,
+                    help="grouped-query attention with this many key/value heads (Table 2 uses 8); 0 = multi-head")
     ap.add_argument("--group", type=int, default=0, help="group size g of --schedule gis (0 = pipeline degree)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -98,6 +102,8 @@ def main():
     from paper_2503_01328_amd.harness import StageRunner
 
     shape = syn.CONFIGS[args.config]
+    if args.kv_heads:
+        shape = dataclasses.replace(shape, n_kv_heads=args.kv_heads)
     sched_name = args.schedule
     if sched_name == "auto":
         sched_name = "1f1b-interleaved" if shape.n_chunks > 1 else "1f1b"
@@ -173,7 +179,7 @@ def main():
         "warmup": args.warmup, "ms_per_step": headline["ms_per_step"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": f"{args.config}: GPT stage, {shape.n_layers} layers, hidden {shape.hidden}, "
-                               f"{shape.n_heads} heads, FFN {shape.ffn}, seq {shape.seq}, {shape.n_microbatches} "
+                               f"{shape.n_heads} heads{' (%d key/value heads)' % shape.n_kv_heads if shape.n_kv_heads else ''}, FFN {shape.ffn}, seq {shape.seq}, {shape.n_microbatches} "
                                f"microbatches, simulated pipeline degree {shape.pipeline_degree}, "
                                f"schedule {sched_name}{' g=%d' % args.group if args.group else ''} rank 0; "
                                f"value is at offload ratio 1",

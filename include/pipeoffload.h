@@ -81,6 +81,9 @@ typedef struct po_config {
   int32_t weight_stream;   /* 1: weight-gradient work (W passes, and the weight half of po_stage_backward) runs on a
                               stream of its own after the unit's input-gradient work, beside the compute stream;
                               results are bit-identical to 0; gradients are complete after po_synchronize */
+  int32_t n_kv_heads;      /* key/value heads of grouped-query attention (Table 2's query groups), a divisor of
+                              n_heads; 0 = n_heads (plain multi-head).  The QKV projection is [h, h + 2 hkv],
+                              hkv = n_kv_heads * h / n_heads, and the saved k and v shrink accordingly */
   int32_t min_gap_passes;  /* run_schedule does not offload a unit with fewer than this many forward / backward
                               passes between its forward and its backward (Section 4.4); 0 = offload all */
   float ln_eps;            /* LayerNorm epsilon */
@@ -232,12 +235,14 @@ int po_op_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32
                const void* A, int32_t lda, const void* B, int32_t ldb, const void* bias, const void* residual,
                void* out, void* gelu_out, const void* gelu_u, float* acc_f32, int32_t force_generic, void* stream);
 
-/* Causal attention forward (row a3): qkv [s, 3h] (q | k | v blocks), o [s, h], lse [a, s] fp32. */
+/* Causal attention forward (row a3): qkv [s, h + 2 hkv] (q | k | v blocks, hkv = n_kv_heads * h / n_heads;
+ * n_kv_heads = 0 means n_heads, i.e. [s, 3h]), o [s, h], lse [a, s] fp32.  With n_kv_heads < n_heads query head t
+ * reads key/value head t / (n_heads / n_kv_heads) (grouped-query attention, Table 2). */
 int po_op_attention_forward(int32_t dtype, const void* qkv, void* o, float* lse, int32_t s, int32_t h,
-                            int32_t n_heads, int32_t force_generic, void* stream);
-/* Causal attention backward (row a16): dqkv [s, 3h]; delta: fp32 workspace [a, s]. */
+                            int32_t n_heads, int32_t n_kv_heads, int32_t force_generic, void* stream);
+/* Causal attention backward (row a16): dqkv laid out like qkv; delta: fp32 workspace [a, s]. */
 int po_op_attention_backward(int32_t dtype, const void* qkv, const void* o, const float* lse, const void* d_o,
-                             void* dqkv, float* delta, int32_t s, int32_t h, int32_t n_heads,
+                             void* dqkv, float* delta, int32_t s, int32_t h, int32_t n_heads, int32_t n_kv_heads,
                              int32_t force_generic, void* stream);
 
 /* acc[N] += column sums of x [rows, N] (bias gradients, rows a12-a17), deterministic: row chunks

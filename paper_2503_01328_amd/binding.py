@@ -33,7 +33,7 @@ class po_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "n_chunks", "hidden", "n_heads", "ffn", "seq", "vocab", "dtype", "pipeline_degree", "rank",
         "prefetch_passes", "copy_streams", "select_policy", "staged_copies", "debug_poison", "profile_kernels",
-        "group", "weight_stream", "min_gap_passes")] + [
+        "group", "weight_stream", "n_kv_heads", "min_gap_passes")] + [
         ("ln_eps", C.c_float), ("host_pool_cap_bytes", C.c_uint64), ("device_pool_cap_bytes", C.c_uint64)]
 
 
@@ -90,8 +90,8 @@ EXPORTS = {
                                                                            C.c_void_p]),
     "po_op_gemm": (C.c_int, [C.c_int32] * 6 + [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32] + [C.c_void_p] * 6 +
                    [C.c_int32, C.c_void_p]),
-    "po_op_attention_forward": (C.c_int, [C.c_int32] + [C.c_void_p] * 3 + [C.c_int32] * 4 + [C.c_void_p]),
-    "po_op_attention_backward": (C.c_int, [C.c_int32] + [C.c_void_p] * 6 + [C.c_int32] * 4 + [C.c_void_p]),
+    "po_op_attention_forward": (C.c_int, [C.c_int32] + [C.c_void_p] * 3 + [C.c_int32] * 5 + [C.c_void_p]),
+    "po_op_attention_backward": (C.c_int, [C.c_int32] + [C.c_void_p] * 6 + [C.c_int32] * 5 + [C.c_void_p]),
     "po_op_colsum_workspace": (C.c_uint64, [C.c_int32, C.c_int32]),
     "po_op_colsum_accumulate": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                           C.c_void_p]),
@@ -265,14 +265,15 @@ def po_op_gemm(dtype, trans_a, trans_b, M, N, K, A, lda, B, ldb, bias=None, resi
                           _ptr(out), _ptr(gelu_out), _ptr(gelu_u), _ptr(acc_f32), force_generic, _stream(stream)))
 
 
-def po_op_attention_forward(dtype, qkv, o, lse, s, h, n_heads, force_generic=0, stream=None):
-    _check(lib.po_op_attention_forward(dtype, _ptr(qkv), _ptr(o), _ptr(lse), s, h, n_heads, force_generic,
-                                       _stream(stream)))
+def po_op_attention_forward(dtype, qkv, o, lse, s, h, n_heads, force_generic=0, stream=None, n_kv_heads=0):
+    _check(lib.po_op_attention_forward(dtype, _ptr(qkv), _ptr(o), _ptr(lse), s, h, n_heads, n_kv_heads,
+                                       force_generic, _stream(stream)))
 
 
-def po_op_attention_backward(dtype, qkv, o, lse, d_o, dqkv, delta, s, h, n_heads, force_generic=0, stream=None):
+def po_op_attention_backward(dtype, qkv, o, lse, d_o, dqkv, delta, s, h, n_heads, force_generic=0, stream=None,
+                             n_kv_heads=0):
     _check(lib.po_op_attention_backward(dtype, _ptr(qkv), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(dqkv), _ptr(delta),
-                                        s, h, n_heads, force_generic, _stream(stream)))
+                                        s, h, n_heads, n_kv_heads, force_generic, _stream(stream)))
 
 
 def po_op_colsum_workspace(rows, n) -> int:

@@ -6,6 +6,10 @@
 // broadcast with shuffles.  Backward is split into a dQ kernel (wave per query
 // row) and a dK/dV kernel (wave per key row), each summing in a fixed order, so
 // there are no atomics and results are reproducible.
+//
+// Grouped-query attention: the qkv matrix is [s, h + 2 hkv] (query block, key block, value block) with
+// hkv = n_kv_heads * dh; query head t reads key/value head t / group, group = n_heads / n_kv_heads.  The dK/dV
+// kernel runs per key/value head and walks its group's query heads in order.
 #include <math.h>
 
 #include "kernels.h"
@@ -18,15 +22,15 @@ constexpr int kDimSlots = kMaxHeadDim / kWave;  // head-dim elements per lane
 template <typename T>
 __global__ __launch_bounds__(256) void attn_fwd_generic_kernel(const T* __restrict__ qkv, T* __restrict__ o,
                                                                float* __restrict__ lse, int s, int h, int dh,
-                                                               float scale) {
+                                                               int hkv, int group, float scale) {
   __shared__ float qs[4][kMaxHeadDim];
   int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   int head = blockIdx.y;
   int i = blockIdx.x * 4 + wave;
   bool active = i < s;
-  int ld = 3 * h;
-  const T* kbase = qkv + h + head * dh;
-  const T* vbase = qkv + 2 * h + head * dh;
+  int ld = h + 2 * hkv;
+  const T* kbase = qkv + h + (head / group) * dh;
+  const T* vbase = qkv + h + hkv + (head / group) * dh;
   if (active)
     for (int e = lane; e < dh; e += kWave) qs[wave][e] = to_f32(qkv[(size_t)i * ld + head * dh + e]) * scale;
   __syncthreads();
@@ -93,16 +97,17 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_generic_kernel(const T* __res
                                                                   const float* __restrict__ lse,
                                                                   const float* __restrict__ delta,
                                                                   const T* __restrict__ d_o, T* __restrict__ dqkv,
-                                                                  int s, int h, int dh, float scale) {
+                                                                  int s, int h, int dh, int hkv, int group,
+                                                                  float scale) {
   __shared__ float qs[4][kMaxHeadDim];
   __shared__ float dos[4][kMaxHeadDim];
   int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   int head = blockIdx.y;
   int i = blockIdx.x * 4 + wave;
   bool active = i < s;
-  int ld = 3 * h;
-  const T* kbase = qkv + h + head * dh;
-  const T* vbase = qkv + 2 * h + head * dh;
+  int ld = h + 2 * hkv;
+  const T* kbase = qkv + h + (head / group) * dh;
+  const T* vbase = qkv + h + hkv + (head / group) * dh;
   if (active)
     for (int e = lane; e < dh; e += kWave) {
       qs[wave][e] = to_f32(qkv[(size_t)i * ld + head * dh + e]) * scale;
@@ -150,51 +155,55 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_generic_kernel(const T* __re
                                                                    const float* __restrict__ lse,
                                                                    const float* __restrict__ delta,
                                                                    const T* __restrict__ d_o, T* __restrict__ dqkv,
-                                                                   int s, int h, int dh, float scale) {
+                                                                   int s, int h, int dh, int hkv, int group,
+                                                                   float scale) {
   __shared__ float ks[4][kMaxHeadDim];
   __shared__ float vs[4][kMaxHeadDim];
   int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  int head = blockIdx.y;
+  int kv_head = blockIdx.y;
   int j = blockIdx.x * 4 + wave;
   bool active = j < s;
-  int ld = 3 * h;
-  const T* qbase = qkv + head * dh;
-  const T* dobase = d_o + head * dh;
+  int ld = h + 2 * hkv;
   if (active)
     for (int e = lane; e < dh; e += kWave) {
-      ks[wave][e] = to_f32(qkv[(size_t)j * ld + h + head * dh + e]) * scale;
-      vs[wave][e] = to_f32(qkv[(size_t)j * ld + 2 * h + head * dh + e]);
+      ks[wave][e] = to_f32(qkv[(size_t)j * ld + h + kv_head * dh + e]) * scale;
+      vs[wave][e] = to_f32(qkv[(size_t)j * ld + h + hkv + kv_head * dh + e]);
     }
   __syncthreads();
   if (!active) return;
   float dk[kDimSlots], dv[kDimSlots];
 #pragma unroll
   for (int r = 0; r < kDimSlots; ++r) dk[r] = dv[r] = 0.f;
-  for (int i0 = j - (j % kWave); i0 < s; i0 += kWave) {
-    int i = i0 + lane;
-    float p = 0.f, ds = 0.f;
-    if (i >= j && i < s) {
-      const T* qr = qbase + (size_t)i * ld;
-      const T* dor = dobase + (size_t)i * h;
-      float sc = 0.f, dp = 0.f;
-      for (int e = 0; e < dh; ++e) {
-        sc = fmaf(ks[wave][e], to_f32(qr[e]), sc);
-        dp = fmaf(vs[wave][e], to_f32(dor[e]), dp);
+  for (int g = 0; g < group; ++g) {  // the query heads that read this key/value head, in head order
+    int head = kv_head * group + g;
+    const T* qbase = qkv + head * dh;
+    const T* dobase = d_o + head * dh;
+    for (int i0 = j - (j % kWave); i0 < s; i0 += kWave) {
+      int i = i0 + lane;
+      float p = 0.f, ds = 0.f;
+      if (i >= j && i < s) {
+        const T* qr = qbase + (size_t)i * ld;
+        const T* dor = dobase + (size_t)i * h;
+        float sc = 0.f, dp = 0.f;
+        for (int e = 0; e < dh; ++e) {
+          sc = fmaf(ks[wave][e], to_f32(qr[e]), sc);
+          dp = fmaf(vs[wave][e], to_f32(dor[e]), dp);
+        }
+        p = __expf(sc - lse[(size_t)head * s + i]);
+        ds = p * (dp - delta[(size_t)head * s + i]);
       }
-      p = __expf(sc - lse[(size_t)head * s + i]);
-      ds = p * (dp - delta[(size_t)head * s + i]);
-    }
-    int ni = min(kWave, s - i0);
-    for (int ii = 0; ii < ni; ++ii) {
-      float pi = __shfl(p, ii, kWave), dsi = __shfl(ds, ii, kWave);
-      const T* qr = qbase + (size_t)(i0 + ii) * ld;
-      const T* dor = dobase + (size_t)(i0 + ii) * h;
+      int ni = min(kWave, s - i0);
+      for (int ii = 0; ii < ni; ++ii) {
+        float pi = __shfl(p, ii, kWave), dsi = __shfl(ds, ii, kWave);
+        const T* qr = qbase + (size_t)(i0 + ii) * ld;
+        const T* dor = dobase + (size_t)(i0 + ii) * h;
 #pragma unroll
-      for (int r = 0; r < kDimSlots; ++r) {
-        int e = lane + kWave * r;
-        if (e < dh) {
-          dv[r] = fmaf(pi, to_f32(dor[e]), dv[r]);
-          dk[r] = fmaf(dsi, to_f32(qr[e]), dk[r]);
+        for (int r = 0; r < kDimSlots; ++r) {
+          int e = lane + kWave * r;
+          if (e < dh) {
+            dv[r] = fmaf(pi, to_f32(dor[e]), dv[r]);
+            dk[r] = fmaf(dsi, to_f32(qr[e]), dk[r]);
+          }
         }
       }
     }
@@ -203,67 +212,74 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_generic_kernel(const T* __re
   for (int r = 0; r < kDimSlots; ++r) {
     int e = lane + kWave * r;
     if (e < dh) {
-      dqkv[(size_t)j * ld + h + head * dh + e] = from_f32<T>(dk[r] * scale);
-      dqkv[(size_t)j * ld + 2 * h + head * dh + e] = from_f32<T>(dv[r]);
+      dqkv[(size_t)j * ld + h + kv_head * dh + e] = from_f32<T>(dk[r] * scale);
+      dqkv[(size_t)j * ld + h + hkv + kv_head * dh + e] = from_f32<T>(dv[r]);
     }
   }
 }
 
-static bool check_attention_shape(const char* what, int s, int h, int n_heads) {
-  if (s <= 0 || h <= 0 || n_heads <= 0 || h % n_heads != 0 || h / n_heads > kMaxHeadDim) {
-    set_error("%s: s=%d h=%d heads=%d (head size must divide h and be <= %d)", what, s, h, n_heads, kMaxHeadDim);
+static bool check_attention_shape(const char* what, int s, int h, int n_heads, int n_kv_heads) {
+  if (s <= 0 || h <= 0 || n_heads <= 0 || h % n_heads != 0 || h / n_heads > kMaxHeadDim || n_kv_heads <= 0 ||
+      n_heads % n_kv_heads != 0) {
+    set_error("%s: s=%d h=%d heads=%d kv_heads=%d (head size must divide h and be <= %d, kv_heads must divide heads)",
+              what, s, h, n_heads, n_kv_heads, kMaxHeadDim);
     return false;
   }
   return true;
 }
 
 bool attention_forward_generic(int dtype, const void* qkv, void* o, float* lse, int s, int h, int n_heads,
-                               hipStream_t stream) {
-  if (!check_attention_shape("attention_forward", s, h, n_heads)) return false;
-  int dh = h / n_heads;
+                               int n_kv_heads, hipStream_t stream) {
+  if (!check_attention_shape("attention_forward", s, h, n_heads, n_kv_heads)) return false;
+  int dh = h / n_heads, hkv = n_kv_heads * dh, group = n_heads / n_kv_heads;
   float scale = 1.0f / sqrtf((float)dh);
   dim3 grid(ceil_div(s, 4), n_heads);
   if (dtype == kF32)
-    attn_fwd_generic_kernel<float><<<grid, 256, 0, stream>>>((const float*)qkv, (float*)o, lse, s, h, dh, scale);
+    attn_fwd_generic_kernel<float><<<grid, 256, 0, stream>>>((const float*)qkv, (float*)o, lse, s, h, dh, hkv, group,
+                                                             scale);
   else
-    attn_fwd_generic_kernel<bf16><<<grid, 256, 0, stream>>>((const bf16*)qkv, (bf16*)o, lse, s, h, dh, scale);
+    attn_fwd_generic_kernel<bf16><<<grid, 256, 0, stream>>>((const bf16*)qkv, (bf16*)o, lse, s, h, dh, hkv, group,
+                                                            scale);
   return launch_ok("attn_fwd_generic_kernel");
 }
 
 bool attention_backward_generic(int dtype, const void* qkv, const void* o, const float* lse, const void* d_o,
-                                void* dqkv, float* delta, int s, int h, int n_heads, hipStream_t stream) {
-  if (!check_attention_shape("attention_backward", s, h, n_heads)) return false;
-  int dh = h / n_heads;
+                                void* dqkv, float* delta, int s, int h, int n_heads, int n_kv_heads,
+                                hipStream_t stream) {
+  if (!check_attention_shape("attention_backward", s, h, n_heads, n_kv_heads)) return false;
+  int dh = h / n_heads, hkv = n_kv_heads * dh, group = n_heads / n_kv_heads;
   float scale = 1.0f / sqrtf((float)dh);
-  dim3 grid(ceil_div(s, 4), n_heads);
+  dim3 grid(ceil_div(s, 4), n_heads), grid_kv(ceil_div(s, 4), n_kv_heads);
   if (dtype == kF32) {
     attn_delta_kernel<float><<<grid, 256, 0, stream>>>((const float*)o, (const float*)d_o, delta, s, h, dh);
     attn_bwd_dq_generic_kernel<float><<<grid, 256, 0, stream>>>((const float*)qkv, lse, delta, (const float*)d_o,
-                                                                (float*)dqkv, s, h, dh, scale);
-    attn_bwd_dkv_generic_kernel<float><<<grid, 256, 0, stream>>>((const float*)qkv, lse, delta, (const float*)d_o,
-                                                                 (float*)dqkv, s, h, dh, scale);
+                                                                (float*)dqkv, s, h, dh, hkv, group, scale);
+    attn_bwd_dkv_generic_kernel<float><<<grid_kv, 256, 0, stream>>>((const float*)qkv, lse, delta,
+                                                                    (const float*)d_o, (float*)dqkv, s, h, dh, hkv,
+                                                                    group, scale);
   } else {
     attn_delta_kernel<bf16><<<grid, 256, 0, stream>>>((const bf16*)o, (const bf16*)d_o, delta, s, h, dh);
     attn_bwd_dq_generic_kernel<bf16><<<grid, 256, 0, stream>>>((const bf16*)qkv, lse, delta, (const bf16*)d_o,
-                                                               (bf16*)dqkv, s, h, dh, scale);
-    attn_bwd_dkv_generic_kernel<bf16><<<grid, 256, 0, stream>>>((const bf16*)qkv, lse, delta, (const bf16*)d_o,
-                                                                (bf16*)dqkv, s, h, dh, scale);
+                                                               (bf16*)dqkv, s, h, dh, hkv, group, scale);
+    attn_bwd_dkv_generic_kernel<bf16><<<grid_kv, 256, 0, stream>>>((const bf16*)qkv, lse, delta, (const bf16*)d_o,
+                                                                   (bf16*)dqkv, s, h, dh, hkv, group, scale);
   }
   return launch_ok("attention backward kernels");
 }
 
-bool attention_forward(int dtype, const void* qkv, void* o, float* lse, int s, int h, int n_heads,
+bool attention_forward(int dtype, const void* qkv, void* o, float* lse, int s, int h, int n_heads, int n_kv_heads,
                        bool force_generic, hipStream_t stream) {
-  if (dtype == kBF16 && !force_generic && attention_mfma_supported(s, h, n_heads))
-    return attention_forward_mfma(qkv, o, lse, s, h, n_heads, stream);
-  return attention_forward_generic(dtype, qkv, o, lse, s, h, n_heads, stream);
+  if (dtype == kBF16 && !force_generic && attention_mfma_supported(s, h, n_heads, n_kv_heads))
+    return attention_forward_mfma(qkv, o, lse, s, h, n_heads, n_kv_heads, stream);
+  return attention_forward_generic(dtype, qkv, o, lse, s, h, n_heads, n_kv_heads, stream);
 }
 
 bool attention_backward(int dtype, const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv,
-                        float* delta, int s, int h, int n_heads, bool force_generic, hipStream_t stream) {
-  if (dtype == kBF16 && !force_generic && attention_mfma_supported(s, h, n_heads))
-    return attention_backward_mfma(qkv, o, lse, d_o, dqkv, delta, s, h, n_heads, stream);
-  return attention_backward_generic(dtype, qkv, o, lse, d_o, dqkv, delta, s, h, n_heads, stream);
+                        float* delta, int s, int h, int n_heads, int n_kv_heads, bool force_generic,
+                        hipStream_t stream) {
+  if (dtype == kBF16 && !force_generic && attention_mfma_supported(s, h, n_heads, n_kv_heads))
+    return attention_backward_mfma(qkv, o, lse, d_o, dqkv, delta, s, h, n_heads, n_kv_heads, stream);
+  return attention_backward_generic(dtype, qkv, o, lse, d_o, dqkv, delta, s, h, n_heads, n_kv_heads, stream);
 }
 
 }  // namespace po

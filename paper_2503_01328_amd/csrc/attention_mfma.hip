@@ -140,7 +140,8 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // ==================================================================================
 template <int DH, int QT>
 __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ o,
-                                                            float* __restrict__ lse, int s, int h, float scale) {
+                                                            float* __restrict__ lse, int s, int h, int hkv, int group,
+                                                            float scale) {
   constexpr int KS = DH / 16;   // 16-deep MFMA steps over the head dimension
   constexpr int DT = DH / 32;   // 32-wide output tiles over the head dimension
   constexpr int BQ = 128 * QT;  // query rows per block
@@ -156,10 +157,10 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_fwd_mfma_kernel(con
   int qblock = gridDim.y - 1 - blockIdx.y;
   int q0 = qblock * BQ;
   int qw0 = q0 + wave * (32 * QT);  // first query row of this wave
-  int ld = 3 * h;
+  int ld = h + 2 * hkv;  // [query block h | key block hkv | value block hkv]
   const bf16* qbase = qkv + head * DH;
-  const bf16* kbase = qkv + h + head * DH;
-  const bf16* vbase = qkv + 2 * h + head * DH;
+  const bf16* kbase = qkv + h + (head / group) * DH;  // query head t reads key/value head t / group
+  const bf16* vbase = qkv + h + hkv + (head / group) * DH;
   const float c = scale * 1.4426950408889634f;  // scores are kept raw; exp(x * scale) = exp2(x * c)
 
   // Q fragments stay in registers: B operand, column = query row.
@@ -314,7 +315,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
                                                                 const bf16* __restrict__ d_o,
                                                                 const float* __restrict__ lse,
                                                                 const float* __restrict__ delta,
-                                                                bf16* __restrict__ dqkv, int s, int h, float scale) {
+                                                                bf16* __restrict__ dqkv, int s, int h, int hkv, int group,
+                                                                float scale) {
   constexpr int KS = DH / 16, DT = DH / 32;
   constexpr int TBYTES = tile_bytes<DH>();
   constexpr int STAGE = 2 * TBYTES + 512;  // Q tile, dO tile, lse[64], delta[64]
@@ -322,14 +324,10 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
 
   int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   int half = lane >> 5, col = lane & 31;
-  int head = blockIdx.x;        // heads vary fastest in dispatch order: heaviest blocks of all heads first
+  int kv_head = blockIdx.x;     // heads vary fastest in dispatch order: heaviest blocks of all heads first
   int kb0 = blockIdx.y * 128;   // first key of the block (the earliest blocks have the most query tiles)
   int kw0 = kb0 + wave * 32;    // first key of this wave
-  int ld = 3 * h;
-  const bf16* qbase = qkv + head * DH;
-  const bf16* dobase = d_o + head * DH;
-  const float* lse_h = lse + (size_t)head * s;
-  const float* delta_h = delta + (size_t)head * s;
+  int ld = h + 2 * hkv;
   const float LOG2E = 1.4426950408889634f;
   const float c = scale * LOG2E;
 
@@ -342,9 +340,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
   bf16x8 kf[KS], vf[V_IN_REG > 0 ? V_IN_REG : 1];
 #pragma unroll
   for (int kk = 0; kk < KS; ++kk) {
-    const bf16* row = qkv + (size_t)(kw0 + col) * ld + head * DH + 16 * kk + 8 * half;
-    kf[kk] = *reinterpret_cast<const bf16x8*>(row + h);
-    bf16x8 v = *reinterpret_cast<const bf16x8*>(row + 2 * h);
+    const bf16* row = qkv + (size_t)(kw0 + col) * ld + h + kv_head * DH + 16 * kk + 8 * half;
+    kf[kk] = *reinterpret_cast<const bf16x8*>(row);
+    bf16x8 v = *reinterpret_cast<const bf16x8*>(row + hkv);
     if (kk < V_IN_REG)
       vf[kk] = v;
     else
@@ -356,36 +354,49 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
 #pragma unroll
     for (int e = 0; e < 16; ++e) dk[d][e] = dv[d][e] = 0.f;
 
-  int q_first = kb0 / kKeysPerTile, q_last = s / kKeysPerTile;  // query tiles [q_first, q_last)
+  // Query tiles [q_first, q_last) of every query head of this key/value head's group, one head after the other:
+  // iteration `it` works on head kv_head * group + it / n_qt, tile q_first + it % n_qt.
+  int q_first = kb0 / kKeysPerTile, q_last = s / kKeysPerTile;
+  int n_qt = q_last - q_first, n_it = group * n_qt;
   // Row statistics enter as the initial value of the accumulators: S starts at -lse / scale, so that
   // exp2((S - lse / scale) * scale * log2 e) = P, and dP starts at -delta, so that dS = P * acc.
   // Threads 0..63 carry lse of a row, 64..127 delta of a row (128..255 repeat them and store nothing).  The
   // load is unconditional and its value is not touched until store_stats, after the tile's arithmetic:
   // any earlier use would wait for this load and with it for the tile loads issued just before it.
-  const float* stat_src = ((tid & 64) ? delta_h - 64 : lse_h) + (tid & 127);
+  const float* stat_src = ((tid & 64) ? delta - 64 : lse) + (tid & 127);
   const float stat_mul = (tid & 64) ? -1.0f : __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(
                                                    __builtin_bit_cast(int, -1.0f / scale)));
   float stat = 0.f;
-  auto load_stats = [&](int q0) { stat = stat_src[q0]; };
+  auto load_stats = [&](int head, int q0) { stat = stat_src[(size_t)head * s + q0]; };
+  auto tile_of = [&](int it, int& head, int& qt) {
+    int g = it / n_qt;
+    head = kv_head * group + g;
+    qt = q_first + it - g * n_qt;
+  };
   auto store_stats = [&](char* stage) {
     if (tid < 128) reinterpret_cast<float*>(stage + 2 * TBYTES)[tid] = stat * stat_mul;
   };
   const unsigned q_lane_off = tile_lane_offset<DH>(ld, wave, lane), do_lane_off = tile_lane_offset<DH>(h, wave, lane);
-  load_tile_async<DH>(qbase, ld, q_first * kKeysPerTile, smem, wave, q_lane_off);
-  load_tile_async<DH>(dobase, h, q_first * kKeysPerTile, smem + TBYTES, wave, do_lane_off);
-  load_stats(q_first * kKeysPerTile);
+  {
+    int head0 = kv_head * group;
+    load_tile_async<DH>(qkv + head0 * DH, ld, q_first * kKeysPerTile, smem, wave, q_lane_off);
+    load_tile_async<DH>(d_o + head0 * DH, h, q_first * kKeysPerTile, smem + TBYTES, wave, do_lane_off);
+    load_stats(head0, q_first * kKeysPerTile);
+  }
   store_stats(smem);
   wait_tile_loads();
   __syncthreads();
 
-  for (int qt = q_first; qt < q_last; ++qt) {
-    int it = qt - q_first;
+  for (int it = 0; it < n_it; ++it) {
+    int head, qt;
+    tile_of(it, head, qt);
+    (void)head;
     const char* qtile = smem + (it & 1) * STAGE;
     const char* dotile = qtile + TBYTES;
     const float* st_lse = reinterpret_cast<const float*>(qtile + 2 * TBYTES);
     const float* st_delta = st_lse + 64;
     char* nxt = smem + ((it + 1) & 1) * STAGE;
-    bool more = qt + 1 < q_last;
+    bool more = it + 1 < n_it;
     // The swizzled LDS addresses are cheap to rebuild (a few XORs); hiding the lane id from the optimiser
     // here keeps it from carrying some twenty address registers across iterations and spilling
     // accumulators instead.
@@ -394,9 +405,11 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
     int col_l = lane_l & 31, half_l = lane_l >> 5;
     const char* vslot_l = smem + 2 * STAGE + (wave * V_IN_LDS * 64 + lane_l) * 16;
     if (more) {  // the other stage was last read before the barrier that ended the previous iteration
-      load_tile_async<DH>(qbase, ld, (qt + 1) * kKeysPerTile, nxt, wave, q_lane_off);
-      load_tile_async<DH>(dobase, h, (qt + 1) * kKeysPerTile, nxt + TBYTES, wave, do_lane_off);
-      load_stats((qt + 1) * kKeysPerTile);
+      int nhead, nqt;
+      tile_of(it + 1, nhead, nqt);
+      load_tile_async<DH>(qkv + nhead * DH, ld, nqt * kKeysPerTile, nxt, wave, q_lane_off);
+      load_tile_async<DH>(d_o + nhead * DH, h, nqt * kKeysPerTile, nxt + TBYTES, wave, do_lane_off);
+      load_stats(nhead, nqt * kKeysPerTile);
     }
     int q0 = qt * kKeysPerTile;
     int key = kw0 + col;
@@ -465,9 +478,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
         vk[r] = (bf16)(dk[d][4 * b + r] * scale);
         vv[r] = (bf16)dv[d][4 * b + r];
       }
-      size_t off = (size_t)key * ld + head * DH + 32 * d + 8 * b + 4 * half;
-      *reinterpret_cast<bf16x4*>(dqkv + off + h) = vk;
-      *reinterpret_cast<bf16x4*>(dqkv + off + 2 * h) = vv;
+      size_t off = (size_t)key * ld + h + kv_head * DH + 32 * d + 8 * b + 4 * half;
+      *reinterpret_cast<bf16x4*>(dqkv + off) = vk;
+      *reinterpret_cast<bf16x4*>(dqkv + off + hkv) = vv;
     }
 }
 
@@ -481,7 +494,8 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_bwd_dq_mfma_kernel(
                                                                const bf16* __restrict__ d_o,
                                                                const float* __restrict__ lse,
                                                                const float* __restrict__ delta,
-                                                               bf16* __restrict__ dqkv, int s, int h, float scale) {
+                                                               bf16* __restrict__ dqkv, int s, int h, int hkv, int group,
+                                                                float scale) {
   constexpr int KS = DH / 16, DT = DH / 32;
   constexpr int BQ = 128 * QT;
   constexpr int KBYTES = tile_bytes<DH>();
@@ -494,9 +508,9 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_bwd_dq_mfma_kernel(
   int qblock = gridDim.y - 1 - blockIdx.y;
   int q0 = qblock * BQ;
   int qw0 = q0 + wave * (32 * QT);
-  int ld = 3 * h;
-  const bf16* kbase = qkv + h + head * DH;
-  const bf16* vbase = qkv + 2 * h + head * DH;
+  int ld = h + 2 * hkv;
+  const bf16* kbase = qkv + h + (head / group) * DH;
+  const bf16* vbase = qkv + h + hkv + (head / group) * DH;
   const float LOG2E = 1.4426950408889634f;
   const float c = scale * LOG2E;
 
@@ -624,14 +638,15 @@ __global__ __launch_bounds__(256) void attn_delta_mfma_path_kernel(const bf16* _
 // ==================================================================================
 // Host side
 // ==================================================================================
-bool attention_mfma_supported(int s, int h, int n_heads) {
-  if (n_heads <= 0 || h % n_heads != 0) return false;
+bool attention_mfma_supported(int s, int h, int n_heads, int n_kv_heads) {
+  if (n_heads <= 0 || h % n_heads != 0 || n_kv_heads <= 0 || n_heads % n_kv_heads != 0) return false;
   int dh = h / n_heads;
   return (dh == 64 || dh == 128) && s >= 128 && s % 128 == 0;
 }
 
 template <int DH, int QT>
-static bool launch_fwd(const bf16* qkv, bf16* o, float* lse, int s, int h, int n_heads, hipStream_t stream) {
+static bool launch_fwd(const bf16* qkv, bf16* o, float* lse, int s, int h, int n_heads, int n_kv_heads,
+                       hipStream_t stream) {
   constexpr int smem = 4 * tile_bytes<DH>();
   auto kern = attn_fwd_mfma_kernel<DH, QT>;
   static bool configured = false;
@@ -641,70 +656,61 @@ static bool launch_fwd(const bf16* qkv, bf16* o, float* lse, int s, int h, int n
     configured = true;
   }
   dim3 grid(n_heads, s / (128 * QT));
-  kern<<<grid, 256, smem, stream>>>(qkv, o, lse, s, h, 1.0f / sqrtf((float)DH));
+  kern<<<grid, 256, smem, stream>>>(qkv, o, lse, s, h, n_kv_heads * DH, n_heads / n_kv_heads,
+                                    1.0f / sqrtf((float)DH));
   return launch_ok("attn_fwd_mfma_kernel");
 }
 
-bool attention_forward_mfma(const void* qkv, void* o, float* lse, int s, int h, int n_heads, hipStream_t stream) {
-  if (!attention_mfma_supported(s, h, n_heads) || !qkv || !o || !lse ||
+bool attention_forward_mfma(const void* qkv, void* o, float* lse, int s, int h, int n_heads, int n_kv_heads,
+                            hipStream_t stream) {
+  if (!attention_mfma_supported(s, h, n_heads, n_kv_heads) || !qkv || !o || !lse ||
       ((uintptr_t)qkv | (uintptr_t)o) % 16 != 0) {
-    set_error("attention_forward_mfma: unsupported s=%d h=%d heads=%d or bad pointers", s, h, n_heads);
+    set_error("attention_forward_mfma: unsupported s=%d h=%d heads=%d kv_heads=%d or bad pointers", s, h, n_heads,
+              n_kv_heads);
     return false;
   }
-  int dh = h / n_heads;
   const bf16* q = (const bf16*)qkv;
   bf16* out = (bf16*)o;
-  // two query tiles per wave once that still fills the chip
-  bool big = false && s % 256 == 0 && (int64_t)(s / 256) * n_heads >= 512;
-  if (dh == 128) {
-    if (big) return launch_fwd<128, 2>(q, out, lse, s, h, n_heads, stream);
-    return launch_fwd<128, 1>(q, out, lse, s, h, n_heads, stream);
-  }
-  if (big) return launch_fwd<64, 2>(q, out, lse, s, h, n_heads, stream);
-  return launch_fwd<64, 1>(q, out, lse, s, h, n_heads, stream);
+  if (h / n_heads == 128) return launch_fwd<128, 1>(q, out, lse, s, h, n_heads, n_kv_heads, stream);
+  return launch_fwd<64, 1>(q, out, lse, s, h, n_heads, n_kv_heads, stream);
 }
 
 template <int DH>
 static bool launch_bwd(const bf16* qkv, const bf16* o, const float* lse, const bf16* d_o, bf16* dqkv, float* delta,
-                       int s, int h, int n_heads, hipStream_t stream) {
+                       int s, int h, int n_heads, int n_kv_heads, hipStream_t stream) {
   constexpr int smem_kv = 2 * (2 * tile_bytes<DH>() + 512) + (DH == 128 ? 8192 : 0);  // + V fragments kept in LDS
   constexpr int smem_q = 4 * tile_bytes<DH>();
   auto kkv = attn_bwd_dkv_mfma_kernel<DH>;
   auto kq1 = attn_bwd_dq_mfma_kernel<DH, 1>;
-  auto kq2 = attn_bwd_dq_mfma_kernel<DH, 2>;
   static bool configured = false;
   if (!configured) {
     PO_HIP_OK(hipFuncSetAttribute(reinterpret_cast<const void*>(kkv), hipFuncAttributeMaxDynamicSharedMemorySize,
                                   smem_kv));
     PO_HIP_OK(hipFuncSetAttribute(reinterpret_cast<const void*>(kq1), hipFuncAttributeMaxDynamicSharedMemorySize,
                                   smem_q));
-    PO_HIP_OK(hipFuncSetAttribute(reinterpret_cast<const void*>(kq2), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  smem_q));
     configured = true;
   }
   float scale = 1.0f / sqrtf((float)DH);
+  int hkv = n_kv_heads * DH, group = n_heads / n_kv_heads;
   attn_delta_mfma_path_kernel<DH><<<dim3(ceil_div(s, 4), n_heads), 256, 0, stream>>>(o, d_o, delta, s, h);
-  kkv<<<dim3(n_heads, s / 128), 256, smem_kv, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, scale);
-  bool big = false && s % 256 == 0 && (int64_t)(s / 256) * n_heads >= 512;
-  if (big)
-    kq2<<<dim3(n_heads, s / 256), 256, smem_q, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, scale);
-  else
-    kq1<<<dim3(n_heads, s / 128), 256, smem_q, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, scale);
+  kkv<<<dim3(n_kv_heads, s / 128), 256, smem_kv, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, hkv, group, scale);
+  kq1<<<dim3(n_heads, s / 128), 256, smem_q, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, hkv, group, scale);
   return launch_ok("attention backward MFMA kernels");
 }
 
 bool attention_backward_mfma(const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv,
-                             float* delta, int s, int h, int n_heads, hipStream_t stream) {
-  if (!attention_mfma_supported(s, h, n_heads) || !qkv || !o || !lse || !d_o || !dqkv || !delta ||
+                             float* delta, int s, int h, int n_heads, int n_kv_heads, hipStream_t stream) {
+  if (!attention_mfma_supported(s, h, n_heads, n_kv_heads) || !qkv || !o || !lse || !d_o || !dqkv || !delta ||
       ((uintptr_t)qkv | (uintptr_t)o | (uintptr_t)d_o | (uintptr_t)dqkv) % 16 != 0) {
-    set_error("attention_backward_mfma: unsupported s=%d h=%d heads=%d or bad pointers", s, h, n_heads);
+    set_error("attention_backward_mfma: unsupported s=%d h=%d heads=%d kv_heads=%d or bad pointers", s, h, n_heads,
+              n_kv_heads);
     return false;
   }
   if (h / n_heads == 128)
     return launch_bwd<128>((const bf16*)qkv, (const bf16*)o, lse, (const bf16*)d_o, (bf16*)dqkv, delta, s, h,
-                           n_heads, stream);
+                           n_heads, n_kv_heads, stream);
   return launch_bwd<64>((const bf16*)qkv, (const bf16*)o, lse, (const bf16*)d_o, (bf16*)dqkv, delta, s, h, n_heads,
-                        stream);
+                        n_kv_heads, stream);
 }
 
 }  // namespace po

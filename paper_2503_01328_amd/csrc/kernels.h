@@ -49,18 +49,23 @@ bool gemm(int dtype, int trans_a, int trans_b, int M, int N, int K, const void* 
           const Epilogue& ep, bool force_generic, hipStream_t stream);
 
 // ---- attention (attention_generic.hip, attention_mfma.hip) -------------------
+// qkv is [s, h + 2 hkv]: query block [h], key block [hkv], value block [hkv], hkv = n_kv_heads * (h / n_heads);
+// query head t reads key/value head t / (n_heads / n_kv_heads).  n_kv_heads = n_heads is plain multi-head.
 bool attention_forward_generic(int dtype, const void* qkv, void* o, float* lse, int s, int h, int n_heads,
-                               hipStream_t stream);
+                               int n_kv_heads, hipStream_t stream);
 bool attention_backward_generic(int dtype, const void* qkv, const void* o, const float* lse, const void* d_o,
-                                void* dqkv, float* delta, int s, int h, int n_heads, hipStream_t stream);
-bool attention_mfma_supported(int s, int h, int n_heads);
-bool attention_forward_mfma(const void* qkv, void* o, float* lse, int s, int h, int n_heads, hipStream_t stream);
+                                void* dqkv, float* delta, int s, int h, int n_heads, int n_kv_heads,
+                                hipStream_t stream);
+bool attention_mfma_supported(int s, int h, int n_heads, int n_kv_heads);
+bool attention_forward_mfma(const void* qkv, void* o, float* lse, int s, int h, int n_heads, int n_kv_heads,
+                            hipStream_t stream);
 bool attention_backward_mfma(const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv,
-                             float* delta, int s, int h, int n_heads, hipStream_t stream);
-bool attention_forward(int dtype, const void* qkv, void* o, float* lse, int s, int h, int n_heads,
+                             float* delta, int s, int h, int n_heads, int n_kv_heads, hipStream_t stream);
+bool attention_forward(int dtype, const void* qkv, void* o, float* lse, int s, int h, int n_heads, int n_kv_heads,
                        bool force_generic, hipStream_t stream);
 bool attention_backward(int dtype, const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv,
-                        float* delta, int s, int h, int n_heads, bool force_generic, hipStream_t stream);
+                        float* delta, int s, int h, int n_heads, int n_kv_heads, bool force_generic,
+                        hipStream_t stream);
 
 #define PO_HIP_OK(expr)                                                                  \
   do {                                                                                   \

@@ -65,6 +65,11 @@ struct ParamLayout {
   int64_t ln1_g, ln1_b, w_qkv, b_qkv, w_o, b_o, ln2_g, ln2_b, w_fc1, b_fc1, w_fc2, b_fc2;
 };
 
+// Key/value heads (0 in the config = as many as query heads) and the width of the QKV projection,
+// h for the queries plus n_kv_heads * head_dim each for keys and values.
+static int kv_heads_of(const po_config& c) { return c.n_kv_heads > 0 ? c.n_kv_heads : c.n_heads; }
+static int qkv_width_of(const po_config& c) { return c.hidden + 2 * kv_heads_of(c) * (c.hidden / c.n_heads); }
+
 int validate_config(const po_config* c) {
   if (!c) {
     set_error("config is NULL");
@@ -76,7 +81,8 @@ int validate_config(const po_config* c) {
       c->rank < 0 || c->rank >= c->pipeline_degree || c->prefetch_passes < 0 ||
       (c->copy_streams != 1 && c->copy_streams != 2) || c->hidden / c->n_heads > 256 ||
       (c->hidden / c->n_heads) % 8 != 0 || !(c->ln_eps > 0.f) || c->group < 0 || c->group > c->pipeline_degree ||
-      (c->group > 0 && 2 * c->group < c->pipeline_degree) || (c->weight_stream != 0 && c->weight_stream != 1) || c->min_gap_passes < 0) {
+      (c->group > 0 && 2 * c->group < c->pipeline_degree) || (c->weight_stream != 0 && c->weight_stream != 1) || c->min_gap_passes < 0 || c->n_kv_heads < 0 ||
+      (c->n_kv_heads > 0 && c->n_heads % c->n_kv_heads != 0)) {
     set_error("invalid config: L=%d v=%d h=%d a=%d f=%d s=%d vocab=%d dtype=%d d=%d rank=%d prefetch=%d copy_streams=%d group=%d",
               c->n_layers, c->n_chunks, c->hidden, c->n_heads, c->ffn, c->seq, c->vocab, c->dtype,
               c->pipeline_degree, c->rank, c->prefetch_passes, c->copy_streams, c->group);
@@ -116,8 +122,8 @@ void build_param_layout(const po_config& c, ParamLayout& pl) {
     bool first = l == 0;
     add_desc(pl, "ln1_g", l, 1, h, first ? &pl.ln1_g : &dummy, base);
     add_desc(pl, "ln1_b", l, 1, h, first ? &pl.ln1_b : &dummy, base);
-    add_desc(pl, "w_qkv", l, h, 3 * h, first ? &pl.w_qkv : &dummy, base);
-    add_desc(pl, "b_qkv", l, 1, 3 * h, first ? &pl.b_qkv : &dummy, base);
+    add_desc(pl, "w_qkv", l, h, qkv_width_of(c), first ? &pl.w_qkv : &dummy, base);
+    add_desc(pl, "b_qkv", l, 1, qkv_width_of(c), first ? &pl.b_qkv : &dummy, base);
     add_desc(pl, "w_o", l, h, h, first ? &pl.w_o : &dummy, base);
     add_desc(pl, "b_o", l, 1, h, first ? &pl.b_o : &dummy, base);
     add_desc(pl, "ln2_g", l, 1, h, first ? &pl.ln2_g : &dummy, base);
@@ -143,7 +149,7 @@ void build_slab_layout(const po_config& c, SlabLayout& sl) {
   size_t E = c.dtype == PO_BF16 ? 2 : 4;
   size_t s = c.seq, h = c.hidden, f = c.ffn, a = c.n_heads;
   sl.sz_x = s * h * E;
-  sl.sz_qkv = s * 3 * h * E;
+  sl.sz_qkv = s * (size_t)qkv_width_of(c) * E;
   sl.sz_o = s * h * E;
   sl.sz_x1 = s * h * E;
   sl.sz_u = s * f * E;
@@ -420,10 +426,11 @@ static int st_attention(po_stage* st, bool backward, const void* qkv, void* o, f
     st->spans[span].flops = (backward ? 4.0 : 2.0) * c.seq * (double)c.seq * c.hidden;
   }
   if (backward)
-    PO_K(attention_backward(c.dtype, qkv, o, lse, d_o, dqkv, st->w_delta, c.seq, c.hidden, c.n_heads, false,
+    PO_K(attention_backward(c.dtype, qkv, o, lse, d_o, dqkv, st->w_delta, c.seq, c.hidden, c.n_heads,
+                            kv_heads_of(c), false,
                             st->compute));
   else
-    PO_K(attention_forward(c.dtype, qkv, o, lse, c.seq, c.hidden, c.n_heads, false, st->compute));
+    PO_K(attention_forward(c.dtype, qkv, o, lse, c.seq, c.hidden, c.n_heads, kv_heads_of(c), false, st->compute));
   return span_end(st, st->compute, span);
 }
 
@@ -447,10 +454,11 @@ static int layer_forward(po_stage* st, int layer, char* slab, void* y_out) {
   float* lse = (float*)(slab + sl.off_lse);
 
   PO_K(layernorm_forward(dt, x, st->P(layer, pl.ln1_g), st->P(layer, pl.ln1_b), st->w_n, s, h, c.ln_eps, q));
-  Epilogue e = make_ep(3 * h);
+  const int wq = qkv_width_of(c);  // h + 2 hkv
+  Epilogue e = make_ep(wq);
   e.bias = st->P(layer, pl.b_qkv);
   e.out = qkv;
-  PO_RC(st_gemm(st, 0, 0, s, 3 * h, h, st->w_n, h, st->P(layer, pl.w_qkv), 3 * h, e));
+  PO_RC(st_gemm(st, 0, 0, s, wq, h, st->w_n, h, st->P(layer, pl.w_qkv), wq, e));
   PO_RC(st_attention(st, false, qkv, o, lse, nullptr, nullptr));
   e = make_ep(h);
   e.bias = st->P(layer, pl.b_o);
@@ -513,7 +521,8 @@ static int layer_backward_input(po_stage* st, int layer, const char* slab, const
   PO_RC(st_attention(st, true, qkv, const_cast<char*>(o), const_cast<float*>(lse), st->w_do, b.dqkv));
   e = make_ep(h);
   e.out = b.dn1;
-  PO_RC(st_gemm(st, 0, 1, s, h, 3 * h, b.dqkv, 3 * h, st->P(layer, pl.w_qkv), 3 * h, e));
+  const int wq = qkv_width_of(c);
+  PO_RC(st_gemm(st, 0, 1, s, h, wq, b.dqkv, wq, st->P(layer, pl.w_qkv), wq, e));
   PO_K(layernorm_backward(dt, b.dn1, x, st->P(layer, pl.ln1_g), b.dx1, dx_out, nullptr, nullptr, b.lnws1, s, h,
                           c.ln_eps, kLnInputGrad, q));
   return PO_OK;
@@ -551,10 +560,11 @@ static int layer_backward_weight(po_stage* st, int layer, const char* slab, cons
   PO_RC(st_gemm(st, 1, 0, h, h, s, o, h, b.dx1, h, e, q));
   PO_K(colsum_accumulate(dt, b.dx1, st->G(layer, pl.b_o), colws, s, h, q));
   PO_K(layernorm_forward(dt, x, st->P(layer, pl.ln1_g), st->P(layer, pl.ln1_b), n_out, s, h, c.ln_eps, q));
-  e = make_ep(3 * h);
+  const int wq = qkv_width_of(c);
+  e = make_ep(wq);
   e.acc_f32 = st->G(layer, pl.w_qkv);
-  PO_RC(st_gemm(st, 1, 0, h, 3 * h, s, n_out, h, b.dqkv, 3 * h, e, q));
-  PO_K(colsum_accumulate(dt, b.dqkv, st->G(layer, pl.b_qkv), colws, s, 3 * h, q));
+  PO_RC(st_gemm(st, 1, 0, h, wq, s, n_out, h, b.dqkv, wq, e, q));
+  PO_K(colsum_accumulate(dt, b.dqkv, st->G(layer, pl.b_qkv), colws, s, wq, q));
   PO_K(layernorm_backward(dt, b.dn1, x, st->P(layer, pl.ln1_g), nullptr, nullptr, st->G(layer, pl.ln1_g),
                           st->G(layer, pl.ln1_b), b.lnws1, s, h, c.ln_eps, kLnParamGrad, q));
   return PO_OK;
@@ -1185,7 +1195,7 @@ int stage_create(const po_config* cfg, void* compute_stream, po_stage** out) {
   }
   // Workspaces: one allocation, carved up.
   size_t s = cfg->seq, h = cfg->hidden, f = cfg->ffn, E = st->E;
-  size_t sh = align_up(s * h * E, 256), sf = align_up(s * f * E, 256), s3h = align_up(s * 3 * h * E, 256);
+  size_t sh = align_up(s * h * E, 256), sf = align_up(s * f * E, 256), s3h = align_up(s * (size_t)qkv_width_of(*cfg) * E, 256);
   size_t delta = align_up((size_t)cfg->n_heads * s * 4, 256);
   size_t lnws = align_up(layernorm_backward_workspace((int)s, (int)h), 256);
   size_t maxn = std::max((size_t)3 * h, f);
@@ -1464,18 +1474,19 @@ int po_op_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32
                  (hipStream_t)stream));
 }
 int po_op_attention_forward(int32_t dtype, const void* qkv, void* o, float* lse, int32_t s, int32_t h,
-                            int32_t n_heads, int32_t force_generic, void* stream) {
+                            int32_t n_heads, int32_t n_kv_heads, int32_t force_generic, void* stream) {
   begin_launch();
   if (!dtype_ok(dtype)) return PO_E_INVAL;
-  return ok(attention_forward(dtype, qkv, o, lse, s, h, n_heads, force_generic != 0, (hipStream_t)stream));
+  return ok(attention_forward(dtype, qkv, o, lse, s, h, n_heads, n_kv_heads > 0 ? n_kv_heads : n_heads,
+                              force_generic != 0, (hipStream_t)stream));
 }
 int po_op_attention_backward(int32_t dtype, const void* qkv, const void* o, const float* lse, const void* d_o,
-                             void* dqkv, float* delta, int32_t s, int32_t h, int32_t n_heads, int32_t force_generic,
-                             void* stream) {
+                             void* dqkv, float* delta, int32_t s, int32_t h, int32_t n_heads, int32_t n_kv_heads,
+                             int32_t force_generic, void* stream) {
   begin_launch();
   if (!dtype_ok(dtype)) return PO_E_INVAL;
-  return ok(attention_backward(dtype, qkv, o, lse, d_o, dqkv, delta, s, h, n_heads, force_generic != 0,
-                               (hipStream_t)stream));
+  return ok(attention_backward(dtype, qkv, o, lse, d_o, dqkv, delta, s, h, n_heads,
+                               n_kv_heads > 0 ? n_kv_heads : n_heads, force_generic != 0, (hipStream_t)stream));
 }
 uint64_t po_op_colsum_workspace(int32_t rows, int32_t n) { return rows > 0 && n > 0 ? colsum_workspace(rows, n) : 0; }
 int po_op_colsum_accumulate(int32_t dtype, const void* x, float* acc, float* workspace, int32_t rows, int32_t n,

@@ -17,7 +17,7 @@ def make_config(shape: syn.StageShape, **overrides) -> po.po_config:
     cfg = po.po_config_default(
         n_layers=shape.n_layers, n_chunks=shape.n_chunks, hidden=shape.hidden, n_heads=shape.n_heads,
         ffn=shape.ffn, seq=shape.seq, vocab=shape.vocab, dtype=po.PO_BF16 if shape.dtype == "bf16" else po.PO_F32,
-        pipeline_degree=shape.pipeline_degree, rank=shape.rank)
+        pipeline_degree=shape.pipeline_degree, rank=shape.rank, n_kv_heads=shape.n_kv_heads)
     for k, v in overrides.items():
         setattr(cfg, k, v)
     return cfg

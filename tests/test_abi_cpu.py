@@ -84,6 +84,20 @@ def test_schedule_ops_reject_bad_arguments():
         assert "schedule" in po.po_last_error()
 
 
+def test_grouped_query_layout_and_saved_bytes():
+    shape = syn.StageShape(2, 1, 4096, 32, 16384, 4096, dtype="bf16", n_kv_heads=8)
+    cfg = harness.make_config(shape)
+    layout = {(d["layer"], d["name"]): d for d in po.po_param_layout(cfg)}
+    assert (layout[(0, "w_qkv")]["rows"], layout[(0, "w_qkv")]["cols"]) == (4096, 4096 + 2 * 8 * 128)
+    assert layout[(1, "b_qkv")]["cols"] == 6144
+    assert po.po_param_count(cfg) == 2 * (4096 * 6144 + 6144 + 4096 * 4096 + 2 * 4096 * 16384 + 4096 * 5 + 16384 + 4096)
+    model = sch.saved_bytes_per_layer(4096, 4096, 32, 2, 8)
+    assert model == (8 * 4096 + 2 * 1024) * 4096 * 2 + 4 * 32 * 4096  # k and v a quarter of the multi-head size
+    assert 0 <= po.po_saved_bytes_per_layer(cfg) - model < 6 * 256
+    with pytest.raises(po.PipeOffloadError):
+        po.po_param_count(harness.make_config(syn.StageShape(2, 1, 4096, 32, 16384, 4096, n_kv_heads=5)))
+
+
 def test_offload_ratio_for_k():
     assert po.po_offload_ratio_for_k(0.5) == 1.0 and po.po_offload_ratio_for_k(1.0) == 1.0
     assert po.po_offload_ratio_for_k(2.0) == 0.5 and abs(po.po_offload_ratio_for_k(1.6) - 0.625) < 1e-12

@@ -165,35 +165,55 @@ def test_attention_mfma(gpu_device, s, h, a):
     _attention_case(gpu_device, "bf16", s, h, a, 0)
 
 
-def _attention_case(gpu_device, dtype, s, h, a, force_generic):
+def _attention_case(gpu_device, dtype, s, h, a, force_generic, akv=0):
     code, tdt, tol = DT[dtype]
-    rng = np.random.default_rng(s * 31 + h + a)
-    qkv = _rand(rng, (s, 3 * h), dtype)
+    rng = np.random.default_rng(s * 31 + h + a + 7 * akv)
+    dh = h // a
+    hkv = (akv or a) * dh
+    group = a // (akv or a)
+    qkv = _rand(rng, (s, h + 2 * hkv), dtype)
     d_o = _rand(rng, (s, h), dtype)
     qd, dod = _dev(qkv, tdt, gpu_device), _dev(d_o, tdt, gpu_device)
     o = torch.empty(s, h, dtype=tdt, device=gpu_device)
     lse = torch.empty(a, s, dtype=torch.float32, device=gpu_device)
-    po.po_op_attention_forward(code, qd, o, lse, s, h, a, force_generic)
+    po.po_op_attention_forward(code, qd, o, lse, s, h, a, force_generic, n_kv_heads=akv)
     q64 = qkv.astype(np.float64)
-    q, k, v = q64[:, :h], q64[:, h:2 * h], q64[:, 2 * h:]
+    q, k, v = q64[:, :h], q64[:, h:h + hkv], q64[:, h + hkv:]
     ro, probs = so.attention_forward(q, k, v, a)
     assert max_rel_err(_np(o), ro) < tol
     # log-sum-exp of the scaled, masked scores: a plain definition
-    dh = h // a
     for t in range(a):
-        sc = (q[:, t * dh:(t + 1) * dh] @ k[:, t * dh:(t + 1) * dh].T) / np.sqrt(dh)
+        kt = k[:, (t // group) * dh:(t // group + 1) * dh]
+        sc = (q[:, t * dh:(t + 1) * dh] @ kt.T) / np.sqrt(dh)
         sc = np.where(np.triu(np.ones((s, s), dtype=bool), 1), -np.inf, sc)
         ref_lse = np.log(np.exp(sc - sc.max(1, keepdims=True)).sum(1)) + sc.max(1)
         assert np.abs(_np(lse[t]) - ref_lse).max() < 1e-3 * max(1.0, np.abs(ref_lse).max())
-    dqkv = torch.empty(s, 3 * h, dtype=tdt, device=gpu_device)
+    dqkv = torch.empty(s, h + 2 * hkv, dtype=tdt, device=gpu_device)
     delta = torch.empty(a, s, dtype=torch.float32, device=gpu_device)
-    po.po_op_attention_backward(code, qd, o, lse, dod, dqkv, delta, s, h, a, force_generic)
+    po.po_op_attention_backward(code, qd, o, lse, dod, dqkv, delta, s, h, a, force_generic, n_kv_heads=akv)
     rdq, rdk, rdv = so.attention_backward(d_o.astype(np.float64), q, k, v, probs, a)
     got = _np(dqkv)
     btol = tol if dtype == "f32" else 3e-2  # o is rounded to bf16 before delta = rowsum(dO * O) is formed
     assert max_rel_err(got[:, :h], rdq) < btol
-    assert max_rel_err(got[:, h:2 * h], rdk) < btol
-    assert max_rel_err(got[:, 2 * h:], rdv) < btol
+    assert max_rel_err(got[:, h:h + hkv], rdk) < btol
+    assert max_rel_err(got[:, h + hkv:], rdv) < btol
+
+
+# grouped-query attention: key/value heads shared by groups of query heads
+@pytest.mark.parametrize("dtype,s,h,a,akv,force_generic", [
+    ("f32", 37, 128, 4, 2, 1), ("f32", 70, 192, 6, 1, 1), ("bf16", 130, 256, 4, 2, 1),
+    ("bf16", 128, 256, 4, 2, 0), ("bf16", 384, 512, 4, 1, 0), ("bf16", 256, 512, 8, 2, 0),
+    ("bf16", 640, 768, 6, 3, 0), ("bf16", 512, 1024, 16, 4, 0), ("bf16", 256, 256, 4, 4, 0)])
+def test_grouped_query_attention(gpu_device, dtype, s, h, a, akv, force_generic):
+    _attention_case(gpu_device, dtype, s, h, a, force_generic, akv)
+
+
+def test_grouped_query_attention_rejects_bad_groups(gpu_device):
+    t = torch.zeros(128, 3 * 256, dtype=torch.bfloat16, device=gpu_device)
+    o = torch.zeros(128, 256, dtype=torch.bfloat16, device=gpu_device)
+    lse = torch.zeros(4, 128, device=gpu_device)
+    with pytest.raises(po.PipeOffloadError):
+        po.po_op_attention_forward(po.PO_BF16, t, o, lse, 128, 256, 4, 0, n_kv_heads=3)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])

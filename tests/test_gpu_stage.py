@@ -314,3 +314,28 @@ def test_short_gap_units_are_not_offloaded(gpu_device):
             assert stats["n_offloads"] == (12 if min_gap == 0 else 0)
             assert stats["peak_resident_units"] == 1
     _assert_bit_identical(snaps[0], snaps[1])
+
+
+# ---- grouped-query attention in the stage (Table 2's query groups) ---------------------------------------------
+@pytest.mark.parametrize("shape,tol", [
+    (syn.StageShape(2, 1, 128, 4, 512, 96, vocab=40, dtype="f32", pipeline_degree=2, n_microbatches=3, n_kv_heads=2), 1e-4),
+    (syn.StageShape(2, 1, 512, 4, 1024, 256, dtype="bf16", pipeline_degree=3, n_microbatches=4, n_kv_heads=1), 2e-2),
+    (syn.StageShape(2, 1, 256, 4, 1024, 384, dtype="bf16", pipeline_degree=2, n_microbatches=3, n_kv_heads=2), 2e-2)],
+    ids=["f32-generic", "bf16-mfma-dh128", "bf16-mfma-dh64"])
+def test_stage_with_grouped_query_attention(gpu_device, shape, tol):
+    m = shape.n_microbatches
+    snaps = {}
+    for ratio in (0.0, 1.0):
+        with StageRunner(shape) as r:
+            if shape.ffn == 4 * shape.hidden:  # the slab is the saved set plus at most six 256-byte alignment gaps
+                model = sch.saved_bytes_per_layer(shape.seq, shape.hidden, shape.n_heads,
+                                                  4 if shape.dtype == "f32" else 2, shape.n_kv_heads)
+                assert 0 <= po.po_saved_bytes_per_layer(r.cfg) - model < 6 * 256
+            r.make_inputs()
+            stats = r.run(po.PO_SCHED_1F1B, ratio)
+            snaps[ratio] = _snapshot(r)
+            if ratio == 0.0:
+                _compare(shape, r.results(), _oracle(shape, r, m), tol)
+            else:
+                assert stats["bytes_d2h"] == m * shape.n_layers * po.po_saved_bytes_per_layer(r.cfg)
+    _assert_bit_identical(snaps[0.0], snaps[1.0])
