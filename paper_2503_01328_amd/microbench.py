@@ -109,13 +109,12 @@ def run(config: str, iters: int = 20):
     add("attention forward (causal model flops 2 s^2 h)", "mfma", 2.0 * s * s * h, t, MFMA_PEAK)
     t = _time(lambda: po.po_op_attention_backward(po.PO_BF16, qkv, o, lse, d_o, dqkv, delta, s, h, a), iters)
     add("attention backward (causal model flops 4 s^2 h)", "mfma", 4.0 * s * s * h, t, MFMA_PEAK)
-    # host link: one layer slab each way, alone and both at once
+    # host link: one layer slab each way (both directions at once are measured inside the stage: bench.py)
     nbytes = sum(sizes)
     host_a = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
     host_b = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
     dev_a = torch.empty(nbytes, dtype=torch.uint8, device=dev)
     dev_b = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
 
     def d2h():
         host_a.copy_(dev_a, non_blocking=True)
@@ -129,16 +128,6 @@ def run(config: str, iters: int = 20):
     t = _time(h2d, 5, 1)
     add("H2D copy of one layer slab (pinned)", "link", nbytes, t, nbytes / t)
 
-    def both():
-        with torch.cuda.stream(s1):
-            d2h()
-        with torch.cuda.stream(s2):
-            h2d()
-        torch.cuda.current_stream().wait_stream(s1)
-        torch.cuda.current_stream().wait_stream(s2)
-
-    t = _time(both, 5, 1)
-    add("D2H + H2D at once on two streams (bytes both ways)", "link", 2 * nbytes, t, 2 * nbytes / t)
     return rows
 
 
