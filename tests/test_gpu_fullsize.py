@@ -119,6 +119,35 @@ def test_attention_full_size_sampled_heads(gpu_device, s, h, a, heads):
         assert max_rel_err(got[2], rdv) < 3e-2
 
 
+def test_grouped_query_attention_full_size_sampled_group(gpu_device):
+    """C3's attention shape with 8 key/value heads (Table 2's query groups): one whole group (4 query heads sharing
+    key/value head 5) against the oracle."""
+    s, h, a, akv, kvh = 4096, 4096, 32, 8, 5
+    dh, group, hkv = h // a, a // akv, akv * (h // a)
+    rng = np.random.default_rng(77)
+    qkv = _bf16_normal(rng, (s, h + 2 * hkv))
+    d_o = _bf16_normal(rng, (s, h))
+    qd, dod = _dev(qkv, gpu_device), _dev(d_o, gpu_device)
+    o = torch.empty(s, h, dtype=BF, device=gpu_device)
+    lse = torch.empty(a, s, dtype=torch.float32, device=gpu_device)
+    dqkv = torch.empty(s, h + 2 * hkv, dtype=BF, device=gpu_device)
+    delta = torch.empty(a, s, dtype=torch.float32, device=gpu_device)
+    po.po_op_attention_forward(po.PO_BF16, qd, o, lse, s, h, a, n_kv_heads=akv)
+    po.po_op_attention_backward(po.PO_BF16, qd, o, lse, dod, dqkv, delta, s, h, a, n_kv_heads=akv)
+    torch.cuda.synchronize()
+    qc = slice(kvh * group * dh, (kvh + 1) * group * dh)  # the group's query columns
+    kc = slice(h + kvh * dh, h + (kvh + 1) * dh)
+    vc = slice(h + hkv + kvh * dh, h + hkv + (kvh + 1) * dh)
+    q, k, v = (qkv[:, c].astype(np.float64) for c in (qc, kc, vc))
+    ro, probs = so.attention_forward(q, k, v, group)
+    assert max_rel_err(_np(o[:, qc]), ro) < 2e-2
+    rdq, rdk, rdv = so.attention_backward(d_o[:, qc].astype(np.float64), q, k, v, probs, group)
+    del probs
+    assert max_rel_err(_np(dqkv[:, qc]), rdq) < 3e-2
+    assert max_rel_err(_np(dqkv[:, kc]), rdk) < 3e-2
+    assert max_rel_err(_np(dqkv[:, vc]), rdv) < 3e-2
+
+
 def test_one_c2_shaped_layer_through_the_stage(gpu_device):
     """Every kernel of the stage at C2's shapes (h 2048, 16 heads, FFN 8192, s 2048), two microbatches of one
     layer under 1F1B with full offload; all outputs and gradients against the fp64 oracle."""
