@@ -240,10 +240,12 @@ int po_op_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32
  * reads key/value head t / (n_heads / n_kv_heads) (grouped-query attention, Table 2). */
 int po_op_attention_forward(int32_t dtype, const void* qkv, void* o, float* lse, int32_t s, int32_t h,
                             int32_t n_heads, int32_t n_kv_heads, int32_t force_generic, void* stream);
-/* Causal attention backward (row a16): dqkv laid out like qkv; delta: fp32 workspace [a, s]. */
+/* Causal attention backward (row a16): dqkv laid out like qkv; delta: fp32 workspace [a, s]; partials: NULL, or
+ * a [s, 2h] workspace of dtype that lets grouped-query shapes with few key/value heads compute dK/dV per query
+ * head and add the groups up afterwards (same result up to the rounding of the per-head terms). */
 int po_op_attention_backward(int32_t dtype, const void* qkv, const void* o, const float* lse, const void* d_o,
-                             void* dqkv, float* delta, int32_t s, int32_t h, int32_t n_heads, int32_t n_kv_heads,
-                             int32_t force_generic, void* stream);
+                             void* dqkv, float* delta, void* partials, int32_t s, int32_t h, int32_t n_heads,
+                             int32_t n_kv_heads, int32_t force_generic, void* stream);
 
 /* acc[N] += column sums of x [rows, N] (bias gradients, rows a12-a17), deterministic: row chunks
  * are reduced to partials in `workspace` (fp32, po_op_colsum_workspace bytes), then added in chunk order. */

@@ -91,7 +91,7 @@ EXPORTS = {
     "po_op_gemm": (C.c_int, [C.c_int32] * 6 + [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32] + [C.c_void_p] * 6 +
                    [C.c_int32, C.c_void_p]),
     "po_op_attention_forward": (C.c_int, [C.c_int32] + [C.c_void_p] * 3 + [C.c_int32] * 5 + [C.c_void_p]),
-    "po_op_attention_backward": (C.c_int, [C.c_int32] + [C.c_void_p] * 6 + [C.c_int32] * 5 + [C.c_void_p]),
+    "po_op_attention_backward": (C.c_int, [C.c_int32] + [C.c_void_p] * 7 + [C.c_int32] * 5 + [C.c_void_p]),
     "po_op_colsum_workspace": (C.c_uint64, [C.c_int32, C.c_int32]),
     "po_op_colsum_accumulate": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                           C.c_void_p]),
@@ -271,9 +271,9 @@ def po_op_attention_forward(dtype, qkv, o, lse, s, h, n_heads, force_generic=0, 
 
 
 def po_op_attention_backward(dtype, qkv, o, lse, d_o, dqkv, delta, s, h, n_heads, force_generic=0, stream=None,
-                             n_kv_heads=0):
+                             n_kv_heads=0, partials=None):
     _check(lib.po_op_attention_backward(dtype, _ptr(qkv), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(dqkv), _ptr(delta),
-                                        s, h, n_heads, n_kv_heads, force_generic, _stream(stream)))
+                                        _ptr(partials), s, h, n_heads, n_kv_heads, force_generic, _stream(stream)))
 
 
 def po_op_colsum_workspace(rows, n) -> int:

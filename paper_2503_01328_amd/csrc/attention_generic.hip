@@ -275,10 +275,10 @@ bool attention_forward(int dtype, const void* qkv, void* o, float* lse, int s, i
 }
 
 bool attention_backward(int dtype, const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv,
-                        float* delta, int s, int h, int n_heads, int n_kv_heads, bool force_generic,
+                        float* delta, void* partials, int s, int h, int n_heads, int n_kv_heads, bool force_generic,
                         hipStream_t stream) {
   if (dtype == kBF16 && !force_generic && attention_mfma_supported(s, h, n_heads, n_kv_heads))
-    return attention_backward_mfma(qkv, o, lse, d_o, dqkv, delta, s, h, n_heads, n_kv_heads, stream);
+    return attention_backward_mfma(qkv, o, lse, d_o, dqkv, delta, partials, s, h, n_heads, n_kv_heads, stream);
   return attention_backward_generic(dtype, qkv, o, lse, d_o, dqkv, delta, s, h, n_heads, n_kv_heads, stream);
 }
 

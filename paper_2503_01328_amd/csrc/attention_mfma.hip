@@ -315,8 +315,14 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
                                                                 const bf16* __restrict__ d_o,
                                                                 const float* __restrict__ lse,
                                                                 const float* __restrict__ delta,
-                                                                bf16* __restrict__ dqkv, int s, int h, int hkv, int group,
-                                                                float scale) {
+                                                                bf16* __restrict__ out, int ld_out, int out_k0,
+                                                                int out_v_delta, int hpb, int s, int h, int hkv,
+                                                                int group, float scale) {
+  // Block b of the x dimension works on the hpb query heads b * hpb .. (all of them read key/value head
+  // b * hpb / group) and writes dK to columns out_k0 + b * DH .., dV out_v_delta columns further, of `out`
+  // (rows ld_out apart).  hpb = group: one block per key/value head writing straight into dqkv.  hpb = 1: one
+  // block per query head writing per-head partial results that a second kernel adds up per group; that keeps
+  // the launch as parallel as with plain multi-head attention when there are few key/value heads.
   constexpr int KS = DH / 16, DT = DH / 32;
   constexpr int TBYTES = tile_bytes<DH>();
   constexpr int STAGE = 2 * TBYTES + 512;  // Q tile, dO tile, lse[64], delta[64]
@@ -324,7 +330,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
 
   int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   int half = lane >> 5, col = lane & 31;
-  int kv_head = blockIdx.x;     // heads vary fastest in dispatch order: heaviest blocks of all heads first
+  int head_first = blockIdx.x * hpb;  // heads vary fastest in dispatch order: heaviest blocks of all heads first
+  int kv_head = head_first / group;
   int kb0 = blockIdx.y * 128;   // first key of the block (the earliest blocks have the most query tiles)
   int kw0 = kb0 + wave * 32;    // first key of this wave
   int ld = h + 2 * hkv;
@@ -354,10 +361,10 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
 #pragma unroll
     for (int e = 0; e < 16; ++e) dk[d][e] = dv[d][e] = 0.f;
 
-  // Query tiles [q_first, q_last) of every query head of this key/value head's group, one head after the other:
-  // iteration `it` works on head kv_head * group + it / n_qt, tile q_first + it % n_qt.
+  // Query tiles [q_first, q_last) of every query head of this block, one head after the other:
+  // iteration `it` works on head head_first + it / n_qt, tile q_first + it % n_qt.
   int q_first = kb0 / kKeysPerTile, q_last = s / kKeysPerTile;
-  int n_qt = q_last - q_first, n_it = group * n_qt;
+  int n_qt = q_last - q_first, n_it = hpb * n_qt;
   // Row statistics enter as the initial value of the accumulators: S starts at -lse / scale, so that
   // exp2((S - lse / scale) * scale * log2 e) = P, and dP starts at -delta, so that dS = P * acc.
   // Threads 0..63 carry lse of a row, 64..127 delta of a row (128..255 repeat them and store nothing).  The
@@ -370,7 +377,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
   auto load_stats = [&](int head, int q0) { stat = stat_src[(size_t)head * s + q0]; };
   auto tile_of = [&](int it, int& head, int& qt) {
     int g = it / n_qt;
-    head = kv_head * group + g;
+    head = head_first + g;
     qt = q_first + it - g * n_qt;
   };
   auto store_stats = [&](char* stage) {
@@ -378,7 +385,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
   };
   const unsigned q_lane_off = tile_lane_offset<DH>(ld, wave, lane), do_lane_off = tile_lane_offset<DH>(h, wave, lane);
   {
-    int head0 = kv_head * group;
+    int head0 = head_first;
     load_tile_async<DH>(qkv + head0 * DH, ld, q_first * kKeysPerTile, smem, wave, q_lane_off);
     load_tile_async<DH>(d_o + head0 * DH, h, q_first * kKeysPerTile, smem + TBYTES, wave, do_lane_off);
     load_stats(head0, q_first * kKeysPerTile);
@@ -478,9 +485,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
         vk[r] = (bf16)(dk[d][4 * b + r] * scale);
         vv[r] = (bf16)dv[d][4 * b + r];
       }
-      size_t off = (size_t)key * ld + h + kv_head * DH + 32 * d + 8 * b + 4 * half;
-      *reinterpret_cast<bf16x4*>(dqkv + off) = vk;
-      *reinterpret_cast<bf16x4*>(dqkv + off + hkv) = vv;
+      size_t off = (size_t)key * ld_out + out_k0 + blockIdx.x * DH + 32 * d + 8 * b + 4 * half;
+      *reinterpret_cast<bf16x4*>(out + off) = vk;
+      *reinterpret_cast<bf16x4*>(out + off + out_v_delta) = vv;
     }
 }
 
@@ -617,6 +624,30 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_bwd_dq_mfma_kernel(
   }
 }
 
+// Adds the per-query-head dK / dV partials [s, 2h] (dK of head t at columns t * DH, dV at h + t * DH) of every
+// group in head order, in fp32, into the key and value blocks of dqkv [s, h + 2 hkv].  One thread per 8 columns.
+template <int DH>
+__global__ __launch_bounds__(256) void attn_group_sum_kernel(const bf16* __restrict__ part, bf16* __restrict__ dqkv,
+                                                             int s, int h, int hkv, int group) {
+  int per_row = 2 * hkv / 8;
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (size_t)s * per_row) return;
+  int row = (int)(idx / per_row), c8 = (int)(idx % per_row) * 8;
+  int is_v = c8 >= hkv;
+  int c = c8 - is_v * hkv;           // column inside the key (or value) block
+  int kv_head = c / DH, e = c % DH;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int g = 0; g < group; ++g) {
+    bf16x8 v = *reinterpret_cast<const bf16x8*>(part + (size_t)row * (2 * h) + is_v * h + (kv_head * group + g) * DH + e);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] += (float)v[i];
+  }
+  bf16x8 o;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) o[i] = (bf16)acc[i];
+  *reinterpret_cast<bf16x8*>(dqkv + (size_t)row * (h + 2 * hkv) + h + c8) = o;
+}
+
 // delta[head][i] = sum_e dO[i, head, e] * O[i, head, e]: one wave per (head, row).
 template <int DH>
 __global__ __launch_bounds__(256) void attn_delta_mfma_path_kernel(const bf16* __restrict__ o,
@@ -677,7 +708,7 @@ bool attention_forward_mfma(const void* qkv, void* o, float* lse, int s, int h, 
 
 template <int DH>
 static bool launch_bwd(const bf16* qkv, const bf16* o, const float* lse, const bf16* d_o, bf16* dqkv, float* delta,
-                       int s, int h, int n_heads, int n_kv_heads, hipStream_t stream) {
+                       bf16* partials, int s, int h, int n_heads, int n_kv_heads, hipStream_t stream) {
   constexpr int smem_kv = 2 * (2 * tile_bytes<DH>() + 512) + (DH == 128 ? 8192 : 0);  // + V fragments kept in LDS
   constexpr int smem_q = 4 * tile_bytes<DH>();
   auto kkv = attn_bwd_dkv_mfma_kernel<DH>;
@@ -693,13 +724,25 @@ static bool launch_bwd(const bf16* qkv, const bf16* o, const float* lse, const b
   float scale = 1.0f / sqrtf((float)DH);
   int hkv = n_kv_heads * DH, group = n_heads / n_kv_heads;
   attn_delta_mfma_path_kernel<DH><<<dim3(ceil_div(s, 4), n_heads), 256, 0, stream>>>(o, d_o, delta, s, h);
-  kkv<<<dim3(n_kv_heads, s / 128), 256, smem_kv, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, hkv, group, scale);
+  // Few key/value heads: one block per query head and a per-group sum afterwards (needs the [s, 2h] workspace),
+  // once the direct launch would not fill the chip's 512 block slots.
+  bool split = group > 1 && partials && (int64_t)n_kv_heads * (s / 128) < 512;
+  if (split) {
+    kkv<<<dim3(n_heads, s / 128), 256, smem_kv, stream>>>(qkv, d_o, lse, delta, partials, 2 * h, 0, h, 1, s, h, hkv,
+                                                         group, scale);
+    size_t n = (size_t)s * (2 * hkv / 8);
+    attn_group_sum_kernel<DH><<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(partials, dqkv, s, h, hkv, group);
+  } else {
+    kkv<<<dim3(n_kv_heads, s / 128), 256, smem_kv, stream>>>(qkv, d_o, lse, delta, dqkv, h + 2 * hkv, h, hkv, group, s,
+                                                            h, hkv, group, scale);
+  }
   kq1<<<dim3(n_heads, s / 128), 256, smem_q, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, hkv, group, scale);
   return launch_ok("attention backward MFMA kernels");
 }
 
 bool attention_backward_mfma(const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv,
-                             float* delta, int s, int h, int n_heads, int n_kv_heads, hipStream_t stream) {
+                             float* delta, void* partials, int s, int h, int n_heads, int n_kv_heads,
+                             hipStream_t stream) {
   if (!attention_mfma_supported(s, h, n_heads, n_kv_heads) || !qkv || !o || !lse || !d_o || !dqkv || !delta ||
       ((uintptr_t)qkv | (uintptr_t)o | (uintptr_t)d_o | (uintptr_t)dqkv) % 16 != 0) {
     set_error("attention_backward_mfma: unsupported s=%d h=%d heads=%d kv_heads=%d or bad pointers", s, h, n_heads,
@@ -707,10 +750,10 @@ bool attention_backward_mfma(const void* qkv, const void* o, const float* lse, c
     return false;
   }
   if (h / n_heads == 128)
-    return launch_bwd<128>((const bf16*)qkv, (const bf16*)o, lse, (const bf16*)d_o, (bf16*)dqkv, delta, s, h,
-                           n_heads, n_kv_heads, stream);
-  return launch_bwd<64>((const bf16*)qkv, (const bf16*)o, lse, (const bf16*)d_o, (bf16*)dqkv, delta, s, h, n_heads,
-                        n_kv_heads, stream);
+    return launch_bwd<128>((const bf16*)qkv, (const bf16*)o, lse, (const bf16*)d_o, (bf16*)dqkv, delta,
+                           (bf16*)partials, s, h, n_heads, n_kv_heads, stream);
+  return launch_bwd<64>((const bf16*)qkv, (const bf16*)o, lse, (const bf16*)d_o, (bf16*)dqkv, delta, (bf16*)partials,
+                        s, h, n_heads, n_kv_heads, stream);
 }
 
 }  // namespace po

@@ -59,12 +59,15 @@ bool attention_backward_generic(int dtype, const void* qkv, const void* o, const
 bool attention_mfma_supported(int s, int h, int n_heads, int n_kv_heads);
 bool attention_forward_mfma(const void* qkv, void* o, float* lse, int s, int h, int n_heads, int n_kv_heads,
                             hipStream_t stream);
+// partials: optional [s, 2h] workspace of the dtype; with it, grouped-query shapes with few key/value heads run
+// dK/dV per query head and add the groups up afterwards.
 bool attention_backward_mfma(const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv,
-                             float* delta, int s, int h, int n_heads, int n_kv_heads, hipStream_t stream);
+                             float* delta, void* partials, int s, int h, int n_heads, int n_kv_heads,
+                             hipStream_t stream);
 bool attention_forward(int dtype, const void* qkv, void* o, float* lse, int s, int h, int n_heads, int n_kv_heads,
                        bool force_generic, hipStream_t stream);
 bool attention_backward(int dtype, const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv,
-                        float* delta, int s, int h, int n_heads, int n_kv_heads, bool force_generic,
+                        float* delta, void* partials, int s, int h, int n_heads, int n_kv_heads, bool force_generic,
                         hipStream_t stream);
 
 #define PO_HIP_OK(expr)                                                                  \

@@ -328,6 +328,7 @@ struct po_stage {
   char* ws = nullptr;
   size_t ws_bytes = 0;
   char *w_n, *w_g, *w_du, *w_dqkv, *w_do, *w_dx1, *w_dn, *w_dn1, *w_dy[2], *w_x0;
+  char* w_dkv_part = nullptr;  // [s, 2h] per-query-head dK/dV of grouped-query attention (null with multi-head)
   char* w_n_w;  // LayerNorm recompute output of the weight-gradient half (own buffer: it may run on its own stream)
   float *w_delta, *w_lnws, *w_lnws1, *w_colws, *w_colws_w;
   // accounting
@@ -426,7 +427,7 @@ static int st_attention(po_stage* st, bool backward, const void* qkv, void* o, f
     st->spans[span].flops = (backward ? 4.0 : 2.0) * c.seq * (double)c.seq * c.hidden;
   }
   if (backward)
-    PO_K(attention_backward(c.dtype, qkv, o, lse, d_o, dqkv, st->w_delta, c.seq, c.hidden, c.n_heads,
+    PO_K(attention_backward(c.dtype, qkv, o, lse, d_o, dqkv, st->w_delta, st->w_dkv_part, c.seq, c.hidden, c.n_heads,
                             kv_heads_of(c), false,
                             st->compute));
   else
@@ -1200,7 +1201,8 @@ int stage_create(const po_config* cfg, void* compute_stream, po_stage** out) {
   size_t lnws = align_up(layernorm_backward_workspace((int)s, (int)h), 256);
   size_t maxn = std::max((size_t)3 * h, f);
   size_t colws = align_up(colsum_workspace((int)s, (int)maxn), 256);
-  size_t total = 9 * sh + 2 * sf + s3h + delta + 2 * lnws + 2 * colws;
+  bool grouped = kv_heads_of(*cfg) < cfg->n_heads;
+  size_t total = 9 * sh + 2 * sf + s3h + delta + 2 * lnws + 2 * colws + (grouped ? 2 * sh : 0);
   // one unit's gradient buffer for the split backward: per layer g, du [s,f]; dn2, dx1, dn1, incoming dy [s,h];
   // dqkv [s,3h]; two LayerNorm workspaces; plus one [s,h] tensor per unit (gradient at the embedding output)
   st->gl_sh = sh;
@@ -1241,6 +1243,7 @@ int stage_create(const po_config* cfg, void* compute_stream, po_stage** out) {
   st->w_lnws1 = (float*)take(lnws);
   st->w_colws = (float*)take(colws);
   st->w_colws_w = (float*)take(colws);
+  if (grouped) st->w_dkv_part = take(2 * sh);
   reset_run_stats(st);
   *out = st;
   return PO_OK;
@@ -1481,11 +1484,11 @@ int po_op_attention_forward(int32_t dtype, const void* qkv, void* o, float* lse,
                               force_generic != 0, (hipStream_t)stream));
 }
 int po_op_attention_backward(int32_t dtype, const void* qkv, const void* o, const float* lse, const void* d_o,
-                             void* dqkv, float* delta, int32_t s, int32_t h, int32_t n_heads, int32_t n_kv_heads,
-                             int32_t force_generic, void* stream) {
+                             void* dqkv, float* delta, void* partials, int32_t s, int32_t h, int32_t n_heads,
+                             int32_t n_kv_heads, int32_t force_generic, void* stream) {
   begin_launch();
   if (!dtype_ok(dtype)) return PO_E_INVAL;
-  return ok(attention_backward(dtype, qkv, o, lse, d_o, dqkv, delta, s, h, n_heads,
+  return ok(attention_backward(dtype, qkv, o, lse, d_o, dqkv, delta, partials, s, h, n_heads,
                                n_kv_heads > 0 ? n_kv_heads : n_heads, force_generic != 0, (hipStream_t)stream));
 }
 uint64_t po_op_colsum_workspace(int32_t rows, int32_t n) { return rows > 0 && n > 0 ? colsum_workspace(rows, n) : 0; }

@@ -165,7 +165,7 @@ def test_attention_mfma(gpu_device, s, h, a):
     _attention_case(gpu_device, "bf16", s, h, a, 0)
 
 
-def _attention_case(gpu_device, dtype, s, h, a, force_generic, akv=0):
+def _attention_case(gpu_device, dtype, s, h, a, force_generic, akv=0, with_partials=False):
     code, tdt, tol = DT[dtype]
     rng = np.random.default_rng(s * 31 + h + a + 7 * akv)
     dh = h // a
@@ -190,7 +190,9 @@ def _attention_case(gpu_device, dtype, s, h, a, force_generic, akv=0):
         assert np.abs(_np(lse[t]) - ref_lse).max() < 1e-3 * max(1.0, np.abs(ref_lse).max())
     dqkv = torch.empty(s, h + 2 * hkv, dtype=tdt, device=gpu_device)
     delta = torch.empty(a, s, dtype=torch.float32, device=gpu_device)
-    po.po_op_attention_backward(code, qd, o, lse, dod, dqkv, delta, s, h, a, force_generic, n_kv_heads=akv)
+    partials = torch.empty(s, 2 * h, dtype=tdt, device=gpu_device) if with_partials else None
+    po.po_op_attention_backward(code, qd, o, lse, dod, dqkv, delta, s, h, a, force_generic, n_kv_heads=akv,
+                                partials=partials)
     rdq, rdk, rdv = so.attention_backward(d_o.astype(np.float64), q, k, v, probs, a)
     got = _np(dqkv)
     btol = tol if dtype == "f32" else 3e-2  # o is rounded to bf16 before delta = rowsum(dO * O) is formed
@@ -204,8 +206,9 @@ def _attention_case(gpu_device, dtype, s, h, a, force_generic, akv=0):
     ("f32", 37, 128, 4, 2, 1), ("f32", 70, 192, 6, 1, 1), ("bf16", 130, 256, 4, 2, 1),
     ("bf16", 128, 256, 4, 2, 0), ("bf16", 384, 512, 4, 1, 0), ("bf16", 256, 512, 8, 2, 0),
     ("bf16", 640, 768, 6, 3, 0), ("bf16", 512, 1024, 16, 4, 0), ("bf16", 256, 256, 4, 4, 0)])
-def test_grouped_query_attention(gpu_device, dtype, s, h, a, akv, force_generic):
-    _attention_case(gpu_device, dtype, s, h, a, force_generic, akv)
+@pytest.mark.parametrize("with_partials", [False, True], ids=["direct", "per-head-then-sum"])
+def test_grouped_query_attention(gpu_device, dtype, s, h, a, akv, force_generic, with_partials):
+    _attention_case(gpu_device, dtype, s, h, a, force_generic, akv, with_partials)
 
 
 def test_grouped_query_attention_rejects_bad_groups(gpu_device):
