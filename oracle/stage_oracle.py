@@ -18,8 +18,9 @@ Readings of points the paper leaves open (each is also listed in the design
 notes): pre-LN decoder layer; LayerNorm with gain and shift, biased variance,
 eps inside the square root; linear layers with bias; GeLU in its tanh form;
 causal softmax attention scaled by 1/sqrt(head_dim), multi-head, or grouped-query
-when the QKV projection is narrower than 3h (Table 2's query groups); no
-dropout; no final LayerNorm; learned token + position embedding when the stage
+when the QKV projection is narrower than 3h (Table 2's query groups); dropout
+off by default, on request the two hidden dropouts (after the attention and
+the MLP output projections) with regenerated masks; no final LayerNorm; learned token + position embedding when the stage
 is the first one.
 
 Precision: ``dtype`` is numpy float64 by default (reference), float32 on
@@ -120,40 +121,97 @@ def attention_backward(do, q, k, v, probs, n_heads):
 
 
 # --------------------------------------------------------------------------- #
+# Dropout whose mask is a function of (seed, layer, site, microbatch, position),
+# so that the backward regenerates it instead of storing it (Appendix C: dropout
+# is among the recomputed operations).  The generator is the published
+# counter-based Philox4x32-10 (Salmon et al., SC'11); the HIP path implements the
+# same generator on its own.
+# --------------------------------------------------------------------------- #
+_PHILOX_M0, _PHILOX_M1 = np.uint64(0xD2511F53), np.uint64(0xCD9E8D57)
+_PHILOX_W0, _PHILOX_W1 = 0x9E3779B9, 0xBB67AE85
+
+
+def philox4x32_10(counter, key):
+    """counter: four uint32 arrays (broadcastable), key: two uint32 scalars.  Ten
+    rounds of: (hi, lo) products of words 0 and 2 with the two multipliers, mixed
+    with words 1 and 3 and the round key; the key advances by the Weyl constants."""
+    c = [np.asarray(x, dtype=np.uint32) for x in counter]
+    k0, k1 = int(key[0]) & 0xFFFFFFFF, int(key[1]) & 0xFFFFFFFF
+    for _ in range(10):
+        p0 = c[0].astype(np.uint64) * _PHILOX_M0
+        p1 = c[2].astype(np.uint64) * _PHILOX_M1
+        hi0, lo0 = (p0 >> np.uint64(32)).astype(np.uint32), p0.astype(np.uint32)
+        hi1, lo1 = (p1 >> np.uint64(32)).astype(np.uint32), p1.astype(np.uint32)
+        c = [hi1 ^ c[1] ^ np.uint32(k0), lo1, hi0 ^ c[3] ^ np.uint32(k1), lo0]
+        k0, k1 = (k0 + _PHILOX_W0) & 0xFFFFFFFF, (k1 + _PHILOX_W1) & 0xFFFFFFFF
+    return c
+
+
+def dropout_threshold(p):
+    """An element is kept iff its 32-bit random word is >= this value."""
+    return min(int(round(p * 2.0 ** 32)), 2 ** 32 - 1)
+
+
+def dropout_keep_mask(seed, layer, site, mb, rows, cols, p):
+    """Boolean [rows, cols] keep mask of one dropout site (0: after the attention
+    output projection, 1: after the MLP output projection) of global layer
+    ``layer`` for microbatch ``mb``.  Element (r, c) uses word c % 4 of
+    Philox4x32-10 with counter (c // 4, r, 2 * layer + site, mb) and key
+    (seed mod 2^32, seed div 2^32)."""
+    r = np.arange(rows, dtype=np.uint32)[:, None]
+    c4 = np.arange((cols + 3) // 4, dtype=np.uint32)[None, :]
+    words = philox4x32_10((c4, r, np.uint32(2 * layer + site), np.uint32(mb)), (seed & 0xFFFFFFFF, seed >> 32))
+    w = np.stack([np.broadcast_to(x, (rows, c4.shape[1])) for x in words], axis=-1).reshape(rows, -1)[:, :cols]
+    return w >= np.uint32(dropout_threshold(p))
+
+
+# --------------------------------------------------------------------------- #
 # One decoder layer
 # --------------------------------------------------------------------------- #
-def layer_forward(x, p, n_heads, eps):
+def layer_forward(x, p, n_heads, eps, drop=None):
+    """drop: None, or (keep mask of site 0, keep mask of site 1, 1 / (1 - p)): the two
+    projections' outputs (bias included) are masked and rescaled before the residual
+    is added."""
     h = x.shape[1]
     n1, ln1 = layernorm_forward(x, p["ln1_g"], p["ln1_b"], eps)
     qkv = n1 @ p["w_qkv"] + p["b_qkv"]
     h_kv = (qkv.shape[1] - h) // 2  # w_qkv is [h, h + 2 h_kv]: query block, key block, value block
     q, k, v = qkv[:, :h], qkv[:, h:h + h_kv], qkv[:, h + h_kv:]
     o, probs = attention_forward(q, k, v, n_heads)
-    x1 = x + o @ p["w_o"] + p["b_o"]
+    z1 = o @ p["w_o"] + p["b_o"]
+    if drop is not None:
+        z1 = z1 * drop[0] * x.dtype.type(drop[2])
+    x1 = x + z1
     n2, ln2 = layernorm_forward(x1, p["ln2_g"], p["ln2_b"], eps)
     u = n2 @ p["w_fc1"] + p["b_fc1"]
     g = gelu(u)
-    y = x1 + g @ p["w_fc2"] + p["b_fc2"]
-    cache = dict(n1=n1, ln1=ln1, q=q, k=k, v=v, probs=probs, o=o, n2=n2, ln2=ln2, u=u, g=g)
+    z2 = g @ p["w_fc2"] + p["b_fc2"]
+    if drop is not None:
+        z2 = z2 * drop[1] * x.dtype.type(drop[2])
+    y = x1 + z2
+    cache = dict(n1=n1, ln1=ln1, q=q, k=k, v=v, probs=probs, o=o, n2=n2, ln2=ln2, u=u, g=g, drop=drop)
     return y, cache
 
 
 def layer_backward(dy, p, c, n_heads):
     grads = {}
-    # y = x1 + g W2 + b2
-    grads["w_fc2"] = c["g"].T @ dy
-    grads["b_fc2"] = dy.sum(axis=0)
-    dg = dy @ p["w_fc2"].T
+    drop = c.get("drop")
+    # y = x1 + D2(g W2 + b2)
+    dz2 = dy if drop is None else dy * drop[1] * dy.dtype.type(drop[2])
+    grads["w_fc2"] = c["g"].T @ dz2
+    grads["b_fc2"] = dz2.sum(axis=0)
+    dg = dz2 @ p["w_fc2"].T
     du = dg * gelu_derivative(c["u"])
     grads["w_fc1"] = c["n2"].T @ du
     grads["b_fc1"] = du.sum(axis=0)
     dn2 = du @ p["w_fc1"].T
     dx1_ln, grads["ln2_g"], grads["ln2_b"] = layernorm_backward(dn2, c["ln2"], p["ln2_g"])
     dx1 = dy + dx1_ln
-    # x1 = x + O Wo + bo
-    grads["w_o"] = c["o"].T @ dx1
-    grads["b_o"] = dx1.sum(axis=0)
-    do = dx1 @ p["w_o"].T
+    # x1 = x + D1(O Wo + bo)
+    dz1 = dx1 if drop is None else dx1 * drop[0] * dx1.dtype.type(drop[2])
+    grads["w_o"] = c["o"].T @ dz1
+    grads["b_o"] = dz1.sum(axis=0)
+    do = dz1 @ p["w_o"].T
     dq, dk, dv = attention_backward(do, c["q"], c["k"], c["v"], c["probs"], n_heads)
     dqkv = np.concatenate([dq, dk, dv], axis=1)
     grads["w_qkv"] = c["n1"].T @ dqkv
@@ -170,7 +228,7 @@ def _cast_layer(p, dtype):
     return {k: np.asarray(a, dtype=dtype) for k, a in p.items()}
 
 
-def unit_forward(params, layer_ids, x_in, n_heads, eps=1e-5, dtype=np.float64, embed=False):
+def unit_forward(params, layer_ids, x_in, n_heads, eps=1e-5, dtype=np.float64, embed=False, dropout=None):
     """x_in: [s, h] activations, or int tokens [s] when ``embed``.  Returns
     (y, tape) where the tape is what unit_backward needs."""
     tape = {"layers": [], "embed": None}
@@ -184,7 +242,13 @@ def unit_forward(params, layer_ids, x_in, n_heads, eps=1e-5, dtype=np.float64, e
         x = np.asarray(x_in, dtype=dtype)
     for l in layer_ids:
         p = _cast_layer(params["layers"][l], dtype)
-        x, cache = layer_forward(x, p, n_heads, eps)
+        drop = None
+        if dropout is not None:  # (p, seed, mb)
+            prob, seed, mb = dropout
+            rows, cols = x.shape
+            drop = (dropout_keep_mask(seed, l, 0, mb, rows, cols, prob), dropout_keep_mask(seed, l, 1, mb, rows, cols, prob),
+                    1.0 / (1.0 - prob))
+        x, cache = layer_forward(x, p, n_heads, eps, drop)
         tape["layers"].append((l, p, cache))
     return x, tape
 
@@ -208,7 +272,8 @@ def unit_backward(params, tape, dy, n_heads, dtype=np.float64):
     return d, grads
 
 
-def run_stage(params, n_layers, n_chunks, n_heads, x_in, dy, vocab=0, eps=1e-5, dtype=np.float64):
+def run_stage(params, n_layers, n_chunks, n_heads, x_in, dy, vocab=0, eps=1e-5, dtype=np.float64, dropout_p=0.0,
+              seed=0):
     """Whole job of one rank: every (chunk, mb) unit forward and backward,
     parameter gradients summed over microbatches in microbatch order.
 
@@ -217,7 +282,8 @@ def run_stage(params, n_layers, n_chunks, n_heads, x_in, dy, vocab=0, eps=1e-5, 
     (in a real pipeline the other ranks sit between two chunks of one rank).
 
     Returns y {(mb, chunk): [s, h]}, dx {(mb, chunk): [s, h] or None}, grads
-    {'layers': [dict per layer], 'wte', 'wpe'}.
+    {'layers': [dict per layer], 'wte', 'wpe'}.  dropout_p > 0 applies the two hidden
+    dropouts of every layer with masks derived from (seed, layer, site, mb).
     """
     lu = n_layers // n_chunks
     y, dx = {}, {}
@@ -225,7 +291,8 @@ def run_stage(params, n_layers, n_chunks, n_heads, x_in, dy, vocab=0, eps=1e-5, 
     for (mb, chunk) in sorted(x_in.keys()):
         ids = list(range(chunk * lu, (chunk + 1) * lu))
         embed = vocab > 0 and chunk == 0
-        out, tape = unit_forward(params, ids, x_in[(mb, chunk)], n_heads, eps, dtype, embed)
+        out, tape = unit_forward(params, ids, x_in[(mb, chunk)], n_heads, eps, dtype, embed,
+                                 (dropout_p, seed, mb) if dropout_p > 0.0 else None)
         y[(mb, chunk)] = out
         d, g = unit_backward(params, tape, dy[(mb, chunk)], n_heads, dtype)
         dx[(mb, chunk)] = d

@@ -371,3 +371,96 @@ def test_grouped_query_attention_against_torch_sdpa():
     (to * torch.tensor(do)).sum().backward()
     for got, want in ((dq, tq.grad), (dk, tk.grad), (dv, tv.grad)):
         np.testing.assert_allclose(got, want.numpy(), rtol=1e-11, atol=1e-12)
+
+
+# ---- dropout with regenerated masks (Appendix C: dropout is recomputed) ---------------------------------------
+def test_philox4x32_10_known_answers():
+    # the three known-answer vectors distributed with the reference implementation of Philox (Random123):
+    # zero counter and key, all-ones, and the digits of pi
+    cases = [((0, 0, 0, 0), (0, 0), (0x6627e8d5, 0xe169c58d, 0xbc57ac4c, 0x9b00dbd8)),
+             ((0xffffffff,) * 4, (0xffffffff,) * 2, (0x408f276d, 0x41c83b0e, 0xa20bc7c6, 0x6d5451fd)),
+             ((0x243f6a88, 0x85a308d3, 0x13198a2e, 0x03707344), (0xa4093822, 0x299f31d0),
+              (0xd16cfe09, 0x94fdcceb, 0x5001e420, 0x24126ea1))]
+    for ctr, key, want in cases:
+        assert tuple(int(x) for x in so.philox4x32_10(ctr, key)) == want
+
+
+def test_dropout_mask_statistics_and_addressing():
+    p = 0.1
+    m = so.dropout_keep_mask(1234, 3, 1, 5, 512, 384, p)
+    assert m.shape == (512, 384) and abs(m.mean() - 0.9) < 5e-3
+    # rows, columns, layers, sites, microbatches and seeds all give different, uncorrelated masks
+    others = [so.dropout_keep_mask(1234, 3, 0, 5, 512, 384, p), so.dropout_keep_mask(1234, 4, 1, 5, 512, 384, p),
+              so.dropout_keep_mask(1234, 3, 1, 6, 512, 384, p), so.dropout_keep_mask(1235, 3, 1, 5, 512, 384, p),
+              so.dropout_keep_mask(2 ** 40 + 1234, 3, 1, 5, 512, 384, p)]
+    for o in others:
+        both_dropped = (~m & ~o).mean()
+        assert abs(both_dropped - p * p) < 3e-3
+    assert abs((~m[:-1] & ~m[1:]).mean() - p * p) < 3e-3 and abs((~m[:, :-1] & ~m[:, 1:]).mean() - p * p) < 3e-3
+    # element (r, c) is word c % 4 of the block at counter (c // 4, r, 2 layer + site, mb)
+    w = so.philox4x32_10((np.uint32(70 // 4), np.uint32(9), np.uint32(7), np.uint32(5)), (1234, 0))
+    assert m[9, 70] == (int(w[70 % 4]) >= so.dropout_threshold(p))
+    # a sub-block is the same function of the absolute position; p = 0 keeps everything
+    assert np.array_equal(so.dropout_keep_mask(1234, 3, 1, 5, 100, 50, p), m[:100, :50])
+    assert so.dropout_keep_mask(1, 0, 0, 0, 8, 8, 0.0).all()
+
+
+def test_dropout_stage_finite_differences_and_expectation():
+    shape = TINY
+    params, x, dy = _tiny_problem(shape, m=2)
+    kw = dict(dropout_p=0.3, seed=99)
+    y, dx, grads = so.run_stage(params, shape.n_layers, 1, shape.n_heads, x, dy, **kw)
+    y0, _, _ = so.run_stage(params, shape.n_layers, 1, shape.n_heads, x, dy)
+    assert any(np.abs(y[u] - y0[u]).max() > 1e-3 for u in y)  # the masks do something
+    loss = lambda: sum(float((v * dy[u]).sum()) for u, v in
+                       so.run_stage(params, shape.n_layers, 1, shape.n_heads, x, dy, **kw)[0].items())
+    eps = 1e-6
+    rng = np.random.default_rng(3)
+    for l, p in enumerate(params["layers"]):
+        for name in ("w_o", "b_o", "w_fc2", "b_fc2", "w_qkv", "w_fc1", "ln2_g"):
+            flat = p[name].reshape(-1)
+            for idx in rng.choice(flat.size, size=5, replace=False):
+                old = flat[idx]
+                flat[idx] = old + eps
+                lp = loss()
+                flat[idx] = old - eps
+                lm = loss()
+                flat[idx] = old
+                an = grads["layers"][l][name].reshape(-1)[idx]
+                assert abs((lp - lm) / (2 * eps) - an) <= 1e-6 * max(1.0, abs(an)), (l, name, idx)
+    u = (0, 0)
+    flat = x[u].reshape(-1)
+    for idx in rng.choice(flat.size, size=8, replace=False):
+        old = flat[idx]
+        flat[idx] = old + eps
+        lp = loss()
+        flat[idx] = old - eps
+        lm = loss()
+        flat[idx] = old
+        assert abs((lp - lm) / (2 * eps) - dx[u].reshape(-1)[idx]) <= 1e-6 * max(1.0, abs(dx[u].reshape(-1)[idx]))
+
+
+def test_dropout_layer_against_torch_with_the_same_masks():
+    import torch.nn.functional as F
+
+    shape = syn.StageShape(1, 1, 32, 4, 64, 24, dtype="f32")
+    params, x, dy = _tiny_problem(shape, m=1, seed=4, scale=5.0)
+    prob, seed = 0.25, 7
+    y, dx, grads = so.run_stage(params, 1, 1, 4, x, dy, dropout_p=prob, seed=seed)
+    m1 = torch.tensor(so.dropout_keep_mask(seed, 0, 0, 0, 24, 32, prob), dtype=torch.float64) / (1 - prob)
+    m2 = torch.tensor(so.dropout_keep_mask(seed, 0, 1, 0, 24, 32, prob), dtype=torch.float64) / (1 - prob)
+    p = {k: torch.tensor(a, dtype=torch.float64, requires_grad=True) for k, a in params["layers"][0].items()}
+    xt = torch.tensor(x[(0, 0)], dtype=torch.float64, requires_grad=True)
+    h, a, dh, s = 32, 4, 8, 24
+    n1 = F.layer_norm(xt, (h,), p["ln1_g"], p["ln1_b"], 1e-5)
+    q, k, v = F.linear(n1, p["w_qkv"].t(), p["b_qkv"]).split(h, dim=1)
+    hd = lambda t: t.reshape(s, a, dh).transpose(0, 1).unsqueeze(0)
+    o = F.scaled_dot_product_attention(hd(q), hd(k), hd(v), is_causal=True).squeeze(0).transpose(0, 1).reshape(s, h)
+    x1 = xt + F.linear(o, p["w_o"].t(), p["b_o"]) * m1
+    n2 = F.layer_norm(x1, (h,), p["ln2_g"], p["ln2_b"], 1e-5)
+    out = x1 + F.linear(F.gelu(F.linear(n2, p["w_fc1"].t(), p["b_fc1"]), approximate="tanh"), p["w_fc2"].t(), p["b_fc2"]) * m2
+    np.testing.assert_allclose(out.detach().numpy(), y[(0, 0)], rtol=1e-10, atol=1e-10)
+    (out * torch.tensor(dy[(0, 0)])).sum().backward()
+    np.testing.assert_allclose(xt.grad.numpy(), dx[(0, 0)], rtol=1e-9, atol=1e-10)
+    for kname, t in p.items():
+        np.testing.assert_allclose(t.grad.numpy(), grads["layers"][0][kname], rtol=1e-9, atol=1e-10, err_msg=kname)
