@@ -87,8 +87,13 @@ typedef struct po_config {
   int32_t min_gap_passes;  /* run_schedule does not offload a unit with fewer than this many forward / backward
                               passes between its forward and its backward (Section 4.4); 0 = offload all */
   float ln_eps;            /* LayerNorm epsilon */
+  float dropout_p;         /* 0 = none; else the outputs of the attention and MLP output projections are dropped
+                              with this probability before the residual add, masks regenerated in backward from
+                              (dropout_seed, layer, site, microbatch, position) instead of being stored (App. C) */
   uint64_t host_pool_cap_bytes;   /* 0 = unlimited; else PO_E_HOST_OOM beyond it */
   uint64_t device_pool_cap_bytes; /* 0 = unlimited; else PO_E_DEVICE_OOM beyond it */
+  uint64_t dropout_seed;          /* key of the counter-based generator; change it between iterations with
+                                     po_set_dropout_seed */
 } po_config;
 
 /* One tensor of the flat parameter (and gradient) buffer. */
@@ -180,6 +185,9 @@ int po_stage_forward(po_stage* st, int32_t mb, int32_t chunk, const void* x_in, 
  * LayerNorm and GeLU outputs are recomputed (Appendix C).  Frees the unit. */
 int po_stage_backward(po_stage* st, int32_t mb, int32_t chunk, const void* dy, void* dx);
 
+/* New dropout key for the following forward passes; PO_E_STATE while a unit is in flight. */
+int po_set_dropout_seed(po_stage* st, uint64_t seed);
+
 /* Split backward (Section 3.2, zero-bubble strategy).  po_stage_backward_input is the B pass: it computes the
  * activation gradients only (dx as in po_stage_backward) and keeps, in a library-owned buffer, what the W pass
  * needs; the unit keeps its activations.  po_stage_backward_weight is the W pass: it adds the unit's parameter
@@ -246,6 +254,13 @@ int po_op_attention_forward(int32_t dtype, const void* qkv, void* o, float* lse,
 int po_op_attention_backward(int32_t dtype, const void* qkv, const void* o, const float* lse, const void* d_o,
                              void* dqkv, float* delta, void* partials, int32_t s, int32_t h, int32_t n_heads,
                              int32_t n_kv_heads, int32_t force_generic, void* stream);
+
+/* out[r, c] = x[r, c] * keep(r, c) / (1 - p): one dropout site (site 0: after the attention output projection,
+ * 1: after the MLP output projection) of global layer `layer` for microbatch `mb`.  keep(r, c) is true iff word
+ * c % 4 of Philox4x32-10 with counter (c / 4, r, 2 * layer + site, mb) and key (seed mod 2^32, seed div 2^32) is
+ * >= round(p * 2^32).  The same map is the site's backward (Appendix C: dropout is recomputed, not stored). */
+int po_op_dropout(int32_t dtype, const void* x, void* out, int32_t rows, int32_t cols, float p, uint64_t seed,
+                  int32_t layer, int32_t site, int32_t mb, void* stream);
 
 /* acc[N] += column sums of x [rows, N] (bias gradients, rows a12-a17), deterministic: row chunks
  * are reduced to partials in `workspace` (fp32, po_op_colsum_workspace bytes), then added in chunk order. */

@@ -149,7 +149,7 @@ def philox4x32_10(counter, key):
 
 def dropout_threshold(p):
     """An element is kept iff its 32-bit random word is >= this value."""
-    return min(int(round(p * 2.0 ** 32)), 2 ** 32 - 1)
+    return min(int(math.floor(p * 2.0 ** 32 + 0.5)), 2 ** 32 - 1)
 
 
 def dropout_keep_mask(seed, layer, site, mb, rows, cols, p):

@@ -34,7 +34,8 @@ class po_config(C.Structure):
         "n_layers", "n_chunks", "hidden", "n_heads", "ffn", "seq", "vocab", "dtype", "pipeline_degree", "rank",
         "prefetch_passes", "copy_streams", "select_policy", "staged_copies", "debug_poison", "profile_kernels",
         "group", "weight_stream", "n_kv_heads", "min_gap_passes")] + [
-        ("ln_eps", C.c_float), ("host_pool_cap_bytes", C.c_uint64), ("device_pool_cap_bytes", C.c_uint64)]
+        ("ln_eps", C.c_float), ("dropout_p", C.c_float), ("host_pool_cap_bytes", C.c_uint64),
+        ("device_pool_cap_bytes", C.c_uint64), ("dropout_seed", C.c_uint64)]
 
 
 class po_param_desc(C.Structure):
@@ -92,6 +93,9 @@ EXPORTS = {
                    [C.c_int32, C.c_void_p]),
     "po_op_attention_forward": (C.c_int, [C.c_int32] + [C.c_void_p] * 3 + [C.c_int32] * 5 + [C.c_void_p]),
     "po_op_attention_backward": (C.c_int, [C.c_int32] + [C.c_void_p] * 7 + [C.c_int32] * 5 + [C.c_void_p]),
+    "po_op_dropout": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_uint64,
+                                C.c_int32, C.c_int32, C.c_int32, C.c_void_p]),
+    "po_set_dropout_seed": (C.c_int, [C.c_void_p, C.c_uint64]),
     "po_op_colsum_workspace": (C.c_uint64, [C.c_int32, C.c_int32]),
     "po_op_colsum_accumulate": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                           C.c_void_p]),
@@ -274,6 +278,14 @@ def po_op_attention_backward(dtype, qkv, o, lse, d_o, dqkv, delta, s, h, n_heads
                              n_kv_heads=0, partials=None):
     _check(lib.po_op_attention_backward(dtype, _ptr(qkv), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(dqkv), _ptr(delta),
                                         _ptr(partials), s, h, n_heads, n_kv_heads, force_generic, _stream(stream)))
+
+
+def po_op_dropout(dtype, x, out, rows, cols, p, seed, layer, site, mb, stream=None):
+    _check(lib.po_op_dropout(dtype, _ptr(x), _ptr(out), rows, cols, p, seed, layer, site, mb, _stream(stream)))
+
+
+def po_set_dropout_seed(stage, seed):
+    _check(lib.po_set_dropout_seed(stage, seed))
 
 
 def po_op_colsum_workspace(rows, n) -> int:

@@ -526,6 +526,55 @@ bool embedding_backward(int dtype, const int32_t* tok, const void* dx, float* dw
 }
 
 // --------------------------------------------------------------------------
+// Dropout with a regenerated mask: out[r, c] = x[r, c] * keep(r, c) * scale.  The backward of a dropout site is
+// the same map applied to the incoming gradient.  One thread per four columns (one generator block).
+// --------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void dropout_apply_kernel(const T* __restrict__ x, T* __restrict__ out, int rows,
+                                                            int cols, DropoutSite d) {
+  int per_row = (cols + 3) >> 2;
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (size_t)rows * per_row) return;
+  int r = (int)(idx / per_row), c4 = (int)(idx % per_row);
+  PhiloxWords w = dropout_words(d, r, c4);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    int c = 4 * c4 + i;
+    if (c < cols) {
+      size_t at = (size_t)r * cols + c;
+      out[at] = from_f32<T>(w.w[i] >= d.threshold ? to_f32(x[at]) * d.scale : 0.f);
+    }
+  }
+}
+
+DropoutSite make_dropout_site(float p, uint64_t seed, int layer, int site, int unit) {
+  DropoutSite d;
+  double t = (double)p * 4294967296.0 + 0.5;
+  d.threshold = t >= 4294967295.0 ? 4294967295u : (uint32_t)t;
+  d.k0 = (uint32_t)seed;
+  d.k1 = (uint32_t)(seed >> 32);
+  d.stream = (uint32_t)(2 * layer + site);
+  d.unit = (uint32_t)unit;
+  d.scale = (float)(1.0 / (1.0 - (double)p));
+  return d;
+}
+
+bool dropout_apply(int dtype, const void* x, void* out, int rows, int cols, const DropoutSite& d,
+                   hipStream_t stream) {
+  if (rows <= 0 || cols <= 0 || !x || !out || d.scale == 0.f) {
+    set_error("dropout_apply: rows=%d cols=%d x=%p out=%p", rows, cols, x, out);
+    return false;
+  }
+  size_t n = (size_t)rows * ((cols + 3) / 4);
+  unsigned grid = (unsigned)((n + 255) / 256);
+  if (dtype == kF32)
+    dropout_apply_kernel<float><<<grid, 256, 0, stream>>>((const float*)x, (float*)out, rows, cols, d);
+  else
+    dropout_apply_kernel<bf16><<<grid, 256, 0, stream>>>((const bf16*)x, (bf16*)out, rows, cols, d);
+  return launch_ok("dropout_apply_kernel");
+}
+
+// --------------------------------------------------------------------------
 // Fill / copy
 // --------------------------------------------------------------------------
 __global__ void fill_u32_kernel(uint32_t* p, uint32_t pattern, size_t n) {

@@ -48,6 +48,11 @@ bool gemm_mfma_bf16(int trans_a, int trans_b, int M, int N, int K, const void* A
 bool gemm(int dtype, int trans_a, int trans_b, int M, int N, int K, const void* A, int lda, const void* B, int ldb,
           const Epilogue& ep, bool force_generic, hipStream_t stream);
 
+// ---- dropout with regenerated masks (elementwise.hip) --------------------------
+// threshold = round(p 2^32) (an element is kept iff its random word is >= it), scale = 1 / (1 - p), key = seed.
+DropoutSite make_dropout_site(float p, uint64_t seed, int layer, int site, int unit);
+bool dropout_apply(int dtype, const void* x, void* out, int rows, int cols, const DropoutSite& d, hipStream_t stream);
+
 // ---- attention (attention_generic.hip, attention_mfma.hip) -------------------
 // qkv is [s, h + 2 hkv]: query block [h], key block [hkv], value block [hkv], hkv = n_kv_heads * (h / n_heads);
 // query head t reads key/value head t / (n_heads / n_kv_heads).  n_kv_heads = n_heads is plain multi-head.

@@ -64,6 +64,46 @@ __device__ __forceinline__ float gelu_grad_f(float u) {
   return 0.5f * (1.0f + t) + 0.5f * u * (1.0f - t * t) * dz;
 }
 
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3", SC'11): a counter-
+// based generator, so a dropout mask is a pure function of its position and can be regenerated in the backward
+// pass instead of being stored.  Each round multiplies words 0 and 2 by fixed odd constants, swaps the high and
+// low halves around while mixing in words 1 and 3 and the round key, and advances the key by Weyl constants.
+struct PhiloxWords {
+  uint32_t w[4];
+};
+__device__ __forceinline__ PhiloxWords philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                                     uint32_t k1) {
+#pragma unroll
+  for (int round = 0; round < 10; ++round) {
+    uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    c0 = hi1 ^ c1 ^ k0;
+    c1 = lo1;
+    c2 = hi0 ^ c3 ^ k1;
+    c3 = lo0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  PhiloxWords r;
+  r.w[0] = c0;
+  r.w[1] = c1;
+  r.w[2] = c2;
+  r.w[3] = c3;
+  return r;
+}
+
+// One dropout site: element (row, col) of the [s, h] tensor is kept iff word col % 4 of the block with counter
+// (col / 4, row, stream, unit) under key (k0, k1) is >= threshold; kept values are multiplied by scale = 1 / (1 - p).
+// stream = 2 * layer + site (site 0: after the attention output projection, 1: after the MLP output projection),
+// unit = microbatch index.  scale == 0 means "no dropout here".
+struct DropoutSite {
+  uint32_t threshold, k0, k1, stream, unit;
+  float scale;
+};
+__device__ __forceinline__ PhiloxWords dropout_words(const DropoutSite& d, int row, int col4) {
+  return philox4x32_10((uint32_t)col4, (uint32_t)row, d.stream, d.unit, d.k0, d.k1);
+}
+
 // What a GEMM does with its fp32 accumulators (all pointers may be null).
 struct Epilogue {
   const void* bias;      // [N] of T
@@ -73,6 +113,7 @@ struct Epilogue {
   const void* gelu_u;    // [M, N] of T: out = acc * gelu'(gelu_u)
   float* acc_f32;        // [M, N] fp32: += acc
   int ldc;               // leading dimension of all [M, N] operands above
+  DropoutSite drop;      // store kinds only: out = residual + dropout(acc + bias); drop.scale == 0: none
 };
 
 // Applies the epilogue to one accumulator value at (m, n).
@@ -84,6 +125,7 @@ __device__ __forceinline__ void epilogue_store(const Epilogue& e, int m, int n, 
     return;
   }
   if (e.bias) acc += to_f32(static_cast<const T*>(e.bias)[n]);
+  if (e.drop.scale != 0.f) acc = dropout_words(e.drop, m, n >> 2).w[n & 3] >= e.drop.threshold ? acc * e.drop.scale : 0.f;
   if (e.residual) acc += to_f32(static_cast<const T*>(e.residual)[idx]);
   if (e.gelu_u) {
     float u = to_f32(static_cast<const T*>(e.gelu_u)[idx]);

@@ -81,7 +81,7 @@ int validate_config(const po_config* c) {
       c->rank < 0 || c->rank >= c->pipeline_degree || c->prefetch_passes < 0 ||
       (c->copy_streams != 1 && c->copy_streams != 2) || c->hidden / c->n_heads > 256 ||
       (c->hidden / c->n_heads) % 8 != 0 || !(c->ln_eps > 0.f) || c->group < 0 || c->group > c->pipeline_degree ||
-      (c->group > 0 && 2 * c->group < c->pipeline_degree) || (c->weight_stream != 0 && c->weight_stream != 1) || c->min_gap_passes < 0 || c->n_kv_heads < 0 ||
+      (c->group > 0 && 2 * c->group < c->pipeline_degree) || (c->weight_stream != 0 && c->weight_stream != 1) || c->min_gap_passes < 0 || c->n_kv_heads < 0 || !(c->dropout_p >= 0.f && c->dropout_p < 1.f) ||
       (c->n_kv_heads > 0 && c->n_heads % c->n_kv_heads != 0)) {
     set_error("invalid config: L=%d v=%d h=%d a=%d f=%d s=%d vocab=%d dtype=%d d=%d rank=%d prefetch=%d copy_streams=%d group=%d",
               c->n_layers, c->n_chunks, c->hidden, c->n_heads, c->ffn, c->seq, c->vocab, c->dtype,
@@ -329,6 +329,7 @@ struct po_stage {
   size_t ws_bytes = 0;
   char *w_n, *w_g, *w_du, *w_dqkv, *w_do, *w_dx1, *w_dn, *w_dn1, *w_dy[2], *w_x0;
   char* w_dkv_part = nullptr;  // [s, 2h] per-query-head dK/dV of grouped-query attention (null with multi-head)
+  char* w_dz[2];  // dropout-masked gradients of the fused backward
   char* w_n_w;  // LayerNorm recompute output of the weight-gradient half (own buffer: it may run on its own stream)
   float *w_delta, *w_lnws, *w_lnws1, *w_colws, *w_colws_w;
   // accounting
@@ -441,7 +442,15 @@ static int st_attention(po_stage* st, bool backward, const void* qkv, void* o, f
     if (rc__) return rc__;   \
   } while (0)
 
-static int layer_forward(po_stage* st, int layer, char* slab, void* y_out) {
+// Dropout site `site` of `layer` for microbatch `mb` (scale 0 = off) with the stage's probability and seed.
+static DropoutSite site_of(const po_stage* st, int layer, int site, int mb) {
+  if (st->cfg.dropout_p > 0.f) return make_dropout_site(st->cfg.dropout_p, st->cfg.dropout_seed, layer, site, mb);
+  DropoutSite d;
+  memset(&d, 0, sizeof(d));
+  return d;
+}
+
+static int layer_forward(po_stage* st, int layer, int mb, char* slab, void* y_out) {
   const po_config& c = st->cfg;
   const ParamLayout& pl = st->pl;
   const SlabLayout& sl = st->sl;
@@ -465,6 +474,7 @@ static int layer_forward(po_stage* st, int layer, char* slab, void* y_out) {
   e.bias = st->P(layer, pl.b_o);
   e.residual = x;
   e.out = x1;
+  e.drop = site_of(st, layer, 0, mb);
   PO_RC(st_gemm(st, 0, 0, s, h, h, o, h, st->P(layer, pl.w_o), h, e));
   PO_K(layernorm_forward(dt, x1, st->P(layer, pl.ln2_g), st->P(layer, pl.ln2_b), st->w_n, s, h, c.ln_eps, q));
   e = make_ep(f);
@@ -476,6 +486,7 @@ static int layer_forward(po_stage* st, int layer, char* slab, void* y_out) {
   e.bias = st->P(layer, pl.b_fc2);
   e.residual = x1;
   e.out = y_out;
+  e.drop = site_of(st, layer, 1, mb);
   PO_RC(st_gemm(st, 0, 0, s, h, f, st->w_g, f, st->P(layer, pl.w_fc2), h, e));
   return PO_OK;
 }
@@ -486,13 +497,15 @@ static int layer_forward(po_stage* st, int layer, char* slab, void* y_out) {
 // time); the split backward (B pass, later W pass) points them into a per-unit buffer that lives from B to W.
 struct BwdBufs {
   char *g, *du, *dn2, *dx1, *dqkv, *dn1;
+  char *dz2, *dz1;  // with dropout: the masked, rescaled gradients at the two output projections
   float *lnws2, *lnws1;
 };
 
 // Input-gradient half of one layer (activation gradients only):
 //   du = (dy W2^T) * gelu'(u) with g = gelu(u) recomputed, dn2 = du W1^T, dx1 = dy + LNbwd(dn2; x1),
 //   dO = dx1 Wo^T, (dq, dk, dv) = attention backward, dn1 = dqkv Wqkv^T, dx = dx1 + LNbwd(dn1; x).
-static int layer_backward_input(po_stage* st, int layer, const char* slab, const void* dy, void* dx_out,
+// With dropout the two projections see dz = dropout(gradient) (mask regenerated), the residual branches do not.
+static int layer_backward_input(po_stage* st, int layer, int mb, const char* slab, const void* dy, void* dx_out,
                                 const BwdBufs& b) {
   const po_config& c = st->cfg;
   const ParamLayout& pl = st->pl;
@@ -506,19 +519,30 @@ static int layer_backward_input(po_stage* st, int layer, const char* slab, const
   const char* u = slab + sl.off_u;
   const float* lse = (const float*)(slab + sl.off_lse);
 
+  const bool drop = c.dropout_p > 0.f;
+  const void* dz2 = dy;
+  if (drop) {
+    PO_K(dropout_apply(dt, dy, b.dz2, s, h, site_of(st, layer, 1, mb), q));
+    dz2 = b.dz2;
+  }
   Epilogue e = make_ep(f);
   e.out = b.du;
   e.gelu_u = u;
   e.gelu_out = b.g;
-  PO_RC(st_gemm(st, 0, 1, s, f, h, dy, h, st->P(layer, pl.w_fc2), h, e));
+  PO_RC(st_gemm(st, 0, 1, s, f, h, dz2, h, st->P(layer, pl.w_fc2), h, e));
   e = make_ep(h);
   e.out = b.dn2;
   PO_RC(st_gemm(st, 0, 1, s, h, f, b.du, f, st->P(layer, pl.w_fc1), f, e));
   PO_K(layernorm_backward(dt, b.dn2, x1, st->P(layer, pl.ln2_g), dy, b.dx1, nullptr, nullptr, b.lnws2, s, h,
                           c.ln_eps, kLnInputGrad, q));
+  const void* dz1 = b.dx1;
+  if (drop) {
+    PO_K(dropout_apply(dt, b.dx1, b.dz1, s, h, site_of(st, layer, 0, mb), q));
+    dz1 = b.dz1;
+  }
   e = make_ep(h);
   e.out = st->w_do;
-  PO_RC(st_gemm(st, 0, 1, s, h, h, b.dx1, h, st->P(layer, pl.w_o), h, e));
+  PO_RC(st_gemm(st, 0, 1, s, h, h, dz1, h, st->P(layer, pl.w_o), h, e));
   PO_RC(st_attention(st, true, qkv, const_cast<char*>(o), const_cast<float*>(lse), st->w_do, b.dqkv));
   e = make_ep(h);
   e.out = b.dn1;
@@ -545,10 +569,13 @@ static int layer_backward_weight(po_stage* st, int layer, const char* slab, cons
   const char* o = slab + sl.off_o;
   const char* x1 = slab + sl.off_x1;
 
+  const bool drop = c.dropout_p > 0.f;
+  const void* dz2 = drop ? (const void*)b.dz2 : dy;  // what the input-gradient half fed the MLP output projection
+  const void* dz1 = drop ? (const void*)b.dz1 : (const void*)b.dx1;
   Epilogue e = make_ep(h);
   e.acc_f32 = st->G(layer, pl.w_fc2);
-  PO_RC(st_gemm(st, 1, 0, f, h, s, b.g, f, dy, h, e, q));
-  PO_K(colsum_accumulate(dt, dy, st->G(layer, pl.b_fc2), colws, s, h, q));
+  PO_RC(st_gemm(st, 1, 0, f, h, s, b.g, f, dz2, h, e, q));
+  PO_K(colsum_accumulate(dt, dz2, st->G(layer, pl.b_fc2), colws, s, h, q));
   PO_K(layernorm_forward(dt, x1, st->P(layer, pl.ln2_g), st->P(layer, pl.ln2_b), n_out, s, h, c.ln_eps, q));
   e = make_ep(f);
   e.acc_f32 = st->G(layer, pl.w_fc1);
@@ -558,8 +585,8 @@ static int layer_backward_weight(po_stage* st, int layer, const char* slab, cons
                           st->G(layer, pl.ln2_b), b.lnws2, s, h, c.ln_eps, kLnParamGrad, q));
   e = make_ep(h);
   e.acc_f32 = st->G(layer, pl.w_o);
-  PO_RC(st_gemm(st, 1, 0, h, h, s, o, h, b.dx1, h, e, q));
-  PO_K(colsum_accumulate(dt, b.dx1, st->G(layer, pl.b_o), colws, s, h, q));
+  PO_RC(st_gemm(st, 1, 0, h, h, s, o, h, dz1, h, e, q));
+  PO_K(colsum_accumulate(dt, dz1, st->G(layer, pl.b_o), colws, s, h, q));
   PO_K(layernorm_forward(dt, x, st->P(layer, pl.ln1_g), st->P(layer, pl.ln1_b), n_out, s, h, c.ln_eps, q));
   const int wq = qkv_width_of(c);
   e = make_ep(wq);
@@ -620,7 +647,7 @@ int stage_forward(po_stage* st, int mb, int chunk, const void* x_in, void* y_out
   for (int l = 0; l < st->Lu; ++l) {
     char* slab = st->dev_pool.bufs[u.layers[l].dev].ptr;
     void* out = (l + 1 < st->Lu) ? (void*)(st->dev_pool.bufs[u.layers[l + 1].dev].ptr + st->sl.off_x) : y_out;
-    rc = layer_forward(st, chunk * st->Lu + l, slab, out);
+    rc = layer_forward(st, chunk * st->Lu + l, mb, slab, out);
     if (rc) return rc;
   }
   rc = span_end(st, st->compute, span);
@@ -856,6 +883,8 @@ static BwdBufs workspace_bufs(po_stage* st) {
   b.dx1 = st->w_dx1;
   b.dqkv = st->w_dqkv;
   b.dn1 = st->w_dn1;
+  b.dz2 = st->w_dz[0];
+  b.dz1 = st->w_dz[1];
   b.lnws2 = st->w_lnws;
   b.lnws1 = st->w_lnws1;
   return b;
@@ -872,7 +901,9 @@ static BwdBufs unit_bufs(const po_stage* st, char* buf, int l, char** dy_in) {
   b.dx1 = b.dn2 + st->gl_sh;
   b.dn1 = b.dx1 + st->gl_sh;
   *dy_in = b.dn1 + st->gl_sh;
-  b.dqkv = *dy_in + st->gl_sh;
+  b.dz2 = *dy_in + st->gl_sh;
+  b.dz1 = b.dz2 + st->gl_sh;
+  b.dqkv = b.dz1 + st->gl_sh;
   b.lnws2 = (float*)(b.dqkv + st->gl_s3h);
   b.lnws1 = (float*)((char*)b.lnws2 + st->gl_lnws);
   return b;
@@ -907,7 +938,7 @@ int stage_backward(po_stage* st, int mb, int chunk, const void* dy, void* dx) {
       out = st->w_dy[l & 1];
     else
       out = embed ? (void*)st->w_dy[0] : dx;
-    rc = layer_backward_input(st, chunk * st->Lu + l, slab, grad, out, bufs);
+    rc = layer_backward_input(st, chunk * st->Lu + l, mb, slab, grad, out, bufs);
     if (rc) return rc;
     rc = layer_backward_weight(st, chunk * st->Lu + l, slab, grad, bufs, st->compute, st->w_n_w, st->w_colws_w);
     if (rc) return rc;
@@ -953,7 +984,7 @@ int stage_backward_input(po_stage* st, int mb, int chunk, const void* dy, void* 
     } else {
       out = embed ? (void*)(buf + (size_t)st->Lu * st->gl_layer) : dx;
     }
-    rc = layer_backward_input(st, chunk * st->Lu + l, slab, grad, out, bufs);
+    rc = layer_backward_input(st, chunk * st->Lu + l, mb, slab, grad, out, bufs);
     if (rc) return rc;
     grad = out;
   }
@@ -1202,14 +1233,15 @@ int stage_create(const po_config* cfg, void* compute_stream, po_stage** out) {
   size_t maxn = std::max((size_t)3 * h, f);
   size_t colws = align_up(colsum_workspace((int)s, (int)maxn), 256);
   bool grouped = kv_heads_of(*cfg) < cfg->n_heads;
-  size_t total = 9 * sh + 2 * sf + s3h + delta + 2 * lnws + 2 * colws + (grouped ? 2 * sh : 0);
-  // one unit's gradient buffer for the split backward: per layer g, du [s,f]; dn2, dx1, dn1, incoming dy [s,h];
+  size_t total = 11 * sh + 2 * sf + s3h + delta + 2 * lnws + 2 * colws + (grouped ? 2 * sh : 0);
+  // one unit's gradient buffer for the split backward: per layer g, du [s,f]; dn2, dx1, dn1, incoming dy, and the
+  // two dropout-masked gradients [s,h];
   // dqkv [s,3h]; two LayerNorm workspaces; plus one [s,h] tensor per unit (gradient at the embedding output)
   st->gl_sh = sh;
   st->gl_sf = sf;
   st->gl_s3h = s3h;
   st->gl_lnws = lnws;
-  st->gl_layer = 2 * sf + 4 * sh + s3h + 2 * lnws;
+  st->gl_layer = 2 * sf + 6 * sh + s3h + 2 * lnws;
   st->grad_pool.host = false;
   st->grad_pool.buf_bytes = (size_t)st->Lu * st->gl_layer + sh;
   st->grad_pool.cap = 0;
@@ -1232,6 +1264,8 @@ int stage_create(const po_config* cfg, void* compute_stream, po_stage** out) {
   st->w_dn = take(sh);
   st->w_dn1 = take(sh);
   st->w_n_w = take(sh);
+  st->w_dz[0] = take(sh);
+  st->w_dz[1] = take(sh);
   st->w_dy[0] = take(sh);
   st->w_dy[1] = take(sh);
   st->w_x0 = take(sh);
@@ -1390,6 +1424,16 @@ int po_stage_backward(po_stage* st, int32_t mb, int32_t chunk, const void* dy, v
   PO_NEED_STAGE(st);
   return stage_backward(st, mb, chunk, dy, dx);
 }
+int po_set_dropout_seed(po_stage* st, uint64_t seed) {
+  PO_NEED_STAGE(st);
+  for (auto& kv : st->units)
+    if (kv.second.live) {
+      set_error("po_set_dropout_seed with units in flight (their backward must regenerate the forward's masks)");
+      return PO_E_STATE;
+    }
+  st->cfg.dropout_seed = seed;
+  return PO_OK;
+}
 int po_stage_backward_input(po_stage* st, int32_t mb, int32_t chunk, const void* dy, void* dx) {
   begin_launch();
   PO_NEED_STAGE(st);
@@ -1466,6 +1510,7 @@ int po_op_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32
   begin_launch();
   if (!dtype_ok(dtype)) return PO_E_INVAL;
   Epilogue e;
+  memset(&e, 0, sizeof(e));
   e.bias = bias;
   e.residual = residual;
   e.out = out;
@@ -1490,6 +1535,16 @@ int po_op_attention_backward(int32_t dtype, const void* qkv, const void* o, cons
   if (!dtype_ok(dtype)) return PO_E_INVAL;
   return ok(attention_backward(dtype, qkv, o, lse, d_o, dqkv, delta, partials, s, h, n_heads,
                                n_kv_heads > 0 ? n_kv_heads : n_heads, force_generic != 0, (hipStream_t)stream));
+}
+int po_op_dropout(int32_t dtype, const void* x, void* out, int32_t rows, int32_t cols, float p, uint64_t seed,
+                  int32_t layer, int32_t site, int32_t mb, void* stream) {
+  begin_launch();
+  if (!dtype_ok(dtype)) return PO_E_INVAL;
+  if (!(p >= 0.f && p < 1.f) || layer < 0 || (site != 0 && site != 1) || mb < 0) {
+    set_error("po_op_dropout: p=%g layer=%d site=%d mb=%d", p, layer, site, mb);
+    return PO_E_INVAL;
+  }
+  return ok(dropout_apply(dtype, x, out, rows, cols, make_dropout_site(p, seed, layer, site, mb), (hipStream_t)stream));
 }
 uint64_t po_op_colsum_workspace(int32_t rows, int32_t n) { return rows > 0 && n > 0 ? colsum_workspace(rows, n) : 0; }
 int po_op_colsum_accumulate(int32_t dtype, const void* x, float* acc, float* workspace, int32_t rows, int32_t n,

@@ -248,3 +248,24 @@ def test_pack_unpack_roundtrip_is_bit_exact(gpu_device):
     with pytest.raises(po.PipeOffloadError):
         po.po_op_pack([(segs[0], 8)], packed)  # not a multiple of 16
     po.po_op_pack([], packed)  # empty is a no-op
+
+
+# ---- dropout with regenerated masks ------------------------------------------------------------------------------
+@pytest.mark.parametrize("rows,cols,p,seed,layer,site,mb", [(37, 130, 0.1, 1234, 0, 0, 0), (64, 256, 0.25, 2 ** 40 + 7, 3, 1, 5),
+                                                            (5, 7, 0.5, 1, 11, 0, 2), (300, 1024, 0.9, 99, 1, 1, 31)])
+def test_dropout_mask_is_the_oracle_mask_bit_for_bit(gpu_device, rows, cols, p, seed, layer, site, mb):
+    p = float(np.float32(p))  # the probability the library sees is the fp32 value
+    x = torch.ones(rows, cols, dtype=torch.float32, device=gpu_device)
+    out = torch.empty_like(x)
+    po.po_op_dropout(po.PO_F32, x, out, rows, cols, p, seed, layer, site, mb)
+    keep = so.dropout_keep_mask(seed, layer, site, mb, rows, cols, p)
+    got = _np(out)
+    assert np.array_equal(got != 0, keep)
+    assert np.all(got[keep] == np.float32(1.0 / (1.0 - p)))
+    # bf16 values through the same mask
+    rng = np.random.default_rng(rows)
+    v = _rand(rng, (rows, cols), "bf16")
+    xb = _dev(v, torch.bfloat16, gpu_device)
+    ob = torch.empty_like(xb)
+    po.po_op_dropout(po.PO_BF16, xb, ob, rows, cols, p, seed, layer, site, mb)
+    assert max_rel_err(_np(ob), v.astype(np.float64) * keep / (1.0 - p)) < 1e-2

@@ -339,3 +339,48 @@ def test_stage_with_grouped_query_attention(gpu_device, shape, tol):
             else:
                 assert stats["bytes_d2h"] == m * shape.n_layers * po.po_saved_bytes_per_layer(r.cfg)
     _assert_bit_identical(snaps[0.0], snaps[1.0])
+
+
+# ---- dropout with regenerated masks (Appendix C) ---------------------------------------------------------------
+@pytest.mark.parametrize("shape,tol", [
+    (syn.StageShape(2, 1, 128, 2, 512, 96, vocab=40, dtype="f32", pipeline_degree=2, n_microbatches=3), 1e-4),
+    (syn.StageShape(2, 1, 256, 2, 1024, 256, dtype="bf16", pipeline_degree=3, n_microbatches=4), 2e-2),
+    (syn.StageShape(1, 1, 192, 3, 320, 200, dtype="bf16", pipeline_degree=2, n_microbatches=2), 2e-2)],
+    ids=["f32-generic", "bf16-mfma", "bf16-ragged"])
+def test_stage_with_dropout_against_oracle_and_bitwise_invariants(gpu_device, shape, tol):
+    m, p, seed = shape.n_microbatches, float(np.float32(0.2)), 4242  # the library holds p in fp32
+    x = {(j, 0): syn.unit_input(shape, j, 0) for j in range(m)}
+    dy = {(j, 0): syn.unit_upstream_grad(shape, j, 0) for j in range(m)}
+    snaps = {}
+    for name, kw, ratio in [("plain", {}, 0.0), ("offload", {}, 1.0), ("weight-stream", dict(weight_stream=1), 1.0)]:
+        with StageRunner(shape, dropout_p=p, dropout_seed=seed, **kw) as r:
+            r.make_inputs()
+            r.run(po.PO_SCHED_1F1B, ratio)
+            snaps[name] = _snapshot(r)
+            if name == "plain":
+                ref = so.run_stage(r.params_np, shape.n_layers, 1, shape.n_heads, x, dy, vocab=shape.vocab,
+                                   dropout_p=p, seed=seed)
+                _compare(shape, r.results(), ref, tol)
+                # without the masks the oracle is far away: the parity above really exercises them
+                nodrop = so.run_stage(r.params_np, shape.n_layers, 1, shape.n_heads, x, dy, vocab=shape.vocab)
+                got_y = r.results()[0][(0, 0)]
+                assert max_rel_err(got_y, nodrop[0][(0, 0)]) > 5 * max_rel_err(got_y, ref[0][(0, 0)])
+                # split backward regenerates the same masks
+                r.zero_grads()
+                for j in range(m):
+                    po.po_stage_forward(r.stage, j, 0, r.x[j], r.y[j])
+                for j in range(m):
+                    po.po_stage_backward_input(r.stage, j, 0, r.dy[j], r.dx[j])
+                    po.po_stage_backward_weight(r.stage, j, 0)
+                _assert_bit_identical(snaps["plain"], _snapshot(r))
+                # another seed, other masks
+                with pytest.raises(po.PipeOffloadError):
+                    po.po_stage_forward(r.stage, 0, 0, r.x[0], r.y[0])
+                    po.po_set_dropout_seed(r.stage, 1)  # a unit is in flight
+                po.po_stage_backward(r.stage, 0, 0, r.dy[0], r.dx[0])
+                po.po_set_dropout_seed(r.stage, seed + 1)
+                r.zero_grads()
+                r.run(po.PO_SCHED_1F1B, 0.0)
+                assert not torch.equal(snaps["plain"][2], r.grads)
+    _assert_bit_identical(snaps["plain"], snaps["offload"])
+    _assert_bit_identical(snaps["plain"], snaps["weight-stream"])
