@@ -89,6 +89,7 @@ def main():
     ap.add_argument("--weight-stream", type=int, default=0, help="1: weight-gradient work on its own stream")
     ap.add_argument("--kv-heads", type=int, default=0,
                     help="grouped-query attention with this many key/value heads (Table 2 uses 8); 0 = multi-head")
+    ap.add_argument("--dropout", type=float, default=0.0, help="hidden dropout probability (masks regenerated in backward)")
     ap.add_argument("--group", type=int, default=0, help="group size g of --schedule gis (0 = pipeline degree)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -114,7 +115,7 @@ def main():
     headline = None
     with StageRunner(shape, device_params=True, copy_streams=args.copy_streams, prefetch_passes=args.prefetch,
                      staged_copies=args.staged, profile_kernels=args.profile_every, group=args.group,
-                     weight_stream=args.weight_stream) as r:
+                     weight_stream=args.weight_stream, dropout_p=args.dropout, dropout_seed=20250301) as r:
         r.make_inputs_on_device()
         def measure(ratio):
             for _ in range(args.warmup):
@@ -184,7 +185,7 @@ def main():
                                f"schedule {sched_name}{' g=%d' % args.group if args.group else ''} rank 0; "
                                f"value is at offload ratio 1",
                    "copy_streams": args.copy_streams, "prefetch_passes": args.prefetch, "staged_copies": args.staged,
-                   "weight_stream": args.weight_stream},
+                   "weight_stream": args.weight_stream, "dropout": args.dropout},
         "ratios": {str(k): v for k, v in ratios.items()},
         "k_eq1_measured_serial": k_meas, "k_eq1_measured_duplex": (k_meas / 2 if k_meas else None),
         "roofline": {"bound": "mfma", "achieved": gemm["gemm_tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",

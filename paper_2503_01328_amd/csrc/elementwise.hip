@@ -529,9 +529,11 @@ bool embedding_backward(int dtype, const int32_t* tok, const void* dx, float* dw
 // Dropout with a regenerated mask: out[r, c] = x[r, c] * keep(r, c) * scale.  The backward of a dropout site is
 // the same map applied to the incoming gradient.  One thread per four columns (one generator block).
 // --------------------------------------------------------------------------
+// `residual` (may be null) is added after the mask: out = residual + dropout(x), the forward of a projection
+// whose output is dropped before it joins the residual stream.
 template <typename T>
-__global__ __launch_bounds__(256) void dropout_apply_kernel(const T* __restrict__ x, T* __restrict__ out, int rows,
-                                                            int cols, DropoutSite d) {
+__global__ __launch_bounds__(256) void dropout_apply_kernel(const T* __restrict__ x, const T* __restrict__ residual,
+                                                            T* __restrict__ out, int rows, int cols, DropoutSite d) {
   int per_row = (cols + 3) >> 2;
   size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (size_t)rows * per_row) return;
@@ -542,7 +544,9 @@ __global__ __launch_bounds__(256) void dropout_apply_kernel(const T* __restrict_
     int c = 4 * c4 + i;
     if (c < cols) {
       size_t at = (size_t)r * cols + c;
-      out[at] = from_f32<T>(w.w[i] >= d.threshold ? to_f32(x[at]) * d.scale : 0.f);
+      float v = w.w[i] >= d.threshold ? to_f32(x[at]) * d.scale : 0.f;
+      if (residual) v += to_f32(residual[at]);
+      out[at] = from_f32<T>(v);
     }
   }
 }
@@ -559,8 +563,8 @@ DropoutSite make_dropout_site(float p, uint64_t seed, int layer, int site, int u
   return d;
 }
 
-bool dropout_apply(int dtype, const void* x, void* out, int rows, int cols, const DropoutSite& d,
-                   hipStream_t stream) {
+bool dropout_apply(int dtype, const void* x, const void* residual, void* out, int rows, int cols,
+                   const DropoutSite& d, hipStream_t stream) {
   if (rows <= 0 || cols <= 0 || !x || !out || d.scale == 0.f) {
     set_error("dropout_apply: rows=%d cols=%d x=%p out=%p", rows, cols, x, out);
     return false;
@@ -568,9 +572,11 @@ bool dropout_apply(int dtype, const void* x, void* out, int rows, int cols, cons
   size_t n = (size_t)rows * ((cols + 3) / 4);
   unsigned grid = (unsigned)((n + 255) / 256);
   if (dtype == kF32)
-    dropout_apply_kernel<float><<<grid, 256, 0, stream>>>((const float*)x, (float*)out, rows, cols, d);
+    dropout_apply_kernel<float><<<grid, 256, 0, stream>>>((const float*)x, (const float*)residual, (float*)out, rows,
+                                                          cols, d);
   else
-    dropout_apply_kernel<bf16><<<grid, 256, 0, stream>>>((const bf16*)x, (bf16*)out, rows, cols, d);
+    dropout_apply_kernel<bf16><<<grid, 256, 0, stream>>>((const bf16*)x, (const bf16*)residual, (bf16*)out, rows,
+                                                         cols, d);
   return launch_ok("dropout_apply_kernel");
 }
 

@@ -160,14 +160,6 @@ __device__ __forceinline__ void epilogue_row_piece(const Epilogue& e, int m, int
 #pragma unroll
     for (int i = 0; i < 8; ++i) a[i] += (float)b.v[i];
   }
-  if (e.drop.scale != 0.f) {  // n is a multiple of 8: two generator blocks cover the piece
-    PhiloxWords w0 = dropout_words(e.drop, m, n >> 2), w1 = dropout_words(e.drop, m, (n >> 2) + 1);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      a[i] = w0.w[i] >= e.drop.threshold ? a[i] * e.drop.scale : 0.f;
-      a[4 + i] = w1.w[i] >= e.drop.threshold ? a[4 + i] * e.drop.scale : 0.f;
-    }
-  }
   if (e.residual) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) a[i] += (float)aux.v[i];

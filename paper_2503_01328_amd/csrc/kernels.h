@@ -51,7 +51,9 @@ bool gemm(int dtype, int trans_a, int trans_b, int M, int N, int K, const void* 
 // ---- dropout with regenerated masks (elementwise.hip) --------------------------
 // threshold = round(p 2^32) (an element is kept iff its random word is >= it), scale = 1 / (1 - p), key = seed.
 DropoutSite make_dropout_site(float p, uint64_t seed, int layer, int site, int unit);
-bool dropout_apply(int dtype, const void* x, void* out, int rows, int cols, const DropoutSite& d, hipStream_t stream);
+// out = (residual ? residual : 0) + dropout(x); x, residual, out are [rows, cols] of dtype.
+bool dropout_apply(int dtype, const void* x, const void* residual, void* out, int rows, int cols,
+                   const DropoutSite& d, hipStream_t stream);
 
 // ---- attention (attention_generic.hip, attention_mfma.hip) -------------------
 // qkv is [s, h + 2 hkv]: query block [h], key block [hkv], value block [hkv], hkv = n_kv_heads * (h / n_heads);

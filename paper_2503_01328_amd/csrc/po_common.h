@@ -113,7 +113,6 @@ struct Epilogue {
   const void* gelu_u;    // [M, N] of T: out = acc * gelu'(gelu_u)
   float* acc_f32;        // [M, N] fp32: += acc
   int ldc;               // leading dimension of all [M, N] operands above
-  DropoutSite drop;      // store kinds only: out = residual + dropout(acc + bias); drop.scale == 0: none
 };
 
 // Applies the epilogue to one accumulator value at (m, n).
@@ -125,7 +124,6 @@ __device__ __forceinline__ void epilogue_store(const Epilogue& e, int m, int n, 
     return;
   }
   if (e.bias) acc += to_f32(static_cast<const T*>(e.bias)[n]);
-  if (e.drop.scale != 0.f) acc = dropout_words(e.drop, m, n >> 2).w[n & 3] >= e.drop.threshold ? acc * e.drop.scale : 0.f;
   if (e.residual) acc += to_f32(static_cast<const T*>(e.residual)[idx]);
   if (e.gelu_u) {
     float u = to_f32(static_cast<const T*>(e.gelu_u)[idx]);

@@ -472,10 +472,13 @@ static int layer_forward(po_stage* st, int layer, int mb, char* slab, void* y_ou
   PO_RC(st_attention(st, false, qkv, o, lse, nullptr, nullptr));
   e = make_ep(h);
   e.bias = st->P(layer, pl.b_o);
-  e.residual = x;
-  e.out = x1;
-  e.drop = site_of(st, layer, 0, mb);
+  // With dropout the projection (bias included) lands in a scratch tensor and one more kernel forms
+  // x1 = x + dropout(projection); fusing the generator into the GEMM epilogue cost the GEMM its registers.
+  const bool drop = c.dropout_p > 0.f;
+  e.residual = drop ? nullptr : x;
+  e.out = drop ? st->w_dz[0] : x1;
   PO_RC(st_gemm(st, 0, 0, s, h, h, o, h, st->P(layer, pl.w_o), h, e));
+  if (drop) PO_K(dropout_apply(dt, st->w_dz[0], x, x1, s, h, site_of(st, layer, 0, mb), q));
   PO_K(layernorm_forward(dt, x1, st->P(layer, pl.ln2_g), st->P(layer, pl.ln2_b), st->w_n, s, h, c.ln_eps, q));
   e = make_ep(f);
   e.bias = st->P(layer, pl.b_fc1);
@@ -484,10 +487,10 @@ static int layer_forward(po_stage* st, int layer, int mb, char* slab, void* y_ou
   PO_RC(st_gemm(st, 0, 0, s, f, h, st->w_n, h, st->P(layer, pl.w_fc1), f, e));
   e = make_ep(h);
   e.bias = st->P(layer, pl.b_fc2);
-  e.residual = x1;
-  e.out = y_out;
-  e.drop = site_of(st, layer, 1, mb);
+  e.residual = drop ? nullptr : x1;
+  e.out = drop ? (void*)st->w_dz[0] : y_out;
   PO_RC(st_gemm(st, 0, 0, s, h, f, st->w_g, f, st->P(layer, pl.w_fc2), h, e));
+  if (drop) PO_K(dropout_apply(dt, st->w_dz[0], x1, y_out, s, h, site_of(st, layer, 1, mb), q));
   return PO_OK;
 }
 
@@ -522,7 +525,7 @@ static int layer_backward_input(po_stage* st, int layer, int mb, const char* sla
   const bool drop = c.dropout_p > 0.f;
   const void* dz2 = dy;
   if (drop) {
-    PO_K(dropout_apply(dt, dy, b.dz2, s, h, site_of(st, layer, 1, mb), q));
+    PO_K(dropout_apply(dt, dy, nullptr, b.dz2, s, h, site_of(st, layer, 1, mb), q));
     dz2 = b.dz2;
   }
   Epilogue e = make_ep(f);
@@ -537,7 +540,7 @@ static int layer_backward_input(po_stage* st, int layer, int mb, const char* sla
                           c.ln_eps, kLnInputGrad, q));
   const void* dz1 = b.dx1;
   if (drop) {
-    PO_K(dropout_apply(dt, b.dx1, b.dz1, s, h, site_of(st, layer, 0, mb), q));
+    PO_K(dropout_apply(dt, b.dx1, nullptr, b.dz1, s, h, site_of(st, layer, 0, mb), q));
     dz1 = b.dz1;
   }
   e = make_ep(h);
@@ -1544,7 +1547,8 @@ int po_op_dropout(int32_t dtype, const void* x, void* out, int32_t rows, int32_t
     set_error("po_op_dropout: p=%g layer=%d site=%d mb=%d", p, layer, site, mb);
     return PO_E_INVAL;
   }
-  return ok(dropout_apply(dtype, x, out, rows, cols, make_dropout_site(p, seed, layer, site, mb), (hipStream_t)stream));
+  return ok(dropout_apply(dtype, x, nullptr, out, rows, cols, make_dropout_site(p, seed, layer, site, mb),
+                          (hipStream_t)stream));
 }
 uint64_t po_op_colsum_workspace(int32_t rows, int32_t n) { return rows > 0 && n > 0 ? colsum_workspace(rows, n) : 0; }
 int po_op_colsum_accumulate(int32_t dtype, const void* x, float* acc, float* workspace, int32_t rows, int32_t n,
