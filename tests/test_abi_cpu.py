@@ -157,3 +157,25 @@ def test_flatten_unflatten_roundtrip():
         for k, a in params["layers"][l].items():
             assert (back["layers"][l][k] == a).all()
     assert (back["wte"] == params["wte"]).all() and (back["wpe"] == params["wpe"]).all()
+
+
+def test_hot_kernels_keep_their_accumulators_in_registers():
+    """The compiler's own resource report (written by the build): no MFMA kernel may use scratch memory - a GEMM
+    whose 256 accumulators spill runs six times slower without failing any numerical test - and the attention
+    kernels must still fit two waves per SIMD."""
+    import json
+
+    from paper_2503_01328_amd import build as b
+
+    if not os.path.exists(b.RESOURCES):
+        b.build(verbose=False)
+    usage = json.load(open(b.RESOURCES))
+    gemm = {k: v for k, v in usage.items() if "gemm_mfma_kernel" in k}
+    attn = {k: v for k, v in usage.items() if "attn_fwd_mfma" in k or "attn_bwd_dkv_mfma" in k or "attn_bwd_dq_mfma" in k}
+    assert len(gemm) == 32 and len(attn) >= 6
+    for name, v in {**gemm, **attn}.items():
+        assert v["ScratchSize"] == 0, (name, v)
+    for name, v in attn.items():
+        assert v["Occupancy"] >= 2, (name, v)
+    for name, v in gemm.items():
+        assert v["VGPRs"] + v["AGPRs"] <= 512
