@@ -24,6 +24,18 @@ independent model, in plain Python integers, of what one pipeline rank executes:
   general the rank-0 peak is g(v-1) + d.
 * pipeline_timeline runs the op lists of all d ranks against each other with
   given pass durations, which yields the bubble sizes of Table 1.
+* Uniform repeating (Section 2; the schedule Section 3.3 calls PO): one
+  microbatch's passes form a building block, here the steady state of the
+  generalized interleaved schedule (a chunk every g slots going forward and
+  coming back, d slots for the round trip through the last chunk, a slot being
+  one F, one B and one W); microbatch n runs the block n periods later, a
+  period being the 3v unit-time passes a rank spends on one microbatch.  A
+  rank's op order is its passes sorted by time.  Passes whose times collide
+  modulo the period on a rank are moved later by whole slots (the paper leaves
+  the collision rule to a cited work; this greedy rule is this build's reading).
+  Peak memory is then about the summed lifespans over the period, which gives
+  the stage-level selective offload of Section 2 (longest lifespan first) its
+  better-than-linear effect.
 
 Op tuples are (kind, mb, chunk) with kind in {"F", "B", "W", "OFFLOAD", "RELOAD"}.
 """
@@ -146,7 +158,110 @@ def pipeline_timeline(rank_ops, d, v, t_f, t_b, t_w):
     return max(free), finished
 
 
+def building_block_template(d, v, g):
+    """Unit-time (F = B = W = 1) start times of one microbatch's passes in the
+    steady state of the generalized interleaved schedule with group size g
+    (Section 3.3): the forward moves one unit per rank and 3g units (g slots) per
+    chunk; the backward of the last chunk starts when its forward has left rank
+    d-1, moves two units per rank (a rank in a one-forward-one-backward rhythm
+    starts B one slot minus one forward after its successor) and 3g units per
+    chunk; W directly follows B.  On rank 0 chunk c then lives for
+    6g(v-1-c) + 3d units, and the lifespans of a rank's chunks divided by the
+    period 3v add up to the g(v-1) + d units of Section 3.3.
+    Keys are (kind, rank, chunk)."""
+    t = {}
+    turn = 3 * g * (v - 1) + d
+    for c in range(v):
+        for i in range(d):
+            t[("F", i, c)] = 3 * g * c + i
+            t[("B", i, c)] = turn + 3 * g * (v - 1 - c) + 2 * (d - 1 - i)
+            t[("W", i, c)] = t[("B", i, c)] + 1
+    return t
+
+
+def building_block(d, v, g):
+    """The template made repeatable with period 3v: passes are placed in dependency
+    order (forwards up the model stages, then backwards down, each W right after
+    its B); a pass that would start before the pass it depends on has ended, or
+    whose time modulo 3v is taken on its rank, moves later by whole slots (3
+    units).  The template puts rank i's F, B and W at times i, i+1 and i+2 modulo
+    3, so whole-slot moves keep every rank in a steady F, B, W rhythm, which is
+    what lets the resulting order run without stalls when the three pass times
+    differ; each kind has v places in the period and v passes, so a place is
+    always found."""
+    want = building_block_template(d, v, g)
+    period = 3 * v
+    used = [set() for _ in range(d)]
+    placed = {}
+
+    def place(key, earliest):
+        t = want[key]
+        while t < earliest or t % period in used[key[1]]:
+            t += 3
+        used[key[1]].add(t % period)
+        placed[key] = t
+        return t
+
+    last = -1
+    for stage in range(d * v):
+        c, i = divmod(stage, d)
+        last = place(("F", i, c), last + 1)
+    for stage in reversed(range(d * v)):
+        c, i = divmod(stage, d)
+        last = place(("B", i, c), last + 1)
+        place(("W", i, c), last + 1)
+    return placed
+
+
+def uniform_repeat(d, rank, v, m, g=None):
+    """Compute passes of the uniformly repeated schedule on ``rank``: microbatch n
+    runs the building block 3v n units later; the rank's order is by start time.
+    g defaults to ceil(d/2), the block of GIS-H that Section 3.3 repeats."""
+    g = math.ceil(d / 2) if g is None else g
+    if not (math.ceil(d / 2) <= g <= d):
+        raise ValueError("the group size must lie in [ceil(d/2), d]")
+    block = building_block(d, v, g)
+    timed = []
+    for (kind, i, c), t in block.items():
+        if i == rank:
+            for n in range(m):
+                timed.append((t + 3 * v * n, kind, n, c))
+    timed.sort()
+    return [(kind, n, c) for _, kind, n, c in timed]
+
+
+def peak_units(passes, offloaded_chunks=()):
+    """Largest number of units a rank holds at once when the chunks in
+    ``offloaded_chunks`` cost nothing (the idealised stage-level offload of Section 2,
+    Figure 4: copies are instantaneous and leave no transient).  A unit is held
+    from its F to its W, or to its B when the backward is fused."""
+    split = any(op[0] == "W" for op in passes)
+    held = peak = 0
+    for kind, _, c in passes:
+        if c in offloaded_chunks:
+            continue
+        if kind == "F":
+            held += 1
+        elif kind == ("W" if split else "B"):
+            held -= 1
+        peak = max(peak, held)
+    return peak
+
+
+def chunks_by_lifespan(passes, v):
+    """Chunks of a rank ordered for selective offload (Section 2): longest mean
+    forward-to-backward gap first, ties by chunk index."""
+    gap = forward_backward_gaps(passes)
+    total, count = [0] * v, [0] * v
+    for (_, c), n in gap.items():
+        total[c] += n
+        count[c] += 1
+    return sorted(range(v), key=lambda c: (-total[c] / max(count[c], 1), c))
+
+
 def compute_passes(schedule, d, rank, v, m, g=None):
+    if schedule == "po":
+        return uniform_repeat(d, rank, v, m, g)
     if schedule == "gis":
         return generalized_interleaved(d, rank, v, m, g)
     if schedule == "1f1b":

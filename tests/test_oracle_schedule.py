@@ -260,3 +260,103 @@ def test_forward_backward_gap_on_rank0_of_1f1b():
     # weight-gradient passes are not counted
     gis = sch.generalized_interleaved(4, 0, 1, 8)
     assert sch.forward_backward_gaps(gis) == sch.forward_backward_gaps([o for o in gis if o[0] != "W"])
+
+
+# ---- uniformly repeated schedule (Section 2; "PO" of Section 3.3 and Table 1) --------------------------------------
+PO_CASES = [(8, 2, 32), (8, 4, 32), (8, 8, 48), (8, 16, 64), (4, 2, 16), (4, 4, 16), (6, 3, 18), (5, 2, 11), (2, 2, 5)]
+
+
+def test_block_template_lifespans_sum_to_the_peak_of_section_3_3():
+    # the lifespans of a rank's chunks over the period 3v are its units in flight: g(v-1) + d on rank 0 for any g,
+    # dv for g = d (Sections 3.2, 3.3), and (v+2)/(8v) of M = dv once the longer-lived half is offloaded (Table 1, PO-H)
+    for d, v in [(8, 2), (8, 4), (8, 16), (4, 2), (6, 4), (16, 8)]:
+        for g in range(-(-d // 2), d + 1):
+            t = sch.building_block_template(d, v, g)
+            life = [t[("W", 0, c)] + 1 - t[("F", 0, c)] for c in range(v)]
+            assert sum(life) == 3 * v * (g * (v - 1) + d)
+            assert life == sorted(life, reverse=True)  # the lower the chunk the longer it lives
+            if 2 * g == d:
+                assert sum(life[v // 2:]) * 8 == 3 * v * (v + 2) * d
+            for i in range(1, d):  # rank i: two slots fewer per rank for the round trip... 3 units per rank in all
+                assert [t[("W", i, c)] + 1 - t[("F", i, c)] for c in range(v)] == [x - 3 * i for x in life]
+
+
+@pytest.mark.parametrize("d,v,m", PO_CASES)
+def test_building_block_is_repeatable_and_ordered(d, v, m):
+    for g in range(-(-d // 2), d + 1):
+        want, got = sch.building_block_template(d, v, g), sch.building_block(d, v, g)
+        assert set(got) == set(want) and all(got[k] >= want[k] for k in want)
+        for i in range(d):  # no two passes of a rank share a residue: copies of the block never overlap
+            res = sorted(got[(kind, i, c)] % (3 * v) for kind in "FBW" for c in range(v))
+            assert res == list(range(3 * v))
+        stages = [(i, c) for c in range(v) for i in range(d)]
+        for (i0, c0), (i1, c1) in zip(stages, stages[1:]):
+            assert got[("F", i1, c1)] > got[("F", i0, c0)]
+            assert got[("B", i0, c0)] > got[("B", i1, c1)]
+        assert got[("B", d - 1, v - 1)] > got[("F", d - 1, v - 1)]
+        assert all(got[("W", i, c)] > got[("B", i, c)] for i, c in stages)
+
+
+@pytest.mark.parametrize("d,v,m", PO_CASES)
+def test_uniform_repeat_is_a_valid_pipeline_schedule(d, v, m):
+    rank_ops = [sch.uniform_repeat(d, i, v, m) for i in range(d)]
+    for ops in rank_ops:
+        assert sch.simulate(ops)["errors"] == []
+        assert sch.check_dependencies(ops, v) == []
+        for kind in "FBW":
+            assert sorted(o[1:] for o in ops if o[0] == kind) == sorted((mb, c) for mb in range(m) for c in range(v))
+    for t in TIMES:
+        # Table 1, last rows: the bubble stays below that of 1F1B, v (d-1)(T_F + T_B + T_W)
+        assert _bubble(rank_ops, d, v, m, t) < v * (d - 1) * sum(t)
+    # every microbatch follows the same pattern: dropping the last microbatch leaves the order of the others as it was
+    if m > 1:
+        for i in (0, d - 1):
+            assert [o for o in rank_ops[i] if o[1] < m - 1] == sch.uniform_repeat(d, i, v, m - 1)
+
+
+def test_uniform_repeat_with_one_chunk_is_one_f_one_b():
+    # one stage per rank: the block is the 1F1B pattern, and repeating it gives 1F1B with split backward
+    for d in (2, 3, 4, 8):
+        for i in range(d):
+            assert sch.uniform_repeat(d, i, 1, 3 * d) == sch.generalized_interleaved(d, i, 1, 3 * d, d)
+            assert sch.peak_units(sch.uniform_repeat(d, i, 1, 3 * d)) == d - i
+
+
+def test_uniform_repeat_peak_and_better_than_linear_offload():
+    for d, v, m in [(8, 2, 32), (8, 4, 32), (8, 8, 48), (8, 16, 64), (4, 2, 16), (4, 4, 16)]:
+        g = d // 2
+        po = sch.uniform_repeat(d, 0, v, m)
+        gis_h = sch.generalized_interleaved(d, 0, v, m - m % g, g)
+        full = sch.peak_units(po)
+        # Section 3.3: a peak similar to GIS-H's g(v-1) + d (moved passes lengthen some lifespans)
+        assert sch.peak_units(gis_h) == g * (v - 1) + d
+        assert g * (v - 1) + d <= full <= 1.2 * (g * (v - 1) + d) + 1
+        assert sch.chunks_by_lifespan(po, v) == list(range(v)) == sch.chunks_by_lifespan(gis_h, v)
+        half = set(range(v // 2))
+        # Table 1, PO-H: about (v+2)/(8v) M with M = dv units
+        assert abs(sch.peak_units(po, half) - (v + 2) * d / 8) <= 0.15 * (v + 2) * d / 8 + 1
+        # Sections 2 and 5.3: better than linear, where the interleaved order saves half for half the stages
+        assert sch.peak_units(po, half) <= sch.peak_units(gis_h, half)
+        if v >= 4:
+            assert sch.peak_units(po, half) <= 0.34 * full
+            assert sch.peak_units(gis_h, half) >= 0.4 * sch.peak_units(gis_h)
+        if v >= 8:
+            assert sch.peak_units(po, half) < 0.8 * sch.peak_units(gis_h, half)
+        # the saving per offloaded chunk shrinks with the chunk's lifespan
+        saved = [full - sch.peak_units(po, {c}) for c in range(v)]
+        assert all(a >= b - 1 for a, b in zip(saved, saved[1:])) and saved[0] > saved[-1]
+    # Section 2: at 8 ranks and 16 stages per rank, half the stages offloaded leaves about a quarter
+    po = sch.uniform_repeat(8, 0, 16, 64)
+    assert 0.2 < sch.peak_units(po, set(range(8))) / sch.peak_units(po) < 0.3
+    # Figure 2 / Table 1 at 8 ranks and 16 stages in all: stage 0 offloaded leaves a quarter of M = dv
+    assert sch.peak_units(sch.uniform_repeat(8, 0, 2, 32), {0}) == 8 * 2 // 4
+
+
+def test_peak_units_against_the_state_machine():
+    # peak_units with nothing offloaded is the resident peak of the op-list state machine
+    for d, v, m in [(4, 2, 8), (8, 2, 16)]:
+        for ops in (sch.uniform_repeat(d, 1, v, m), sch.generalized_interleaved(d, 1, v, m), sch.interleaved_one_f_one_b(d, 1, v, m)):
+            assert sch.peak_units(ops) == sch.simulate(ops)["peak_resident"]
+    # brute force on a hand-written list: units (0,0) (1,0) (0,1) held, chunk 0 free of charge
+    ops = [("F", 0, 0), ("F", 1, 0), ("F", 0, 1), ("B", 0, 1), ("W", 0, 1), ("B", 0, 0), ("W", 0, 0), ("B", 1, 0), ("W", 1, 0)]
+    assert sch.peak_units(ops) == 3 and sch.peak_units(ops, {0}) == 1 and sch.peak_units(ops, {1}) == 2
