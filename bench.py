@@ -80,9 +80,10 @@ def main():
     ap.add_argument("--copy-streams", type=int, default=2)
     ap.add_argument("--prefetch", type=int, default=2)
     ap.add_argument("--staged", type=int, default=0)
-    ap.add_argument("--schedule", default="auto", choices=["auto", "1f1b", "1f1b-interleaved", "gis"],
+    ap.add_argument("--schedule", default="auto", choices=["auto", "1f1b", "1f1b-interleaved", "gis", "po"],
                     help="auto: 1F1B, or interleaved 1F1B for a workload with several chunks; gis: generalized "
-                         "interleaved schedule with split backward (Sections 3.2, 3.3)")
+                         "interleaved schedule with split backward (Sections 3.2, 3.3); po: the uniformly repeated "
+                         "schedule (Section 2, Table 1), which selects whole chunks by lifespan")
     ap.add_argument("--profile-every", type=int, default=5,
                     help="bracket every k-th GEMM / attention launch of the timed steps with HIP events (1 = all; an "
                          "event pair idles the stream for a few microseconds, which costs about 7 %% at C2 with k = 1)")
@@ -90,7 +91,11 @@ def main():
     ap.add_argument("--kv-heads", type=int, default=0,
                     help="grouped-query attention with this many key/value heads (Table 2 uses 8); 0 = multi-head")
     ap.add_argument("--dropout", type=float, default=0.0, help="hidden dropout probability (masks regenerated in backward)")
-    ap.add_argument("--group", type=int, default=0, help="group size g of --schedule gis (0 = pipeline degree)")
+    ap.add_argument("--group", type=int, default=0,
+                    help="group size g of --schedule gis (0 = pipeline degree) or po (0 = half the pipeline degree)")
+    ap.add_argument("--select", default="auto", choices=["auto", "alternate-mb", "longest-lifespan"],
+                    help="how a ratio picks units: every other microbatch, or the longest-lived chunks of every "
+                         "microbatch (auto: the latter for --schedule po)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs one pipeline rank on one GPU; --gpus must be 1", file=sys.stderr)
@@ -109,13 +114,16 @@ def main():
     if sched_name == "auto":
         sched_name = "1f1b-interleaved" if shape.n_chunks > 1 else "1f1b"
     sched = {"1f1b": po.PO_SCHED_1F1B, "1f1b-interleaved": po.PO_SCHED_1F1B_INTERLEAVED,
-             "gis": po.PO_SCHED_GIS}[sched_name]
+             "gis": po.PO_SCHED_GIS, "po": po.PO_SCHED_PO}[sched_name]
+    select = args.select if args.select != "auto" else ("longest-lifespan" if sched_name == "po" else "alternate-mb")
+    policy = {"alternate-mb": po.PO_SEL_ALTERNATE_MB, "longest-lifespan": po.PO_SEL_LONGEST_LIFESPAN}[select]
     tokens = shape.n_microbatches * shape.seq
     ratios = {}
     headline = None
     with StageRunner(shape, device_params=True, copy_streams=args.copy_streams, prefetch_passes=args.prefetch,
                      staged_copies=args.staged, profile_kernels=args.profile_every, group=args.group,
-                     weight_stream=args.weight_stream, dropout_p=args.dropout, dropout_seed=20250301) as r:
+                     weight_stream=args.weight_stream, dropout_p=args.dropout, dropout_seed=20250301,
+                     select_policy=policy) as r:
         r.make_inputs_on_device()
         def measure(ratio):
             for _ in range(args.warmup):
@@ -185,7 +193,7 @@ def main():
                                f"schedule {sched_name}{' g=%d' % args.group if args.group else ''} rank 0; "
                                f"value is at offload ratio 1",
                    "copy_streams": args.copy_streams, "prefetch_passes": args.prefetch, "staged_copies": args.staged,
-                   "weight_stream": args.weight_stream, "dropout": args.dropout},
+                   "weight_stream": args.weight_stream, "dropout": args.dropout, "select": select},
         "ratios": {str(k): v for k, v in ratios.items()},
         "k_eq1_measured_serial": k_meas, "k_eq1_measured_duplex": (k_meas / 2 if k_meas else None),
         "roofline": {"bound": "mfma", "achieved": gemm["gemm_tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",

@@ -41,7 +41,11 @@ typedef enum { PO_F32 = 0, PO_BF16 = 1 } po_dtype;
 /* PO_SCHED_GIS: generalized interleaved schedule with split backward (Sections 3.2, 3.3): every input-gradient
  * pass B is directly followed by the unit's weight-gradient pass W, warm-up g(v-1) + d-i-1 forwards, inner loop
  * over g = po_config.group microbatches (g = d: the paper's GIS, g = ceil(d/2): GIS-H). */
-typedef enum { PO_SCHED_1F1B = 0, PO_SCHED_1F1B_INTERLEAVED = 1, PO_SCHED_GIS = 2 } po_schedule;
+/* PO_SCHED_PO: the uniformly repeated schedule (Section 2; PO in Section 3.3 and Table 1): every microbatch runs
+ * the same building block (the steady state of the generalized interleaved schedule with group size g, default
+ * ceil(d/2)), 3v unit passes after the previous one; split backward; any m.  With LONGEST_LIFESPAN selection a
+ * ratio of 0.5 is the paper's PO-H and 1 its PO-F. */
+typedef enum { PO_SCHED_1F1B = 0, PO_SCHED_1F1B_INTERLEAVED = 1, PO_SCHED_GIS = 2, PO_SCHED_PO = 3 } po_schedule;
 
 /* How a whole-job offload ratio picks units.  ALTERNATE_MB: microbatch j is
  * offloaded iff floor((j+1) r) > floor(j r).  LONGEST_LIFESPAN (Section 2):
@@ -77,7 +81,7 @@ typedef struct po_config {
   int32_t profile_kernels; /* k > 0: po_run_schedule brackets every k-th GEMM launch and every k-th attention
                               launch with HIP events (1 = all; an event pair idles the stream for a few
                               microseconds, so benchmarks sample with an odd k) */
-  int32_t group;           /* g of PO_SCHED_GIS, ceil(d/2) <= g <= d; 0 = d */
+  int32_t group;           /* g, ceil(d/2) <= g <= d; 0 = d for PO_SCHED_GIS, ceil(d/2) for PO_SCHED_PO */
   int32_t weight_stream;   /* 1: weight-gradient work (W passes, and the weight half of po_stage_backward) runs on a
                               stream of its own after the unit's input-gradient work, beside the compute stream;
                               results are bit-identical to 0; gradients are complete after po_synchronize */

@@ -23,7 +23,7 @@ if not os.path.exists(_LIB_PATH):
 lib = C.CDLL(_LIB_PATH)
 
 PO_F32, PO_BF16 = 0, 1
-PO_SCHED_1F1B, PO_SCHED_1F1B_INTERLEAVED, PO_SCHED_GIS = 0, 1, 2
+PO_SCHED_1F1B, PO_SCHED_1F1B_INTERLEAVED, PO_SCHED_GIS, PO_SCHED_PO = 0, 1, 2, 3
 PO_SEL_ALTERNATE_MB, PO_SEL_LONGEST_LIFESPAN = 0, 1
 PO_OK, PO_E_INVAL, PO_E_STATE, PO_E_DEVICE_OOM, PO_E_HOST_OOM, PO_E_HIP = 0, -1, -2, -3, -4, -5
 OP_KINDS = ("F", "B", "OFFLOAD", "RELOAD", "W")

@@ -13,6 +13,13 @@
 // g(v-1) + d-i-1 warm-up forwards, and every input-gradient pass B is directly
 // followed by the unit's weight-gradient pass W.  g = d is the paper's GIS (dv units
 // in flight on rank 0), g = ceil(d/2) its GIS-H; in general the peak is g(v-1) + d.
+// Uniformly repeated schedule (Section 2; the PO rows of Table 1, Section 3.3): every microbatch runs the same
+// building block, shifted by the 3v unit-time passes a rank spends per microbatch.  The block is the steady state
+// of the generalized interleaved schedule: forward one unit per rank and g slots (3g units) per chunk, backward two
+// units per rank and g slots per chunk, W right after B.  A pass that would overlap the pass it depends on, or a
+// pass of an earlier or later microbatch on its rank, is delayed by whole slots, which keeps each rank's F, B, W
+// rhythm.  The rank's order is by start time.  (The paper leaves the collision rule to a cited work; delaying by
+// whole slots in dependency order is the rule chosen here.)
 // Offload placement (Section 4.2 collapsed to one rank with its own copy queues):
 // OFFLOAD directly after the unit's forward; RELOAD `prefetch` compute passes
 // before the unit's backward (W passes not counted: a B and its W together are one
@@ -21,6 +28,7 @@
 // (Section 4.4: their round trip cannot be hidden and they add nothing to the peak).
 #include <math.h>
 
+#include <algorithm>
 #include <vector>
 
 #include "../../include/pipeoffload.h"
@@ -40,11 +48,71 @@ static void unit_of(int n, int g, int v, bool backward, int& mb, int& chunk) {
   mb = group * g + within % g;
 }
 
+// Start times (unit passes) of one microbatch's passes on `rank`: f, b, w indexed by chunk.
+static void repeatable_block(int d, int rank, int v, int g, std::vector<long>& f, std::vector<long>& b,
+                             std::vector<long>& w) {
+  const long period = 3L * v, slot = 3;
+  std::vector<char> taken((size_t)d * period, 0);
+  auto settle = [&](int r, long t, long not_before) {
+    while (t < not_before || taken[(size_t)r * period + t % period]) t += slot;
+    taken[(size_t)r * period + t % period] = 1;
+    return t;
+  };
+  f.assign(v, 0);
+  b.assign(v, 0);
+  w.assign(v, 0);
+  long prev_end = 0;
+  for (int c = 0; c < v; ++c)
+    for (int r = 0; r < d; ++r) {
+      long t = settle(r, 3L * g * c + r, prev_end);
+      prev_end = t + 1;
+      if (r == rank) f[c] = t;
+    }
+  const long turn = 3L * g * (v - 1) + d;  // the last forward has left the last rank
+  for (int c = v - 1; c >= 0; --c)
+    for (int r = d - 1; r >= 0; --r) {
+      long t = settle(r, turn + 3L * g * (v - 1 - c) + 2L * (d - 1 - r), prev_end);
+      prev_end = t + 1;
+      long tw = settle(r, turn + 3L * g * (v - 1 - c) + 2L * (d - 1 - r) + 1, prev_end);
+      if (r == rank) {
+        b[c] = t;
+        w[c] = tw;
+      }
+    }
+}
+
+static bool uniform_repeat_passes(int d, int rank, int v, int m, int g, std::vector<Pass>& out) {
+  if (g <= 0) g = (d + 1) / 2;
+  if (g > d || 2 * g < d) {
+    set_error("schedule: group size %d outside [ceil(d/2), d] for d=%d", g, d);
+    return false;
+  }
+  std::vector<long> f, b, w;
+  repeatable_block(d, rank, v, g, f, b, w);
+  struct Timed {
+    long t;
+    Pass p;
+  };
+  std::vector<Timed> all;
+  all.reserve((size_t)3 * v * m);
+  for (int n = 0; n < m; ++n)
+    for (int c = 0; c < v; ++c) {
+      long shift = 3L * v * n;
+      all.push_back(Timed{f[c] + shift, Pass{0, n, c}});
+      all.push_back(Timed{b[c] + shift, Pass{1, n, c}});
+      all.push_back(Timed{w[c] + shift, Pass{4, n, c}});
+    }
+  std::sort(all.begin(), all.end(), [](const Timed& x, const Timed& y) { return x.t < y.t; });  // times are distinct
+  for (const Timed& e : all) out.push_back(e.p);
+  return true;
+}
+
 static bool compute_passes(int schedule, int d, int rank, int v, int m, int g, std::vector<Pass>& out) {
   if (d < 1 || rank < 0 || rank >= d || v < 1 || m < 1) {
     set_error("schedule: d=%d rank=%d v=%d m=%d", d, rank, v, m);
     return false;
   }
+  if (schedule == PO_SCHED_PO) return uniform_repeat_passes(d, rank, v, m, g, out);
   int total, warm;
   if (schedule == PO_SCHED_1F1B) {
     if (v != 1) {

@@ -1146,8 +1146,8 @@ int stage_run_schedule(po_stage* st, int schedule, int m, float ratio, const voi
     switch (op.kind) {
       case 0: rc = stage_forward(st, op.mb, op.chunk, x_in[i], y_out[i]); break;
       case 1:  // a schedule with W passes runs its B passes as input-gradient passes
-        rc = schedule == PO_SCHED_GIS ? stage_backward_input(st, op.mb, op.chunk, dy[i], dx[i])
-                                      : stage_backward(st, op.mb, op.chunk, dy[i], dx[i]);
+        rc = (schedule == PO_SCHED_GIS || schedule == PO_SCHED_PO) ? stage_backward_input(st, op.mb, op.chunk, dy[i], dx[i])
+                                                                   : stage_backward(st, op.mb, op.chunk, dy[i], dx[i]);
         break;
       case 2: rc = stage_offload(st, op.mb, op.chunk, op.ratio); break;
       case 3: rc = stage_reload(st, op.mb, op.chunk); break;

@@ -69,6 +69,27 @@ def test_short_gap_units_are_skipped_like_in_the_oracle_model(name, d, v, m, min
             assert got == want
 
 
+@pytest.mark.parametrize("d,v,m,g", [(8, 2, 32, 0), (8, 2, 11, 4), (8, 4, 16, 6), (4, 3, 7, 2), (4, 4, 16, 4), (6, 3, 18, 0),
+                                     (5, 2, 9, 0), (2, 2, 5, 1), (4, 1, 8, 0), (8, 16, 24, 0), (16, 2, 16, 0)])
+@pytest.mark.parametrize("ratio", [0.0, 0.5, 1.0])
+def test_uniform_repeat_schedule_ops_match_the_oracle_model(d, v, m, g, ratio):
+    for rank in sorted({0, d // 2, d - 1}):
+        for policy, pname in ((po.PO_SEL_ALTERNATE_MB, "alternate-mb"), (po.PO_SEL_LONGEST_LIFESPAN, "longest-lifespan")):
+            for prefetch in (0, 2):
+                got = po.po_schedule_ops(po.PO_SCHED_PO, d, rank, v, m, ratio, policy, prefetch, group=g)
+                passes = sch.compute_passes("po", d, rank, v, m, g or None)
+                want = sch.with_offload(passes, sch.selected_units(m, v, ratio, pname), prefetch)
+                assert got == want
+                assert sch.simulate(got)["errors"] == []
+
+
+def test_uniform_repeat_rejects_bad_groups():
+    for g in (3, 9):
+        with pytest.raises(po.PipeOffloadError) as e:
+            po.po_schedule_ops(po.PO_SCHED_PO, 8, 0, 2, 32, 0.5, group=g)
+        assert e.value.code == po.PO_E_INVAL
+
+
 def test_gis_schedule_rejects_bad_groups():
     for g, m in [(3, 32), (9, 32), (8, 30)]:
         with pytest.raises(po.PipeOffloadError) as e:

@@ -302,6 +302,38 @@ def test_gis_schedule_against_oracle_and_schedule_model(gpu_device, group):
         _assert_bit_identical(results[0.0], _snapshot(r))
 
 
+@pytest.mark.parametrize("rank,m", [(0, 8), (0, 7), (3, 6)])
+def test_uniform_repeat_schedule_against_oracle_and_schedule_model(gpu_device, rank, m):
+    """The uniformly repeated schedule (Section 2; PO of Table 1) with stage-level selection: ratio 0.5 offloads
+    chunk 0 of every microbatch (PO-H), ratio 1 both chunks (PO-F); any number of microbatches."""
+    d, v = 4, 2
+    shape = syn.StageShape(4, v, 128, 2, 512, 64, dtype="bf16", pipeline_degree=d, rank=rank, n_microbatches=m)
+    results = {}
+    for ratio in (0.0, 0.5, 1.0):
+        with StageRunner(shape, select_policy=po.PO_SEL_LONGEST_LIFESPAN) as r:
+            r.make_inputs()
+            stats = r.run(po.PO_SCHED_PO, ratio)
+            results[ratio] = _snapshot(r)
+            passes = sch.uniform_repeat(d, rank, v, m)
+            ops = sch.with_offload(passes, sch.selected_units(m, v, ratio, "longest-lifespan"), r.cfg.prefetch_passes)
+            model = sch.simulate(ops)
+            assert model["errors"] == []
+            assert stats["peak_in_flight_units"] == model["peak_in_flight"]
+            assert stats["peak_resident_units"] == model["peak_resident"]
+            assert stats["n_compute_passes"] == 3 * m * v
+            assert stats["n_offloads"] == stats["n_reloads"] == int(ratio * v) * m * shape.layers_per_chunk  # per layer slab
+            if ratio == 0.0:
+                _compare(shape, r.results(), _oracle(shape, r, m), 2e-2)
+    for ratio in (0.5, 1.0):
+        _assert_bit_identical(results[0.0], results[ratio])
+    # each chunk still sees its microbatches in ascending order: same sums, same order as the fused interleaved run
+    if m % d == 0:
+        with StageRunner(shape) as r:
+            r.make_inputs()
+            r.run(po.PO_SCHED_1F1B_INTERLEAVED, 0.0)
+            _assert_bit_identical(results[0.0], _snapshot(r))
+
+
 def test_short_gap_units_are_not_offloaded(gpu_device):
     # last rank of 1F1B: every backward directly follows its forward; with min_gap_passes = 1 nothing moves
     shape = syn.StageShape(2, 1, 128, 2, 512, 64, dtype="bf16", pipeline_degree=4, rank=3, n_microbatches=6)
