@@ -466,6 +466,155 @@ bool colsum_accumulate(int dtype, const void* x, float* acc, float* workspace, i
 }
 
 // --------------------------------------------------------------------------
+// Batched column reductions: the jobs' column blocks are laid end to end on grid.x
+// --------------------------------------------------------------------------
+struct ReduceBatch {
+  ReduceJob job[kMaxReduceJobs];
+  int first128[kMaxReduceJobs + 1];  // first 128-column block of job j on the partial kernel's grid.x
+  int first64[kMaxReduceJobs + 1];   // first 64-column block of job j on the final kernel's grid.x
+  int n_jobs;
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void reduce_batch_partial_kernel(ReduceBatch b, int rows, int rows_per_chunk) {
+  __shared__ float red[4][128][2];
+  int j = 0;
+  while (j + 1 < b.n_jobs && (int)blockIdx.x >= b.first128[j + 1]) ++j;
+  const ReduceJob& job = b.job[j];
+  int n = job.n;
+  int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  int col0 = ((int)blockIdx.x - b.first128[j]) * 128;
+  int col = col0 + lane * 2;
+  int r0 = blockIdx.y * rows_per_chunk;
+  int r1 = min(rows, r0 + rows_per_chunk);
+  const T* a = static_cast<const T*>(job.a);
+  if (job.x == nullptr) {  // plain column sum, as colsum_partial_kernel
+    float a0 = 0.f, a1 = 0.f;
+    if (col < n) {
+      for (int r = r0 + wave; r < r1; r += 4) {
+        a0 += to_f32(a[(size_t)r * n + col]);
+        a1 += to_f32(a[(size_t)r * n + col + 1]);
+      }
+    }
+    red[wave][lane * 2][0] = a0;
+    red[wave][lane * 2 + 1][0] = a1;
+    __syncthreads();
+    if (threadIdx.x < 128) {
+      int c = col0 + threadIdx.x;
+      if (c < n)
+        job.partials[(size_t)blockIdx.y * n + c] =
+            red[0][threadIdx.x][0] + red[1][threadIdx.x][0] + red[2][threadIdx.x][0] + red[3][threadIdx.x][0];
+    }
+  } else {  // LayerNorm gain / shift partials, as ln_backward_cols_kernel
+    const T* x = static_cast<const T*>(job.x);
+    const float* stats = job.stats;
+    float g0 = 0.f, g1 = 0.f, b0 = 0.f, b1 = 0.f;
+    if (col < n) {
+      for (int r = r0 + wave; r < r1; r += 4) {
+        float mean = stats[2 * r], rstd = stats[2 * r + 1];
+        float d0 = to_f32(a[(size_t)r * n + col]), d1 = to_f32(a[(size_t)r * n + col + 1]);
+        float x0 = to_f32(x[(size_t)r * n + col]), x1 = to_f32(x[(size_t)r * n + col + 1]);
+        g0 += d0 * (x0 - mean) * rstd;
+        g1 += d1 * (x1 - mean) * rstd;
+        b0 += d0;
+        b1 += d1;
+      }
+    }
+    red[wave][lane * 2][0] = g0;
+    red[wave][lane * 2 + 1][0] = g1;
+    red[wave][lane * 2][1] = b0;
+    red[wave][lane * 2 + 1][1] = b1;
+    __syncthreads();
+    if (threadIdx.x < 128) {
+      int c = col0 + threadIdx.x;
+      if (c < n) {
+        float sg = 0.f, sb = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          sg += red[w][threadIdx.x][0];
+          sb += red[w][threadIdx.x][1];
+        }
+        job.partials[((size_t)blockIdx.y * 2 + 0) * n + c] = sg;
+        job.partials[((size_t)blockIdx.y * 2 + 1) * n + c] = sb;
+      }
+    }
+  }
+}
+
+// The fixed tree of chunk_partials_final_kernel, per job with one or two output planes.
+__global__ __launch_bounds__(256) void reduce_batch_final_kernel(ReduceBatch b, int n_chunks) {
+  __shared__ float red[2][4][64];
+  int j = 0;
+  while (j + 1 < b.n_jobs && (int)blockIdx.x >= b.first64[j + 1]) ++j;
+  const ReduceJob& job = b.job[j];
+  int n = job.n;
+  int n_out = job.x ? 2 : 1;
+  int part = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  int c = ((int)blockIdx.x - b.first64[j]) * 64 + lane;
+  float acc[2] = {0.f, 0.f};
+  if (c < n) {
+#pragma unroll
+    for (int o = 0; o < 2; ++o) {
+      if (o < n_out) {
+        float v[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          int k = part + 4 * i;
+          v[i] = k < n_chunks ? job.partials[((size_t)k * n_out + o) * n + c] : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[o] += v[i];
+      }
+    }
+  }
+  red[0][part][lane] = acc[0];
+  red[1][part][lane] = acc[1];
+  __syncthreads();
+  if (part == 0 && c < n) {
+    job.out0[c] += ((red[0][0][lane] + red[0][1][lane]) + red[0][2][lane]) + red[0][3][lane];
+    if (n_out == 2) job.out1[c] += ((red[1][0][lane] + red[1][1][lane]) + red[1][2][lane]) + red[1][3][lane];
+  }
+}
+
+size_t column_reductions_workspace(int rows, int n) { return (size_t)reduce_chunks(rows) * n * sizeof(float); }
+
+bool column_reductions(int dtype, const ReduceJob* jobs, int n_jobs, int rows, hipStream_t stream) {
+  if (n_jobs < 1 || n_jobs > kMaxReduceJobs || rows <= 0 || !jobs) {
+    set_error("column_reductions: n_jobs=%d rows=%d", n_jobs, rows);
+    return false;
+  }
+  ReduceBatch b;
+  b.n_jobs = n_jobs;
+  b.first128[0] = b.first64[0] = 0;
+  for (int j = 0; j < n_jobs; ++j) {
+    const ReduceJob& job = jobs[j];
+    if (job.n <= 0 || job.n % 2 != 0 || !job.a || !job.out0 || !job.partials ||
+        (job.x && (!job.stats || !job.out1))) {
+      set_error("column_reductions: job %d: n=%d a=%p out0=%p partials=%p x=%p stats=%p out1=%p", j, job.n, job.a,
+                (void*)job.out0, (void*)job.partials, job.x, (const void*)job.stats, (void*)job.out1);
+      return false;
+    }
+    b.job[j] = job;
+    b.first128[j + 1] = b.first128[j] + ceil_div(job.n, 128);
+    b.first64[j + 1] = b.first64[j] + ceil_div(job.n, 64);
+  }
+  for (int j = n_jobs; j < kMaxReduceJobs; ++j) {
+    b.job[j] = ReduceJob{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0};
+    b.first128[j + 1] = b.first128[n_jobs];
+    b.first64[j + 1] = b.first64[n_jobs];
+  }
+  int n_chunks = reduce_chunks(rows);
+  int rows_per_chunk = ceil_div(rows, n_chunks);
+  dim3 g(b.first128[n_jobs], n_chunks);
+  if (dtype == kF32)
+    reduce_batch_partial_kernel<float><<<g, 256, 0, stream>>>(b, rows, rows_per_chunk);
+  else
+    reduce_batch_partial_kernel<bf16><<<g, 256, 0, stream>>>(b, rows, rows_per_chunk);
+  reduce_batch_final_kernel<<<b.first64[n_jobs], 256, 0, stream>>>(b, n_chunks);
+  return launch_ok("column reduction kernels");
+}
+
+// --------------------------------------------------------------------------
 // Embedding: x[p] = wte[tok[p]] + wpe[p]; backward adds dx into dwpe row by row
 // and into dwte with one block per vocabulary row scanning positions in order
 // (repeated tokens are summed in position order: deterministic, no atomics).

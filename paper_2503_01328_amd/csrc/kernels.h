@@ -22,6 +22,21 @@ bool layernorm_backward(int dtype, const void* dn, const void* x, const void* ga
                         hipStream_t stream);
 size_t colsum_workspace(int rows, int n);
 bool colsum_accumulate(int dtype, const void* x, float* acc, float* workspace, int rows, int n, hipStream_t stream);
+// Several column reductions over the same number of rows in two launches (all partial sums, then all final
+// sums) instead of two per tensor: the bias gradients and LayerNorm gain / shift gradients of one layer.
+// Per job the arithmetic and its order are those of colsum_accumulate / layernorm_backward(kLnParamGrad).
+struct ReduceJob {
+  const void* a;       // [rows, n] of dtype: the tensor summed over rows, or dn of a LayerNorm
+  const void* x;       // LayerNorm input [rows, n]; null: plain column sum
+  const float* stats;  // LayerNorm row statistics [rows][2] (mean, 1/std) left by kLnInputGrad; null for a sum
+  float* out0;         // [n] fp32, += column sum, or += gain gradient
+  float* out1;         // [n] fp32, += shift gradient (LayerNorm only)
+  float* partials;     // fp32 workspace: column_reductions_workspace(rows, n) floats, x2 for a LayerNorm job
+  int n;               // columns, even
+};
+constexpr int kMaxReduceJobs = 8;
+size_t column_reductions_workspace(int rows, int n);  // bytes per output plane
+bool column_reductions(int dtype, const ReduceJob* jobs, int n_jobs, int rows, hipStream_t stream);
 bool embedding_forward(int dtype, const int32_t* tok, const void* wte, const void* wpe, void* x, int s, int h,
                        int vocab, hipStream_t stream);
 bool embedding_backward(int dtype, const int32_t* tok, const void* dx, float* dwte, float* dwpe, int s, int h,

@@ -575,29 +575,40 @@ static int layer_backward_weight(po_stage* st, int layer, const char* slab, cons
   const bool drop = c.dropout_p > 0.f;
   const void* dz2 = drop ? (const void*)b.dz2 : dy;  // what the input-gradient half fed the MLP output projection
   const void* dz1 = drop ? (const void*)b.dz1 : (const void*)b.dx1;
+  const int wq = qkv_width_of(c);
+  // All six column reductions of the layer (four bias gradients, two LayerNorm gain / shift pairs) in two
+  // launches; their inputs are complete once the input-gradient half has run.
+  {
+    const size_t plane = column_reductions_workspace(s, 1) / sizeof(float);  // floats per column
+    float* ws = colws;
+    ReduceJob jobs[6];
+    auto sum_job = [&](const void* a, float* out, int n) {
+      ReduceJob j{a, nullptr, nullptr, out, nullptr, ws, n};
+      ws += plane * n;
+      return j;
+    };
+    jobs[0] = sum_job(dz2, st->G(layer, pl.b_fc2), h);
+    jobs[1] = sum_job(b.du, st->G(layer, pl.b_fc1), f);
+    jobs[2] = sum_job(dz1, st->G(layer, pl.b_o), h);
+    jobs[3] = sum_job(b.dqkv, st->G(layer, pl.b_qkv), wq);
+    jobs[4] = ReduceJob{b.dn2, x1, b.lnws2, st->G(layer, pl.ln2_g), st->G(layer, pl.ln2_b), b.lnws2 + (size_t)s * 2, h};
+    jobs[5] = ReduceJob{b.dn1, x, b.lnws1, st->G(layer, pl.ln1_g), st->G(layer, pl.ln1_b), b.lnws1 + (size_t)s * 2, h};
+    PO_K(column_reductions(dt, jobs, 6, s, q));
+  }
   Epilogue e = make_ep(h);
   e.acc_f32 = st->G(layer, pl.w_fc2);
   PO_RC(st_gemm(st, 1, 0, f, h, s, b.g, f, dz2, h, e, q));
-  PO_K(colsum_accumulate(dt, dz2, st->G(layer, pl.b_fc2), colws, s, h, q));
   PO_K(layernorm_forward(dt, x1, st->P(layer, pl.ln2_g), st->P(layer, pl.ln2_b), n_out, s, h, c.ln_eps, q));
   e = make_ep(f);
   e.acc_f32 = st->G(layer, pl.w_fc1);
   PO_RC(st_gemm(st, 1, 0, h, f, s, n_out, h, b.du, f, e, q));
-  PO_K(colsum_accumulate(dt, b.du, st->G(layer, pl.b_fc1), colws, s, f, q));
-  PO_K(layernorm_backward(dt, b.dn2, x1, st->P(layer, pl.ln2_g), nullptr, nullptr, st->G(layer, pl.ln2_g),
-                          st->G(layer, pl.ln2_b), b.lnws2, s, h, c.ln_eps, kLnParamGrad, q));
   e = make_ep(h);
   e.acc_f32 = st->G(layer, pl.w_o);
   PO_RC(st_gemm(st, 1, 0, h, h, s, o, h, dz1, h, e, q));
-  PO_K(colsum_accumulate(dt, dz1, st->G(layer, pl.b_o), colws, s, h, q));
   PO_K(layernorm_forward(dt, x, st->P(layer, pl.ln1_g), st->P(layer, pl.ln1_b), n_out, s, h, c.ln_eps, q));
-  const int wq = qkv_width_of(c);
   e = make_ep(wq);
   e.acc_f32 = st->G(layer, pl.w_qkv);
   PO_RC(st_gemm(st, 1, 0, h, wq, s, n_out, h, b.dqkv, wq, e, q));
-  PO_K(colsum_accumulate(dt, b.dqkv, st->G(layer, pl.b_qkv), colws, s, wq, q));
-  PO_K(layernorm_backward(dt, b.dn1, x, st->P(layer, pl.ln1_g), nullptr, nullptr, st->G(layer, pl.ln1_g),
-                          st->G(layer, pl.ln1_b), b.lnws1, s, h, c.ln_eps, kLnParamGrad, q));
   return PO_OK;
 }
 
@@ -1233,8 +1244,8 @@ int stage_create(const po_config* cfg, void* compute_stream, po_stage** out) {
   size_t sh = align_up(s * h * E, 256), sf = align_up(s * f * E, 256), s3h = align_up(s * (size_t)qkv_width_of(*cfg) * E, 256);
   size_t delta = align_up((size_t)cfg->n_heads * s * 4, 256);
   size_t lnws = align_up(layernorm_backward_workspace((int)s, (int)h), 256);
-  size_t maxn = std::max((size_t)3 * h, f);
-  size_t colws = align_up(colsum_workspace((int)s, (int)maxn), 256);
+  // partial sums of the four bias-gradient reductions of a layer, side by side
+  size_t colws = align_up(column_reductions_workspace((int)s, (int)(2 * h + f + (size_t)qkv_width_of(*cfg))), 256);
   bool grouped = kv_heads_of(*cfg) < cfg->n_heads;
   size_t total = 11 * sh + 2 * sf + s3h + delta + 2 * lnws + 2 * colws + (grouped ? 2 * sh : 0);
   // one unit's gradient buffer for the split backward: per layer g, du [s,f]; dn2, dx1, dn1, incoming dy, and the
