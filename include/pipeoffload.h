@@ -128,6 +128,7 @@ typedef struct po_stats {
   double gemm_flops;        /* profile_kernels: 2 M N K summed over those launches */
   double attn_busy_s;       /* profile_kernels: sum of the timed attention forward/backward launches' durations */
   double attn_flops;        /* profile_kernels: causal model flops of those, 2 s^2 h forward, 4 s^2 h backward */
+  double copy_hidden_s;     /* part of d2h_busy_s + h2d_busy_s during which a compute pass was running as well */
   uint64_t bytes_d2h, bytes_h2d;
   uint64_t peak_slab_bytes;      /* high-water mark of activation slab bytes in use (incl. staging) */
   uint64_t pool_bytes_allocated; /* device bytes the slab pool holds */

@@ -50,7 +50,7 @@ class po_op(C.Structure):
 class po_stats(C.Structure):
     _fields_ = [(n, C.c_double) for n in ("wall_s", "tokens_per_s", "compute_busy_s", "d2h_busy_s", "h2d_busy_s",
                                            "pack_busy_s", "compute_span_s", "gemm_busy_s", "gemm_flops",
-                                           "attn_busy_s", "attn_flops")] + \
+                                           "attn_busy_s", "attn_flops", "copy_hidden_s")] + \
                [(n, C.c_uint64) for n in ("bytes_d2h", "bytes_h2d", "peak_slab_bytes", "pool_bytes_allocated",
                                           "host_bytes_allocated", "workspace_bytes")] + \
                [(n, C.c_int32) for n in ("peak_resident_units", "peak_in_flight_units", "n_compute_passes",

@@ -1104,6 +1104,33 @@ static int collect_spans(po_stage* st) {
       }
     }
   }
+  // Copy time hidden behind compute: every offload / reload span intersected with the union of the compute spans.
+  if (!st->spans.empty()) {
+    hipEvent_t origin = st->spans[0].start;
+    std::vector<std::pair<float, float>> comp, copies;
+    for (const TimedSpan& sp : st->spans) {
+      if (sp.kind > 2) continue;
+      float a = 0.f, b = 0.f;
+      PO_HIP(hipEventElapsedTime(&a, origin, sp.start));
+      PO_HIP(hipEventElapsedTime(&b, origin, sp.stop));
+      (sp.kind == 0 ? comp : copies).push_back({a, b});
+    }
+    std::sort(comp.begin(), comp.end());
+    std::vector<std::pair<float, float>> merged;
+    for (const auto& iv : comp) {
+      if (!merged.empty() && iv.first <= merged.back().second)
+        merged.back().second = std::max(merged.back().second, iv.second);
+      else
+        merged.push_back(iv);
+    }
+    double hidden = 0.0;
+    for (const auto& cp : copies)
+      for (const auto& iv : merged) {
+        float lo = std::max(cp.first, iv.first), hi = std::min(cp.second, iv.second);
+        if (hi > lo) hidden += hi - lo;
+      }
+    st->stats.copy_hidden_s = hidden * 1e-3;
+  }
   st->stats.compute_busy_s = busy[0];
   st->stats.d2h_busy_s = busy[1];
   st->stats.h2d_busy_s = busy[2];
