@@ -64,6 +64,10 @@ def run(config: str, iters: int = 20):
     ws2 = torch.empty(po.po_op_colsum_workspace(s, f) // 4, device=dev)
     t = _time(lambda: po.po_op_colsum_accumulate(po.PO_BF16, du, acc, ws2, s, f), iters)
     add("column sums [s,f] (bias gradient)", "hbm", s * f * E, t, HBM_PEAK)
+    # hidden dropout with a regenerated mask: out = residual + dropout(x)
+    xo = torch.empty(s, h, device=dev, dtype=bf)
+    t = _time(lambda: po.po_op_dropout(po.PO_BF16, dn, xo, s, h, 0.1, 1234, 0, 0, 0), iters)
+    add("dropout [s,h] (Philox mask regenerated, x -> out)", "hbm", 2 * s * h * E, t, HBM_PEAK)
     # pack / unpack of one layer's saved set
     sizes = [s * h * E, s * 3 * h * E, s * h * E, s * h * E, s * f * E, a * s * 4]
     segs = [torch.empty(n, dtype=torch.uint8, device=dev) for n in sizes]
