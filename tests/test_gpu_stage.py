@@ -105,6 +105,10 @@ def test_offload_is_bit_identical_in_every_mode(gpu_device, shape):
             stats2 = r.run(po.PO_SCHED_1F1B, ratio)
             _assert_bit_identical(snap, _snapshot(r))
             assert stats2["pool_bytes_allocated"] == stats["pool_bytes_allocated"]
+            # copy time hidden behind compute: none without copies, never more than the copies took
+            busy = stats2["d2h_busy_s"] + stats2["h2d_busy_s"]
+            assert 0.0 <= stats2["copy_hidden_s"] <= busy * (1 + 1e-6) + 1e-9
+            assert (busy == 0.0) == (ratio == 0.0)
         if base is None:
             base = snap
         else:
