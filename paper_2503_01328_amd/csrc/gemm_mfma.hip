@@ -2,7 +2,8 @@
 //
 // One 256-thread block (4 waves, 2 x 2) owns a (64*WTM) x (64*WTN) tile of C; a
 // wave owns WTM x WTN MFMA tiles of 32 x 32, i.e. up to 128 x 128 with 256 fp32
-// accumulators per lane.  K is walked in slices of 64, double-buffered in LDS.
+// accumulators per lane.  K is walked in slices of 64 through a ring of LDS stages: two for the
+// 256 x 256 tile, four for the 128 x 128 tile, whose slices are too short to cover a memory round trip.
 //
 // Operand slices travel HBM -> LDS directly (global_load_lds_dwordx4: lane L of
 // a wave deposits its 16 bytes at LDS base + 16 L), so no registers and no
@@ -90,7 +91,11 @@ __device__ __forceinline__ void load_slice(const bf16* __restrict__ base, int ld
   }
 }
 
-__device__ __forceinline__ void wait_slice_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// Waits until at most N of this wave's loads are outstanding (they complete in issue order).
+template <int N>
+__device__ __forceinline__ void wait_slice_loads() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 
 // ---- LDS -> MFMA fragment: 32 rows (row0 + lane % 32), k = 16 kk + 8 (lane / 32) + 0..7 ----
 template <int R, bool KMAJOR>
@@ -216,10 +221,25 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int K, const bf16* __res
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+  // The slices travel through a ring of NSTAGE LDS stages; slice kt + NSTAGE - 1 is requested while slice kt
+  // is multiplied, and a wave lets the NSTAGE - 2 youngest requested slices stay in flight when it waits for
+  // the slice that the next barrier publishes.  The big tile has room for two stages (its slice takes about a
+  // microsecond, which covers the round trip); the small tile's slice is four times shorter, so it gets four.
+  constexpr int NSTAGE = (WTM * WTN >= 16) ? 2 : 4;
+  constexpr int PER_SLICE = (BM + BN) * 128 / 1024 / 4;  // load instructions of one wave per slice
   int nk = K / kBK;
-  load_slice<BM, TA>(a_base, lda, 0, smem, wave, lane);
-  load_slice<BN, TB>(b_base, ldb, 0, smem + A_BYTES, wave, lane);
-  wait_slice_loads();
+  auto request = [&](int kt, int part) {
+    char* st = smem + (kt % NSTAGE) * STAGE;
+    load_slice<BM, TA>(a_base, lda, kt * kBK, st, wave, lane, part);
+    load_slice<BN, TB>(b_base, ldb, kt * kBK, st + A_BYTES, wave, lane, part);
+  };
+  {
+    int ahead = min(nk, NSTAGE - 1);
+    for (int t = 0; t < ahead; ++t) request(t, -1);
+    if (ahead >= 3) wait_slice_loads<2 * PER_SLICE>();
+    else if (ahead == 2) wait_slice_loads<PER_SLICE>();
+    else wait_slice_loads<0>();
+  }
   __syncthreads();
 
   bf16x8 fa[2][WTM], fb[2][WTN];
@@ -235,22 +255,22 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int K, const bf16* __res
   };
   load_fragments(smem, 0, 0);
 
-  // One slice: MFMAs on `cur`; with MORE, the next slice streams into `nxt` meanwhile.  The last
-  // slice is peeled off so that the steady-state loop body has no branches.
-  auto slice = [&](int kt, auto more_tag) {
-    constexpr bool MORE = decltype(more_tag)::value;
-    char* cur = smem + (kt & 1) * STAGE;
-    char* nxt = smem + ((kt + 1) & 1) * STAGE;
+  // One slice: MFMAs on stage kt % NSTAGE.  ISSUE: slice kt + NSTAGE - 1 is requested meanwhile.  KEEP: how
+  // many requested slices may still be in flight at the wait before the barrier (-1: last slice, nothing to
+  // publish).  The tail slices are peeled off so that the steady-state loop body has no branches.
+  auto slice = [&](int kt, auto issue_tag, auto keep_tag) {
+    constexpr bool ISSUE = decltype(issue_tag)::value;
+    constexpr int KEEP = decltype(keep_tag)::value;
+    constexpr bool MORE = KEEP >= 0;
+    char* cur = smem + (kt % NSTAGE) * STAGE;
+    char* nxt = smem + ((kt + 1) % NSTAGE) * STAGE;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       if (kk < 3) load_fragments(cur, kk + 1, (kk + 1) & 1);
-      if (MORE && kk < 2) {  // the next slice is issued under the first two k-steps (half each): early
-                             // enough to land before the barrier, spread enough not to stall the issue
+      if (ISSUE && kk < 2) {  // the request is spread over the first two k-steps (half each): early enough
+                              // to land in time, spread enough not to stall the issue
 #pragma unroll
-        for (int q = 2 * kk; q < 2 * kk + 2; ++q) {
-          load_slice<BM, TA>(a_base, lda, (kt + 1) * kBK, nxt, wave, lane, q);
-          load_slice<BN, TB>(b_base, ldb, (kt + 1) * kBK, nxt + A_BYTES, wave, lane, q);
-        }
+        for (int q = 2 * kk; q < 2 * kk + 2; ++q) request(kt + NSTAGE - 1, q);
       }
 #pragma unroll
       for (int t = 0; t < (WTM > WTN ? WTM : WTN); ++t) {  // ring t of the growing square
@@ -274,12 +294,22 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int K, const bf16* __res
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (MORE) wait_slice_loads();
+    if (MORE) wait_slice_loads<(KEEP > 0 ? KEEP : 0) * PER_SLICE>();
     __syncthreads();
     if (MORE) load_fragments(nxt, 0, 0);
   };
-  for (int kt = 0; kt + 1 < nk; ++kt) slice(kt, std::true_type{});
-  slice(nk - 1, std::false_type{});
+  {
+    using T = std::true_type;
+    using F = std::false_type;
+    int kt = 0;
+    for (; kt + NSTAGE - 1 < nk; ++kt) slice(kt, T{}, std::integral_constant<int, NSTAGE - 2>{});
+    // nothing left to request: the last NSTAGE - 1 slices, each letting one slice less stay in flight
+    if (NSTAGE == 4) {
+      if (nk >= 3) slice(nk - 3, F{}, std::integral_constant<int, 1>{});
+      if (nk >= 2) slice(nk - 2, F{}, std::integral_constant<int, 0>{});
+    }
+    slice(nk - 1, F{}, std::integral_constant<int, -1>{});
+  }
 
   // Epilogue.  acc[i][j][4q + r] = C[m][n], m = strip row (lane & 31), n = 32 j + 8 q + 4 (lane >> 5) + r.
   // Each wave owns a private [32][WTN*32 + 4] fp32 strip in LDS (the operand buffers are free now).
@@ -346,7 +376,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int K, const bf16* __res
 
 // ---- host side ------------------------------------------------------------------
 // 256 x 256 tiles once they fill three quarters of the 256 CUs in one round (measured: 192 big tiles beat 768
-// small ones, 57 against 63 us at M = 2048, N = 6144, K = 2048); below that the 128 x 128 tile.
+// small ones, 58 against 63 us at M = 2048, N = 6144, K = 2048); below that the 128 x 128 tile.
 static int tile_threshold() { return 192; }
 static void pick_tile(int M, int N, int& wtm, int& wtn) {
   wtm = wtn = 0;
@@ -369,7 +399,7 @@ template <int WTM, int WTN, bool TA, bool TB, int EPI>
 static bool launch_mfma_epi(int M, int N, int K, const bf16* A, int lda, const bf16* B, int ldb, const Epilogue& ep,
                             hipStream_t stream) {
   constexpr int BM = 64 * WTM, BN = 64 * WTN;
-  constexpr int smem_ops = 2 * (BM + BN) * 128;
+  constexpr int smem_ops = ((WTM * WTN >= 16) ? 2 : 4) * (BM + BN) * 128;
   constexpr int smem_epi = 4 * 32 * (WTN * 32 + 4) * 4;
   constexpr int smem = smem_ops > smem_epi ? smem_ops : smem_epi;
   auto kern = gemm_mfma_kernel<WTM, WTN, TA, TB, EPI>;
