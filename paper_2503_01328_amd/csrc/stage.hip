@@ -331,7 +331,7 @@ struct po_stage {
   char* w_dkv_part = nullptr;  // [s, 2h] per-query-head dK/dV of grouped-query attention (null with multi-head)
   char* w_dz[2];  // dropout-masked gradients of the fused backward
   char* w_n_w;  // LayerNorm recompute output of the weight-gradient half (own buffer: it may run on its own stream)
-  float *w_delta, *w_lnws, *w_lnws1, *w_colws, *w_colws_w;
+  float *w_delta, *w_lnws, *w_lnws1, *w_colws_w;
   // accounting
   int resident_units = 0, in_flight_units = 0;
   po_stats stats;
@@ -1274,7 +1274,7 @@ int stage_create(const po_config* cfg, void* compute_stream, po_stage** out) {
   // partial sums of the four bias-gradient reductions of a layer, side by side
   size_t colws = align_up(column_reductions_workspace((int)s, (int)(2 * h + f + (size_t)qkv_width_of(*cfg))), 256);
   bool grouped = kv_heads_of(*cfg) < cfg->n_heads;
-  size_t total = 11 * sh + 2 * sf + s3h + delta + 2 * lnws + 2 * colws + (grouped ? 2 * sh : 0);
+  size_t total = 11 * sh + 2 * sf + s3h + delta + 2 * lnws + colws + (grouped ? 2 * sh : 0);
   // one unit's gradient buffer for the split backward: per layer g, du [s,f]; dn2, dx1, dn1, incoming dy, and the
   // two dropout-masked gradients [s,h];
   // dqkv [s,3h]; two LayerNorm workspaces; plus one [s,h] tensor per unit (gradient at the embedding output)
@@ -1316,7 +1316,6 @@ int stage_create(const po_config* cfg, void* compute_stream, po_stage** out) {
   st->w_delta = (float*)take(delta);
   st->w_lnws = (float*)take(lnws);
   st->w_lnws1 = (float*)take(lnws);
-  st->w_colws = (float*)take(colws);
   st->w_colws_w = (float*)take(colws);
   if (grouped) st->w_dkv_part = take(2 * sh);
   reset_run_stats(st);
