@@ -94,6 +94,9 @@ def main():
     ap.add_argument("--kv-heads", type=int, default=0,
                     help="grouped-query attention with this many key/value heads (Table 2 uses 8); 0 = multi-head")
     ap.add_argument("--dropout", type=float, default=0.0, help="hidden dropout probability (masks regenerated in backward)")
+    ap.add_argument("--only-ratio-0", action="store_true",
+                    help="measure ratio 0 only (for a kernel profile of the compute path without copy kernels beside "
+                         "it); value is then the tokens/s at ratio 0 and the workload string says so")
     ap.add_argument("--group", type=int, default=0,
                     help="group size g of --schedule gis (0 = pipeline degree) or po (0 = half the pipeline degree)")
     ap.add_argument("--select", default="auto", choices=["auto", "alternate-mb", "longest-lifespan"],
@@ -161,16 +164,17 @@ def main():
                 attn_busy_ms=agg["attn_busy_s"] * 1e3 * args.profile_every,
                 mfu=model_flops_per_run(shape) / dt / (PEAK_BF16_TFLOPS * 1e12),
             )
-        for ratio in (0.0, 0.5, 1.0):
+        for ratio in ((0.0,) if args.only_ratio_0 else (0.0, 0.5, 1.0)):
             ratios[ratio] = measure(ratio)
+        top = max(ratios)  # 1.0 unless --only-ratio-0
         # Largest ratio whose transfers should still hide: k measured as the busier copy direction at ratio 1 over
         # the step time at ratio 0 (both directions run at once on this machine), ratio = min(1, 1 / k).
-        one = ratios[1.0]
+        one = ratios[top]
         busy = [b for b in ((one["d2h_busy_ms"], one["h2d_busy_ms"])) if b]
         k_transfer = (max(busy) / ratios[0.0]["ms_per_step"]) if busy else None
         if k_transfer and not args.no_auto_ratio:
             auto = po.po_offload_ratio_for_k(k_transfer)
-            ratios["auto"] = dict(ratios[1.0]) if auto >= 1.0 else measure(auto)
+            ratios["auto"] = dict(ratios[top]) if auto >= 1.0 else measure(auto)
             ratios["auto"]["ratio"] = auto
             ratios["auto"]["k_transfer_measured"] = k_transfer
         base = ratios[0.0]["ms_per_step"]
@@ -180,7 +184,7 @@ def main():
             else:
                 d["overlap"] = None
             d["throughput_vs_no_offload"] = base / d["ms_per_step"]
-        headline = ratios[1.0]
+        headline = ratios[top]
         # Eq. 1 with measured rates: compute rate = model flops / compute time at ratio 0, link rate = measured D2H
         bc = model_flops_per_run(shape) / (ratios[0.0]["ms_per_step"] * 1e-3)
         bo = (headline["d2h_gb_per_s"] or 0) * 1e9
@@ -197,7 +201,7 @@ def main():
                                f"{shape.n_heads} heads{' (%d key/value heads)' % shape.n_kv_heads if shape.n_kv_heads else ''}, FFN {shape.ffn}, seq {shape.seq}, {shape.n_microbatches} "
                                f"microbatches, simulated pipeline degree {shape.pipeline_degree}, "
                                f"schedule {sched_name}{' g=%d' % args.group if args.group else ''} rank 0; "
-                               f"value is at offload ratio 1",
+                               f"value is at offload ratio {top:g}",
                    "copy_streams": args.copy_streams, "prefetch_passes": args.prefetch, "staged_copies": args.staged,
                    "weight_stream": args.weight_stream, "dropout": args.dropout, "select": select},
         "ratios": {str(k): v for k, v in ratios.items()},
