@@ -36,6 +36,10 @@ independent model, in plain Python integers, of what one pipeline rank executes:
   Peak memory is then about the summed lifespans over the period, which gives
   the stage-level selective offload of Section 2 (longest lifespan first) its
   better-than-linear effect.
+* Slot placement (Section 4.2): on the unsqueezed uniformly repeated timeline a
+  single copy stream is cut into alternating offload and reload slots whose
+  length follows from k; offloads take the earliest free slot after their
+  forward, reloads the latest free slot before their backward.
 
 Op tuples are (kind, mb, chunk) with kind in {"F", "B", "W", "OFFLOAD", "RELOAD"}.
 """
@@ -228,6 +232,69 @@ def uniform_repeat(d, rank, v, m, g=None):
                 timed.append((t + 3 * v * n, kind, n, c))
     timed.sort()
     return [(kind, n, c) for _, kind, n, c in timed]
+
+
+def uniform_repeat_times(d, rank, v, m, g=None):
+    """The uniformly repeated schedule of ``rank`` with its unit-time start times (bubbles kept): a list of
+    (start, kind, mb, chunk) sorted by start."""
+    g = math.ceil(d / 2) if g is None else g
+    block = building_block(d, v, g)
+    timed = [(t + 3 * v * n, kind, n, c) for (kind, i, c), t in block.items() if i == rank for n in range(m)]
+    timed.sort()
+    return timed
+
+
+def slot_placement(timed, offload_chunks, k):
+    """Offload and reload slots on one shared copy stream (Section 4.2, Figure 7).
+
+    ``timed``: a rank's passes with unit-time starts (F = B = W = 1).  k (Eq. 1): a unit's round trip over its
+    F + B + W time, so an offload takes 1.5 k units and a reload the same.  The stream is cut into slots in a
+    one-offload-one-reload pattern from time 0: offload slot i is [3 k i, 3 k i + 1.5 k), reload slot i follows
+    it up to 3 k (i + 1).  The units of the chosen chunks are taken left to right by the end of their forward
+    and get the earliest free offload slot that starts no earlier; then right to left by the start of their
+    backward and get the latest free reload slot that ends no later.  A unit whose reload slot would start
+    before its offload slot has ended is not offloaded at all (Section 4.4: its gap is shorter than the round
+    trip); its slots stay empty, like every slot nobody claimed.
+    Returns {(mb, chunk): (offload_slot, reload_slot)}."""
+    if k <= 0:
+        raise ValueError("k must be positive")
+    pair = 3.0 * k
+    f_end, b_start = {}, {}
+    for start, kind, mb, c in timed:
+        if c in offload_chunks:
+            if kind == "F":
+                f_end[(mb, c)] = start + 1
+            elif kind == "B":
+                b_start[(mb, c)] = start
+    eps = 1e-9
+    off_slot, used = {}, set()
+    for u in sorted(f_end, key=lambda u: (f_end[u], u)):
+        i = max(0, math.ceil(f_end[u] / pair - eps))
+        while i in used:
+            i += 1
+        used.add(i)
+        off_slot[u] = i
+    rel_slot, used = {}, set()
+    for u in sorted(b_start, key=lambda u: (-b_start[u], u)):
+        i = math.floor(b_start[u] / pair + eps) - 1  # reload slot i ends at pair (i + 1)
+        while i in used:
+            i -= 1
+        used.add(i)
+        rel_slot[u] = i
+    # reload slot i starts at pair i + pair / 2, offload slot j ends at pair j + pair / 2
+    return {u: (off_slot[u], rel_slot[u]) for u in off_slot if rel_slot[u] >= off_slot[u]}
+
+
+def with_slot_offload(timed, placement, k):
+    """Op list of the slot plan: compute passes by start time, OFFLOAD / RELOAD ops at the start times of
+    their slots (a copy that starts together with a pass is listed first)."""
+    pair = 3.0 * k
+    events = [(start, 1, (kind, mb, c)) for start, kind, mb, c in timed]
+    for (mb, c), (i, j) in placement.items():
+        events.append((pair * i, 0, ("OFFLOAD", mb, c)))
+        events.append((pair * j + pair / 2, 0, ("RELOAD", mb, c)))
+    events.sort(key=lambda e: (e[0], e[1], e[2][0] != "RELOAD", e[2][1:]))
+    return [op for _, _, op in events]
 
 
 def peak_units(passes, offloaded_chunks=()):

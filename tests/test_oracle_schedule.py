@@ -360,3 +360,100 @@ def test_peak_units_against_the_state_machine():
     # brute force on a hand-written list: units (0,0) (1,0) (0,1) held, chunk 0 free of charge
     ops = [("F", 0, 0), ("F", 1, 0), ("F", 0, 1), ("B", 0, 1), ("W", 0, 1), ("B", 0, 0), ("W", 0, 0), ("B", 1, 0), ("W", 1, 0)]
     assert sch.peak_units(ops) == 3 and sch.peak_units(ops, {0}) == 1 and sch.peak_units(ops, {1}) == 2
+
+
+# ---- slot placement on one shared copy stream (Section 4.2, Figure 7) --------------------------------------------
+def _slot_times(placement, k):
+    pair = 3.0 * k
+    off = {u: (pair * i, pair * i + pair / 2) for u, (i, _) in placement.items()}
+    rel = {u: (pair * j + pair / 2, pair * (j + 1)) for u, (_, j) in placement.items()}
+    return off, rel
+
+
+@pytest.mark.parametrize("d,v,m,chunks,k", [(8, 2, 16, {0}, 1.0), (4, 2, 8, {0}, 1.0), (8, 4, 16, {0, 1}, 1.0),
+                                            (8, 4, 12, {0}, 0.5), (4, 2, 9, {0, 1}, 0.4), (6, 3, 10, {0}, 1.7)])
+def test_slot_placement_respects_passes_and_slots(d, v, m, chunks, k):
+    for rank in (0, d // 2, d - 1):
+        timed = sch.uniform_repeat_times(d, rank, v, m)
+        assert [(kind, mb, c) for _, kind, mb, c in timed] == sch.uniform_repeat(d, rank, v, m)
+        placement = sch.slot_placement(timed, chunks, k)
+        f_end = {(mb, c): t + 1 for t, kind, mb, c in timed if kind == "F"}
+        b_start = {(mb, c): t for t, kind, mb, c in timed if kind == "B"}
+        off, rel = _slot_times(placement, k)
+        for u in placement:
+            assert u[1] in chunks
+            assert off[u][0] >= f_end[u] - 1e-9       # offload no earlier than the end of the forward
+            assert rel[u][1] <= b_start[u] + 1e-9     # reload done by the start of the backward
+            assert rel[u][0] >= off[u][1] - 1e-9      # and not before the offload has ended
+        # one copy at a time on the shared stream
+        spans = sorted(list(off.values()) + list(rel.values()))
+        assert all(a[1] <= b[0] + 1e-9 for a, b in zip(spans, spans[1:]))
+        assert len({i for i, _ in placement.values()}) == len(placement) == len({j for _, j in placement.values()})
+        ops = sch.with_slot_offload(timed, placement, k)
+        r = sch.simulate(ops)
+        assert r["errors"] == []
+        assert [o for o in ops if o[0] in "FBW"] == sch.uniform_repeat(d, rank, v, m)
+        assert r["peak_resident"] <= r["peak_in_flight"]
+
+
+def test_slot_placement_figure7_setting_places_every_unit():
+    # Figure 7: one stage offloaded per device, k = 1: every microbatch's unit of that stage finds its slots, the
+    # offload within one slot pair of the end of its forward
+    for d, v in [(8, 2), (4, 2), (8, 4)]:
+        timed = sch.uniform_repeat_times(d, 0, v, 4 * d)
+        placement = sch.slot_placement(timed, {0}, 1.0)
+        assert len(placement) == 4 * d
+        f_end = {(mb, c): t + 1 for t, kind, mb, c in timed if kind == "F"}
+        off, _ = _slot_times(placement, 1.0)
+        assert max(off[u][0] - f_end[u] for u in placement) < 3.0 + 1e-9
+
+
+def test_slot_placement_is_the_extreme_assignment_by_brute_force():
+    # left to right, earliest slot: no assignment that keeps every offload after its forward is lexicographically
+    # smaller; right to left, latest slot: none that keeps every reload before its backward is larger
+    import itertools
+    d, v, m, k = 4, 2, 3, 0.9
+    timed = sch.uniform_repeat_times(d, 0, v, m)
+    chunks = {0, 1}
+    pair = 3.0 * k
+    f_end = {(mb, c): t + 1 for t, kind, mb, c in timed if kind == "F"}
+    b_start = {(mb, c): t for t, kind, mb, c in timed if kind == "B"}
+    units_f = sorted(f_end, key=lambda u: (f_end[u], u))
+    units_b = sorted(b_start, key=lambda u: (-b_start[u], u))
+    horizon = int(max(b_start.values()) / pair) + 2
+    best_off = min(a for a in itertools.permutations(range(horizon), len(units_f))
+                   if all(pair * i >= f_end[u] - 1e-9 for u, i in zip(units_f, a)))
+    best_rel = max(a for a in itertools.permutations(range(horizon), len(units_b))
+                   if all(pair * (j + 1) <= b_start[u] + 1e-9 for u, j in zip(units_b, a)))
+    placement = sch.slot_placement(timed, chunks, k)
+    want = {u: (i, dict(zip(units_b, best_rel))[u]) for u, i in zip(units_f, best_off)}
+    assert placement == {u: ij for u, ij in want.items() if ij[1] >= ij[0]}
+    assert len(placement) >= 1
+
+
+def test_slot_placement_drops_units_whose_gap_is_shorter_than_the_round_trip():
+    d, v, m = 8, 2, 16
+    timed = sch.uniform_repeat_times(d, 0, v, m)
+    placed = [len(sch.slot_placement(timed, {0, 1}, k)) for k in (0.25, 0.5, 1.0, 2.0, 4.0, 16.0)]
+    assert placed[0] == 2 * m            # a fast link moves everything
+    assert all(a >= b for a, b in zip(placed, placed[1:])) and placed[-1] == 0
+    # the last rank's chunk v-1 has its backward right after its forward: never offloaded (Section 4.4)
+    last = sch.uniform_repeat_times(d, d - 1, v, m)
+    assert all(c != v - 1 for (_, c) in sch.slot_placement(last, {0, 1}, 0.25))
+
+
+def test_slot_demand_beyond_the_stream_capacity_drifts():
+    # one slot pair lasts 3k units and a microbatch arrives every 3v units: n chunks fit while n k <= v (Section 2:
+    # k tells which share can be offloaded); beyond that the offloads queue up further and further behind
+    d, v = 8, 2
+    def lag(k, m):
+        timed = sch.uniform_repeat_times(d, 0, v, m)
+        f_end = {(mb, c): t + 1 for t, kind, mb, c in timed if kind == "F"}
+        pl = sch.slot_placement(timed, {0}, k)
+        return max(3.0 * k * i - f_end[u] for u, (i, _) in pl.items()) if pl else 0.0
+    assert lag(2.0, 32) <= 6.0 + 1e-9 and lag(2.0, 64) <= 6.0 + 1e-9   # n k = v: keeps up
+    assert lag(1.0, 64) <= 3.0 + 1e-9
+
+
+def test_po_in_compute_passes_dispatch():
+    assert sch.compute_passes("po", 4, 1, 2, 6) == sch.uniform_repeat(4, 1, 2, 6)
