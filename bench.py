@@ -94,6 +94,9 @@ def main():
     ap.add_argument("--kv-heads", type=int, default=0,
                     help="grouped-query attention with this many key/value heads (Table 2 uses 8); 0 = multi-head")
     ap.add_argument("--dropout", type=float, default=0.0, help="hidden dropout probability (masks regenerated in backward)")
+    ap.add_argument("--slot-k", type=float, default=0.0,
+                    help="with --schedule po: place the copies into the slots of Section 4.2 for this k (a unit's "
+                         "round trip over its F + B + W time) instead of the prefetch rule; 0 = prefetch rule")
     ap.add_argument("--only-ratio-0", action="store_true",
                     help="measure ratio 0 only (for a kernel profile of the compute path without copy kernels beside "
                          "it); value is then the tokens/s at ratio 0 and the workload string says so")
@@ -129,7 +132,7 @@ def main():
     with StageRunner(shape, device_params=True, copy_streams=args.copy_streams, prefetch_passes=args.prefetch,
                      staged_copies=args.staged, profile_kernels=args.profile_every, group=args.group,
                      weight_stream=args.weight_stream, dropout_p=args.dropout, dropout_seed=20250301,
-                     select_policy=policy) as r:
+                     select_policy=policy, slot_k=args.slot_k) as r:
         r.make_inputs_on_device()
         def measure(ratio):
             for _ in range(args.warmup):
@@ -203,7 +206,8 @@ def main():
                                f"schedule {sched_name}{' g=%d' % args.group if args.group else ''} rank 0; "
                                f"value is at offload ratio {top:g}",
                    "copy_streams": args.copy_streams, "prefetch_passes": args.prefetch, "staged_copies": args.staged,
-                   "weight_stream": args.weight_stream, "dropout": args.dropout, "select": select},
+                   "weight_stream": args.weight_stream, "dropout": args.dropout, "select": select,
+                   "slot_k": args.slot_k},
         "ratios": {str(k): v for k, v in ratios.items()},
         "k_eq1_measured_serial": k_meas, "k_eq1_measured_duplex": (k_meas / 2 if k_meas else None),
         "roofline": {"bound": "mfma", "achieved": gemm["gemm_tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",

@@ -94,6 +94,8 @@ typedef struct po_config {
   float dropout_p;         /* 0 = none; else the outputs of the attention and MLP output projections are dropped
                               with this probability before the residual add, masks regenerated in backward from
                               (dropout_seed, layer, site, microbatch, position) instead of being stored (App. C) */
+  float slot_k;            /* > 0 with PO_SCHED_PO: po_run_schedule places the copies with po_schedule_ops_slots(k =
+                              slot_k) instead of the prefetch rule (Section 4.2); 0 = prefetch rule */
   uint64_t host_pool_cap_bytes;   /* 0 = unlimited; else PO_E_HOST_OOM beyond it */
   uint64_t device_pool_cap_bytes; /* 0 = unlimited; else PO_E_DEVICE_OOM beyond it */
   uint64_t dropout_seed;          /* key of the counter-based generator; change it between iterations with
@@ -160,6 +162,16 @@ int po_saved_bytes_per_layer(const po_config* cfg, uint64_t* bytes);
  * ahead of the backward).  out may be NULL to query *n. */
 int po_schedule_ops(int32_t schedule, int32_t d, int32_t rank, int32_t v, int32_t m, int32_t group, float ratio,
                     int32_t policy, int32_t prefetch, int32_t min_gap, po_op* out, int32_t* n);
+
+/* Section 4.2 (Figure 7): op list of the uniformly repeated schedule (PO_SCHED_PO, group as there) with the copies
+ * of chunks 0 .. n_offload_chunks-1 of every microbatch placed into the slots of one shared copy stream on the
+ * schedule's unit-time timeline (F = B = W = 1, bubbles kept): slot pairs of 3k units, an offload slot followed
+ * by a reload slot, k = a unit's round trip over its F + B + W time (Eq. 1).  Offloads take the earliest free
+ * slot that starts after their forward has ended, reloads the latest free slot that ends before their backward
+ * starts; a unit whose reload slot would start before its offload slot has ended is not offloaded (Section 4.4).
+ * A copy op stands before the first pass that starts no earlier than its slot.  out may be NULL to query *n. HOST. */
+int po_schedule_ops_slots(int32_t d, int32_t rank, int32_t v, int32_t m, int32_t group, int32_t n_offload_chunks,
+                          double k, po_op* out, int32_t* n);
 
 /* Eq. 1: k = 10 / (3 (6h + s)) * B_c / B_o, with B_c in flop/s and B_o in byte/s. */
 double po_offload_k(int32_t h, int32_t s, double compute_flops_per_s, double link_bytes_per_s);

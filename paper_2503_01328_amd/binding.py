@@ -34,7 +34,7 @@ class po_config(C.Structure):
         "n_layers", "n_chunks", "hidden", "n_heads", "ffn", "seq", "vocab", "dtype", "pipeline_degree", "rank",
         "prefetch_passes", "copy_streams", "select_policy", "staged_copies", "debug_poison", "profile_kernels",
         "group", "weight_stream", "n_kv_heads", "min_gap_passes")] + [
-        ("ln_eps", C.c_float), ("dropout_p", C.c_float), ("host_pool_cap_bytes", C.c_uint64),
+        ("ln_eps", C.c_float), ("dropout_p", C.c_float), ("slot_k", C.c_float), ("host_pool_cap_bytes", C.c_uint64),
         ("device_pool_cap_bytes", C.c_uint64), ("dropout_seed", C.c_uint64)]
 
 
@@ -68,6 +68,7 @@ EXPORTS = {
     "po_saved_bytes_per_layer": (C.c_int, [C.POINTER(po_config), C.POINTER(C.c_uint64)]),
     "po_schedule_ops": (C.c_int, [C.c_int32] * 6 + [C.c_float, C.c_int32, C.c_int32, C.c_int32, C.POINTER(po_op),
                                                     C.POINTER(C.c_int32)]),
+    "po_schedule_ops_slots": (C.c_int, [C.c_int32] * 6 + [C.c_double, C.POINTER(po_op), C.POINTER(C.c_int32)]),
     "po_offload_k": (C.c_double, [C.c_int32, C.c_int32, C.c_double, C.c_double]),
     "po_offload_ratio_for_k": (C.c_double, [C.c_double]),
     "po_stage_create": (C.c_int, [C.POINTER(po_config), C.c_void_p, C.POINTER(C.c_void_p)]),
@@ -175,6 +176,14 @@ def po_schedule_ops(schedule, d, rank, v, m, ratio, policy=0, prefetch=2, group=
     _check(lib.po_schedule_ops(schedule, d, rank, v, m, group, ratio, policy, prefetch, min_gap, None, C.byref(n)))
     arr = (po_op * n.value)()
     _check(lib.po_schedule_ops(schedule, d, rank, v, m, group, ratio, policy, prefetch, min_gap, arr, C.byref(n)))
+    return [(OP_KINDS[o.kind], o.mb, o.chunk) for o in arr]
+
+
+def po_schedule_ops_slots(d, rank, v, m, n_offload_chunks, k, group=0):
+    n = C.c_int32(0)
+    _check(lib.po_schedule_ops_slots(d, rank, v, m, group, n_offload_chunks, k, None, C.byref(n)))
+    arr = (po_op * n.value)()
+    _check(lib.po_schedule_ops_slots(d, rank, v, m, group, n_offload_chunks, k, arr, C.byref(n)))
     return [(OP_KINDS[o.kind], o.mb, o.chunk) for o in arr]
 
 

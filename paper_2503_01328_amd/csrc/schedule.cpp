@@ -107,6 +107,97 @@ static bool uniform_repeat_passes(int d, int rank, int v, int m, int g, std::vec
   return true;
 }
 
+// Slot plan of Section 4.2 on the uniformly repeated timeline of `rank` (unit pass times, bubbles kept): one copy
+// stream cut into slot pairs of 3k units, an offload slot followed by a reload slot of 1.5k units each
+// (k = a unit's round trip over its F + B + W time, Eq. 1).  The units of chunks 0 .. n_sel-1 take, in the order
+// their forwards end, the earliest free offload slot that starts no earlier, and, in the reverse order of their
+// backwards, the latest free reload slot that ends no later; a unit whose reload would start before its offload
+// has ended keeps its activations on the device (Section 4.4).  The op list holds the passes by start time and
+// each copy at the start time of its slot (a copy that starts together with a pass comes first).
+bool build_slot_schedule(int d, int rank, int v, int m, int g, int n_sel, double k, std::vector<po_op>& ops) {
+  if (d < 1 || rank < 0 || rank >= d || v < 1 || m < 1 || n_sel < 0 || n_sel > v || !(k > 0.0)) {
+    set_error("slot schedule: d=%d rank=%d v=%d m=%d chunks=%d k=%g", d, rank, v, m, n_sel, k);
+    return false;
+  }
+  if (g <= 0) g = (d + 1) / 2;
+  if (g > d || 2 * g < d) {
+    set_error("schedule: group size %d outside [ceil(d/2), d] for d=%d", g, d);
+    return false;
+  }
+  std::vector<long> f, b, w;
+  repeatable_block(d, rank, v, g, f, b, w);
+  const double pair = 3.0 * k, eps = 1e-9;
+  struct UnitTime {
+    long t;
+    int mb, chunk;
+  };
+  std::vector<UnitTime> by_forward, by_backward;
+  for (int n = 0; n < m; ++n)
+    for (int c = 0; c < n_sel; ++c) {
+      by_forward.push_back(UnitTime{f[c] + 3L * v * n + 1, n, c});  // end of the forward
+      by_backward.push_back(UnitTime{b[c] + 3L * v * n, n, c});     // start of the backward
+    }
+  auto less_unit = [](const UnitTime& x, const UnitTime& y) {
+    if (x.t != y.t) return x.t < y.t;
+    if (x.mb != y.mb) return x.mb < y.mb;
+    return x.chunk < y.chunk;
+  };
+  std::sort(by_forward.begin(), by_forward.end(), less_unit);
+  std::sort(by_backward.begin(), by_backward.end(), [&](const UnitTime& x, const UnitTime& y) {
+    if (x.t != y.t) return x.t > y.t;
+    if (x.mb != y.mb) return x.mb < y.mb;
+    return x.chunk < y.chunk;
+  });
+  std::vector<long> off_slot((size_t)m * v, -1), rel_slot((size_t)m * v, -1);
+  std::vector<long> taken;  // kept sorted
+  auto is_taken = [&](long i) { return std::binary_search(taken.begin(), taken.end(), i); };
+  auto take = [&](long i) { taken.insert(std::upper_bound(taken.begin(), taken.end(), i), i); };
+  for (const UnitTime& u : by_forward) {
+    long i = (long)ceil((double)u.t / pair - eps);
+    if (i < 0) i = 0;
+    while (is_taken(i)) ++i;
+    take(i);
+    off_slot[(size_t)u.chunk * m + u.mb] = i;
+  }
+  taken.clear();
+  for (const UnitTime& u : by_backward) {
+    long j = (long)floor((double)u.t / pair + eps) - 1;  // reload slot j ends at pair (j + 1)
+    while (is_taken(j)) --j;
+    take(j);
+    rel_slot[(size_t)u.chunk * m + u.mb] = j;
+  }
+  struct Event {
+    double t;
+    int is_pass, not_reload;
+    po_op op;
+  };
+  std::vector<Event> ev;
+  for (int n = 0; n < m; ++n)
+    for (int c = 0; c < v; ++c) {
+      long shift = 3L * v * n;
+      ev.push_back(Event{(double)(f[c] + shift), 1, 1, po_op{0, n, c, 0.f}});
+      ev.push_back(Event{(double)(b[c] + shift), 1, 1, po_op{1, n, c, 0.f}});
+      ev.push_back(Event{(double)(w[c] + shift), 1, 1, po_op{4, n, c, 0.f}});
+      if (c < n_sel) {
+        long i = off_slot[(size_t)c * m + n], j = rel_slot[(size_t)c * m + n];
+        if (j >= i) {
+          ev.push_back(Event{pair * (double)i, 0, 1, po_op{2, n, c, 1.0f}});
+          ev.push_back(Event{pair * (double)j + pair / 2, 0, 0, po_op{3, n, c, 1.0f}});
+        }
+      }
+    }
+  std::sort(ev.begin(), ev.end(), [](const Event& x, const Event& y) {
+    if (x.t != y.t) return x.t < y.t;
+    if (x.is_pass != y.is_pass) return x.is_pass < y.is_pass;
+    if (x.not_reload != y.not_reload) return x.not_reload < y.not_reload;
+    if (x.op.mb != y.op.mb) return x.op.mb < y.op.mb;
+    return x.op.chunk < y.op.chunk;
+  });
+  ops.clear();
+  for (const Event& e : ev) ops.push_back(e.op);
+  return true;
+}
+
 static bool compute_passes(int schedule, int d, int rank, int v, int m, int g, std::vector<Pass>& out) {
   if (d < 1 || rank < 0 || rank >= d || v < 1 || m < 1) {
     set_error("schedule: d=%d rank=%d v=%d m=%d", d, rank, v, m);

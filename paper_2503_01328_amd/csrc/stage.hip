@@ -36,6 +36,7 @@ namespace po {
 bool build_schedule(int schedule, int d, int rank, int v, int m, int group, float ratio, int policy, int prefetch,
                     int min_gap,
                     std::vector<po_op>& ops);
+bool build_slot_schedule(int d, int rank, int v, int m, int g, int n_sel, double k, std::vector<po_op>& ops);
 
 #define PO_HIP(expr)                                                                          \
   do {                                                                                        \
@@ -81,7 +82,7 @@ int validate_config(const po_config* c) {
       c->rank < 0 || c->rank >= c->pipeline_degree || c->prefetch_passes < 0 ||
       (c->copy_streams != 1 && c->copy_streams != 2) || c->hidden / c->n_heads > 256 ||
       (c->hidden / c->n_heads) % 8 != 0 || !(c->ln_eps > 0.f) || c->group < 0 || c->group > c->pipeline_degree ||
-      (c->group > 0 && 2 * c->group < c->pipeline_degree) || (c->weight_stream != 0 && c->weight_stream != 1) || c->min_gap_passes < 0 || c->n_kv_heads < 0 || !(c->dropout_p >= 0.f && c->dropout_p < 1.f) ||
+      (c->group > 0 && 2 * c->group < c->pipeline_degree) || (c->weight_stream != 0 && c->weight_stream != 1) || c->min_gap_passes < 0 || c->n_kv_heads < 0 || !(c->dropout_p >= 0.f && c->dropout_p < 1.f) || !(c->slot_k >= 0.f) ||
       (c->n_kv_heads > 0 && c->n_heads % c->n_kv_heads != 0)) {
     set_error("invalid config: L=%d v=%d h=%d a=%d f=%d s=%d vocab=%d dtype=%d d=%d rank=%d prefetch=%d copy_streams=%d group=%d",
               c->n_layers, c->n_chunks, c->hidden, c->n_heads, c->ffn, c->seq, c->vocab, c->dtype,
@@ -1165,9 +1166,18 @@ int stage_run_schedule(po_stage* st, int schedule, int m, float ratio, const voi
     return PO_E_INVAL;
   }
   std::vector<po_op> ops;
-  if (!build_schedule(schedule, c.pipeline_degree, c.rank, c.n_chunks, m, c.group, ratio, c.select_policy,
-                      c.prefetch_passes, c.min_gap_passes, ops))
+  if (schedule == PO_SCHED_PO && c.slot_k > 0.f) {  // Section 4.2's slot plan; whole chunks, longest-lived first
+    if (!(ratio >= 0.f && ratio <= 1.f)) {
+      set_error("run_schedule: ratio %g outside [0, 1]", ratio);
+      return PO_E_INVAL;
+    }
+    int n_sel = (int)ceil((double)ratio * c.n_chunks - 1e-9);
+    if (!build_slot_schedule(c.pipeline_degree, c.rank, c.n_chunks, m, c.group, n_sel, (double)c.slot_k, ops))
+      return PO_E_INVAL;
+  } else if (!build_schedule(schedule, c.pipeline_degree, c.rank, c.n_chunks, m, c.group, ratio, c.select_policy,
+                             c.prefetch_passes, c.min_gap_passes, ops)) {
     return PO_E_INVAL;
+  }
   for (auto& kv : st->units)
     if (kv.second.live) {
       set_error("run_schedule with units still in flight");
@@ -1404,6 +1414,23 @@ int po_schedule_ops(int32_t schedule, int32_t d, int32_t rank, int32_t v, int32_
   if (out) {
     int32_t k = *n < have ? *n : have;
     for (int32_t i = 0; i < k; ++i) out[i] = ops[i];
+  }
+  *n = have;
+  return PO_OK;
+}
+
+int po_schedule_ops_slots(int32_t d, int32_t rank, int32_t v, int32_t m, int32_t group, int32_t n_offload_chunks,
+                          double k, po_op* out, int32_t* n) {
+  if (!n) {
+    set_error("po_schedule_ops_slots: n is NULL");
+    return PO_E_INVAL;
+  }
+  std::vector<po_op> ops;
+  if (!build_slot_schedule(d, rank, v, m, group, n_offload_chunks, k, ops)) return PO_E_INVAL;
+  int32_t have = (int32_t)ops.size();
+  if (out) {
+    int32_t take = *n < have ? *n : have;
+    for (int32_t i = 0; i < take; ++i) out[i] = ops[i];
   }
   *n = have;
   return PO_OK;

@@ -83,6 +83,27 @@ def test_uniform_repeat_schedule_ops_match_the_oracle_model(d, v, m, g, ratio):
                 assert sch.simulate(got)["errors"] == []
 
 
+@pytest.mark.parametrize("d,v,m,g", [(8, 2, 16, 0), (4, 2, 9, 0), (8, 4, 12, 6), (6, 3, 10, 0), (4, 1, 8, 0), (2, 2, 5, 1)])
+@pytest.mark.parametrize("k", [0.25, 0.5, 0.9, 1.0, 1.7, 3.0, 40.0])
+def test_slot_schedule_ops_match_the_oracle_model(d, v, m, g, k):
+    for rank in sorted({0, d // 2, d - 1}):
+        for n_sel in range(v + 1):
+            got = po.po_schedule_ops_slots(d, rank, v, m, n_sel, k, group=g)
+            timed = sch.uniform_repeat_times(d, rank, v, m, g or None)
+            placement = sch.slot_placement(timed, set(range(n_sel)), k)
+            assert got == sch.with_slot_offload(timed, placement, k)
+            assert sch.simulate(got)["errors"] == []
+
+
+def test_slot_schedule_rejects_bad_arguments():
+    for args in [(4, 0, 2, 8, 3, 1.0), (4, 0, 2, 8, 1, 0.0), (4, 0, 2, 8, 1, -1.0), (4, 4, 2, 8, 1, 1.0), (4, 0, 2, 0, 1, 1.0)]:
+        with pytest.raises(po.PipeOffloadError) as e:
+            po.po_schedule_ops_slots(*args)
+        assert e.value.code == po.PO_E_INVAL
+    with pytest.raises(po.PipeOffloadError):
+        po.po_schedule_ops_slots(8, 0, 2, 8, 1, 1.0, group=3)
+
+
 def test_uniform_repeat_rejects_bad_groups():
     for g in (3, 9):
         with pytest.raises(po.PipeOffloadError) as e:

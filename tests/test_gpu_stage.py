@@ -338,6 +338,32 @@ def test_uniform_repeat_schedule_against_oracle_and_schedule_model(gpu_device, r
             _assert_bit_identical(results[0.0], _snapshot(r))
 
 
+@pytest.mark.parametrize("k,copy_streams", [(1.0, 1), (0.5, 1), (1.5, 2)])
+def test_slot_placed_copies_on_the_uniformly_repeated_schedule(gpu_device, k, copy_streams):
+    """Section 4.2's slot plan (one-offload-one-reload slots of a shared copy stream) drives the stage: same
+    results as the resident run, and as many units move, and as many stay resident, as the schedule model says."""
+    import numpy as np
+    d, v, m = 4, 2, 8
+    shape = syn.StageShape(4, v, 128, 2, 512, 64, dtype="bf16", pipeline_degree=d, n_microbatches=m)
+    with StageRunner(shape) as r:
+        r.make_inputs()
+        r.run(po.PO_SCHED_PO, 0.0)
+        base = _snapshot(r)
+    kf = float(np.float32(k))  # the config holds k in single precision
+    for ratio in (0.5, 1.0):
+        with StageRunner(shape, slot_k=k, copy_streams=copy_streams, debug_poison=1) as r:
+            r.make_inputs()
+            stats = r.run(po.PO_SCHED_PO, ratio)
+            _assert_bit_identical(base, _snapshot(r))
+            timed = sch.uniform_repeat_times(d, 0, v, m)
+            placement = sch.slot_placement(timed, set(range(int(ratio * v))), kf)
+            model = sch.simulate(sch.with_slot_offload(timed, placement, kf))
+            assert model["errors"] == []
+            assert stats["n_offloads"] == stats["n_reloads"] == len(placement) * shape.layers_per_chunk
+            assert stats["peak_resident_units"] == model["peak_resident"]
+            assert len(placement) > 0 or k * ratio * v > v  # more copy time asked for than a period holds
+
+
 def test_short_gap_units_are_not_offloaded(gpu_device):
     # last rank of 1F1B: every backward directly follows its forward; with min_gap_passes = 1 nothing moves
     shape = syn.StageShape(2, 1, 128, 2, 512, 64, dtype="bf16", pipeline_degree=4, rank=3, n_microbatches=6)
