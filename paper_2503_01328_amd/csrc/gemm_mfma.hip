@@ -152,9 +152,10 @@ __device__ __forceinline__ void epilogue_row_piece(const Epilogue& e, int m, int
     bf16x8_t o, g;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      float uf = (float)u.v[i];
-      g.v[i] = (bf16)gelu_f(uf);
-      o.v[i] = (bf16)(a[i] * gelu_grad_f(uf));
+      float gf, dgf;
+      gelu_and_grad_f((float)u.v[i], gf, dgf);
+      g.v[i] = (bf16)gf;
+      o.v[i] = (bf16)(a[i] * dgf);
     }
     if (e.gelu_out) *reinterpret_cast<bf16x8_t*>(static_cast<bf16*>(e.gelu_out) + idx) = g;
     *reinterpret_cast<bf16x8_t*>(static_cast<bf16*>(e.out) + idx) = o;

@@ -51,17 +51,34 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
-// GeLU in its tanh form, and its derivative.  tanh(z) = 1 - 2 / (1 + exp(2z)).
-__device__ __forceinline__ float tanh_fast(float z) { return 1.0f - 2.0f / (1.0f + __expf(2.0f * z)); }
+// GeLU in its tanh form, and its derivative, in terms of r = 1 / (1 + exp(2z)), z = c (u + 0.044715 u^3):
+//   tanh(z) = 1 - 2r,  gelu(u) = 0.5 u (1 + tanh z) = u (1 - r),
+//   gelu'(u) = 0.5 (1 + tanh z) + 0.5 u (1 - tanh^2 z) z'(u) = (1 - r) (1 + 2 u r z'(u)),  z' = c (1 + 3 * 0.044715 u^2).
+// exp(2z) is one exp2 of a cubic in u with the constants folded, the reciprocal is the hardware's (1 ulp): about
+// fourteen operations for both values, where a division and two separate tanh cost thirty.  u -> +inf gives
+// r = 0 (gelu = u, slope 1), u -> -inf gives r = 1 (gelu = 0, slope 0).
+__device__ __forceinline__ float gelu_gate(float u) {  // r(u)
+  const float k1 = 2.0f * 0.7978845608028654f * 1.4426950408889634f;  // 2 c log2(e)
+  const float k2 = k1 * 0.044715f;
+  float e = __builtin_amdgcn_exp2f(u * (k1 + k2 * u * u));
+  return __builtin_amdgcn_rcpf(1.0f + e);
+}
 __device__ __forceinline__ float gelu_f(float u) {
+  float r = gelu_gate(u);
+  return u - u * r;
+}
+__device__ __forceinline__ void gelu_and_grad_f(float u, float& g, float& dg) {
   const float c = 0.7978845608028654f;
-  return 0.5f * u * (1.0f + tanh_fast(c * (u + 0.044715f * u * u * u)));
+  float r = gelu_gate(u);
+  float keep = 1.0f - r;
+  float dz = c + (3.0f * 0.044715f * c) * u * u;
+  g = u * keep;
+  dg = keep * (1.0f + 2.0f * u * r * dz);
 }
 __device__ __forceinline__ float gelu_grad_f(float u) {
-  const float c = 0.7978845608028654f;
-  float t = tanh_fast(c * (u + 0.044715f * u * u * u));
-  float dz = c * (1.0f + 3.0f * 0.044715f * u * u);
-  return 0.5f * (1.0f + t) + 0.5f * u * (1.0f - t * t) * dz;
+  float g, dg;
+  gelu_and_grad_f(u, g, dg);
+  return dg;
 }
 
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3", SC'11): a counter-
@@ -127,8 +144,10 @@ __device__ __forceinline__ void epilogue_store(const Epilogue& e, int m, int n, 
   if (e.residual) acc += to_f32(static_cast<const T*>(e.residual)[idx]);
   if (e.gelu_u) {
     float u = to_f32(static_cast<const T*>(e.gelu_u)[idx]);
-    if (e.gelu_out) static_cast<T*>(e.gelu_out)[idx] = from_f32<T>(gelu_f(u));
-    acc *= gelu_grad_f(u);
+    float g, dg;
+    gelu_and_grad_f(u, g, dg);
+    if (e.gelu_out) static_cast<T*>(e.gelu_out)[idx] = from_f32<T>(g);
+    acc *= dg;
     static_cast<T*>(e.out)[idx] = from_f32<T>(acc);
     return;
   }
