@@ -301,6 +301,176 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_fwd_mfma_kernel(con
 }
 
 // ==================================================================================
+// Forward for launches too small to give every CU two blocks (heads * s / 128 <= 256): the block
+// has eight waves, and waves w and w + 4 own the same 32 query rows but alternate key tiles (group 0
+// the even ones, group 1 the odd ones, each group with its own pair of LDS stages).  A wave's chain of
+// dependent tiles is half as long and every SIMD holds two waves, whose softmax arithmetic and MFMAs
+// overlap.  At the end group 1 hands its running maximum, sum and output accumulators to group 0
+// through LDS, which merges the two softmax states and writes the result.
+// ==================================================================================
+template <int DH>
+__global__ __launch_bounds__(512, 1) void attn_fwd_split_mfma_kernel(const bf16* __restrict__ qkv,
+                                                                    bf16* __restrict__ o, float* __restrict__ lse,
+                                                                    int s, int h, int hkv, int group, float scale) {
+  constexpr int KS = DH / 16;
+  constexpr int DT = DH / 32;
+  constexpr int BQ = 128;
+  constexpr int KBYTES = tile_bytes<DH>();
+  constexpr int STAGE = 2 * KBYTES;  // K tile, V tile
+  extern __shared__ __align__(16) char smem_all[];
+
+  int tid = threadIdx.x, lane = tid & 63;
+  int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);
+  int grp = wave8 >> 2, wave = wave8 & 3;
+  char* smem = smem_all + grp * (2 * STAGE);
+  int half = lane >> 5, col = lane & 31;
+  int head = blockIdx.x;
+  int qblock = gridDim.y - 1 - blockIdx.y;
+  int q0 = qblock * BQ;
+  int qw0 = q0 + wave * 32;
+  int ld = h + 2 * hkv;
+  const bf16* qbase = qkv + head * DH;
+  const bf16* kbase = qkv + h + (head / group) * DH;
+  const bf16* vbase = qkv + h + hkv + (head / group) * DH;
+  const float c = scale * 1.4426950408889634f;
+
+  bf16x8 qf[KS];
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk)
+    qf[kk] = *reinterpret_cast<const bf16x8*>(qbase + (size_t)(qw0 + col) * ld + 16 * kk + 8 * half);
+
+  f32x16 oacc[DT];
+  float m_run = -INFINITY, l_run = 0.f;
+#pragma unroll
+  for (int d = 0; d < DT; ++d)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) oacc[d][e] = 0.f;
+
+  int nkv = (q0 + BQ) / kKeysPerTile;  // even: both groups walk nkv / 2 tiles
+  int n_it = nkv / 2;
+  const unsigned lane_off = tile_lane_offset<DH>(ld, wave, lane);
+  load_tile_async<DH>(kbase, ld, grp * kKeysPerTile, smem, wave, lane_off);
+  load_tile_async<DH>(vbase, ld, grp * kKeysPerTile, smem + KBYTES, wave, lane_off);
+  wait_tile_loads();
+  __syncthreads();
+
+  for (int it = 0; it < n_it; ++it) {
+    int kt = 2 * it + grp;
+    const char* ktile = smem + (it & 1) * STAGE;
+    const char* vtile = ktile + KBYTES;
+    char* nxt = smem + ((it + 1) & 1) * STAGE;
+    if (it + 1 < n_it) {  // the other stage of this group was last read before the previous barrier
+      load_tile_async<DH>(kbase, ld, (kt + 2) * kKeysPerTile, nxt, wave, lane_off);
+      load_tile_async<DH>(vbase, ld, (kt + 2) * kKeysPerTile, nxt + KBYTES, wave, lane_off);
+    }
+    int key0 = kt * kKeysPerTile;
+    if (key0 <= qw0 + 31) {
+      f32x16 sacc[2];
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) sacc[j][e] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          bf16x8 kf = read_row_fragment<DH>(ktile, 32 * j + col, 2 * kk + half);
+          sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[j], 0, 0, 0);
+        }
+      }
+      int q = qw0 + col;
+      if (key0 + kKeysPerTile - 1 > qw0) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int e = 0; e < 16; ++e)
+            if (key0 + 32 * j + 8 * (e >> 2) + 4 * half + (e & 3) > q) sacc[j][e] = -INFINITY;
+      }
+      float mx = -INFINITY;
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[j][e]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      float m_new = fmaxf(m_run, mx);
+      // a tile can be all masked for a row (the odd tile of the diagonal pair): keep the state finite
+      float m_use = m_new == -INFINITY ? 0.f : m_new;
+      float alpha = fast_exp2((m_run - m_use) * c);
+      float mc = m_use * c;
+      float sum = 0.f;
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          float p = fast_exp2(sacc[j][e] * c - mc);
+          sacc[j][e] = p;
+          sum += p;
+        }
+      l_run = l_run * alpha + sum;
+      bool moved = __builtin_amdgcn_ballot_w64(m_new > m_run) != 0;
+      m_run = m_new;
+      if (moved) {
+#pragma unroll
+        for (int d = 0; d < DT; ++d)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) oacc[d][e] *= alpha;
+      }
+      bf16x8 pf[2][2];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        pf[j][0] = pack_bf16x8(sacc[j], 0);
+        pf[j][1] = pack_bf16x8(sacc[j], 8);
+      }
+#pragma unroll
+      for (int d = 0; d < DT; ++d)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int st = 0; st < 2; ++st) {
+            bf16x8 vf = read_tr_fragment<DH>(vtile, 32 * j + 16 * st, 32 * d, lane);
+            oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[j][st], oacc[d], 0, 0, 0);
+          }
+    }
+    wait_tile_loads();
+    __syncthreads();
+  }
+
+  // Merge: group 1 -> LDS -> group 0.  Per wave of group 1: DT * 16 floats per lane, then m and l.
+  float* xch = reinterpret_cast<float*>(smem_all) + wave * (64 * (DT * 16 + 2));
+  if (grp == 1) {
+#pragma unroll
+    for (int d = 0; d < DT; ++d)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) xch[(d * 16 + e) * 64 + lane] = oacc[d][e];
+    xch[(DT * 16) * 64 + lane] = m_run;
+    xch[(DT * 16 + 1) * 64 + lane] = l_run;
+  }
+  __syncthreads();
+  if (grp == 0) {
+    float m1 = xch[(DT * 16) * 64 + lane], l1 = xch[(DT * 16 + 1) * 64 + lane];
+    float m = fmaxf(m_run, m1);  // group 0 has seen key 0, so m is finite
+    float a0 = fast_exp2((m_run - m) * c), a1 = fast_exp2((m1 - m) * c);
+    float l = l_run * a0 + l1 * a1;
+    l += __shfl_xor(l, 32, 64);
+    float inv = 1.0f / l;
+    int q = qw0 + col;
+#pragma unroll
+    for (int d = 0; d < DT; ++d)
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        bf16x4 v;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          int e = 4 * b + r;
+          v[r] = (bf16)((oacc[d][e] * a0 + xch[(d * 16 + e) * 64 + lane] * a1) * inv);
+        }
+        *reinterpret_cast<bf16x4*>(o + (size_t)q * h + head * DH + 32 * d + 8 * b + 4 * half) = v;
+      }
+    if (half == 0) lse[(size_t)head * s + q] = m * scale + __logf(l);
+  }
+}
+
+// ==================================================================================
 // Backward, part 1: dK and dV.  Block = 128 keys (a wave owns 32), loop over the
 // 64-row query tiles at or below the diagonal.  The Q and dO tiles in LDS serve both
 // kinds of reads: ds_read_b128 fragments (contraction over the head dimension, for S
@@ -626,6 +796,129 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_bwd_dq_mfma_kernel(
 
 // Adds the per-query-head dK / dV partials [s, 2h] (dK of head t at columns t * DH, dV at h + t * DH) of every
 // group in head order, in fp32, into the key and value blocks of dqkv [s, h + 2 hkv].  One thread per 8 columns.
+// dQ for launches too small to give every CU two blocks: eight waves, waves w and w + 4 own the same 32
+// query rows and alternate key tiles, as in attn_fwd_split_mfma_kernel; group 1's partial dQ goes to group 0
+// through LDS at the end (one addition per element, always in the same order).
+template <int DH>
+__global__ __launch_bounds__(512, 1) void attn_bwd_dq_split_mfma_kernel(const bf16* __restrict__ qkv,
+                                                                       const bf16* __restrict__ d_o,
+                                                                       const float* __restrict__ lse,
+                                                                       const float* __restrict__ delta,
+                                                                       bf16* __restrict__ dqkv, int s, int h, int hkv,
+                                                                       int group, float scale) {
+  constexpr int KS = DH / 16, DT = DH / 32;
+  constexpr int BQ = 128;
+  constexpr int KBYTES = tile_bytes<DH>();
+  constexpr int STAGE = 2 * KBYTES;  // K tile, V tile
+  extern __shared__ __align__(16) char smem_all[];
+
+  int tid = threadIdx.x, lane = tid & 63;
+  int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);
+  int grp = wave8 >> 2, wave = wave8 & 3;
+  char* smem = smem_all + grp * (2 * STAGE);
+  int half = lane >> 5, col = lane & 31;
+  int head = blockIdx.x;
+  int qblock = gridDim.y - 1 - blockIdx.y;
+  int q0 = qblock * BQ;
+  int qw0 = q0 + wave * 32;
+  int ld = h + 2 * hkv;
+  const bf16* kbase = qkv + h + (head / group) * DH;
+  const bf16* vbase = qkv + h + hkv + (head / group) * DH;
+  const float LOG2E = 1.4426950408889634f;
+  const float c = scale * LOG2E;
+
+  bf16x8 qf[KS], dof[KS];
+  int q = qw0 + col;
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk) {
+    qf[kk] = *reinterpret_cast<const bf16x8*>(qkv + (size_t)q * ld + head * DH + 16 * kk + 8 * half);
+    dof[kk] = *reinterpret_cast<const bf16x8*>(d_o + (size_t)q * h + head * DH + 16 * kk + 8 * half);
+  }
+  float lse_q = lse[(size_t)head * s + q] * LOG2E;
+  float delta_q = delta[(size_t)head * s + q];
+  f32x16 dq[DT];
+#pragma unroll
+  for (int d = 0; d < DT; ++d)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) dq[d][e] = 0.f;
+
+  int n_it = (q0 + BQ) / kKeysPerTile / 2;  // tiles per group
+  const unsigned lane_off = tile_lane_offset<DH>(ld, wave, lane);
+  load_tile_async<DH>(kbase, ld, grp * kKeysPerTile, smem, wave, lane_off);
+  load_tile_async<DH>(vbase, ld, grp * kKeysPerTile, smem + KBYTES, wave, lane_off);
+  wait_tile_loads();
+  __syncthreads();
+
+  for (int it = 0; it < n_it; ++it) {
+    int kt = 2 * it + grp;
+    const char* ktile = smem + (it & 1) * STAGE;
+    const char* vtile = ktile + KBYTES;
+    char* nxt = smem + ((it + 1) & 1) * STAGE;
+    if (it + 1 < n_it) {
+      load_tile_async<DH>(kbase, ld, (kt + 2) * kKeysPerTile, nxt, wave, lane_off);
+      load_tile_async<DH>(vbase, ld, (kt + 2) * kKeysPerTile, nxt + KBYTES, wave, lane_off);
+    }
+    int key0 = kt * kKeysPerTile;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      int ks0 = key0 + 32 * j;
+      if (ks0 > qw0 + 31) continue;
+      f32x16 sacc, pacc;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) sacc[e] = pacc[e] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk) {
+        bf16x8 ka = read_row_fragment<DH>(ktile, 32 * j + col, 2 * kk + half);
+        bf16x8 va = read_row_fragment<DH>(vtile, 32 * j + col, 2 * kk + half);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[kk], sacc, 0, 0, 0);
+        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, dof[kk], pacc, 0, 0, 0);
+      }
+#pragma unroll
+      for (int e = 0; e < 16; ++e) sacc[e] = fast_exp2(sacc[e] * c - lse_q);
+      if (ks0 + 31 > qw0) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (ks0 + 8 * (e >> 2) + 4 * half + (e & 3) > q) sacc[e] = 0.f;
+      }
+#pragma unroll
+      for (int e = 0; e < 16; ++e) pacc[e] = sacc[e] * (pacc[e] - delta_q);
+      bf16x8 dsf[2] = {pack_bf16x8(pacc, 0), pack_bf16x8(pacc, 8)};
+#pragma unroll
+      for (int d = 0; d < DT; ++d)
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+          bf16x8 ktr = read_tr_fragment<DH>(ktile, 32 * j + 16 * st, 32 * d, lane);
+          dq[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktr, dsf[st], dq[d], 0, 0, 0);
+        }
+    }
+    wait_tile_loads();
+    __syncthreads();
+  }
+
+  float* xch = reinterpret_cast<float*>(smem_all) + wave * (64 * DT * 16);
+  if (grp == 1) {
+#pragma unroll
+    for (int d = 0; d < DT; ++d)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) xch[(d * 16 + e) * 64 + lane] = dq[d][e];
+  }
+  __syncthreads();
+  if (grp == 0) {
+#pragma unroll
+    for (int d = 0; d < DT; ++d)
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        bf16x4 v;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          int e = 4 * b + r;
+          v[r] = (bf16)((dq[d][e] + xch[(d * 16 + e) * 64 + lane]) * scale);
+        }
+        *reinterpret_cast<bf16x4*>(dqkv + (size_t)q * ld + head * DH + 32 * d + 8 * b + 4 * half) = v;
+      }
+  }
+}
+
 template <int DH>
 __global__ __launch_bounds__(256) void attn_group_sum_kernel(const bf16* __restrict__ part, bf16* __restrict__ dqkv,
                                                              int s, int h, int hkv, int group) {
@@ -687,6 +980,19 @@ static bool launch_fwd(const bf16* qkv, bf16* o, float* lse, int s, int h, int n
     configured = true;
   }
   dim3 grid(n_heads, s / (128 * QT));
+  if (QT == 1 && (int64_t)n_heads * (s / 128) <= 256) {  // one block per CU at most: the eight-wave kernel
+    constexpr int smem_split = 8 * tile_bytes<DH>();
+    auto ksplit = attn_fwd_split_mfma_kernel<DH>;
+    static bool split_configured = false;
+    if (!split_configured) {
+      PO_HIP_OK(hipFuncSetAttribute(reinterpret_cast<const void*>(ksplit),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, smem_split));
+      split_configured = true;
+    }
+    ksplit<<<grid, 512, smem_split, stream>>>(qkv, o, lse, s, h, n_kv_heads * DH, n_heads / n_kv_heads,
+                                             1.0f / sqrtf((float)DH));
+    return launch_ok("attn_fwd_split_mfma_kernel");
+  }
   kern<<<grid, 256, smem, stream>>>(qkv, o, lse, s, h, n_kv_heads * DH, n_heads / n_kv_heads,
                                     1.0f / sqrtf((float)DH));
   return launch_ok("attn_fwd_mfma_kernel");
@@ -736,7 +1042,19 @@ static bool launch_bwd(const bf16* qkv, const bf16* o, const float* lse, const b
     kkv<<<dim3(n_kv_heads, s / 128), 256, smem_kv, stream>>>(qkv, d_o, lse, delta, dqkv, h + 2 * hkv, h, hkv, group, s,
                                                             h, hkv, group, scale);
   }
-  kq1<<<dim3(n_heads, s / 128), 256, smem_q, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, hkv, group, scale);
+  if ((int64_t)n_heads * (s / 128) <= 256) {  // one block per CU at most: the eight-wave kernel
+    constexpr int smem_split = 8 * tile_bytes<DH>();
+    auto kqs = attn_bwd_dq_split_mfma_kernel<DH>;
+    static bool split_configured = false;
+    if (!split_configured) {
+      PO_HIP_OK(hipFuncSetAttribute(reinterpret_cast<const void*>(kqs), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    smem_split));
+      split_configured = true;
+    }
+    kqs<<<dim3(n_heads, s / 128), 512, smem_split, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, hkv, group, scale);
+  } else {
+    kq1<<<dim3(n_heads, s / 128), 256, smem_q, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, hkv, group, scale);
+  }
   return launch_ok("attention backward MFMA kernels");
 }
 
