@@ -661,6 +661,216 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
     }
 }
 
+// dK, dV for launches too small to give every CU two blocks: the kernel above with eight waves per block.
+template <int DH>
+__global__ __launch_bounds__(512, 1) void attn_bwd_dkv_split_mfma_kernel(const bf16* __restrict__ qkv,
+                                                                const bf16* __restrict__ d_o,
+                                                                const float* __restrict__ lse,
+                                                                const float* __restrict__ delta,
+                                                                bf16* __restrict__ out, int ld_out, int out_k0,
+                                                                int out_v_delta, int hpb, int s, int h, int hkv,
+                                                                int group, float scale) {
+  // Block b of the x dimension works on the hpb query heads b * hpb .. (all of them read key/value head
+  // b * hpb / group) and writes dK to columns out_k0 + b * DH .., dV out_v_delta columns further, of `out`
+  // (rows ld_out apart).  hpb = group: one block per key/value head writing straight into dqkv.  hpb = 1: one
+  // block per query head writing per-head partial results that a second kernel adds up per group; that keeps
+  // the launch as parallel as with plain multi-head attention when there are few key/value heads.
+  constexpr int KS = DH / 16, DT = DH / 32;
+  constexpr int TBYTES = tile_bytes<DH>();
+  constexpr int STAGE = 2 * TBYTES + 512;  // Q tile, dO tile, lse[64], delta[64]
+  extern __shared__ __align__(16) char smem_all[];
+
+  // Eight waves: waves w and w + 4 own the same 32 keys; group 0 takes the even iterations, group 1 the odd
+  // ones, each with its own pair of stages, and group 1's dK, dV go to group 0 through LDS at the end.
+  int lane = threadIdx.x & 63, wave8 = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+  int grp = wave8 >> 2, wave = wave8 & 3, tid = threadIdx.x & 255;
+  char* smem = smem_all + grp * (2 * STAGE);
+  char* vslots = smem_all + 4 * STAGE;
+  int half = lane >> 5, col = lane & 31;
+  int head_first = blockIdx.x * hpb;  // heads vary fastest in dispatch order: heaviest blocks of all heads first
+  int kv_head = head_first / group;
+  int kb0 = blockIdx.y * 128;   // first key of the block (the earliest blocks have the most query tiles)
+  int kw0 = kb0 + wave * 32;    // first key of this wave
+  int ld = h + 2 * hkv;
+  const float LOG2E = 1.4426950408889634f;
+  const float c = scale * LOG2E;
+
+  // K and V fragments of this wave's keys: B operands, column = key, contraction over the head dimension.
+  // With DH = 128 the last two V fragments live in LDS (a private 16-byte slot per lane and fragment)
+  // instead of registers: at two waves per SIMD the register file cannot hold them without spilling.
+  constexpr int V_IN_LDS = DH == 128 ? 2 : 0;
+  constexpr int V_IN_REG = KS - V_IN_LDS;
+  char* vslot = vslots + (wave8 * V_IN_LDS * 64 + lane) * 16;
+  bf16x8 kf[KS], vf[V_IN_REG > 0 ? V_IN_REG : 1];
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk) {
+    const bf16* row = qkv + (size_t)(kw0 + col) * ld + h + kv_head * DH + 16 * kk + 8 * half;
+    kf[kk] = *reinterpret_cast<const bf16x8*>(row);
+    bf16x8 v = *reinterpret_cast<const bf16x8*>(row + hkv);
+    if (kk < V_IN_REG)
+      vf[kk] = v;
+    else
+      *reinterpret_cast<bf16x8*>(vslot + (kk - V_IN_REG) * 1024) = v;
+  }
+  f32x16 dk[DT], dv[DT];
+#pragma unroll
+  for (int d = 0; d < DT; ++d)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) dk[d][e] = dv[d][e] = 0.f;
+
+  // Query tiles [q_first, q_last) of every query head of this block, one head after the other:
+  // iteration `it` works on head head_first + it / n_qt, tile q_first + it % n_qt.
+  int q_first = kb0 / kKeysPerTile, q_last = s / kKeysPerTile;
+  int n_qt = q_last - q_first, n_it = hpb * n_qt;
+  // Row statistics enter as the initial value of the accumulators: S starts at -lse / scale, so that
+  // exp2((S - lse / scale) * scale * log2 e) = P, and dP starts at -delta, so that dS = P * acc.
+  // Threads 0..63 carry lse of a row, 64..127 delta of a row (128..255 repeat them and store nothing).  The
+  // load is unconditional and its value is not touched until store_stats, after the tile's arithmetic:
+  // any earlier use would wait for this load and with it for the tile loads issued just before it.
+  const float* stat_src = ((tid & 64) ? delta - 64 : lse) + (tid & 127);
+  const float stat_mul = (tid & 64) ? -1.0f : __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(
+                                                   __builtin_bit_cast(int, -1.0f / scale)));
+  float stat = 0.f;
+  auto load_stats = [&](int head, int q0) { stat = stat_src[(size_t)head * s + q0]; };
+  auto tile_of = [&](int it, int& head, int& qt) {
+    int g = it / n_qt;
+    head = head_first + g;
+    qt = q_first + it - g * n_qt;
+  };
+  auto store_stats = [&](char* stage) {
+    if (tid < 128) reinterpret_cast<float*>(stage + 2 * TBYTES)[tid] = stat * stat_mul;
+  };
+  const unsigned q_lane_off = tile_lane_offset<DH>(ld, wave, lane), do_lane_off = tile_lane_offset<DH>(h, wave, lane);
+  {  // n_it >= 2 (a key block has at least two query tiles at or below it): both groups have a first tile
+    int head0, qt0;
+    tile_of(grp, head0, qt0);
+    load_tile_async<DH>(qkv + head0 * DH, ld, qt0 * kKeysPerTile, smem, wave, q_lane_off);
+    load_tile_async<DH>(d_o + head0 * DH, h, qt0 * kKeysPerTile, smem + TBYTES, wave, do_lane_off);
+    load_stats(head0, qt0 * kKeysPerTile);
+  }
+  store_stats(smem);
+  wait_tile_loads();
+  __syncthreads();
+
+  int n_round = (n_it + 1) / 2;
+  for (int rnd = 0; rnd < n_round; ++rnd) {
+    int it = 2 * rnd + grp;
+    bool active = it < n_it;  // the last round of group 1 is empty when n_it is odd
+    int head, qt;
+    tile_of(active ? it : 0, head, qt);
+    (void)head;
+    const char* qtile = smem + (rnd & 1) * STAGE;
+    const char* dotile = qtile + TBYTES;
+    const float* st_lse = reinterpret_cast<const float*>(qtile + 2 * TBYTES);
+    const float* st_delta = st_lse + 64;
+    char* nxt = smem + ((rnd + 1) & 1) * STAGE;
+    bool more = it + 2 < n_it;
+    // The swizzled LDS addresses are cheap to rebuild (a few XORs); hiding the lane id from the optimiser
+    // here keeps it from carrying some twenty address registers across iterations and spilling
+    // accumulators instead.
+    int lane_l = lane;
+    asm volatile("" : "+v"(lane_l));
+    int col_l = lane_l & 31, half_l = lane_l >> 5;
+    const char* vslot_l = vslots + (wave8 * V_IN_LDS * 64 + lane_l) * 16;
+    if (more) {  // the other stage was last read before the barrier that ended the previous iteration
+      int nhead, nqt;
+      tile_of(it + 2, nhead, nqt);
+      load_tile_async<DH>(qkv + nhead * DH, ld, nqt * kKeysPerTile, nxt, wave, q_lane_off);
+      load_tile_async<DH>(d_o + nhead * DH, h, nqt * kKeysPerTile, nxt + TBYTES, wave, do_lane_off);
+      load_stats(nhead, nqt * kKeysPerTile);
+    }
+    int q0 = qt * kKeysPerTile;
+    int key = kw0 + col;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {  // 32-row halves of the query tile, one at a time (keeps registers low)
+      int qs0 = q0 + 32 * j;
+      if (!active || qs0 + 31 < kw0) continue;  // nothing to do, or every row of this half is above every key
+      f32x16 sacc, pacc;
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {  // accumulator row 8 b + 4 half + r is query row 32 j + that
+        f32x4 l4 = *reinterpret_cast<const f32x4*>(st_lse + 32 * j + 8 * b + 4 * half_l);
+        f32x4 d4 = *reinterpret_cast<const f32x4*>(st_delta + 32 * j + 8 * b + 4 * half_l);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          sacc[4 * b + r] = l4[r];
+          pacc[4 * b + r] = d4[r];
+        }
+      }
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk) {
+        bf16x8 qa = read_row_fragment<DH>(qtile, 32 * j + col_l, 2 * kk + half_l);
+        bf16x8 da = read_row_fragment<DH>(dotile, 32 * j + col_l, 2 * kk + half_l);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[kk], sacc, 0, 0, 0);
+        bf16x8 vb;
+        if (kk < V_IN_REG)
+          vb = vf[kk];
+        else
+          vb = *reinterpret_cast<const bf16x8*>(vslot_l + (kk - V_IN_REG) * 1024);
+        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vb, pacc, 0, 0, 0);
+      }
+      bool need_mask = qs0 < kw0 + 31;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) sacc[e] = fast_exp2(sacc[e] * c);
+      if (need_mask) {  // only tiles that straddle the diagonal pay for the mask
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (key > qs0 + 8 * (e >> 2) + 4 * half + (e & 3)) sacc[e] = 0.f;
+      }
+#pragma unroll
+      for (int e = 0; e < 16; ++e) pacc[e] *= sacc[e];
+      bf16x8 pf[2] = {pack_bf16x8(sacc, 0), pack_bf16x8(sacc, 8)};
+      bf16x8 dsf[2] = {pack_bf16x8(pacc, 0), pack_bf16x8(pacc, 8)};
+#pragma unroll
+      for (int d = 0; d < DT; ++d)
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+          bf16x8 dot = read_tr_fragment<DH>(dotile, 32 * j + 16 * st, 32 * d, lane_l);
+          bf16x8 qtr = read_tr_fragment<DH>(qtile, 32 * j + 16 * st, 32 * d, lane_l);
+          dv[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dot, pf[st], dv[d], 0, 0, 0);
+          dk[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qtr, dsf[st], dk[d], 0, 0, 0);
+        }
+    }
+    if (more) store_stats(nxt);
+    wait_tile_loads();
+    __syncthreads();
+  }
+
+  // group 1 -> LDS -> group 0: 2 * DT * 16 floats per lane (the stages are free after the last barrier)
+  // The lane id is rebuilt here (two mbcnt instructions) rather than kept in a register across the loop, where
+  // every register is taken.
+  int lane_e = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+  float* xch = reinterpret_cast<float*>(smem_all) + wave * (64 * 2 * DT * 16) + lane_e;
+  if (grp == 1) {
+#pragma unroll
+    for (int d = 0; d < DT; ++d)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        xch[(d * 16 + e) * 64] = dk[d][e];
+        xch[((DT + d) * 16 + e) * 64] = dv[d][e];
+      }
+  }
+  __syncthreads();
+  if (grp == 0) {
+    int half = lane_e >> 5;
+    int key = kw0 + (lane_e & 31);
+#pragma unroll
+    for (int d = 0; d < DT; ++d)
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        bf16x4 vk, vv;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          int e = 4 * b + r;
+          vk[r] = (bf16)((dk[d][e] + xch[(d * 16 + e) * 64]) * scale);
+          vv[r] = (bf16)(dv[d][e] + xch[((DT + d) * 16 + e) * 64]);
+        }
+        size_t off = (size_t)key * ld_out + out_k0 + blockIdx.x * DH + 32 * d + 8 * b + 4 * half;
+        *reinterpret_cast<bf16x4*>(out + off) = vk;
+        *reinterpret_cast<bf16x4*>(out + off + out_v_delta) = vv;
+      }
+  }
+}
+
 // ==================================================================================
 // Backward, part 2: dQ.  Block = 128 QT query rows (a wave owns 32 QT), loop over the
 // key tiles up to the diagonal.  The K tile is read both ways (row fragments for
@@ -1033,11 +1243,28 @@ static bool launch_bwd(const bf16* qkv, const bf16* o, const float* lse, const b
   // Few key/value heads: one block per query head and a per-group sum afterwards (needs the [s, 2h] workspace),
   // once the direct launch would not fill the chip's 512 block slots.
   bool split = group > 1 && partials && (int64_t)n_kv_heads * (s / 128) < 512;
+  // At most one block per CU: the eight-wave kernel, which halves a wave's chain of tiles.
+  constexpr int smem_kv8 = 4 * (2 * tile_bytes<DH>() + 512) + (DH == 128 ? 16384 : 0);
+  auto kkv8 = attn_bwd_dkv_split_mfma_kernel<DH>;
+  bool eight = (int64_t)(split ? n_heads : n_kv_heads) * (s / 128) <= 256;
+  static bool eight_configured = false;
+  if (eight && !eight_configured) {
+    PO_HIP_OK(hipFuncSetAttribute(reinterpret_cast<const void*>(kkv8), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  smem_kv8));
+    eight_configured = true;
+  }
   if (split) {
-    kkv<<<dim3(n_heads, s / 128), 256, smem_kv, stream>>>(qkv, d_o, lse, delta, partials, 2 * h, 0, h, 1, s, h, hkv,
-                                                         group, scale);
+    if (eight)
+      kkv8<<<dim3(n_heads, s / 128), 512, smem_kv8, stream>>>(qkv, d_o, lse, delta, partials, 2 * h, 0, h, 1, s, h,
+                                                              hkv, group, scale);
+    else
+      kkv<<<dim3(n_heads, s / 128), 256, smem_kv, stream>>>(qkv, d_o, lse, delta, partials, 2 * h, 0, h, 1, s, h,
+                                                           hkv, group, scale);
     size_t n = (size_t)s * (2 * hkv / 8);
     attn_group_sum_kernel<DH><<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(partials, dqkv, s, h, hkv, group);
+  } else if (eight) {
+    kkv8<<<dim3(n_kv_heads, s / 128), 512, smem_kv8, stream>>>(qkv, d_o, lse, delta, dqkv, h + 2 * hkv, h, hkv,
+                                                               group, s, h, hkv, group, scale);
   } else {
     kkv<<<dim3(n_kv_heads, s / 128), 256, smem_kv, stream>>>(qkv, d_o, lse, delta, dqkv, h + 2 * hkv, h, hkv, group, s,
                                                             h, hkv, group, scale);
