@@ -125,10 +125,18 @@ class StageRunner:
         g = torch.Generator(device=self.device)
         g.manual_seed(self.seed + seed)
         dt = torch_dtype(self.cfg)
-        self.x = [torch.randn(s, h, generator=g, device=self.device, dtype=torch.float32).to(dt) for _ in range(n)]
+        vocab = self.shape.vocab
+        self.x, self.dx = [], []
+        for i in range(n):
+            embed = vocab > 0 and i < self.m  # units of chunk 0 take token ids and have no input gradient
+            if embed:
+                self.x.append(torch.randint(0, vocab, (s,), generator=g, device=self.device, dtype=torch.int32))
+                self.dx.append(None)
+            else:
+                self.x.append(torch.randn(s, h, generator=g, device=self.device, dtype=torch.float32).to(dt))
+                self.dx.append(torch.empty(s, h, dtype=dt, device=self.device))
         self.dy = [torch.randn(s, h, generator=g, device=self.device, dtype=torch.float32).to(dt) for _ in range(n)]
         self.y = [torch.empty(s, h, dtype=dt, device=self.device) for _ in range(n)]
-        self.dx = [torch.empty(s, h, dtype=dt, device=self.device) for _ in range(n)]
         torch.cuda.synchronize()
 
     def zero_grads(self):
