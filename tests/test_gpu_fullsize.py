@@ -167,9 +167,9 @@ def test_one_c2_shaped_layer_through_the_stage(gpu_device):
         assert max_rel_err(g["layers"][0][k], a) < 2e-2, k
 
 
-@pytest.mark.parametrize("name,layers,m", [("C3", 2, 4), ("C5", 1, 2)], ids=["C3", "C5"])
+@pytest.mark.parametrize("name,layers,m", [("C2", 2, 4), ("C3", 2, 4), ("C5", 1, 2)], ids=["C2", "C3", "C5"])
 def test_offload_is_bit_identical_at_full_shapes(gpu_device, name, layers, m):
-    """The shapes of C3 and C5 (h 4096 / 5120, s 4096 / 16384) through the stage with fewer layers and
+    """The shapes of C2, C3 and C5 (h 2048 / 4096 / 5120, s 2048 / 4096 / 16384) through the stage with fewer layers and
     microbatches: outputs, input gradients and parameter gradients with every unit offloaded and reloaded are
     bit-identical to the run that keeps everything on the device, under 1F1B and under the split-backward
     schedule; the device holds fewer units at once."""
