@@ -181,7 +181,8 @@ def test_invalid_configs_are_rejected_without_touching_the_gpu():
     good = harness.make_config(syn.CONFIGS["C1"])
     assert po.po_param_count(good) > 0
     for field, value in [("n_layers", 0), ("n_chunks", 3), ("hidden", 100), ("n_heads", 7), ("seq", 0),
-                         ("dtype", 5), ("rank", 2), ("copy_streams", 3), ("ln_eps", 0.0)]:
+                         ("dtype", 5), ("rank", 2), ("copy_streams", 3), ("ln_eps", 0.0), ("slot_k", -1.0), ("dropout_p", 1.0),
+                         ("group", 5), ("min_gap_passes", -1), ("n_kv_heads", 3), ("weight_stream", 2)]:
         cfg = harness.make_config(syn.CONFIGS["C1"])
         setattr(cfg, field, value)
         with pytest.raises(po.PipeOffloadError) as e:
