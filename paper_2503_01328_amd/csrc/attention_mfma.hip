@@ -209,6 +209,7 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_fwd_mfma_kernel(con
         for (int j = 0; j < 2; ++j)
 #pragma unroll
           for (int e = 0; e < 16; ++e) sacc[t][j][e] = 0.f;
+      __builtin_amdgcn_s_setprio(1);
 #pragma unroll
       for (int kk = 0; kk < KS; ++kk) {
         bf16x8 kf[2];
@@ -220,6 +221,7 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_fwd_mfma_kernel(con
           for (int j = 0; j < 2; ++j)
             sacc[t][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j], qf[t][kk], sacc[t][j], 0, 0, 0);
       }
+      __builtin_amdgcn_s_setprio(0);
       bf16x8 pf[QT][2][2];  // [q tile][key sub-tile][16-key step]
 #pragma unroll
       for (int t = 0; t < QT; ++t) {
@@ -266,6 +268,7 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_fwd_mfma_kernel(con
         }
       }
       // O^T += V^T P^T : rows = head dimension, columns = query rows, contraction over keys
+      __builtin_amdgcn_s_setprio(1);
 #pragma unroll
       for (int d = 0; d < DT; ++d)
 #pragma unroll
@@ -277,6 +280,7 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_fwd_mfma_kernel(con
             for (int t = 0; t < QT; ++t)
               oacc[t][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[t][j][st], oacc[t][d], 0, 0, 0);
           }
+      __builtin_amdgcn_s_setprio(0);
     }
     wait_tile_loads();
     __syncthreads();
@@ -370,6 +374,7 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_split_mfma_kernel(const bf16*
       for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int e = 0; e < 16; ++e) sacc[j][e] = 0.f;
+      __builtin_amdgcn_s_setprio(1);
 #pragma unroll
       for (int kk = 0; kk < KS; ++kk) {
 #pragma unroll
@@ -378,6 +383,7 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_split_mfma_kernel(const bf16*
           sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[j], 0, 0, 0);
         }
       }
+      __builtin_amdgcn_s_setprio(0);
       int q = qw0 + col;
       if (key0 + kKeysPerTile - 1 > qw0) {
 #pragma unroll
@@ -421,6 +427,7 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_split_mfma_kernel(const bf16*
         pf[j][0] = pack_bf16x8(sacc[j], 0);
         pf[j][1] = pack_bf16x8(sacc[j], 8);
       }
+      __builtin_amdgcn_s_setprio(1);
 #pragma unroll
       for (int d = 0; d < DT; ++d)
 #pragma unroll
@@ -430,6 +437,7 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_split_mfma_kernel(const bf16*
             bf16x8 vf = read_tr_fragment<DH>(vtile, 32 * j + 16 * st, 32 * d, lane);
             oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[j][st], oacc[d], 0, 0, 0);
           }
+      __builtin_amdgcn_s_setprio(0);
     }
     wait_tile_loads();
     __syncthreads();
