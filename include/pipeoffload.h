@@ -191,8 +191,8 @@ void po_stage_destroy(po_stage* st);
  * number of fp32 elements; backward ADDS into it, the caller zeroes it. */
 int po_bind_params(po_stage* st, const void* params, float* grads);
 
-/* Forward of unit (mb, chunk) on the compute stream (rows a0-a7: LN, QKV, causal
- * attention, out-proj + residual, LN, FC1 + GeLU, FC2 + residual per layer).
+/* Forward of unit (mb, chunk) on the compute stream (per layer: LN, QKV, causal
+ * attention, out-proj + residual, LN, FC1 + GeLU, FC2 + residual).
  * x_in: DEVICE [s, h] of cfg.dtype, or int32 tokens [s] when vocab > 0 and chunk == 0.
  * y_out: DEVICE [s, h].  The unit becomes RESIDENT. */
 int po_stage_forward(po_stage* st, int32_t mb, int32_t chunk, const void* x_in, void* y_out);
@@ -241,17 +241,18 @@ int po_get_stats(const po_stage* st, po_stats* out);
 /* ---- single operations (what the stage is built from; for tests and
  * micro-benchmarks).  All pointers DEVICE, stream = hipStream_t or NULL. ----- */
 
-/* y = LN(x) * gain + shift, rows x h (row a1/a5). */
+/* y = LN(x) * gain + shift, rows x h (either LayerNorm of a layer; recomputed in backward, Appendix C). */
 int po_op_layernorm_forward(int32_t dtype, const void* x, const void* gain, const void* shift, void* y,
                             int32_t rows, int32_t h, float eps, void* stream);
-/* dx = dres + LNbwd(dn; x, gain); dgain += ..., dshift += ... (fp32) (rows a14/a18).
+/* dx = dres + LNbwd(dn; x, gain); dgain += ..., dshift += ... (fp32): backward of either LayerNorm of a layer.
  * partials: fp32 workspace of po_op_layernorm_backward_workspace(rows, h) bytes. */
 int po_op_layernorm_backward(int32_t dtype, const void* dn, const void* x, const void* gain, const void* dres,
                              void* dx, float* dgain, float* dshift, float* partials, int32_t rows, int32_t h,
                              float eps, void* stream);
 uint64_t po_op_layernorm_backward_workspace(int32_t rows, int32_t h);
 
-/* C = op(A) op(B) with the epilogues of the stage (rows a2, a4, a6, a7, a12-a17).
+/* C = op(A) op(B) with the epilogues of the stage (the four projections of a layer: forward, input gradient
+ * and weight gradient).
  * trans_a == 0: A is [M, K]; 1: A is [K, M].  trans_b == 0: B is [K, N]; 1: B is [N, K].
  * bias [N] and residual [M, N] may be NULL.  out [M, N] of dtype may be NULL.
  * gelu_out: if not NULL receives gelu(out).  gelu_u: if not NULL, out = result * gelu'(gelu_u)
@@ -260,12 +261,12 @@ int po_op_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32
                const void* A, int32_t lda, const void* B, int32_t ldb, const void* bias, const void* residual,
                void* out, void* gelu_out, const void* gelu_u, float* acc_f32, int32_t force_generic, void* stream);
 
-/* Causal attention forward (row a3): qkv [s, h + 2 hkv] (q | k | v blocks, hkv = n_kv_heads * h / n_heads;
+/* Causal attention forward: qkv [s, h + 2 hkv] (q | k | v blocks, hkv = n_kv_heads * h / n_heads;
  * n_kv_heads = 0 means n_heads, i.e. [s, 3h]), o [s, h], lse [a, s] fp32.  With n_kv_heads < n_heads query head t
  * reads key/value head t / (n_heads / n_kv_heads) (grouped-query attention, Table 2). */
 int po_op_attention_forward(int32_t dtype, const void* qkv, void* o, float* lse, int32_t s, int32_t h,
                             int32_t n_heads, int32_t n_kv_heads, int32_t force_generic, void* stream);
-/* Causal attention backward (row a16): dqkv laid out like qkv; delta: fp32 workspace [a, s]; partials: NULL, or
+/* Causal attention backward: dqkv laid out like qkv; delta: fp32 workspace [a, s]; partials: NULL, or
  * a [s, 2h] workspace of dtype that lets grouped-query shapes with few key/value heads compute dK/dV per query
  * head and add the groups up afterwards (same result up to the rounding of the per-head terms). */
 int po_op_attention_backward(int32_t dtype, const void* qkv, const void* o, const float* lse, const void* d_o,
@@ -279,13 +280,14 @@ int po_op_attention_backward(int32_t dtype, const void* qkv, const void* o, cons
 int po_op_dropout(int32_t dtype, const void* x, void* out, int32_t rows, int32_t cols, float p, uint64_t seed,
                   int32_t layer, int32_t site, int32_t mb, void* stream);
 
-/* acc[N] += column sums of x [rows, N] (bias gradients, rows a12-a17), deterministic: row chunks
+/* acc[N] += column sums of x [rows, N] (bias gradients), deterministic: row chunks
  * are reduced to partials in `workspace` (fp32, po_op_colsum_workspace bytes), then added in chunk order. */
 uint64_t po_op_colsum_workspace(int32_t rows, int32_t n);
 int po_op_colsum_accumulate(int32_t dtype, const void* x, float* acc, float* workspace, int32_t rows, int32_t n,
                             void* stream);
 
-/* Gather n_seg segments into one contiguous buffer / scatter them back (rows a8/a11).
+/* Gather n_seg segments into one contiguous buffer / scatter them back (a layer's saved set to and from a
+ * staging buffer, Section 4.2).
  * seg_ptrs: HOST array of DEVICE pointers; seg_bytes: HOST array, each a multiple of 16.
  * Segments land back to back in `packed` in array order. */
 int po_op_pack(const void* const* seg_ptrs, const uint64_t* seg_bytes, int32_t n_seg, void* packed, void* stream);

@@ -82,11 +82,15 @@ int validate_config(const po_config* c) {
       c->rank < 0 || c->rank >= c->pipeline_degree || c->prefetch_passes < 0 ||
       (c->copy_streams != 1 && c->copy_streams != 2) || c->hidden / c->n_heads > 256 ||
       (c->hidden / c->n_heads) % 8 != 0 || !(c->ln_eps > 0.f) || c->group < 0 || c->group > c->pipeline_degree ||
-      (c->group > 0 && 2 * c->group < c->pipeline_degree) || (c->weight_stream != 0 && c->weight_stream != 1) || c->min_gap_passes < 0 || c->n_kv_heads < 0 || !(c->dropout_p >= 0.f && c->dropout_p < 1.f) || !(c->slot_k >= 0.f) ||
-      (c->n_kv_heads > 0 && c->n_heads % c->n_kv_heads != 0)) {
-    set_error("invalid config: L=%d v=%d h=%d a=%d f=%d s=%d vocab=%d dtype=%d d=%d rank=%d prefetch=%d copy_streams=%d group=%d",
-              c->n_layers, c->n_chunks, c->hidden, c->n_heads, c->ffn, c->seq, c->vocab, c->dtype,
-              c->pipeline_degree, c->rank, c->prefetch_passes, c->copy_streams, c->group);
+      (c->group > 0 && 2 * c->group < c->pipeline_degree) || (c->weight_stream != 0 && c->weight_stream != 1) ||
+      c->min_gap_passes < 0 || c->n_kv_heads < 0 || !(c->dropout_p >= 0.f && c->dropout_p < 1.f) ||
+      !(c->slot_k >= 0.f) || (c->n_kv_heads > 0 && c->n_heads % c->n_kv_heads != 0)) {
+    set_error(
+        "invalid config: L=%d v=%d h=%d a=%d kv_heads=%d f=%d s=%d vocab=%d dtype=%d d=%d rank=%d prefetch=%d "
+        "copy_streams=%d group=%d weight_stream=%d min_gap=%d dropout_p=%g slot_k=%g ln_eps=%g",
+        c->n_layers, c->n_chunks, c->hidden, c->n_heads, c->n_kv_heads, c->ffn, c->seq, c->vocab, c->dtype,
+        c->pipeline_degree, c->rank, c->prefetch_passes, c->copy_streams, c->group, c->weight_stream,
+        c->min_gap_passes, (double)c->dropout_p, (double)c->slot_k, (double)c->ln_eps);
     return PO_E_INVAL;
   }
   return PO_OK;
@@ -224,7 +228,11 @@ struct Pool {
                   hipGetErrorString(e));
         return host ? PO_E_HOST_OOM : PO_E_DEVICE_OOM;
       }
-      PO_HIP(hipEventCreateWithFlags(&b.free_event, hipEventDisableTiming));
+      if (hipEventCreateWithFlags(&b.free_event, hipEventDisableTiming) != hipSuccess) {
+        (void)(host ? hipHostFree(b.ptr) : hipFree(b.ptr));
+        set_error("creating a pool buffer's guard event failed");
+        return PO_E_HIP;
+      }
       bufs.push_back(b);
       idx = (int)bufs.size() - 1;
     }
@@ -726,7 +734,11 @@ int stage_offload(po_stage* st, int mb, int chunk, float ratio) {
     if (st->cfg.staged_copies) {
       int stg;
       rc = st->dev_pool.acquire(q, &stg);
-      if (rc) return rc;
+      if (rc) {  // the layer stays resident; its host buffer goes back unused
+        (void)st->host_pool.release(L.hostbuf, q);
+        L.hostbuf = -1;
+        return rc;
+      }
       st->note_usage();
       char* staging = st->dev_pool.bufs[stg].ptr;
       void* ptrs[6];
@@ -1530,8 +1542,11 @@ int po_run_schedule(po_stage* st, int32_t schedule, int32_t m, float ratio, cons
 int po_synchronize(po_stage* st) {
   PO_NEED_STAGE(st);
   int rc = stage_synchronize(st);
-  if (rc == PO_OK && st->in_flight_units == 0) st->sync_events.reset();  // nothing refers to them any more
-  return rc;
+  if (rc != PO_OK) return rc;
+  for (const auto& kv : st->units)
+    if (kv.second.live) return PO_OK;  // a unit between passes still holds some of the events
+  st->sync_events.reset();
+  return PO_OK;
 }
 int po_get_stats(const po_stage* st, po_stats* out) {
   PO_NEED_STAGE(st);
