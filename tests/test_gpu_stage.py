@@ -177,6 +177,42 @@ def test_manual_calls_partial_ratio_and_state_errors(gpu_device):
         assert torch.equal(partial[0], r.dx[0]) and torch.equal(partial[1], r.grads) and torch.equal(partial[2], r.y[0])
 
 
+def test_manual_calls_in_a_long_loop_keep_pools_and_results_stable(gpu_device):
+    """The four stage calls driven by hand for many microbatches (two units in flight, every unit offloaded and
+    reloaded, a po_synchronize now and then): the pools stop growing after the first units and a repeated input
+    gives the same output and input gradient, bit for bit, every time."""
+    shape = syn.StageShape(2, 1, 128, 2, 512, 64, dtype="bf16", pipeline_degree=2, n_microbatches=2)
+    with StageRunner(shape) as r:
+        r.make_inputs()
+        st = r.stage
+        first = {}
+        grown = None
+        po.po_stage_forward(st, 0, 0, r.x[0], r.y[0])
+        po.po_offload(st, 0, 0, 1.0)
+        for n in range(1, 61):
+            cur, prev = n % 2, (n - 1) % 2
+            po.po_stage_forward(st, n, 0, r.x[cur], r.y[cur])
+            po.po_offload(st, n, 0, 1.0)
+            po.po_reload(st, n - 1, 0)
+            po.po_stage_backward(st, n - 1, 0, r.dy[prev], r.dx[prev])
+            if n % 7 == 0:
+                po.po_synchronize(st)
+                s = po.po_get_stats(st)
+                sizes = (s["pool_bytes_allocated"], s["host_bytes_allocated"])
+                assert grown is None or sizes == grown
+                grown = sizes
+                snap = (r.y[prev].clone(), r.dx[prev].clone())
+                if prev in first:
+                    assert torch.equal(first[prev][0], snap[0]) and torch.equal(first[prev][1], snap[1])
+                else:
+                    first[prev] = snap
+        po.po_reload(st, 60, 0)
+        po.po_stage_backward(st, 60, 0, r.dy[0], r.dx[0])
+        po.po_synchronize(st)
+        assert len(first) == 2 and torch.isfinite(r.grads).all()
+        assert po.po_get_stats(st)["n_offloads"] == 61 * 2
+
+
 def test_pool_caps_give_oom_codes(gpu_device):
     shape = syn.StageShape(2, 1, 128, 2, 512, 64, dtype="f32", pipeline_degree=4, n_microbatches=4)
     layer_bytes = po.po_saved_bytes_per_layer(po.po_config_default(
