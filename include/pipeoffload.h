@@ -261,6 +261,11 @@ int po_op_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32
                const void* A, int32_t lda, const void* B, int32_t ldb, const void* bias, const void* residual,
                void* out, void* gelu_out, const void* gelu_u, float* acc_f32, int32_t force_generic, void* stream);
 
+/* Pure host code: the output tile (rows, columns) of the bf16 matrix-core kernel that po_op_gemm and the stage
+ * use for an M x N result whose K is a multiple of 64: 256 x 256, 256 x 192 or 128 x 128, chosen so that a round of
+ * tiles fills the 256 compute units; 0, 0 when M, N fit none of them (the shape-generic kernel runs instead). */
+int po_op_gemm_tile(int32_t M, int32_t N, int32_t* tile_rows, int32_t* tile_cols);
+
 /* Causal attention forward: qkv [s, h + 2 hkv] (q | k | v blocks, hkv = n_kv_heads * h / n_heads;
  * n_kv_heads = 0 means n_heads, i.e. [s, 3h]), o [s, h], lse [a, s] fp32.  With n_kv_heads < n_heads query head t
  * reads key/value head t / (n_heads / n_kv_heads) (grouped-query attention, Table 2). */

@@ -92,6 +92,7 @@ EXPORTS = {
                                                                            C.c_void_p]),
     "po_op_gemm": (C.c_int, [C.c_int32] * 6 + [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32] + [C.c_void_p] * 6 +
                    [C.c_int32, C.c_void_p]),
+    "po_op_gemm_tile": (C.c_int, [C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "po_op_attention_forward": (C.c_int, [C.c_int32] + [C.c_void_p] * 3 + [C.c_int32] * 5 + [C.c_void_p]),
     "po_op_attention_backward": (C.c_int, [C.c_int32] + [C.c_void_p] * 7 + [C.c_int32] * 5 + [C.c_void_p]),
     "po_op_dropout": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_uint64,
@@ -276,6 +277,13 @@ def po_op_gemm(dtype, trans_a, trans_b, M, N, K, A, lda, B, ldb, bias=None, resi
                gelu_u=None, acc_f32=None, force_generic=0, stream=None):
     _check(lib.po_op_gemm(dtype, trans_a, trans_b, M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(bias), _ptr(residual),
                           _ptr(out), _ptr(gelu_out), _ptr(gelu_u), _ptr(acc_f32), force_generic, _stream(stream)))
+
+
+def po_op_gemm_tile(M, N):
+    """(tile rows, tile columns) of the bf16 matrix-core GEMM for an M x N result; (0, 0) if it has none."""
+    bm, bn = C.c_int32(0), C.c_int32(0)
+    _check(lib.po_op_gemm_tile(M, N, C.byref(bm), C.byref(bn)))
+    return bm.value, bn.value
 
 
 def po_op_attention_forward(dtype, qkv, o, lse, s, h, n_heads, force_generic=0, stream=None, n_kv_heads=0):

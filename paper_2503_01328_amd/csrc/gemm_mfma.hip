@@ -3,7 +3,9 @@
 // One 256-thread block (4 waves, 2 x 2) owns a (64*WTM) x (64*WTN) tile of C; a
 // wave owns WTM x WTN MFMA tiles of 32 x 32, i.e. up to 128 x 128 with 256 fp32
 // accumulators per lane.  K is walked in slices of 64 through a ring of LDS stages: two for the
-// 256 x 256 tile, four for the 128 x 128 tile, whose slices are too short to cover a memory round trip.
+// 256 x 256 and 256 x 192 tiles, four for the 128 x 128 tile, whose slices are too short to cover a
+// memory round trip.  The 256 x 192 tile exists for outputs whose 256 x 256 tiles would leave a
+// quarter of the chip idle (192 of them where 256 of the narrower ones fit).
 //
 // Operand slices travel HBM -> LDS directly (global_load_lds_dwordx4: lane L of
 // a wave deposits its 16 bytes at LDS base + 16 L), so no registers and no
@@ -17,7 +19,7 @@
 //     an MFMA fragment is one ds_read_b128.
 //   operand whose contiguous index is m or n (B of forward, both of wgrad):
 //     "k-major tile" [64][rows] bf16, 32-byte unit u of a row stored at
-//     u ^ (k & 7); an MFMA fragment is two transposing reads (ds_read_b64_tr_b16),
+//     u ^ (k & 7) (u ^ (k & 3) when a row has 12 units); an MFMA fragment is two transposing reads (ds_read_b64_tr_b16),
 //     arranged so that a lane receives k = 16 kk + 8 half + 0..7 exactly as the
 //     ds_read_b128 path does, which lets the two kinds be mixed in one MFMA.
 // Nothing is transposed in registers.
@@ -32,6 +34,7 @@
 // modulo 8) work on neighbouring tiles and share operand slices in that XCD's L2.
 #include <type_traits>
 
+#include <stdint.h>
 #include <stdlib.h>
 
 #include "kernels.h"
@@ -58,16 +61,25 @@ enum EpiKind : int { kEpiStore = 0, kEpiStoreGelu = 1, kEpiGeluBackward = 2, kEp
 // `base` points at (first row of the tile, k = 0); the slice starts at k0.
 // The slice is issued in four quarters (part = 0..3) so that the issue can be spread between the MFMAs
 // of the four k-steps of the slice being consumed; part < 0 issues everything.
+// Swizzle of the k-major tile: row k keeps unit u at position u ^ (k & mask).  The position must stay inside
+// the row, so a row of 12 units (R = 192) swaps only within groups of four; the fragment reads of four
+// consecutive k and two neighbouring units still fall into eight different 32-byte bank groups.
+template <int R>
+__device__ __forceinline__ int kmajor_unit(int u, int k) {
+  static_assert(R % 64 == 0, "rows of the k-major tile are whole groups of four units");
+  constexpr int MASK = (R % 128 == 0) ? 7 : 3;
+  return u ^ (k & MASK);
+}
+
 template <int R, bool KMAJOR>
 __device__ __forceinline__ void load_slice(const bf16* __restrict__ base, int ld, int k0, char* lds, int wave,
                                            int lane, int part = -1) {
   constexpr int N_INST = R * 128 / 1024;  // wave-level 1 KiB loads in the slice
   constexpr int PER_WAVE = N_INST / 4;
-  constexpr int PER_PART = PER_WAVE / 4;
-  static_assert(PER_PART >= 1, "tile too small to split the slice in four");
+  static_assert(N_INST % 4 == 0 && PER_WAVE >= 4, "tile too small to split the slice in four");
 #pragma unroll
   for (int u = 0; u < PER_WAVE; ++u) {
-    if (part >= 0 && u / PER_PART != part) continue;
+    if (part >= 0 && u * 4 / PER_WAVE != part) continue;
     int g = u * 4 + wave;  // which 1 KiB piece of the tile this wave fills now
     const bf16* src;
     if (!KMAJOR) {
@@ -79,7 +91,7 @@ __device__ __forceinline__ void load_slice(const bf16* __restrict__ base, int ld
       int byte = g * 1024 + lane * 16;
       int k = byte / ROW_BYTES;
       int pos16 = (byte % ROW_BYTES) >> 4;
-      int unit = (pos16 >> 1) ^ (k & 7);
+      int unit = kmajor_unit<R>(pos16 >> 1, k);
       src = base + (size_t)(k0 + k) * ld + (unit * 2 + (pos16 & 1)) * 8;
     }
     // Issued as inline assembly on purpose: through the builtin the compiler treats every later
@@ -115,8 +127,8 @@ __device__ __forceinline__ bf16x8 read_fragment(const char* lds, int row0, int k
     int k = 16 * kk + 8 * (grp >> 1) + (i >> 2);
     int unit = m >> 4;
     int inner = (m & 15) * 2;
-    const char* p0 = lds + k * ROW_BYTES + ((unit ^ (k & 7)) << 5) + inner;
-    const char* p1 = lds + (k + 4) * ROW_BYTES + ((unit ^ ((k + 4) & 7)) << 5) + inner;
+    const char* p0 = lds + k * ROW_BYTES + (kmajor_unit<R>(unit, k) << 5) + inner;
+    const char* p1 = lds + (k + 4) * ROW_BYTES + (kmajor_unit<R>(unit, k + 4) << 5) + inner;
     s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PO_LDS_S16X4(p0));
     s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PO_LDS_S16X4(p1));
     union {
@@ -182,6 +194,9 @@ __device__ __forceinline__ void epilogue_row_piece(const Epilogue& e, int m, int
   }
 }
 
+// LDS stages of a tile: what fits into 160 KiB at (BM + BN) * 128 bytes per stage.
+constexpr int stages_of(int wtm, int wtn) { return wtm * wtn >= 12 ? 2 : 4; }
+
 // ---- the kernel ---------------------------------------------------------------
 // TA: A is [K, M] (m-contiguous).  TB: B is [K, N] (n-contiguous).
 template <int WTM, int WTN, bool TA, bool TB, int EPI>
@@ -226,7 +241,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int K, const bf16* __res
   // is multiplied, and a wave lets the NSTAGE - 2 youngest requested slices stay in flight when it waits for
   // the slice that the next barrier publishes.  The big tile has room for two stages (its slice takes about a
   // microsecond, which covers the round trip); the small tile's slice is four times shorter, so it gets four.
-  constexpr int NSTAGE = (WTM * WTN >= 16) ? 2 : 4;
+  constexpr int NSTAGE = stages_of(WTM, WTN);
   constexpr int PER_SLICE = (BM + BN) * 128 / 1024 / 4;  // load instructions of one wave per slice
   int nk = K / kBK;
   auto request = [&](int kt, int part) {
@@ -333,39 +348,45 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int K, const bf16* __res
     if (EPI == kEpiAccumulate) {
       // fp32 read-modify-write of the strip: all loads of the old values are issued before the first
       // add, so that a wave keeps 16 KiB in flight instead of one access at a time.
-      constexpr int LPR = STRIP_N / 4;  // lanes per row, 4 floats each
-      constexpr int RPI = 64 / LPR;     // rows per wave-wide access
-      constexpr int NIT = 32 / RPI;
+      constexpr int LPR = STRIP_N / 4;       // lanes per row, 4 floats each
+      constexpr int NIT = 32 * LPR / 64;     // wave-wide accesses per strip; piece it * 64 + lane of the strip
+      static_assert(32 * LPR % 64 == 0, "strip is a whole number of wave-wide accesses");
       f32x4 old[NIT];
-      float* cbase = ep.acc_f32 + (size_t)(mrow0 + lane / LPR) * ep.ldc + ncol0 + (lane % LPR) * 4;
-#pragma unroll
-      for (int it = 0; it < NIT; ++it)
-        old[it] = *reinterpret_cast<const f32x4*>(cbase + (size_t)(it * RPI) * ep.ldc);
+      float* cbase = ep.acc_f32 + (size_t)mrow0 * ep.ldc + ncol0;
 #pragma unroll
       for (int it = 0; it < NIT; ++it) {
-        int r = it * RPI + lane / LPR;
-        int c = (lane % LPR) * 4;
+        int piece = it * 64 + lane;
+        old[it] = *reinterpret_cast<const f32x4*>(cbase + (size_t)(piece / LPR) * ep.ldc + (piece % LPR) * 4);
+      }
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) {
+        int piece = it * 64 + lane;
+        int r = piece / LPR;
+        int c = (piece % LPR) * 4;
         f32x4 v = *reinterpret_cast<const f32x4*>(strip + r * STRIP_LD + c);
-        *reinterpret_cast<f32x4*>(cbase + (size_t)(it * RPI) * ep.ldc) = old[it] + v;
+        *reinterpret_cast<f32x4*>(cbase + (size_t)r * ep.ldc + c) = old[it] + v;
       }
     } else {
       constexpr int LPR = STRIP_N / 8;  // lanes per row, 8 values each
-      constexpr int RPI = 64 / LPR;
-      constexpr int NIT = 32 / RPI;
+      constexpr int NIT = 32 * LPR / 64;
+      static_assert(32 * LPR % 64 == 0, "strip is a whole number of wave-wide accesses");
       // the strip's pieces of u (GeLU backward) or of the residual are all requested before the first use
       bf16x8_t aux[NIT];
       const bf16* aux_src = EPI == kEpiGeluBackward ? static_cast<const bf16*>(ep.gelu_u)
                                                     : static_cast<const bf16*>(ep.residual);
       if (aux_src) {
-        const bf16* abase = aux_src + (size_t)(mrow0 + lane / LPR) * ep.ldc + ncol0 + (lane % LPR) * 8;
+        const bf16* abase = aux_src + (size_t)mrow0 * ep.ldc + ncol0;
 #pragma unroll
-        for (int it = 0; it < NIT; ++it)
-          aux[it] = *reinterpret_cast<const bf16x8_t*>(abase + (size_t)(it * RPI) * ep.ldc);
+        for (int it = 0; it < NIT; ++it) {
+          int piece = it * 64 + lane;
+          aux[it] = *reinterpret_cast<const bf16x8_t*>(abase + (size_t)(piece / LPR) * ep.ldc + (piece % LPR) * 8);
+        }
       }
 #pragma unroll
       for (int it = 0; it < NIT; ++it) {
-        int r = it * RPI + lane / LPR;
-        int c = (lane % LPR) * 8;
+        int piece = it * 64 + lane;
+        int r = piece / LPR;
+        int c = (piece % LPR) * 8;
         f32x4 v0 = *reinterpret_cast<const f32x4*>(strip + r * STRIP_LD + c);
         f32x4 v1 = *reinterpret_cast<const f32x4*>(strip + r * STRIP_LD + c + 4);
         float vv[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
@@ -377,8 +398,13 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int K, const bf16* __res
 
 // ---- host side ------------------------------------------------------------------
 // 256 x 256 tiles once they fill three quarters of the 256 CUs in one round (measured: 192 big tiles beat 768
-// small ones, 58 against 63 us at M = 2048, N = 6144, K = 2048); below that the 128 x 128 tile.
+// small ones, 58 against 63 us at M = 2048, N = 6144, K = 2048); below that the 128 x 128 tile.  Where N is a
+// multiple of 192 the 256 x 192 tile takes over when its rounds cost less: a round is as long as its slowest
+// block, so 256 narrower tiles in one round beat 192 big ones with a quarter of the CUs idle, and 512 in two
+// rounds beat 384 big ones (a narrow tile's round takes about 0.8 of a big tile's: 3/4 of the flops at
+// slightly more operand bytes per flop).
 static int tile_threshold() { return 192; }
+static int64_t rounds(int64_t tiles) { return (tiles + 255) / 256; }
 static void pick_tile(int M, int N, int& wtm, int& wtn) {
   wtm = wtn = 0;
   if (M % 256 == 0 && N % 256 == 0 && (int64_t)(M / 256) * (N / 256) >= tile_threshold()) {
@@ -386,6 +412,22 @@ static void pick_tile(int M, int N, int& wtm, int& wtn) {
   } else if (M % 128 == 0 && N % 128 == 0) {
     wtm = wtn = 2;
   }
+  if (M % 256 == 0 && N % 192 == 0 && (int64_t)(M / 256) * (N / 192) >= tile_threshold()) {
+    int64_t narrow = 8 * rounds((int64_t)(M / 256) * (N / 192));  // in tenths of a big tile's round
+    int64_t other = wtm == 4 ? 10 * rounds((int64_t)(M / 256) * (N / 256))
+                             : (wtm == 2 ? 4 * rounds((int64_t)(M / 128) * (N / 128)) : INT64_MAX);
+    if (narrow < other) {
+      wtm = 4;
+      wtn = 3;
+    }
+  }
+}
+
+void gemm_mfma_tile(int M, int N, int* bm, int* bn) {
+  int wtm = 0, wtn = 0;
+  if (M > 0 && N > 0) pick_tile(M, N, wtm, wtn);
+  *bm = 64 * wtm;
+  *bn = 64 * wtn;
 }
 
 bool gemm_mfma_supported(int trans_a, int trans_b, int M, int N, int K, int lda, int ldb, int ldc) {
@@ -400,7 +442,7 @@ template <int WTM, int WTN, bool TA, bool TB, int EPI>
 static bool launch_mfma_epi(int M, int N, int K, const bf16* A, int lda, const bf16* B, int ldb, const Epilogue& ep,
                             hipStream_t stream) {
   constexpr int BM = 64 * WTM, BN = 64 * WTN;
-  constexpr int smem_ops = ((WTM * WTN >= 16) ? 2 : 4) * (BM + BN) * 128;
+  constexpr int smem_ops = stages_of(WTM, WTN) * (BM + BN) * 128;
   constexpr int smem_epi = 4 * 32 * (WTN * 32 + 4) * 4;
   constexpr int smem = smem_ops > smem_epi ? smem_ops : smem_epi;
   auto kern = gemm_mfma_kernel<WTM, WTN, TA, TB, EPI>;
@@ -456,6 +498,7 @@ bool gemm_mfma_bf16(int trans_a, int trans_b, int M, int N, int K, const void* A
   pick_tile(M, N, wtm, wtn);
   const bf16* a = (const bf16*)A;
   const bf16* b = (const bf16*)B;
+  if (wtm == 4 && wtn == 3) return dispatch_trans<4, 3>(trans_a, trans_b, M, N, K, a, lda, b, ldb, ep, stream);
   if (wtm == 4) return dispatch_trans<4, 4>(trans_a, trans_b, M, N, K, a, lda, b, ldb, ep, stream);
   return dispatch_trans<2, 2>(trans_a, trans_b, M, N, K, a, lda, b, ldb, ep, stream);
 }

@@ -57,6 +57,8 @@ bool gemm_generic(int dtype, int trans_a, int trans_b, int M, int N, int K, cons
                   int ldb, const Epilogue& ep, hipStream_t stream);
 // bf16 MFMA path; returns false (with error text) if the shape is not supported.
 bool gemm_mfma_supported(int trans_a, int trans_b, int M, int N, int K, int lda, int ldb, int ldc);
+// Output tile (rows, columns) the bf16 MFMA path uses for an M x N result; 0, 0 if it has none for the shape.
+void gemm_mfma_tile(int M, int N, int* bm, int* bn);
 bool gemm_mfma_bf16(int trans_a, int trans_b, int M, int N, int K, const void* A, int lda, const void* B, int ldb,
                     const Epilogue& ep, hipStream_t stream);
 // Picks the MFMA kernel for bf16 when the shape allows it, else the generic one.

@@ -1603,6 +1603,17 @@ int po_op_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32
   return ok(gemm(dtype, trans_a != 0, trans_b != 0, M, N, K, A, lda, B, ldb, e, force_generic != 0,
                  (hipStream_t)stream));
 }
+int po_op_gemm_tile(int32_t M, int32_t N, int32_t* tile_rows, int32_t* tile_cols) {
+  if (!tile_rows || !tile_cols) {
+    set_error("po_op_gemm_tile: NULL output");
+    return PO_E_INVAL;
+  }
+  int bm, bn;
+  gemm_mfma_tile(M, N, &bm, &bn);
+  *tile_rows = bm;
+  *tile_cols = bn;
+  return PO_OK;
+}
 int po_op_attention_forward(int32_t dtype, const void* qkv, void* o, float* lse, int32_t s, int32_t h,
                             int32_t n_heads, int32_t n_kv_heads, int32_t force_generic, void* stream) {
   begin_launch();

@@ -202,6 +202,31 @@ def test_flatten_unflatten_roundtrip():
     assert (back["wte"] == params["wte"]).all() and (back["wpe"] == params["wpe"]).all()
 
 
+def test_gemm_tile_choice_fills_the_chip():
+    """Host logic of the bf16 GEMM: which output tile a shape gets.  The GEMM shapes of the five workloads, the
+    grouped-query QKV projection, and shapes that fit no tile."""
+    tile = po.po_op_gemm_tile
+    # C2 (tokens 2048, h 2048, f 8192): 2048 x 2048 results have only 64 big tiles -> 128 x 128;
+    # the QKV projection's 192 big tiles would leave 64 compute units idle -> 256 of the 256 x 192 tiles
+    assert tile(2048, 2048) == (128, 128)
+    assert tile(2048, 8192) == (256, 256) and tile(8192, 2048) == (256, 256)
+    assert tile(2048, 6144) == (256, 192)
+    # C3 / C5: whole rounds of big tiles
+    assert tile(4096, 4096) == (256, 256) and tile(4096, 12288) == (256, 256) and tile(4096, 16384) == (256, 256)
+    assert tile(16384, 15360) == (256, 256) and tile(16384, 5120) == (256, 256) and tile(5120, 15360) == (256, 256)
+    # C3 with 8 key/value heads: 384 big tiles need two rounds, 512 narrower ones too, at 3/4 of the work each
+    assert tile(4096, 6144) == (256, 192)
+    # too few tiles for the big shapes; no 192-wide tile when the row count is no multiple of 256
+    assert tile(256, 384) == (128, 128) and tile(128, 6144) == (128, 128) and tile(384, 128) == (128, 128)
+    # nothing fits: the shape-generic kernel runs
+    assert tile(200, 130) == (0, 0) and tile(64, 64) == (0, 0) and tile(0, 128) == (0, 0)
+    for M in range(128, 4097, 128):
+        for N in range(64, 6145, 64):
+            bm, bn = tile(M, N)
+            assert (bm, bn) in ((0, 0), (128, 128), (256, 192), (256, 256))
+            assert bm == 0 or (M % bm == 0 and N % bn == 0)
+
+
 def test_hot_kernels_keep_their_accumulators_in_registers():
     """The compiler's own resource report (written by the build): no MFMA kernel may use scratch memory - a GEMM
     whose 256 accumulators spill runs six times slower without failing any numerical test - and the attention
@@ -215,7 +240,9 @@ def test_hot_kernels_keep_their_accumulators_in_registers():
     usage = json.load(open(b.RESOURCES))
     gemm = {k: v for k, v in usage.items() if "gemm_mfma_kernel" in k}
     attn = {k: v for k, v in usage.items() if "attn_" in k and "_mfma_kernel" in k and "delta" not in k}
-    assert len(gemm) == 32 and len(attn) >= 12  # three kernels and their eight-wave forms, two head dimensions
+    # GEMM: three tiles x four operand layouts x four epilogues; attention: three kernels and their eight-wave
+    # forms, two head dimensions
+    assert len(gemm) == 48 and len(attn) >= 12
     for name, v in {**gemm, **attn}.items():
         assert v["ScratchSize"] == 0, (name, v)
     for name, v in attn.items():

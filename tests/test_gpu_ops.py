@@ -121,8 +121,14 @@ def test_gemm_generic_epilogues(gpu_device, dtype, epilogue):
     _gemm_case(gpu_device, dtype, 0, 0, 70, 130, 45, epilogue, 1)
 
 
-# MFMA path: 128-tiles (M, N multiples of 128) and 256-tiles (>= 200 tiles of 256 x 256), K multiple of 64
-MFMA_SHAPES = [(128, 128, 64), (256, 384, 192), (384, 128, 1024), (4096, 3328, 128)]
+# MFMA path: 128-tiles (M, N multiples of 128), 256-tiles (>= 192 tiles of 256 x 256) and 256 x 192 tiles (N a
+# multiple of 192 and a round of them cheaper), K multiple of 64 (one, two, three and many slices)
+MFMA_SHAPES = [(128, 128, 64), (256, 384, 192), (384, 128, 1024), (4096, 3328, 128), (2048, 6144, 64),
+               (4096, 3072, 192), (4096, 6144, 128), (2048, 6144, 512)]
+
+
+def test_gemm_mfma_shapes_cover_every_tile():
+    assert {po.po_op_gemm_tile(M, N) for M, N, _ in MFMA_SHAPES} == {(128, 128), (256, 256), (256, 192)}
 
 
 @pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0), (1, 1)])
@@ -132,7 +138,7 @@ def test_gemm_mfma_all_forms(gpu_device, ta, tb, shape):
 
 
 @pytest.mark.parametrize("epilogue", ["bias_residual", "bias_gelu", "gelu_backward", "accumulate"])
-@pytest.mark.parametrize("shape", [(256, 384, 192), (4096, 3328, 128)])
+@pytest.mark.parametrize("shape", [(256, 384, 192), (4096, 3328, 128), (2048, 6144, 192)])
 def test_gemm_mfma_epilogues(gpu_device, epilogue, shape):
     form = {"accumulate": (1, 0), "gelu_backward": (0, 1)}.get(epilogue, (0, 0))
     _gemm_case(gpu_device, "bf16", *form, *shape, epilogue, 0)
