@@ -1159,22 +1159,30 @@ __global__ __launch_bounds__(256) void attn_group_sum_kernel(const bf16* __restr
   *reinterpret_cast<bf16x8*>(dqkv + (size_t)row * (h + 2 * hkv) + h + c8) = o;
 }
 
-// delta[head][i] = sum_e dO[i, head, e] * O[i, head, e]: one wave per (head, row).
+// delta[head][i] = sum_e dO[i, head, e] * O[i, head, e].  Thread t takes the t-th group of eight consecutive
+// elements of the [s, h] tensors (16-byte loads, consecutive lanes read consecutive addresses); the DH / 8 lanes
+// that share a (row, head) add their partial sums with a butterfly, so every one of them ends with the total.
 template <int DH>
 __global__ __launch_bounds__(256) void attn_delta_mfma_path_kernel(const bf16* __restrict__ o,
                                                                    const bf16* __restrict__ d_o,
                                                                    float* __restrict__ delta, int s, int h) {
-  int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  int head = blockIdx.y;
-  int i = blockIdx.x * 4 + wave;
-  if (i >= s) return;
+  constexpr int LPR = DH / 8;  // lanes per (row, head)
+  size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+  size_t total = (size_t)s * h / 8;  // a multiple of LPR: a lane group is inside or outside as a whole
   float d = 0.f;
-  if (lane * 2 < DH) {
-    size_t idx = (size_t)i * h + head * DH + lane * 2;
-    d = (float)o[idx] * (float)d_o[idx] + (float)o[idx + 1] * (float)d_o[idx + 1];
+  if (t < total) {
+    bf16x8 a = *reinterpret_cast<const bf16x8*>(o + t * 8);
+    bf16x8 b = *reinterpret_cast<const bf16x8*>(d_o + t * 8);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) d += (float)a[e] * (float)b[e];
   }
-  d = wave_sum(d);
-  if (lane == 0) delta[(size_t)head * s + i] = d;
+#pragma unroll
+  for (int m = 1; m < LPR; m <<= 1) d += __shfl_xor(d, m);
+  if (t < total && threadIdx.x % LPR == 0) {
+    size_t row = t * 8 / h;
+    int head = (int)(t * 8 % h) / DH;
+    delta[(size_t)head * s + row] = d;
+  }
 }
 
 // ==================================================================================
@@ -1247,7 +1255,7 @@ static bool launch_bwd(const bf16* qkv, const bf16* o, const float* lse, const b
   }
   float scale = 1.0f / sqrtf((float)DH);
   int hkv = n_kv_heads * DH, group = n_heads / n_kv_heads;
-  attn_delta_mfma_path_kernel<DH><<<dim3(ceil_div(s, 4), n_heads), 256, 0, stream>>>(o, d_o, delta, s, h);
+  attn_delta_mfma_path_kernel<DH><<<(unsigned)(((size_t)s * h / 8 + 255) / 256), 256, 0, stream>>>(o, d_o, delta, s, h);
   // Few key/value heads: one block per query head and a per-group sum afterwards (needs the [s, 2h] workspace),
   // once the direct launch would not fill the chip's 512 block slots.
   bool split = group > 1 && partials && (int64_t)n_kv_heads * (s / 128) < 512;
