@@ -214,13 +214,17 @@ int po_set_dropout_seed(po_stage* st, uint64_t seed);
 int po_stage_backward_input(po_stage* st, int32_t mb, int32_t chunk, const void* dy, void* dx);
 int po_stage_backward_weight(po_stage* st, int32_t mb, int32_t chunk);
 
-/* Asynchronously moves ceil(ratio * Lu) layers (lowest first) of a RESIDENT unit
- * to pinned host memory on the offload stream once its forward has finished, and
- * releases their device slabs (Section 4.2; Appendix C buffer management). */
+/* Asynchronously moves the ceil(ratio * Lu) lowest layers of a RESIDENT unit to pinned
+ * host memory on the offload stream once its forward has finished, and releases their
+ * device slabs (Section 4.2; Appendix C buffer management).  The copies are issued from
+ * the highest of those layers down: the reload brings layers back in the same order, and
+ * the layer the backward needs first should not be the one that leaves last. */
 int po_offload(po_stage* st, int32_t mb, int32_t chunk, float ratio);
 
-/* Asynchronously brings an offloaded unit back on the reload stream; a no-op for
- * a unit with nothing offloaded. */
+/* Asynchronously brings an offloaded unit back on the reload stream, top layer first;
+ * a no-op for a unit with nothing offloaded.  The backward then waits for each layer's
+ * copy right before it reads that layer, so the lower layers travel while the upper
+ * ones are differentiated. */
 int po_reload(po_stage* st, int32_t mb, int32_t chunk);
 
 /* Runs a whole rank-local schedule: po_schedule_ops(schedule, d, rank, v, m, ratio, ...)

@@ -720,7 +720,10 @@ int stage_offload(po_stage* st, int mb, int chunk, float ratio) {
   bool was_resident = unit_has_resident_layer(*u);
   hipStream_t q = st->offload;
   if (n > 0) PO_HIP(hipStreamWaitEvent(q, u->fwd_done, 0));
-  for (int l = 0; l < n; ++l) {
+  // The n lowest layers go, the top one of them first: the reload brings the layers back in that order too (the
+  // backward starts at the top), and a layer can only come back once it has gone, so the layer that is needed
+  // first must not be the one that leaves last.
+  for (int l = n - 1; l >= 0; --l) {
     UnitLayer& L = u->layers[l];
     if (L.h2d_done) {  // reloaded and offloaded again without a backward in between
       PO_HIP(hipStreamWaitEvent(q, L.h2d_done, 0));
@@ -796,7 +799,9 @@ int stage_reload(po_stage* st, int mb, int chunk) {
   if (rc) return rc;
   PO_HIP(hipEventRecord(gate, st->compute));
   PO_HIP(hipStreamWaitEvent(q, gate, 0));
-  for (int l = 0; l < st->Lu; ++l) {
+  // Top layer first: the backward consumes the layers from the top down and waits for each on its own, so the
+  // lower layers travel while the upper ones are already being differentiated.
+  for (int l = st->Lu - 1; l >= 0; --l) {
     UnitLayer& L = u->layers[l];
     if (L.state != L_HOST) continue;
     if (q != st->offload) PO_HIP(hipStreamWaitEvent(q, L.d2h_done, 0));
@@ -850,7 +855,7 @@ int stage_reload(po_stage* st, int mb, int chunk) {
   return PO_OK;
 }
 
-// Checks shared by the three backward entry points; waits for pending reloads of the unit.
+// Checks shared by the three backward entry points.
 static int backward_prologue(po_stage* st, int mb, int chunk, const void* dy, void* dx, const char* what,
                              Unit** out) {
   const po_config& c = st->cfg;
@@ -879,12 +884,16 @@ static int backward_prologue(po_stage* st, int mb, int chunk, const void* dy, vo
                 l);
       return PO_E_STATE;
     }
-  for (UnitLayer& L : u->layers)
-    if (L.h2d_done) {
-      PO_HIP(hipStreamWaitEvent(st->compute, L.h2d_done, 0));
-      L.h2d_done = nullptr;
-    }
   *out = u;
+  return PO_OK;
+}
+
+// The compute stream waits for a layer's outstanding reload right before the first kernel that reads its slab.
+static int await_layer(po_stage* st, UnitLayer& L) {
+  if (L.h2d_done) {
+    PO_HIP(hipStreamWaitEvent(st->compute, L.h2d_done, 0));
+    L.h2d_done = nullptr;
+  }
   return PO_OK;
 }
 
@@ -959,6 +968,8 @@ int stage_backward(po_stage* st, int mb, int chunk, const void* dy, void* dx) {
   BwdBufs bufs = workspace_bufs(st);
   const void* grad = dy;
   for (int l = st->Lu - 1; l >= 0; --l) {
+    rc = await_layer(st, u->layers[l]);
+    if (rc) return rc;
     const char* slab = st->dev_pool.bufs[u->layers[l].dev].ptr;
     void* out;
     if (l > 0)
@@ -999,6 +1010,8 @@ int stage_backward_input(po_stage* st, int mb, int chunk, const void* dy, void* 
   if (rc) return rc;
   const void* grad = dy;
   for (int l = st->Lu - 1; l >= 0; --l) {
+    rc = await_layer(st, u->layers[l]);
+    if (rc) return rc;
     const char* slab = st->dev_pool.bufs[u->layers[l].dev].ptr;
     char* dy_in;
     BwdBufs bufs = unit_bufs(st, buf, l, &dy_in);
