@@ -28,7 +28,7 @@ PEAK_BF16_TFLOPS = 2500.0
 # HBM bytes per GEMM launch (average over all bf16 GEMM launches of a step) from the rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE passes summarised in profiles/hbm_traffic_c2.md, scaled by the copy-kernel calibration given there.
 # Counters cannot be read inside this script, so the figure is carried here per workload; None = not collected.
-MEASURED_GEMM_TRAFFIC_BYTES = {"C2": 160375233}
+MEASURED_GEMM_TRAFFIC_BYTES = {"C2": 160372993}
 
 
 def model_flops_per_run(shape):

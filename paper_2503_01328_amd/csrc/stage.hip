@@ -889,11 +889,14 @@ static int backward_prologue(po_stage* st, int mb, int chunk, const void* dy, vo
 }
 
 // The compute stream waits for a layer's outstanding reload right before the first kernel that reads its slab.
-static int await_layer(po_stage* st, UnitLayer& L) {
-  if (L.h2d_done) {
-    PO_HIP(hipStreamWaitEvent(st->compute, L.h2d_done, 0));
-    L.h2d_done = nullptr;
-  }
+// A wait in the middle of a pass closes the pass's timed span and opens a new one behind it, so that time spent
+// waiting for a copy is not booked as compute (span == nullptr: no span is open yet).
+static int await_layer(po_stage* st, UnitLayer& L, size_t* span) {
+  if (!L.h2d_done) return PO_OK;
+  if (span) PO_RC(span_end(st, st->compute, *span));
+  PO_HIP(hipStreamWaitEvent(st->compute, L.h2d_done, 0));
+  L.h2d_done = nullptr;
+  if (span) PO_RC(span_begin(st, st->compute, 0, span));
   return PO_OK;
 }
 
@@ -962,13 +965,15 @@ int stage_backward(po_stage* st, int mb, int chunk, const void* dy, void* dx) {
   int rc = backward_prologue(st, mb, chunk, dy, dx, "backward", &u);
   if (rc) return rc;
   bool embed = c.vocab > 0 && chunk == 0;
+  rc = await_layer(st, u->layers[st->Lu - 1], nullptr);
+  if (rc) return rc;
   size_t span;
   rc = span_begin(st, st->compute, 0, &span);
   if (rc) return rc;
   BwdBufs bufs = workspace_bufs(st);
   const void* grad = dy;
   for (int l = st->Lu - 1; l >= 0; --l) {
-    rc = await_layer(st, u->layers[l]);
+    rc = await_layer(st, u->layers[l], &span);
     if (rc) return rc;
     const char* slab = st->dev_pool.bufs[u->layers[l].dev].ptr;
     void* out;
@@ -1005,12 +1010,14 @@ int stage_backward_input(po_stage* st, int mb, int chunk, const void* dy, void* 
   rc = st->grad_pool.acquire(st->compute, &u->grad_buf);
   if (rc) return rc;
   char* buf = st->grad_pool.bufs[u->grad_buf].ptr;
+  rc = await_layer(st, u->layers[st->Lu - 1], nullptr);
+  if (rc) return rc;
   size_t span;
   rc = span_begin(st, st->compute, 0, &span);
   if (rc) return rc;
   const void* grad = dy;
   for (int l = st->Lu - 1; l >= 0; --l) {
-    rc = await_layer(st, u->layers[l]);
+    rc = await_layer(st, u->layers[l], &span);
     if (rc) return rc;
     const char* slab = st->dev_pool.bufs[u->layers[l].dev].ptr;
     char* dy_in;
