@@ -265,6 +265,16 @@ int po_op_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32
                const void* A, int32_t lda, const void* B, int32_t ldb, const void* bias, const void* residual,
                void* out, void* gelu_out, const void* gelu_u, float* acc_f32, int32_t force_generic, void* stream);
 
+/* n <= 4 independent weight-gradient products in one launch (bf16 operands, the matrix-core kernel only):
+ * acc_f32[i] [M[i], N[i]] += A[i]^T B[i] with A[i] DEVICE [K[i], M[i]] (row stride lda[i]) and B[i] DEVICE
+ * [K[i], N[i]] (row stride ldb[i]); acc_f32[i] DEVICE fp32 with row stride ldc[i].  The arrays themselves are HOST
+ * arrays of length n.  Every M[i], N[i] must be a multiple of 256 and every K[i] of 64, else PO_E_INVAL (use
+ * po_op_gemm per product then).  Each product equals po_op_gemm(trans_a = 1, trans_b = 0, acc_f32) bit for bit;
+ * the stage runs the four parameter-gradient products of a layer this way (Section 3.2's W pass). */
+int po_op_gemm_grouped(int32_t n, const int32_t* M, const int32_t* N, const int32_t* K, const void* const* A,
+                       const int32_t* lda, const void* const* B, const int32_t* ldb, float* const* acc_f32,
+                       const int32_t* ldc, void* stream);
+
 /* Pure host code: the output tile (rows, columns) of the bf16 matrix-core kernel that po_op_gemm and the stage
  * use for an M x N result whose K is a multiple of 64: 256 x 256, 256 x 192 or 128 x 128, chosen so that a round of
  * tiles fills the 256 compute units; 0, 0 when M, N fit none of them (the shape-generic kernel runs instead). */

@@ -92,6 +92,8 @@ EXPORTS = {
                                                                            C.c_void_p]),
     "po_op_gemm": (C.c_int, [C.c_int32] * 6 + [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32] + [C.c_void_p] * 6 +
                    [C.c_int32, C.c_void_p]),
+    "po_op_gemm_grouped": (C.c_int, [C.c_int32] + [C.POINTER(C.c_int32)] * 3 + [C.POINTER(C.c_void_p), C.POINTER(C.c_int32)] * 2 +
+                           [C.POINTER(C.c_void_p), C.POINTER(C.c_int32), C.c_void_p]),
     "po_op_gemm_tile": (C.c_int, [C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "po_op_attention_forward": (C.c_int, [C.c_int32] + [C.c_void_p] * 3 + [C.c_int32] * 5 + [C.c_void_p]),
     "po_op_attention_backward": (C.c_int, [C.c_int32] + [C.c_void_p] * 7 + [C.c_int32] * 5 + [C.c_void_p]),
@@ -277,6 +279,15 @@ def po_op_gemm(dtype, trans_a, trans_b, M, N, K, A, lda, B, ldb, bias=None, resi
                gelu_u=None, acc_f32=None, force_generic=0, stream=None):
     _check(lib.po_op_gemm(dtype, trans_a, trans_b, M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(bias), _ptr(residual),
                           _ptr(out), _ptr(gelu_out), _ptr(gelu_u), _ptr(acc_f32), force_generic, _stream(stream)))
+
+
+def po_op_gemm_grouped(problems, stream=None):
+    """problems: list of (M, N, K, A [K, M], lda, B [K, N], ldb, acc_f32 [M, N], ldc); acc_f32 += A^T B for each."""
+    n = len(problems)
+    ints = lambda k: (C.c_int32 * n)(*[p[k] for p in problems])
+    ptrs = lambda k: _ptr_array([p[k] for p in problems])
+    _check(lib.po_op_gemm_grouped(n, ints(0), ints(1), ints(2), ptrs(3), ints(4), ptrs(5), ints(6), ptrs(7), ints(8),
+                                  _stream(stream)))
 
 
 def po_op_gemm_tile(M, N):

@@ -36,6 +36,7 @@
 
 #include <stdint.h>
 #include <stdlib.h>
+#include <string.h>
 
 #include "kernels.h"
 
@@ -97,7 +98,9 @@ __device__ __forceinline__ void load_slice(const bf16* __restrict__ base, int ld
     // Issued as inline assembly on purpose: through the builtin the compiler treats every later
     // LDS read as dependent on the load and waits for it at once, which would undo the double
     // buffering.  The caller waits (wait_slice_loads) before the barrier that publishes the slice.
-    unsigned lds_addr = (unsigned)(size_t)PO_LDS3(lds + g * 1024);
+    // (the LDS base of the piece is the same in every lane by construction; saying so keeps it in a scalar
+    // register where the compiler cannot prove it, as inside the loop over tiles of the grouped kernel)
+    unsigned lds_addr = __builtin_amdgcn_readfirstlane((unsigned)(size_t)PO_LDS3(lds + g * 1024));
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(src)
                  : "memory");
   }
@@ -197,29 +200,27 @@ __device__ __forceinline__ void epilogue_row_piece(const Epilogue& e, int m, int
 // LDS stages of a tile: what fits into 160 KiB at (BM + BN) * 128 bytes per stage.
 constexpr int stages_of(int wtm, int wtn) { return wtm * wtn >= 12 ? 2 : 4; }
 
-// ---- the kernel ---------------------------------------------------------------
-// TA: A is [K, M] (m-contiguous).  TB: B is [K, N] (n-contiguous).
-template <int WTM, int WTN, bool TA, bool TB, int EPI>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(int K, const bf16* __restrict__ A, int lda,
-                                                        const bf16* __restrict__ B, int ldb, Epilogue ep,
-                                                        int tiles_m, int tiles_n) {
-  constexpr int BM = 64 * WTM, BN = 64 * WTN;
-  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128;
-  constexpr int STAGE = A_BYTES + B_BYTES;
-  extern __shared__ __align__(16) char smem[];
-
-  // XCD-aware remap: ids equal modulo 8 share an XCD; give each XCD a contiguous run of tiles,
-  // and walk the tiles in groups of 4 tile rows so that a run is compact in both dimensions.
-  int n_tiles = tiles_m * tiles_n;
-  int pid = blockIdx.x;
-  int lin = (n_tiles % 8 == 0) ? (pid % 8) * (n_tiles / 8) + pid / 8 : pid;
+// Tiles are walked in groups of 4 tile rows, so that a run of consecutive tile numbers is compact in both
+// dimensions (the blocks of one XCD take such a run and share operand slices in that XCD's L2).
+__device__ __forceinline__ void tile_of(int lin, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
   constexpr int GROUP = 4;
   int width = GROUP * tiles_n;
   int group_id = lin / width;
   int first_m = group_id * GROUP;
   int gsize = min(tiles_m - first_m, GROUP);
-  int tile_m = first_m + (lin % width) % gsize;
-  int tile_n = (lin % width) / gsize;
+  tile_m = first_m + (lin % width) % gsize;
+  tile_n = (lin % width) / gsize;
+}
+
+// ---- one output tile -----------------------------------------------------------
+// TA: A is [K, M] (m-contiguous).  TB: B is [K, N] (n-contiguous).  All 256 threads of the block call it with
+// the same arguments; `smem` is the block's dynamic LDS (stages, then reused by the epilogue strips).
+template <int WTM, int WTN, bool TA, bool TB, int EPI>
+__device__ __forceinline__ void gemm_tile(int K, const bf16* __restrict__ A, int lda, const bf16* __restrict__ B,
+                                          int ldb, const Epilogue& ep, int tile_m, int tile_n, char* smem) {
+  constexpr int BM = 64 * WTM, BN = 64 * WTN;
+  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128;
+  constexpr int STAGE = A_BYTES + B_BYTES;
 
   int tid = threadIdx.x, lane = tid & 63;
   int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -396,6 +397,70 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int K, const bf16* __res
   }
 }
 
+// Tells the compiler that a value is the same in every lane (it is: it derives from the block id and the kernel
+// arguments only), so that it stays in scalar registers.
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ const bf16* uniform(const bf16* p) {
+  uintptr_t v = reinterpret_cast<uintptr_t>(p);
+  unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+  return reinterpret_cast<const bf16*>(((uintptr_t)hi << 32) | lo);
+}
+
+// ---- the kernels -----------------------------------------------------------------
+// One tile per block.  XCD-aware remap: ids equal modulo 8 share an XCD; each XCD gets a contiguous run of tiles.
+template <int WTM, int WTN, bool TA, bool TB, int EPI>
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(int K, const bf16* __restrict__ A, int lda,
+                                                        const bf16* __restrict__ B, int ldb, Epilogue ep,
+                                                        int tiles_m, int tiles_n) {
+  extern __shared__ __align__(16) char smem[];
+  int n_tiles = tiles_m * tiles_n;
+  int pid = blockIdx.x;
+  int lin = (n_tiles % 8 == 0) ? (pid % 8) * (n_tiles / 8) + pid / 8 : pid;
+  int tile_m, tile_n;
+  tile_of(lin, tiles_m, tiles_n, tile_m, tile_n);
+  gemm_tile<WTM, WTN, TA, TB, EPI>(K, A, lda, B, ldb, ep, tile_m, tile_n, smem);
+}
+
+// Several independent GEMMs of one form in one launch: the 256 x 256 tiles of all problems are numbered one
+// problem after the other and the blocks (at most one per CU) take them round by round, so that a round is full
+// as long as tiles are left, whatever the shape of a single problem (a 2048 x 2048 result alone has 64 tiles,
+// a 2048 x 6144 one 192), and a block's epilogue no longer marks the end of a launch.
+constexpr int kMaxGroupedGemms = 4;
+struct GroupedProblem {
+  const bf16* A;
+  const bf16* B;
+  Epilogue ep;
+  int K, lda, ldb, tiles_m, tiles_n, first_tile;
+};
+struct GroupedArgs {
+  GroupedProblem p[kMaxGroupedGemms];
+  int n, total_tiles;
+};
+
+template <bool TA, bool TB, int EPI>
+__global__ __launch_bounds__(256) void gemm_mfma_grouped_kernel(GroupedArgs g) {
+  extern __shared__ __align__(16) char smem[];
+  int pid = blockIdx.x, nb = gridDim.x;
+  int slot = (nb % 8 == 0) ? (pid % 8) * (nb / 8) + pid / 8 : pid;  // an XCD's blocks take a run of tile numbers
+  for (int base = 0; base < g.total_tiles; base += nb) {
+    int lin = base + slot;
+    if (lin < g.total_tiles) {  // the same for every thread of the block
+      // The problem that owns tile `lin`, picked with constant indices only: a run-time index into the argument
+      // block would send it through private memory and the compiler would no longer know that K, the strides
+      // and the LDS addresses derived from them are the same in every lane.
+      GroupedProblem P = g.p[0];
+#pragma unroll
+      for (int i = 1; i < kMaxGroupedGemms; ++i)
+        if (i < g.n && lin >= g.p[i].first_tile) P = g.p[i];
+      int tile_m, tile_n;
+      tile_of(lin - P.first_tile, P.tiles_m, P.tiles_n, tile_m, tile_n);
+      gemm_tile<4, 4, TA, TB, EPI>(uniform(P.K), uniform(P.A), uniform(P.lda), uniform(P.B), uniform(P.ldb), P.ep,
+                                   uniform(tile_m), uniform(tile_n), smem);
+    }
+    __syncthreads();  // the next tile's operand loads overwrite the epilogue strips of every wave
+  }
+}
+
 // ---- host side ------------------------------------------------------------------
 // 256 x 256 tiles once they fill three quarters of the 256 CUs in one round (measured: 192 big tiles beat 768
 // small ones, 58 against 63 us at M = 2048, N = 6144, K = 2048); below that the 128 x 128 tile.  Where N is a
@@ -501,6 +566,56 @@ bool gemm_mfma_bf16(int trans_a, int trans_b, int M, int N, int K, const void* A
   if (wtm == 4 && wtn == 3) return dispatch_trans<4, 3>(trans_a, trans_b, M, N, K, a, lda, b, ldb, ep, stream);
   if (wtm == 4) return dispatch_trans<4, 4>(trans_a, trans_b, M, N, K, a, lda, b, ldb, ep, stream);
   return dispatch_trans<2, 2>(trans_a, trans_b, M, N, K, a, lda, b, ldb, ep, stream);
+}
+
+// ---- grouped launch ---------------------------------------------------------------
+bool gemm_mfma_grouped_supported(int n, const GemmProblem* p) {
+  if (n < 1 || n > kMaxGroupedGemms || !p) return false;
+  for (int i = 0; i < n; ++i) {
+    const GemmProblem& q = p[i];
+    if (q.M <= 0 || q.N <= 0 || q.K <= 0 || q.M % 256 != 0 || q.N % 256 != 0 || q.K % kBK != 0 || q.lda % 8 != 0 ||
+        q.ldb % 8 != 0 || q.ldc % 8 != 0 || q.lda < q.M || q.ldb < q.N || q.ldc < q.N || !q.A || !q.B || !q.acc_f32 ||
+        ((uintptr_t)q.A | (uintptr_t)q.B | (uintptr_t)q.acc_f32) % 16 != 0)
+      return false;
+  }
+  return true;
+}
+
+bool gemm_mfma_grouped_accumulate(int n, const GemmProblem* p, hipStream_t stream) {
+  if (!gemm_mfma_grouped_supported(n, p)) {
+    set_error("gemm_mfma_grouped: %d problems, or a shape, stride or pointer the grouped kernel does not take", n);
+    return false;
+  }
+  GroupedArgs g;
+  memset(&g, 0, sizeof(g));
+  g.n = n;
+  int total = 0;
+  for (int i = 0; i < n; ++i) {
+    GroupedProblem& q = g.p[i];
+    q.A = static_cast<const bf16*>(p[i].A);
+    q.B = static_cast<const bf16*>(p[i].B);
+    q.ep.acc_f32 = p[i].acc_f32;
+    q.ep.ldc = p[i].ldc;
+    q.K = p[i].K;
+    q.lda = p[i].lda;
+    q.ldb = p[i].ldb;
+    q.tiles_m = p[i].M / 256;
+    q.tiles_n = p[i].N / 256;
+    q.first_tile = total;
+    total += q.tiles_m * q.tiles_n;
+  }
+  g.total_tiles = total;
+  constexpr int smem = stages_of(4, 4) * (256 + 256) * 128;
+  auto kern = gemm_mfma_grouped_kernel<true, true, kEpiAccumulate>;
+  static bool configured = false;
+  if (!configured) {
+    PO_HIP_OK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  smem));
+    configured = true;
+  }
+  int blocks = total < 256 ? total : 256;  // one block per CU; more tiles mean more rounds per block
+  kern<<<blocks, 256, smem, stream>>>(g);
+  return launch_ok("gemm_mfma_grouped_kernel");
 }
 
 }  // namespace po

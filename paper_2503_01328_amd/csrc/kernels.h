@@ -61,6 +61,20 @@ bool gemm_mfma_supported(int trans_a, int trans_b, int M, int N, int K, int lda,
 void gemm_mfma_tile(int M, int N, int* bm, int* bn);
 bool gemm_mfma_bf16(int trans_a, int trans_b, int M, int N, int K, const void* A, int lda, const void* B, int ldb,
                     const Epilogue& ep, hipStream_t stream);
+// Several weight-gradient GEMMs in one launch, C_i [M_i, N_i] (fp32) += A_i^T B_i with A_i [K_i, M_i] and
+// B_i [K_i, N_i] bf16: the form of the four parameter-gradient products of a layer.  Supported when every M_i and
+// N_i is a multiple of 256 and every K_i of 64 (at most 4 problems); results equal the single launches bit for bit.
+struct GemmProblem {
+  int M, N, K;
+  const void* A;
+  int lda;
+  const void* B;
+  int ldb;
+  float* acc_f32;
+  int ldc;
+};
+bool gemm_mfma_grouped_supported(int n, const GemmProblem* p);
+bool gemm_mfma_grouped_accumulate(int n, const GemmProblem* p, hipStream_t stream);
 // Picks the MFMA kernel for bf16 when the shape allows it, else the generic one.
 bool gemm(int dtype, int trans_a, int trans_b, int M, int N, int K, const void* A, int lda, const void* B, int ldb,
           const Epilogue& ep, bool force_generic, hipStream_t stream);

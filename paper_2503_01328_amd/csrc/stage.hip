@@ -339,7 +339,7 @@ struct po_stage {
   char *w_n, *w_g, *w_du, *w_dqkv, *w_do, *w_dx1, *w_dn, *w_dn1, *w_dy[2], *w_x0;
   char* w_dkv_part = nullptr;  // [s, 2h] per-query-head dK/dV of grouped-query attention (null with multi-head)
   char* w_dz[2];  // dropout-masked gradients of the fused backward
-  char* w_n_w;  // LayerNorm recompute output of the weight-gradient half (own buffer: it may run on its own stream)
+  char* w_n_w;  // the two LayerNorm outputs recomputed by the weight-gradient half (own buffers: it may run on its own stream)
   float *w_delta, *w_lnws, *w_lnws1, *w_colws_w;
   // accounting
   int resident_units = 0, in_flight_units = 0;
@@ -423,6 +423,18 @@ static int st_gemm(po_stage* st, int ta, int tb, int M, int N, int K, const void
     st->spans[span].flops = 2.0 * M * N * K;
   }
   PO_K(gemm(st->cfg.dtype, ta, tb, M, N, K, A, lda, B, ldb, e, false, q));
+  return span_end(st, q, span);
+}
+
+static int st_gemm_grouped(po_stage* st, int n, const GemmProblem* prob, hipStream_t q) {
+  bool prof = sample_launch(st, st->gemm_launch_counter);
+  size_t span = (size_t)-1;
+  if (prof) {
+    int rc = span_begin(st, q, 4, &span);
+    if (rc) return rc;
+    for (int i = 0; i < n; ++i) st->spans[span].flops += 2.0 * prob[i].M * prob[i].N * prob[i].K;
+  }
+  PO_K(gemm_mfma_grouped_accumulate(n, prob, q));
   return span_end(st, q, span);
 }
 
@@ -604,20 +616,29 @@ static int layer_backward_weight(po_stage* st, int layer, const char* slab, cons
     jobs[5] = ReduceJob{b.dn1, x, b.lnws1, st->G(layer, pl.ln1_g), st->G(layer, pl.ln1_b), b.lnws1 + (size_t)s * 2, h};
     PO_K(column_reductions(dt, jobs, 6, s, q));
   }
-  Epilogue e = make_ep(h);
-  e.acc_f32 = st->G(layer, pl.w_fc2);
-  PO_RC(st_gemm(st, 1, 0, f, h, s, b.g, f, dz2, h, e, q));
-  PO_K(layernorm_forward(dt, x1, st->P(layer, pl.ln2_g), st->P(layer, pl.ln2_b), n_out, s, h, c.ln_eps, q));
-  e = make_ep(f);
-  e.acc_f32 = st->G(layer, pl.w_fc1);
-  PO_RC(st_gemm(st, 1, 0, h, f, s, n_out, h, b.du, f, e, q));
-  e = make_ep(h);
-  e.acc_f32 = st->G(layer, pl.w_o);
-  PO_RC(st_gemm(st, 1, 0, h, h, s, o, h, dz1, h, e, q));
-  PO_K(layernorm_forward(dt, x, st->P(layer, pl.ln1_g), st->P(layer, pl.ln1_b), n_out, s, h, c.ln_eps, q));
-  e = make_ep(wq);
-  e.acc_f32 = st->G(layer, pl.w_qkv);
-  PO_RC(st_gemm(st, 1, 0, h, wq, s, n_out, h, b.dqkv, wq, e, q));
+  // The four products dW = operand^T gradient.  They do not depend on each other, so where the matrix-core
+  // kernel can take them as one grouped launch (both LayerNorm outputs recomputed first, into two buffers) the
+  // chip works through the tiles of all four without a launch boundary in between; else one launch each.
+  char* n2 = n_out;
+  char* n1 = n_out + st->gl_sh;
+  GemmProblem prob[4] = {
+      {f, h, s, b.g, f, dz2, h, st->G(layer, pl.w_fc2), h},
+      {h, f, s, n2, h, b.du, f, st->G(layer, pl.w_fc1), f},
+      {h, h, s, o, h, dz1, h, st->G(layer, pl.w_o), h},
+      {h, wq, s, n1, h, b.dqkv, wq, st->G(layer, pl.w_qkv), wq},
+  };
+  if (dt == PO_BF16 && gemm_mfma_grouped_supported(4, prob)) {
+    PO_K(layernorm_forward(dt, x1, st->P(layer, pl.ln2_g), st->P(layer, pl.ln2_b), n2, s, h, c.ln_eps, q));
+    PO_K(layernorm_forward(dt, x, st->P(layer, pl.ln1_g), st->P(layer, pl.ln1_b), n1, s, h, c.ln_eps, q));
+    return st_gemm_grouped(st, 4, prob, q);
+  }
+  for (int i = 0; i < 4; ++i) {
+    if (i == 1) PO_K(layernorm_forward(dt, x1, st->P(layer, pl.ln2_g), st->P(layer, pl.ln2_b), n2, s, h, c.ln_eps, q));
+    if (i == 3) PO_K(layernorm_forward(dt, x, st->P(layer, pl.ln1_g), st->P(layer, pl.ln1_b), n1, s, h, c.ln_eps, q));
+    Epilogue e = make_ep(prob[i].ldc);
+    e.acc_f32 = prob[i].acc_f32;
+    PO_RC(st_gemm(st, 1, 0, prob[i].M, prob[i].N, prob[i].K, prob[i].A, prob[i].lda, prob[i].B, prob[i].ldb, e, q));
+  }
   return PO_OK;
 }
 
@@ -1316,7 +1337,7 @@ int stage_create(const po_config* cfg, void* compute_stream, po_stage** out) {
   // partial sums of the four bias-gradient reductions of a layer, side by side
   size_t colws = align_up(column_reductions_workspace((int)s, (int)(2 * h + f + (size_t)qkv_width_of(*cfg))), 256);
   bool grouped = kv_heads_of(*cfg) < cfg->n_heads;
-  size_t total = 11 * sh + 2 * sf + s3h + delta + 2 * lnws + colws + (grouped ? 2 * sh : 0);
+  size_t total = 12 * sh + 2 * sf + s3h + delta + 2 * lnws + colws + (grouped ? 2 * sh : 0);
   // one unit's gradient buffer for the split backward: per layer g, du [s,f]; dn2, dx1, dn1, incoming dy, and the
   // two dropout-masked gradients [s,h];
   // dqkv [s,3h]; two LayerNorm workspaces; plus one [s,h] tensor per unit (gradient at the embedding output)
@@ -1346,7 +1367,7 @@ int stage_create(const po_config* cfg, void* compute_stream, po_stage** out) {
   st->w_dx1 = take(sh);
   st->w_dn = take(sh);
   st->w_dn1 = take(sh);
-  st->w_n_w = take(sh);
+  st->w_n_w = take(2 * sh);  // LN2 and LN1 outputs of the weight-gradient half, side by side
   st->w_dz[0] = take(sh);
   st->w_dz[1] = take(sh);
   st->w_dy[0] = take(sh);
@@ -1622,6 +1643,18 @@ int po_op_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32
   e.ldc = N;
   return ok(gemm(dtype, trans_a != 0, trans_b != 0, M, N, K, A, lda, B, ldb, e, force_generic != 0,
                  (hipStream_t)stream));
+}
+int po_op_gemm_grouped(int32_t n, const int32_t* M, const int32_t* N, const int32_t* K, const void* const* A,
+                       const int32_t* lda, const void* const* B, const int32_t* ldb, float* const* acc_f32,
+                       const int32_t* ldc, void* stream) {
+  begin_launch();
+  if (n < 1 || n > 4 || !M || !N || !K || !A || !lda || !B || !ldb || !acc_f32 || !ldc) {
+    set_error("po_op_gemm_grouped: n=%d (1..4) or a NULL array", n);
+    return PO_E_INVAL;
+  }
+  GemmProblem prob[4];
+  for (int i = 0; i < n; ++i) prob[i] = GemmProblem{M[i], N[i], K[i], A[i], lda[i], B[i], ldb[i], acc_f32[i], ldc[i]};
+  return ok(gemm_mfma_grouped_accumulate(n, prob, (hipStream_t)stream));
 }
 int po_op_gemm_tile(int32_t M, int32_t N, int32_t* tile_rows, int32_t* tile_cols) {
   if (!tile_rows || !tile_cols) {

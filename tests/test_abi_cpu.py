@@ -239,11 +239,13 @@ def test_hot_kernels_keep_their_accumulators_in_registers():
         b.build(verbose=False)
     usage = json.load(open(b.RESOURCES))
     gemm = {k: v for k, v in usage.items() if "gemm_mfma_kernel" in k}
+    grouped = {k: v for k, v in usage.items() if "gemm_mfma_grouped_kernel" in k}
+    assert len(grouped) == 1
     attn = {k: v for k, v in usage.items() if "attn_" in k and "_mfma_kernel" in k and "delta" not in k}
     # GEMM: three tiles x four operand layouts x four epilogues; attention: three kernels and their eight-wave
     # forms, two head dimensions
     assert len(gemm) == 48 and len(attn) >= 12
-    for name, v in {**gemm, **attn}.items():
+    for name, v in {**gemm, **grouped, **attn}.items():
         assert v["ScratchSize"] == 0, (name, v)
     for name, v in attn.items():
         assert v["Occupancy"] >= 2, (name, v)

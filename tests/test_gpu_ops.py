@@ -144,6 +144,44 @@ def test_gemm_mfma_epilogues(gpu_device, epilogue, shape):
     _gemm_case(gpu_device, "bf16", *form, *shape, epilogue, 0)
 
 
+def test_gemm_grouped_equals_single_launches_and_the_oracle(gpu_device):
+    """Four weight-gradient products of different shapes in one launch: each accumulator equals, bit for bit, what
+    the single launch of that product leaves, and the fp64 product within the bf16 tolerance.  Tile counts
+    8 + 24 + 4 + 257 = 293 make two rounds, the second one ragged."""
+    rng = np.random.default_rng(11)
+    shapes = [(512, 1024, 192), (2048, 768, 64), (256, 1024, 128), (256, 65792, 64)]
+    probs, single, refs, acc0s = [], [], [], []
+    for M, N, K in shapes:
+        A = _rand(rng, (K, M), "bf16")
+        B = _rand(rng, (K, N), "bf16", 0.05)
+        acc0 = rng.standard_normal((M, N)).astype(np.float32)
+        Ad, Bd = _dev(A, torch.bfloat16, gpu_device), _dev(B, torch.bfloat16, gpu_device)
+        acc = torch.from_numpy(acc0).to(gpu_device)
+        alone = torch.from_numpy(acc0).to(gpu_device)
+        po.po_op_gemm(po.PO_BF16, 1, 0, M, N, K, Ad, M, Bd, N, acc_f32=alone)
+        probs.append((M, N, K, Ad, M, Bd, N, acc, N))
+        single.append(alone)
+        refs.append(A.T.astype(np.float64) @ B.astype(np.float64))
+        acc0s.append(acc0)
+    po.po_op_gemm_grouped(probs)
+    torch.cuda.synchronize()
+    for p, alone, ref, acc0 in zip(probs, single, refs, acc0s):
+        assert torch.equal(p[7], alone)
+        assert max_rel_err(_np(p[7]) - acc0, ref) < 2e-2
+    # one problem alone, fewer tiles than compute units
+    M, N, K = 256, 512, 64
+    A = _rand(rng, (K, M), "bf16")
+    B = _rand(rng, (K, N), "bf16")
+    acc = torch.zeros(M, N, device=gpu_device)
+    po.po_op_gemm_grouped([(M, N, K, _dev(A, torch.bfloat16, gpu_device), M, _dev(B, torch.bfloat16, gpu_device), N,
+                            acc, N)])
+    assert max_rel_err(_np(acc), A.T.astype(np.float64) @ B.astype(np.float64)) < 2e-2
+    with pytest.raises(po.PipeOffloadError):  # 384 is no multiple of 256
+        po.po_op_gemm_grouped([(384, 512, 64, acc, 384, acc, 512, acc, 512)])
+    with pytest.raises(po.PipeOffloadError):
+        po.po_op_gemm_grouped([(256, 512, 64, acc, 256, acc, 512, acc, 512)] * 5)
+
+
 def test_gemm_rejects_bad_arguments(gpu_device):
     a = torch.zeros(64, 64, device=gpu_device)
     with pytest.raises(po.PipeOffloadError):
