@@ -28,7 +28,7 @@ PEAK_BF16_TFLOPS = 2500.0
 # HBM bytes per GEMM launch (average over all bf16 GEMM launches of a step) from the rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE passes summarised in profiles/hbm_traffic_c2.md, scaled by the copy-kernel calibration given there.
 # Counters cannot be read inside this script, so the figure is carried here per workload; None = not collected.
-MEASURED_GEMM_TRAFFIC_BYTES = {"C2": 160372993}
+MEASURED_GEMM_TRAFFIC_BYTES = {"C2": 210026173}
 
 
 def model_flops_per_run(shape):
@@ -213,9 +213,10 @@ def main():
         "roofline": {"bound": "mfma", "achieved": gemm["gemm_tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": (gemm["gemm_tflops"] / PEAK_BF16_TFLOPS) if gemm["gemm_tflops"] else None,
                      "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(args.config),
-                     "kernel": f"gemm_mfma_kernel (every {args.profile_every}-th GEMM launch of the timed steps at "
-                               f"ratio 0, which walks through all 12 per-layer shapes: sum of 2MNK flops / sum of "
-                               f"event-timed durations)",
+                     "kernel": f"gemm_mfma_kernel and its grouped form (every {args.profile_every}-th GEMM launch of "
+                               f"the timed steps at ratio 0, which walks through all 9 launches of a layer, the "
+                               f"four weight-gradient products being one: sum of 2MNK flops / sum of event-timed "
+                               f"durations)",
                      "launches_timed_per_step": gemm["n_gemm_launches_timed"],
                      "busy_ms_per_step_estimate": gemm["gemm_busy_ms"]},
     }

@@ -103,6 +103,14 @@ def run(config: str, iters: int = 20):
         t = _time(lambda: po.po_op_gemm(po.PO_BF16, ta, tb, M, N, K, A, A.shape[1], B, B.shape[1], **kw), iters)
         add(f"{name} M={M} N={N} K={K}", "mfma", 2.0 * M * N * K, t, MFMA_PEAK)
         del A, B, kw
+    # the four weight-gradient products of a layer as one grouped launch (what the stage runs)
+    probs = []
+    for M, N in ((f, h), (h, f), (h, h), (h, 3 * h)):
+        probs.append((M, N, s, rn(s, M), M, rn(s, N), N, torch.zeros(M, N, device=dev), N))
+    t = _time(lambda: po.po_op_gemm_grouped(probs), iters)
+    add("gemm wgrad, four products in one grouped launch", "mfma", sum(2.0 * p[0] * p[1] * p[2] for p in probs), t,
+        MFMA_PEAK)
+    del probs
     # attention
     qkv, d_o = rn(s, 3 * h), rn(s, h)
     o = torch.empty(s, h, device=dev, dtype=bf)
