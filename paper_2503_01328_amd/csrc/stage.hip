@@ -17,8 +17,10 @@
 // stream after the unit's forward-done event; H2D copies run on the reload
 // stream (the same stream when copy_streams == 1, Section 4.2) after an event
 // recorded on the compute stream when po_reload is called, so a reload never
-// starts earlier than the compute work enqueued before it.  Backward waits for
-// the reload-done events of the layers it reads.
+// starts earlier than the compute work enqueued before it.  A unit's layers are
+// copied from the top layer down in both directions, and the backward waits for
+// a layer's reload-done event only when it reaches that layer, so the lower
+// layers travel while the upper ones are differentiated.
 #include <algorithm>
 #include <chrono>
 #include <deque>
