@@ -240,6 +240,11 @@ int po_run_schedule(po_stage* st, int32_t schedule, int32_t n_microbatches, floa
                     po_stats* stats);
 
 int po_synchronize(po_stage* st);
+/* Abandons every unit that is still in flight: waits for all streams, then returns the units' device slabs, pinned
+ * buffers and gradient buffers to the pools (nothing is freed, parameter gradients already added stay).  After a
+ * call that failed half way (a pool cap, for example) this brings the stage back to a state in which
+ * po_stage_forward and po_run_schedule are legal again. */
+int po_stage_reset(po_stage* st);
 int po_get_stats(const po_stage* st, po_stats* out);
 
 /* ---- single operations (what the stage is built from; for tests and

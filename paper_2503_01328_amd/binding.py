@@ -84,6 +84,7 @@ EXPORTS = {
                                   C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
                                   C.POINTER(po_stats)]),
     "po_synchronize": (C.c_int, [C.c_void_p]),
+    "po_stage_reset": (C.c_int, [C.c_void_p]),
     "po_get_stats": (C.c_int, [C.c_void_p, C.POINTER(po_stats)]),
     "po_op_layernorm_forward": (C.c_int, [C.c_int32] + [C.c_void_p] * 4 + [C.c_int32, C.c_int32, C.c_float,
                                                                           C.c_void_p]),
@@ -253,6 +254,10 @@ def po_run_schedule(stage, schedule, n_microbatches, offload_ratio, x_in, y_out,
 
 def po_synchronize(stage):
     _check(lib.po_synchronize(stage))
+
+
+def po_stage_reset(stage):
+    _check(lib.po_stage_reset(stage))
 
 
 def po_get_stats(stage) -> dict:

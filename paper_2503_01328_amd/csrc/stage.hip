@@ -1119,12 +1119,36 @@ static int backward_weight_impl(po_stage* st, int mb, int chunk, bool count_pass
 
 int stage_backward_weight(po_stage* st, int mb, int chunk) { return backward_weight_impl(st, mb, chunk, true); }
 
+// Drops every unit that is still in flight (after a failed call, or to abandon a step): waits for all streams,
+// then hands the units' device slabs, host slabs and gradient buffers back to their pools.  Nothing is freed.
+int stage_reset(po_stage* st);
+
 int stage_synchronize(po_stage* st) {
   PO_HIP(hipStreamSynchronize(st->compute));
   if (st->wstream) PO_HIP(hipStreamSynchronize(st->wstream));
   PO_HIP(hipStreamSynchronize(st->offload));
   if (st->reload != st->offload) PO_HIP(hipStreamSynchronize(st->reload));
   return PO_OK;
+}
+
+int stage_reset(po_stage* st) {
+  int rc = stage_synchronize(st);
+  if (rc) return rc;
+  for (auto& kv : st->units) {
+    Unit& u = kv.second;
+    if (!u.live) continue;
+    for (UnitLayer& L : u.layers) {
+      if (L.dev >= 0) PO_RC(st->dev_pool.release(L.dev, st->compute));
+      if (L.hostbuf >= 0) PO_RC(st->host_pool.release(L.hostbuf, st->compute));
+      L = UnitLayer();
+    }
+    if (u.grad_buf >= 0) PO_RC(st->grad_pool.release(u.grad_buf, st->compute));
+    u = Unit();
+  }
+  st->resident_units = 0;
+  st->in_flight_units = 0;
+  st->sync_events.reset();
+  return stage_synchronize(st);
 }
 
 // Folds the recorded spans into the stats (all streams must be drained).
@@ -1590,6 +1614,10 @@ int po_synchronize(po_stage* st) {
     if (kv.second.live) return PO_OK;  // a unit between passes still holds some of the events
   st->sync_events.reset();
   return PO_OK;
+}
+int po_stage_reset(po_stage* st) {
+  PO_NEED_STAGE(st);
+  return stage_reset(st);
 }
 int po_get_stats(const po_stage* st, po_stats* out) {
   PO_NEED_STAGE(st);

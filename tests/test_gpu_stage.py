@@ -229,6 +229,37 @@ def test_pool_caps_give_oom_codes(gpu_device):
         assert e.value.code == po.PO_E_HOST_OOM
 
 
+def test_reset_after_a_failed_run_makes_the_stage_usable_again(gpu_device):
+    """A run that stops at the device pool cap leaves units in flight; po_stage_reset drops them, and the same stage
+    then gives, with two microbatches (which fit the cap), exactly what a fresh stage gives."""
+    shape = syn.StageShape(2, 1, 128, 2, 512, 64, dtype="f32", pipeline_degree=4, n_microbatches=4)
+    layer_bytes = po.po_saved_bytes_per_layer(po.po_config_default(
+        n_layers=2, hidden=128, n_heads=2, ffn=512, seq=64))
+    small = syn.StageShape(2, 1, 128, 2, 512, 64, dtype="f32", pipeline_degree=1, n_microbatches=2)
+    with StageRunner(small, n_microbatches=2) as ref:
+        ref.make_inputs()
+        ref.run(po.PO_SCHED_1F1B, 0.0)
+        want = _snapshot(ref)
+    with StageRunner(shape, device_pool_cap_bytes=3 * layer_bytes) as r:
+        r.make_inputs()
+        with pytest.raises(po.PipeOffloadError):
+            r.run(po.PO_SCHED_1F1B, 0.0)
+        with pytest.raises(po.PipeOffloadError) as e:
+            po.po_stage_forward(r.stage, 0, 0, r.x[0], r.y[0])  # still in flight from the failed run
+        assert e.value.code == po.PO_E_STATE
+        po.po_stage_reset(r.stage)
+        r.zero_grads()
+        for j in range(2):
+            po.po_stage_forward(r.stage, j, 0, r.x[j], r.y[j])
+            po.po_stage_backward(r.stage, j, 0, r.dy[j], r.dx[j])
+        po.po_synchronize(r.stage)
+        got = _snapshot(r)
+        for a, b in zip(want[0] + want[1], got[0][:2] + got[1][:2]):
+            assert torch.equal(a, b)
+        assert torch.equal(want[2], got[2])
+        po.po_stage_reset(r.stage)  # nothing in flight: a no-op
+
+
 def test_peak_slab_bytes_follow_the_schedule_model(gpu_device):
     shape = syn.StageShape(1, 1, 128, 2, 512, 64, dtype="bf16", pipeline_degree=6, n_microbatches=12)
     layer_bytes = None
