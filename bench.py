@@ -25,6 +25,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0
+PEAK_F32_VECTOR_TFLOPS = 157.3
 # HBM bytes per GEMM launch (average over all bf16 GEMM launches of a step) from the rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE passes summarised in profiles/hbm_traffic_c2.md, scaled by the copy-kernel calibration given there.
 # Counters cannot be read inside this script, so the figure is carried here per workload; None = not collected.
@@ -194,6 +195,7 @@ def main():
         k_meas = po.po_offload_k(shape.hidden, shape.seq, bc, bo) if bo else None
         gemm = ratios[0.0]
         dtype = "bf16" if shape.dtype == "bf16" else "f32"
+        peak_tflops = PEAK_BF16_TFLOPS if dtype == "bf16" else PEAK_F32_VECTOR_TFLOPS
 
     out = {
         "metric": "stage tokens/sec at offload ratio 0/0.5/1; peak activation HBM GB; overlap %",
@@ -210,13 +212,18 @@ def main():
                    "slot_k": args.slot_k},
         "ratios": {str(k): v for k, v in ratios.items()},
         "k_eq1_measured_serial": k_meas, "k_eq1_measured_duplex": (k_meas / 2 if k_meas else None),
-        "roofline": {"bound": "mfma", "achieved": gemm["gemm_tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": (gemm["gemm_tflops"] / PEAK_BF16_TFLOPS) if gemm["gemm_tflops"] else None,
+        # bf16 workloads: the matrix-core GEMM against the dense bf16 MFMA peak.  The fp32 debug workload (C1) runs the
+        # shape-generic fp32 kernel, plain vector arithmetic, priced against the fp32 vector peak.
+        "roofline": {"bound": "mfma" if dtype == "bf16" else "alu", "achieved": gemm["gemm_tflops"],
+                     "peak": peak_tflops, "unit": "TFLOP/s",
+                     "frac": (gemm["gemm_tflops"] / peak_tflops) if gemm["gemm_tflops"] else None,
                      "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(args.config),
-                     "kernel": f"gemm_mfma_kernel and its grouped form (every {args.profile_every}-th GEMM launch of "
-                               f"the timed steps at ratio 0, which walks through all 9 launches of a layer, the "
-                               f"four weight-gradient products being one: sum of 2MNK flops / sum of event-timed "
-                               f"durations)",
+                     "kernel": (f"gemm_mfma_kernel and its grouped form (every {args.profile_every}-th GEMM launch of "
+                                f"the timed steps at ratio 0, which walks through all 9 launches of a layer, the "
+                                f"four weight-gradient products being one: sum of 2MNK flops / sum of event-timed "
+                                f"durations)") if dtype == "bf16" else
+                               (f"gemm_generic_kernel, fp32 (every {args.profile_every}-th GEMM launch of the timed "
+                                f"steps at ratio 0: sum of 2MNK flops / sum of event-timed durations)"),
                      "launches_timed_per_step": gemm["n_gemm_launches_timed"],
                      "busy_ms_per_step_estimate": gemm["gemm_busy_ms"]},
     }
