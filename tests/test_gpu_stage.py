@@ -513,3 +513,44 @@ def test_stage_with_dropout_against_oracle_and_bitwise_invariants(gpu_device, sh
                 assert not torch.equal(snaps["plain"][2], r.grads)
     _assert_bit_identical(snaps["plain"], snaps["offload"])
     _assert_bit_identical(snaps["plain"], snaps["weight-stream"])
+
+
+def test_features_together_across_schedules_and_offload_policies(gpu_device):
+    """Grouped key/value heads, hidden dropout, an embedding chunk and two chunks per rank at once: the oracle's
+    result within the bf16 tolerance, and the same bits under interleaved 1F1B with full offload, the split-backward
+    schedule with alternate microbatches offloaded, the uniformly repeated schedule with the longest-lived chunk
+    offloaded (prefetch rule and slot plan), on one copy stream and on two."""
+    shape = syn.StageShape(4, 2, 256, 4, 1024, 256, vocab=60, dtype="bf16", pipeline_degree=3, n_microbatches=6,
+                           n_kv_heads=2)
+    p, seed, m = float(np.float32(0.1)), 99, 6
+    x = {(j, c): syn.unit_input(shape, j, c) for j in range(m) for c in range(2)}
+    dy = {(j, c): syn.unit_upstream_grad(shape, j, c) for j in range(m) for c in range(2)}
+    runs = [
+        ("interleaved, resident", po.PO_SCHED_1F1B_INTERLEAVED, 0.0, {}),
+        ("interleaved, full offload", po.PO_SCHED_1F1B_INTERLEAVED, 1.0, {}),
+        ("interleaved, full offload, one stream, staged", po.PO_SCHED_1F1B_INTERLEAVED, 1.0,
+         dict(copy_streams=1, staged_copies=1)),
+        ("split backward, alternate microbatches", po.PO_SCHED_GIS, 0.5, dict(group=2)),
+        ("uniform repeat, chunk 0 offloaded", po.PO_SCHED_PO, 0.5,
+         dict(select_policy=po.PO_SEL_LONGEST_LIFESPAN, prefetch_passes=3)),
+        ("uniform repeat, slot plan", po.PO_SCHED_PO, 0.5, dict(slot_k=1.0, copy_streams=1)),
+        ("uniform repeat, weight stream", po.PO_SCHED_PO, 1.0,
+         dict(select_policy=po.PO_SEL_LONGEST_LIFESPAN, weight_stream=1)),
+    ]
+    base = None
+    for name, sched, ratio, kw in runs:
+        with StageRunner(shape, dropout_p=p, dropout_seed=seed, **kw) as r:
+            r.make_inputs()
+            stats = r.run(sched, ratio)
+            snap = _snapshot(r)
+            assert (stats["n_offloads"] > 0) == (ratio > 0.0), name
+            if base is None:
+                base = snap
+                ref = so.run_stage(r.params_np, shape.n_layers, 2, shape.n_heads, x, dy, vocab=shape.vocab,
+                                   dropout_p=p, seed=seed)
+                _compare(shape, r.results(), ref, 2e-2)
+            else:
+                for a, b in zip(base[0] + [base[2]], snap[0] + [snap[2]]):
+                    assert torch.equal(a, b), name
+                for a, b in zip(base[1], snap[1]):
+                    assert (a is None and b is None) or torch.equal(a, b), name
