@@ -554,3 +554,27 @@ def test_features_together_across_schedules_and_offload_policies(gpu_device):
                     assert torch.equal(a, b), name
                 for a, b in zip(base[1], snap[1]):
                     assert (a is None and b is None) or torch.equal(a, b), name
+
+
+@pytest.mark.parametrize("shape,tol", [
+    (syn.StageShape(1, 1, 64, 1, 64, 1, dtype="f32", pipeline_degree=1, n_microbatches=1), 1e-4),
+    (syn.StageShape(2, 2, 64, 2, 64, 3, vocab=5, dtype="f32", pipeline_degree=1, n_microbatches=2), 1e-4),
+    (syn.StageShape(1, 1, 64, 1, 64, 1, dtype="bf16", pipeline_degree=1, n_microbatches=1), 2e-2),
+    (syn.StageShape(3, 1, 128, 2, 64, 2, dtype="bf16", pipeline_degree=5, n_microbatches=2), 2e-2)],
+    ids=["one-token-f32", "three-tokens-two-chunks-embedding", "one-token-bf16", "more-ranks-than-microbatches"])
+def test_degenerate_stage_shapes(gpu_device, shape, tol):
+    """The smallest stages the configuration allows (one token, one head, the narrowest widths, one microbatch, a
+    pipeline degree above the microbatch count) with everything offloaded: oracle parity and the same bits as the
+    resident run."""
+    m, v = shape.n_microbatches, shape.n_chunks
+    sched = po.PO_SCHED_1F1B_INTERLEAVED if v > 1 else po.PO_SCHED_1F1B
+    snaps = []
+    for ratio in (1.0, 0.0):
+        with StageRunner(shape) as r:
+            r.make_inputs()
+            stats = r.run(sched, ratio)
+            snaps.append(_snapshot(r))
+            if ratio == 1.0:
+                assert stats["n_offloads"] == m * shape.n_layers and stats["n_reloads"] == m * shape.n_layers
+                _compare(shape, r.results(), _oracle(shape, r, m), tol)
+    _assert_bit_identical(snaps[0], snaps[1])
