@@ -667,7 +667,7 @@ int stage_forward(po_stage* st, int mb, int chunk, const void* x_in, void* y_out
     int rc = st->dev_pool.acquire(st->compute, &u.layers[l].dev);
     if (rc) {
       for (int k = 0; k < l; ++k) st->dev_pool.release(u.layers[k].dev, st->compute);
-      u.layers.clear();
+      st->units.erase(unit_key(mb, chunk));
       return rc;
     }
     u.layers[l].state = L_RESIDENT;
@@ -1017,6 +1017,7 @@ int stage_backward(po_stage* st, int mb, int chunk, const void* dy, void* dx) {
   if (rc) return rc;
   rc = retire_unit(st, u, st->compute);
   if (rc) return rc;
+  st->units.erase(unit_key(mb, chunk));  // (u is gone) a long run with ever new microbatch numbers must not grow the map
   --st->in_flight_units;
   ++st->stats.n_compute_passes;
   return PO_OK;
@@ -1113,6 +1114,7 @@ static int backward_weight_impl(po_stage* st, int mb, int chunk, bool count_pass
   u->b_done = nullptr;
   rc = retire_unit(st, u, q);
   if (rc) return rc;
+  st->units.erase(unit_key(mb, chunk));  // (u is gone)
   if (count_pass) ++st->stats.n_compute_passes;
   return PO_OK;
 }
@@ -1143,8 +1145,8 @@ int stage_reset(po_stage* st) {
       L = UnitLayer();
     }
     if (u.grad_buf >= 0) PO_RC(st->grad_pool.release(u.grad_buf, st->compute));
-    u = Unit();
   }
+  st->units.clear();
   st->resident_units = 0;
   st->in_flight_units = 0;
   st->sync_events.reset();
