@@ -251,3 +251,17 @@ def test_hot_kernels_keep_their_accumulators_in_registers():
         assert v["Occupancy"] >= 2, (name, v)
     for name, v in gemm.items():
         assert v["VGPRs"] + v["AGPRs"] <= 512
+
+
+def test_trace_viewer_reads_the_span_file(tmp_path):
+    """The span file format of PIPEOFFLOAD_TRACE ("# run" separators, "kind start_ms stop_ms" lines) and the viewer."""
+    from paper_2503_01328_amd import trace
+
+    f = tmp_path / "t.txt"
+    f.write_text("# run\n0 0.0 1.0\n1 1.0 2.5\n# run\n0 0.0 2.0\n0 2.5 3.0\n2 1.0 4.0\n")
+    runs = trace.read_runs(str(f))
+    assert [len(r) for r in runs] == [2, 3]
+    text = trace.render(runs[-1])
+    assert "run of 4.00 ms, 3 spans" in text and "compute: 2 spans, busy 2.50 ms" in text
+    assert "H2D: 1 spans, busy 3.00 ms" in text and "gap  0.50" in text
+    assert trace.main(["trace", str(f), "0"]) == 0 and trace.main(["trace"]) == 2
