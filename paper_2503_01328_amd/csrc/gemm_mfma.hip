@@ -53,15 +53,18 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 #define PO_LDS_S16X4(p) ((s16x4 __attribute__((address_space(3)))*)(p))
 
 constexpr int kBK = 64;
+#ifndef PO_GEMM_EARLY
+#define PO_GEMM_EARLY 1
+#endif
+#ifndef PO_GEMM_LOAD_STEPS
+#define PO_GEMM_LOAD_STEPS 2
+#endif
 
 enum EpiKind : int { kEpiStore = 0, kEpiStoreGelu = 1, kEpiGeluBackward = 2, kEpiAccumulate = 3 };
 
 // ---- HBM -> LDS, one operand slice -----------------------------------------------
 // KMAJOR == false: operand is [R rows][K], slice = R rows x 64 k, row tile in LDS.
 // KMAJOR == true : operand is [K][R], slice = 64 k x R, k-major tile in LDS.
-// `base` points at (first row of the tile, k = 0); the slice starts at k0.
-// The slice is issued in four quarters (part = 0..3) so that the issue can be spread between the MFMAs
-// of the four k-steps of the slice being consumed; part < 0 issues everything.
 // Swizzle of the k-major tile: row k keeps unit u at position u ^ (k & mask).  The position must stay inside
 // the row, so a row of 12 units (R = 192) swaps only within groups of four; the fragment reads of four
 // consecutive k and two neighbouring units still fall into eight different 32-byte bank groups.
@@ -72,39 +75,57 @@ __device__ __forceinline__ int kmajor_unit(int u, int k) {
   return u ^ (k & MASK);
 }
 
+// Byte address of a pointer into the block's LDS as the hardware counts it (the generic -> LDS conversion and
+// its null check happen here, once, instead of at every load).
+__device__ __forceinline__ unsigned lds_address(const void* p) { return (unsigned)(size_t)PO_LDS3(p); }
+
+// The slice is R * 128 bytes = R / 8 wave-wide loads of 1 KiB; wave w issues pieces w, w + 4, w + 8, ...
+// What a lane fetches for piece u never changes from slice to slice except for a step that is the same for every
+// lane, so the lane keeps one 32-bit byte offset per piece and the wave one 64-bit slice pointer in scalar
+// registers: a load costs its own instruction and the M0 set-up, no address arithmetic.
 template <int R, bool KMAJOR>
-__device__ __forceinline__ void load_slice(const bf16* __restrict__ base, int ld, int k0, char* lds, int wave,
-                                           int lane, int part = -1) {
-  constexpr int N_INST = R * 128 / 1024;  // wave-level 1 KiB loads in the slice
-  constexpr int PER_WAVE = N_INST / 4;
-  static_assert(N_INST % 4 == 0 && PER_WAVE >= 4, "tile too small to split the slice in four");
+struct SliceLoader {
+  static constexpr int N_INST = R * 128 / 1024;
+  static constexpr int PER_WAVE = N_INST / 4;
+  static_assert(N_INST % 4 == 0 && PER_WAVE >= 4, "tile too small for four waves");
+  unsigned voff[PER_WAVE];  // this lane's byte offset from the slice pointer, per piece
+  const char* slice;        // first byte of the next slice to request (same in every lane)
+  unsigned step;            // bytes from one slice to the next
+
+  // `base` points at (first row of the tile, k = 0).
+  __device__ __forceinline__ void init(const bf16* base, int ld, int wave, int lane) {
 #pragma unroll
-  for (int u = 0; u < PER_WAVE; ++u) {
-    if (part >= 0 && u * 4 / PER_WAVE != part) continue;
-    int g = u * 4 + wave;  // which 1 KiB piece of the tile this wave fills now
-    const bf16* src;
-    if (!KMAJOR) {
-      int row = 8 * g + (lane >> 3);
-      int c = (lane & 7) ^ (row & 7);
-      src = base + (size_t)row * ld + k0 + c * 8;
-    } else {
-      constexpr int ROW_BYTES = 2 * R;
-      int byte = g * 1024 + lane * 16;
-      int k = byte / ROW_BYTES;
-      int pos16 = (byte % ROW_BYTES) >> 4;
-      int unit = kmajor_unit<R>(pos16 >> 1, k);
-      src = base + (size_t)(k0 + k) * ld + (unit * 2 + (pos16 & 1)) * 8;
+    for (int u = 0; u < PER_WAVE; ++u) {
+      int g = u * 4 + wave;  // which 1 KiB piece of the tile
+      unsigned elem;
+      if (!KMAJOR) {
+        int row = 8 * g + (lane >> 3);
+        int c = (lane & 7) ^ (row & 7);
+        elem = (unsigned)row * (unsigned)ld + c * 8;
+      } else {
+        constexpr int ROW_BYTES = 2 * R;
+        int byte = g * 1024 + lane * 16;
+        int k = byte / ROW_BYTES;
+        int pos16 = (byte % ROW_BYTES) >> 4;
+        int unit = kmajor_unit<R>(pos16 >> 1, k);
+        elem = (unsigned)k * (unsigned)ld + (unit * 2 + (pos16 & 1)) * 8;
+      }
+      voff[u] = elem * 2;
     }
-    // Issued as inline assembly on purpose: through the builtin the compiler treats every later
-    // LDS read as dependent on the load and waits for it at once, which would undo the double
-    // buffering.  The caller waits (wait_slice_loads) before the barrier that publishes the slice.
-    // (the LDS base of the piece is the same in every lane by construction; saying so keeps it in a scalar
-    // register where the compiler cannot prove it, as inside the loop over tiles of the grouped kernel)
-    unsigned lds_addr = __builtin_amdgcn_readfirstlane((unsigned)(size_t)PO_LDS3(lds + g * 1024));
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(src)
+    slice = reinterpret_cast<const char*>(base);
+    step = KMAJOR ? 128u * (unsigned)ld : 128u;
+  }
+  // Piece u of the slice at `slice` -> LDS at lds_wave + 4096 u (lds_wave: the LDS address of this wave's piece 0
+  // in the target stage).  Issued as inline assembly on purpose: through the builtin the compiler treats every
+  // later LDS read as dependent on the load and waits for it at once, which would undo the double buffering.
+  // The caller waits (wait_slice_loads) before the barrier that publishes the slice.
+  __device__ __forceinline__ void issue(int u, unsigned lds_wave) const {
+    unsigned dst = lds_wave + 4096u * u;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(voff[u]), "s"(slice)
                  : "memory");
   }
-}
+  __device__ __forceinline__ void advance() { slice += step; }
+};
 
 // Waits until at most N of this wave's loads are outstanding (they complete in issue order).
 template <int N>
@@ -212,6 +233,15 @@ __device__ __forceinline__ void tile_of(int lin, int tiles_m, int tiles_n, int& 
   tile_n = (lin % width) / gsize;
 }
 
+// Tells the compiler that a value is the same in every lane (it is: it derives from the block id and the kernel
+// arguments only), so that it stays in scalar registers.
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ const bf16* uniform(const bf16* p) {
+  uintptr_t v = reinterpret_cast<uintptr_t>(p);
+  unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+  return reinterpret_cast<const bf16*>(((uintptr_t)hi << 32) | lo);
+}
+
 // ---- one output tile -----------------------------------------------------------
 // TA: A is [K, M] (m-contiguous).  TB: B is [K, N] (n-contiguous).  All 256 threads of the block call it with
 // the same arguments; `smem` is the block's dynamic LDS (stages, then reused by the epilogue strips).
@@ -243,16 +273,32 @@ __device__ __forceinline__ void gemm_tile(int K, const bf16* __restrict__ A, int
   // the slice that the next barrier publishes.  The big tile has room for two stages (its slice takes about a
   // microsecond, which covers the round trip); the small tile's slice is four times shorter, so it gets four.
   constexpr int NSTAGE = stages_of(WTM, WTN);
-  constexpr int PER_SLICE = (BM + BN) * 128 / 1024 / 4;  // load instructions of one wave per slice
+  using LoaderA = SliceLoader<BM, TA>;
+  using LoaderB = SliceLoader<BN, TB>;
+  constexpr int PER_SLICE = LoaderA::PER_WAVE + LoaderB::PER_WAVE;  // load instructions of one wave per slice
   int nk = K / kBK;
-  auto request = [&](int kt, int part) {
-    char* st = smem + (kt % NSTAGE) * STAGE;
-    load_slice<BM, TA>(a_base, lda, kt * kBK, st, wave, lane, part);
-    load_slice<BN, TB>(b_base, ldb, kt * kBK, st + A_BYTES, wave, lane, part);
+  LoaderA la;
+  LoaderB lb;
+  la.init(a_base, lda, wave, lane);
+  lb.init(b_base, ldb, wave, lane);
+  const unsigned lds0 = uniform((int)lds_address(smem)) + 1024u * wave;  // this wave's piece 0 of stage 0, operand A
+  // Load q (0 .. PER_SLICE - 1, A's pieces first) of the slice the loaders point at, into stage `st`.
+  auto issue_load = [&](int q, unsigned st) {
+    unsigned base = lds0 + st * STAGE;
+    if (q < LoaderA::PER_WAVE) la.issue(q, base);
+    else lb.issue(q - LoaderA::PER_WAVE, base + A_BYTES);
+  };
+  auto next_slice = [&]() {
+    la.advance();
+    lb.advance();
   };
   {
     int ahead = min(nk, NSTAGE - 1);
-    for (int t = 0; t < ahead; ++t) request(t, -1);
+    for (int t = 0; t < ahead; ++t) {
+#pragma unroll
+      for (int q = 0; q < PER_SLICE; ++q) issue_load(q, t);
+      next_slice();
+    }
     if (ahead >= 3) wait_slice_loads<2 * PER_SLICE>();
     else if (ahead == 2) wait_slice_loads<PER_SLICE>();
     else wait_slice_loads<0>();
@@ -263,54 +309,104 @@ __device__ __forceinline__ void gemm_tile(int K, const bf16* __restrict__ A, int
   // Fragments are fetched in the order a0 b0 a1 b1 ... and the MFMAs of a k-step walk the
   // (i, j) grid as a growing square, so the first MFMAs need only the first fragments fetched
   // and the fragment fetched last is needed last.
+  constexpr int NFRAG = WTM + WTN;
+  auto load_fragment = [&](const char* stage, int kk, int buf, int r) {  // r-th fragment of the order above
+    // (with WTM != WTN the longer operand's surplus fragments come last)
+    constexpr int PAIRS = WTM < WTN ? WTM : WTN;
+    bool is_a;
+    int t;
+    if (r < 2 * PAIRS) {
+      is_a = (r & 1) == 0;
+      t = r >> 1;
+    } else {
+      is_a = WTM > WTN;
+      t = PAIRS + (r - 2 * PAIRS);
+    }
+    if (is_a) fa[buf][t] = read_fragment<BM, TA>(stage, wm * (WTM * 32) + t * 32, kk, lane);
+    else fb[buf][t] = read_fragment<BN, TB>(stage + A_BYTES, wn * (WTN * 32) + t * 32, kk, lane);
+  };
   auto load_fragments = [&](const char* stage, int kk, int buf) {
 #pragma unroll
-    for (int t = 0; t < (WTM > WTN ? WTM : WTN); ++t) {
-      if (t < WTM) fa[buf][t] = read_fragment<BM, TA>(stage, wm * (WTM * 32) + t * 32, kk, lane);
-      if (t < WTN) fb[buf][t] = read_fragment<BN, TB>(stage + A_BYTES, wn * (WTN * 32) + t * 32, kk, lane);
-    }
+    for (int r = 0; r < NFRAG; ++r) load_fragment(stage, kk, buf, r);
   };
   load_fragments(smem, 0, 0);
 
   // One slice: MFMAs on stage kt % NSTAGE.  ISSUE: slice kt + NSTAGE - 1 is requested meanwhile.  KEEP: how
   // many requested slices may still be in flight at the wait before the barrier (-1: last slice, nothing to
   // publish).  The tail slices are peeled off so that the steady-state loop body has no branches.
+  //
+  // Inside a k-step the three instruction streams are woven by hand, and scheduling barriers keep the compiler
+  // from undoing it: after every few MFMAs one LDS fragment read for the next k-step and, in the first
+  // kLoadSteps k-steps, one HBM -> LDS load of the slice being requested.  A wave has a single MFMA pipe to
+  // keep busy and no other wave on its SIMD to fill in, so anything issued in a clump (sixteen loads with their
+  // scalar set-up back to back) is time the matrix core stands still.
+  constexpr int NMFMA = WTM * WTN;
+  constexpr int kLoadSteps = PO_GEMM_LOAD_STEPS;
+  constexpr int LOADS_PER_STEP = (PER_SLICE + kLoadSteps - 1) / kLoadSteps;
+  // kEarly: the barrier that publishes slice kt + 1 stands before the last k-step of slice kt instead of after
+  // it, and the first fragments of slice kt + 1 are read under that k-step's MFMAs, so no wave starts a slice
+  // waiting for LDS.  Every wave has all its reads of stage kt % NSTAGE behind it at that barrier (it waits
+  // for them), which is what allows the loads that overwrite the stage to be issued from the next slice on.
+  constexpr bool kEarly = (NSTAGE == 4) ? (PO_GEMM_EARLY & 1) != 0 : (PO_GEMM_EARLY & 2) != 0;
   auto slice = [&](int kt, auto issue_tag, auto keep_tag) {
     constexpr bool ISSUE = decltype(issue_tag)::value;
     constexpr int KEEP = decltype(keep_tag)::value;
     constexpr bool MORE = KEEP >= 0;
     char* cur = smem + (kt % NSTAGE) * STAGE;
     char* nxt = smem + ((kt + 1) % NSTAGE) * STAGE;
+    unsigned load_stage = (unsigned)((kt + NSTAGE - 1) % NSTAGE);
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      if (kk < 3) load_fragments(cur, kk + 1, (kk + 1) & 1);
-      if (ISSUE && kk < 2) {  // the request is spread over the first two k-steps (half each): early enough
-                              // to land in time, spread enough not to stall the issue
-#pragma unroll
-        for (int q = 2 * kk; q < 2 * kk + 2; ++q) request(kt + NSTAGE - 1, q);
+      if (kEarly && MORE && kk == 3) {
+        wait_slice_loads<(KEEP > 0 ? KEEP : 0) * PER_SLICE>();
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
       }
+      int n = 0;  // MFMAs issued in this k-step
+      auto after_mfma = [&]() {
+        ++n;
+        // the share of the other two streams that belongs behind MFMA n of NMFMA
+        bool any = false;
+        if (kk < 3 || (kEarly && MORE)) {
+#pragma unroll
+          for (int r = (n - 1) * NFRAG / NMFMA; r < n * NFRAG / NMFMA; ++r) {
+            if (kk < 3) load_fragment(cur, kk + 1, (kk + 1) & 1, r);
+            else load_fragment(nxt, 0, 0, r);
+            any = true;
+          }
+        }
+        if (ISSUE && kk < kLoadSteps) {
+#pragma unroll
+          for (int q = (n - 1) * LOADS_PER_STEP / NMFMA; q < n * LOADS_PER_STEP / NMFMA; ++q) {
+            int ql = kk * LOADS_PER_STEP + q;
+            if (ql < PER_SLICE) {
+              issue_load(ql, load_stage);
+              any = true;
+            }
+          }
+        }
+        if (any) __builtin_amdgcn_sched_barrier(0);
+      };
 #pragma unroll
       for (int t = 0; t < (WTM > WTN ? WTM : WTN); ++t) {  // ring t of the growing square
 #pragma unroll
         for (int j = 0; j < t && j < WTN; ++j)
-          if (t < WTM)
+          if (t < WTM) {
             acc[t][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][j], fa[kk & 1][t], acc[t][j], 0, 0, 0);
+            after_mfma();
+          }
 #pragma unroll
         for (int i = 0; i <= t && i < WTM; ++i)
-          if (t < WTN)
+          if (t < WTN) {
             acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][t], fa[kk & 1][i], acc[i][t], 0, 0, 0);
-      }
-      // Pin the order inside the k-step: the LDS reads of the next k-step's fragments are spread
-      // between this k-step's MFMAs (which do not depend on them), so their latency is hidden.
-      if (kk < 3) {
-#pragma unroll
-        for (int r = 0; r < WTM + WTN; ++r) {
-          __builtin_amdgcn_sched_group_barrier(0x100, TA || TB ? 2 : 1, 0);  // LDS reads
-          __builtin_amdgcn_sched_group_barrier(0x008, (WTM * WTN) / (WTM + WTN), 0);  // MFMAs
-        }
+            after_mfma();
+          }
       }
       __builtin_amdgcn_sched_barrier(0);
     }
+    if (ISSUE) next_slice();
+    if (kEarly && MORE) return;
     if (MORE) wait_slice_loads<(KEEP > 0 ? KEEP : 0) * PER_SLICE>();
     __syncthreads();
     if (MORE) load_fragments(nxt, 0, 0);
@@ -395,15 +491,6 @@ __device__ __forceinline__ void gemm_tile(int K, const bf16* __restrict__ A, int
       }
     }
   }
-}
-
-// Tells the compiler that a value is the same in every lane (it is: it derives from the block id and the kernel
-// arguments only), so that it stays in scalar registers.
-__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
-__device__ __forceinline__ const bf16* uniform(const bf16* p) {
-  uintptr_t v = reinterpret_cast<uintptr_t>(p);
-  unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
-  return reinterpret_cast<const bf16*>(((uintptr_t)hi << 32) | lo);
 }
 
 // ---- the kernels -----------------------------------------------------------------
