@@ -53,11 +53,11 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 #define PO_LDS_S16X4(p) ((s16x4 __attribute__((address_space(3)))*)(p))
 
 constexpr int kBK = 64;
-#ifndef PO_GEMM_EARLY
-#define PO_GEMM_EARLY 1
-#endif
 #ifndef PO_GEMM_LOAD_STEPS
 #define PO_GEMM_LOAD_STEPS 2
+#endif
+#ifndef PO_GEMM_LOAD_STEPS_SMALL
+#define PO_GEMM_LOAD_STEPS_SMALL 3
 #endif
 
 enum EpiKind : int { kEpiStore = 0, kEpiStoreGelu = 1, kEpiGeluBackward = 2, kEpiAccumulate = 3 };
@@ -268,10 +268,14 @@ __device__ __forceinline__ void gemm_tile(int K, const bf16* __restrict__ A, int
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  // The slices travel through a ring of NSTAGE LDS stages; slice kt + NSTAGE - 1 is requested while slice kt
-  // is multiplied, and a wave lets the NSTAGE - 2 youngest requested slices stay in flight when it waits for
-  // the slice that the next barrier publishes.  The big tile has room for two stages (its slice takes about a
-  // microsecond, which covers the round trip); the small tile's slice is four times shorter, so it gets four.
+  // Pipeline.  Three streams feed the MFMAs, each running ahead of them by a fixed distance:
+  //   HBM -> LDS   slice kt + NSTAGE is requested during slice kt, into the stage slice kt occupies, from the
+  //                moment every wave is done reading it (the barrier below);
+  //   LDS -> regs  the fragments of a k-step are read three k-steps (most of a slice) before their MFMAs, into a
+  //                ring of four register buffers, so an LDS round trip is never waited for;
+  //   barrier      one per slice, before k-step 1: it publishes slice kt + 1 (whose first fragments are read
+  //                from k-step 1 on) and releases stage kt % NSTAGE (whose last fragments were read in k-step 0).
+  // The big tiles have room for two stages, the small tile (a slice is four times shorter) gets four.
   constexpr int NSTAGE = stages_of(WTM, WTN);
   using LoaderA = SliceLoader<BM, TA>;
   using LoaderB = SliceLoader<BN, TB>;
@@ -293,24 +297,26 @@ __device__ __forceinline__ void gemm_tile(int K, const bf16* __restrict__ A, int
     lb.advance();
   };
   {
-    int ahead = min(nk, NSTAGE - 1);
+    int ahead = min(nk, NSTAGE);
     for (int t = 0; t < ahead; ++t) {
 #pragma unroll
       for (int q = 0; q < PER_SLICE; ++q) issue_load(q, t);
       next_slice();
     }
-    if (ahead >= 3) wait_slice_loads<2 * PER_SLICE>();
+    // slice 0 has landed when at most ahead - 1 slices are still in flight
+    if (ahead >= 4) wait_slice_loads<3 * PER_SLICE>();
+    else if (ahead == 3) wait_slice_loads<2 * PER_SLICE>();
     else if (ahead == 2) wait_slice_loads<PER_SLICE>();
     else wait_slice_loads<0>();
   }
   __syncthreads();
 
-  bf16x8 fa[2][WTM], fb[2][WTN];
+  bf16x8 fa[4][WTM], fb[4][WTN];
   // Fragments are fetched in the order a0 b0 a1 b1 ... and the MFMAs of a k-step walk the
   // (i, j) grid as a growing square, so the first MFMAs need only the first fragments fetched
   // and the fragment fetched last is needed last.
   constexpr int NFRAG = WTM + WTN;
-  auto load_fragment = [&](const char* stage, int kk, int buf, int r) {  // r-th fragment of the order above
+  auto load_fragment = [&](const char* stage, int kk, int r) {  // r-th fragment of k-step kk, into buffer kk
     // (with WTM != WTN the longer operand's surplus fragments come last)
     constexpr int PAIRS = WTM < WTN ? WTM : WTN;
     bool is_a;
@@ -322,43 +328,37 @@ __device__ __forceinline__ void gemm_tile(int K, const bf16* __restrict__ A, int
       is_a = WTM > WTN;
       t = PAIRS + (r - 2 * PAIRS);
     }
-    if (is_a) fa[buf][t] = read_fragment<BM, TA>(stage, wm * (WTM * 32) + t * 32, kk, lane);
-    else fb[buf][t] = read_fragment<BN, TB>(stage + A_BYTES, wn * (WTN * 32) + t * 32, kk, lane);
+    if (is_a) fa[kk][t] = read_fragment<BM, TA>(stage, wm * (WTM * 32) + t * 32, kk, lane);
+    else fb[kk][t] = read_fragment<BN, TB>(stage + A_BYTES, wn * (WTN * 32) + t * 32, kk, lane);
   };
-  auto load_fragments = [&](const char* stage, int kk, int buf) {
 #pragma unroll
-    for (int r = 0; r < NFRAG; ++r) load_fragment(stage, kk, buf, r);
-  };
-  load_fragments(smem, 0, 0);
+  for (int kk = 0; kk < 3; ++kk)
+#pragma unroll
+    for (int r = 0; r < NFRAG; ++r) load_fragment(smem, kk, r);
 
-  // One slice: MFMAs on stage kt % NSTAGE.  ISSUE: slice kt + NSTAGE - 1 is requested meanwhile.  KEEP: how
-  // many requested slices may still be in flight at the wait before the barrier (-1: last slice, nothing to
-  // publish).  The tail slices are peeled off so that the steady-state loop body has no branches.
+  // One slice: MFMAs on the fragments of stage kt % NSTAGE.  ISSUE: slice kt + NSTAGE is requested meanwhile.
+  // MORE: a slice follows.  The tail slices are peeled off so that the steady-state loop body has no branches.
   //
   // Inside a k-step the three instruction streams are woven by hand, and scheduling barriers keep the compiler
-  // from undoing it: after every few MFMAs one LDS fragment read for the next k-step and, in the first
-  // kLoadSteps k-steps, one HBM -> LDS load of the slice being requested.  A wave has a single MFMA pipe to
-  // keep busy and no other wave on its SIMD to fill in, so anything issued in a clump (sixteen loads with their
-  // scalar set-up back to back) is time the matrix core stands still.
+  // from undoing it: behind every few MFMAs one LDS fragment read and, in k-steps 1 .. kLoadSteps, one
+  // HBM -> LDS load.  A wave has a single MFMA pipe to keep busy and no other wave on its SIMD to fill in, so
+  // anything issued in a clump (sixteen loads with their scalar set-up back to back) is time the matrix core
+  // stands still.
   constexpr int NMFMA = WTM * WTN;
-  constexpr int kLoadSteps = PO_GEMM_LOAD_STEPS;
+  constexpr int kLoadSteps = NSTAGE == 4 ? PO_GEMM_LOAD_STEPS_SMALL : PO_GEMM_LOAD_STEPS;  // 1 .. 3
   constexpr int LOADS_PER_STEP = (PER_SLICE + kLoadSteps - 1) / kLoadSteps;
-  // kEarly: the barrier that publishes slice kt + 1 stands before the last k-step of slice kt instead of after
-  // it, and the first fragments of slice kt + 1 are read under that k-step's MFMAs, so no wave starts a slice
-  // waiting for LDS.  Every wave has all its reads of stage kt % NSTAGE behind it at that barrier (it waits
-  // for them), which is what allows the loads that overwrite the stage to be issued from the next slice on.
-  constexpr bool kEarly = (NSTAGE == 4) ? (PO_GEMM_EARLY & 1) != 0 : (PO_GEMM_EARLY & 2) != 0;
-  auto slice = [&](int kt, auto issue_tag, auto keep_tag) {
+  auto slice = [&](int kt, auto issue_tag, auto more_tag) {
     constexpr bool ISSUE = decltype(issue_tag)::value;
-    constexpr int KEEP = decltype(keep_tag)::value;
-    constexpr bool MORE = KEEP >= 0;
-    char* cur = smem + (kt % NSTAGE) * STAGE;
+    constexpr bool MORE = decltype(more_tag)::value;
+    unsigned st_cur = (unsigned)(kt % NSTAGE);
+    char* cur = smem + st_cur * STAGE;
     char* nxt = smem + ((kt + 1) % NSTAGE) * STAGE;
-    unsigned load_stage = (unsigned)((kt + NSTAGE - 1) % NSTAGE);
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      if (kEarly && MORE && kk == 3) {
-        wait_slice_loads<(KEEP > 0 ? KEEP : 0) * PER_SLICE>();
+      if (MORE && kk == 1) {
+        // slice kt + 1 complete (in steady state NSTAGE - 2 younger slices may stay in flight; the tail slices
+        // simply wait for everything), own reads of stage kt % NSTAGE complete, then the barrier
+        wait_slice_loads<(ISSUE ? NSTAGE - 2 : 0) * PER_SLICE>();
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __syncthreads();
         __builtin_amdgcn_sched_barrier(0);
@@ -368,20 +368,28 @@ __device__ __forceinline__ void gemm_tile(int K, const bf16* __restrict__ A, int
         ++n;
         // the share of the other two streams that belongs behind MFMA n of NMFMA
         bool any = false;
-        if (kk < 3 || (kEarly && MORE)) {
+        if (kk == 0) {
+          // the last reads of this stage: all in the first half of the k-step, so that they have come back
+          // when the wave waits for them at the barrier
+#pragma unroll
+          for (int r = (n - 1) * NFRAG * 2 / NMFMA; r < n * NFRAG * 2 / NMFMA; ++r)
+            if (r < NFRAG) {
+              load_fragment(cur, 3, r);
+              any = true;
+            }
+        } else if (MORE) {
 #pragma unroll
           for (int r = (n - 1) * NFRAG / NMFMA; r < n * NFRAG / NMFMA; ++r) {
-            if (kk < 3) load_fragment(cur, kk + 1, (kk + 1) & 1, r);
-            else load_fragment(nxt, 0, 0, r);
+            load_fragment(nxt, kk - 1, r);
             any = true;
           }
         }
-        if (ISSUE && kk < kLoadSteps) {
+        if (ISSUE && kk >= 1 && kk <= kLoadSteps) {
 #pragma unroll
           for (int q = (n - 1) * LOADS_PER_STEP / NMFMA; q < n * LOADS_PER_STEP / NMFMA; ++q) {
-            int ql = kk * LOADS_PER_STEP + q;
+            int ql = (kk - 1) * LOADS_PER_STEP + q;
             if (ql < PER_SLICE) {
-              issue_load(ql, load_stage);
+              issue_load(ql, st_cur);
               any = true;
             }
           }
@@ -393,36 +401,29 @@ __device__ __forceinline__ void gemm_tile(int K, const bf16* __restrict__ A, int
 #pragma unroll
         for (int j = 0; j < t && j < WTN; ++j)
           if (t < WTM) {
-            acc[t][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][j], fa[kk & 1][t], acc[t][j], 0, 0, 0);
+            acc[t][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk][j], fa[kk][t], acc[t][j], 0, 0, 0);
             after_mfma();
           }
 #pragma unroll
         for (int i = 0; i <= t && i < WTM; ++i)
           if (t < WTN) {
-            acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][t], fa[kk & 1][i], acc[i][t], 0, 0, 0);
+            acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk][t], fa[kk][i], acc[i][t], 0, 0, 0);
             after_mfma();
           }
       }
       __builtin_amdgcn_sched_barrier(0);
     }
     if (ISSUE) next_slice();
-    if (kEarly && MORE) return;
-    if (MORE) wait_slice_loads<(KEEP > 0 ? KEEP : 0) * PER_SLICE>();
-    __syncthreads();
-    if (MORE) load_fragments(nxt, 0, 0);
   };
   {
     using T = std::true_type;
     using F = std::false_type;
     int kt = 0;
-    for (; kt + NSTAGE - 1 < nk; ++kt) slice(kt, T{}, std::integral_constant<int, NSTAGE - 2>{});
-    // nothing left to request: the last NSTAGE - 1 slices, each letting one slice less stay in flight
-    if (NSTAGE == 4) {
-      if (nk >= 3) slice(nk - 3, F{}, std::integral_constant<int, 1>{});
-      if (nk >= 2) slice(nk - 2, F{}, std::integral_constant<int, 0>{});
-    }
-    slice(nk - 1, F{}, std::integral_constant<int, -1>{});
+    for (; kt + NSTAGE < nk; ++kt) slice(kt, T{}, T{});
+    for (; kt + 1 < nk; ++kt) slice(kt, F{}, T{});  // nothing left to request
+    slice(nk - 1, F{}, F{});
   }
+  __syncthreads();  // the epilogue strips reuse the operand stages
 
   // Epilogue.  acc[i][j][4q + r] = C[m][n], m = strip row (lane & 31), n = 32 j + 8 q + 4 (lane >> 5) + r.
   // Each wave owns a private [32][WTN*32 + 4] fp32 strip in LDS (the operand buffers are free now).
