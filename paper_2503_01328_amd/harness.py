@@ -176,3 +176,22 @@ def max_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     if denom == 0.0:
         return float(np.abs(got).max())
     return float(np.abs(got.astype(np.float64) - ref.astype(np.float64)).max() / denom)
+
+
+def rel_l2_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """||got - ref||_2 / ||ref||_2 over one tensor."""
+    g, r = got.astype(np.float64), ref.astype(np.float64)
+    denom = float(np.sqrt((r * r).sum()))
+    num = float(np.sqrt(((g - r) ** 2).sum()))
+    return num if denom == 0.0 else num / denom
+
+
+def check_parity(got: np.ndarray, ref: np.ndarray, tol: float, what: str) -> tuple:
+    """Asserts both error norms of one tensor against `tol` and prints them (pytest -s shows the lines; a failure
+    shows them anyway): the per-tensor max norm max|got - ref| / max|ref| and the relative L2 norm."""
+    mx, l2 = max_rel_err(got, ref), rel_l2_err(got, ref)
+    print(f"parity {what}: max-norm {mx:.3e}  rel-L2 {l2:.3e}  (tolerance {tol:g})")
+    assert mx < tol, f"{what}: max|got - ref| / max|ref| = {mx:.3e} >= {tol:g}"
+    assert l2 < tol, f"{what}: ||got - ref|| / ||ref|| = {l2:.3e} >= {tol:g}"
+    return mx, l2
+

@@ -2,8 +2,9 @@
 
 The oracle cannot run whole C3 / C5 jobs in test time, so outputs are sampled: GEMM entries are
 checked one by one against fp64 dot products, attention is checked on whole heads (every row and
-column of the sampled head, fp64 oracle on that head's slices), and one C2-shaped layer is checked
-in full through the stage.  Tolerance as everywhere in bf16: max |got - ref| / max |ref| < 2e-2."""
+column of the sampled head, fp64 oracle on that head's slices), C2 runs in full (4 layers, 8
+microbatches, full offload) and one C3 layer in full through the stage against the oracle.  Tolerance as
+everywhere in bf16: 2e-2, on max |got - ref| / max |ref| and on the relative L2 norm, both printed."""
 import dataclasses
 
 import numpy as np
@@ -13,7 +14,7 @@ import torch
 from oracle import stage_oracle as so
 from paper_2503_01328_amd import binding as po
 from paper_2503_01328_amd import inputs as syn
-from paper_2503_01328_amd.harness import StageRunner, max_rel_err
+from paper_2503_01328_amd.harness import StageRunner, check_parity, max_rel_err
 
 pytestmark = pytest.mark.gpu
 BF = torch.bfloat16
@@ -110,13 +111,13 @@ def test_attention_full_size_sampled_heads(gpu_device, s, h, a, heads):
         k = qkv[:, h + t * dh: h + (t + 1) * dh].astype(np.float64)
         v = qkv[:, 2 * h + t * dh: 2 * h + (t + 1) * dh].astype(np.float64)
         ro, probs = so.attention_forward(q, k, v, 1)
-        assert max_rel_err(_np(o[:, c]), ro) < 2e-2
+        check_parity(_np(o[:, c]), ro, 2e-2, f"attention O head {t} s={s}")
         rdq, rdk, rdv = so.attention_backward(d_o[:, c].astype(np.float64), q, k, v, probs, 1)
         del probs
         got = _np(dqkv[:, c]), _np(dqkv[:, h + t * dh: h + (t + 1) * dh]), _np(dqkv[:, 2 * h + t * dh: 2 * h + (t + 1) * dh])
-        assert max_rel_err(got[0], rdq) < 3e-2
-        assert max_rel_err(got[1], rdk) < 3e-2
-        assert max_rel_err(got[2], rdv) < 3e-2
+        check_parity(got[0], rdq, 2e-2, f"attention dQ head {t} s={s}")
+        check_parity(got[1], rdk, 2e-2, f"attention dK head {t} s={s}")
+        check_parity(got[2], rdv, 2e-2, f"attention dV head {t} s={s}")
 
 
 def test_grouped_query_attention_full_size_sampled_group(gpu_device):
@@ -140,31 +141,52 @@ def test_grouped_query_attention_full_size_sampled_group(gpu_device):
     vc = slice(h + hkv + kvh * dh, h + hkv + (kvh + 1) * dh)
     q, k, v = (qkv[:, c].astype(np.float64) for c in (qc, kc, vc))
     ro, probs = so.attention_forward(q, k, v, group)
-    assert max_rel_err(_np(o[:, qc]), ro) < 2e-2
+    check_parity(_np(o[:, qc]), ro, 2e-2, "grouped-query attention O")
     rdq, rdk, rdv = so.attention_backward(d_o[:, qc].astype(np.float64), q, k, v, probs, group)
     del probs
-    assert max_rel_err(_np(dqkv[:, qc]), rdq) < 3e-2
-    assert max_rel_err(_np(dqkv[:, kc]), rdk) < 3e-2
-    assert max_rel_err(_np(dqkv[:, vc]), rdv) < 3e-2
+    check_parity(_np(dqkv[:, qc]), rdq, 2e-2, "grouped-query attention dQ")
+    check_parity(_np(dqkv[:, kc]), rdk, 2e-2, "grouped-query attention dK")
+    check_parity(_np(dqkv[:, vc]), rdv, 2e-2, "grouped-query attention dV")
 
 
-def test_one_c2_shaped_layer_through_the_stage(gpu_device):
-    """Every kernel of the stage at C2's shapes (h 2048, 16 heads, FFN 8192, s 2048), two microbatches of one
-    layer under 1F1B with full offload; all outputs and gradients against the fp64 oracle."""
-    shape = dataclasses.replace(syn.CONFIGS["C2"], n_layers=1, n_microbatches=2)
-    with StageRunner(shape, seed=77) as r:
+def _stage_against_oracle(shape, seed, schedule, ratio, expect_offloads, tol=2e-2):
+    """Runs the whole job of `shape` through the C ABI and through the oracle (its float32 instantiation: the
+    reference arithmetic the task names) on the same seeded bf16-valued inputs; every output, input gradient and
+    parameter gradient tensor is compared in both norms."""
+    m = shape.n_microbatches
+    with StageRunner(shape, seed=seed) as r:
         r.make_inputs()
-        stats = r.run(po.PO_SCHED_1F1B, 1.0)
+        stats = r.run(schedule, ratio)
         y, dx, g = r.results()
-        assert stats["n_offloads"] == 2
-    x = {(j, 0): syn.unit_input(shape, j, 0, 77) for j in range(2)}
-    dy = {(j, 0): syn.unit_upstream_grad(shape, j, 0, 77) for j in range(2)}
-    ry, rdx, rg = so.run_stage(r.params_np, 1, 1, shape.n_heads, x, dy)
-    for u in ry:
-        assert max_rel_err(y[u], ry[u]) < 2e-2
-        assert max_rel_err(dx[u], rdx[u]) < 2e-2
-    for k, a in rg["layers"][0].items():
-        assert max_rel_err(g["layers"][0][k], a) < 2e-2, k
+        params = r.params_np
+    assert stats["n_offloads"] == expect_offloads
+    x = {(j, 0): syn.unit_input(shape, j, 0, seed) for j in range(m)}
+    dy = {(j, 0): syn.unit_upstream_grad(shape, j, 0, seed) for j in range(m)}
+    ry, rdx, rg = so.run_stage(params, shape.n_layers, 1, shape.n_heads, x, dy, dtype=np.float32)
+    for u in sorted(ry):
+        check_parity(y[u], ry[u], tol, f"y mb {u[0]}")
+        check_parity(dx[u], rdx[u], tol, f"dx mb {u[0]}")
+    for l in range(shape.n_layers):
+        for k, a in rg["layers"][l].items():
+            check_parity(g["layers"][l][k], a, tol, f"grad layer {l} {k}")
+
+
+@pytest.mark.timeout(900)
+def test_c2_in_full_against_the_oracle(gpu_device):
+    """The benchmark's workload as bench.py runs it: C2 (4 layers, h 2048, 16 heads, FFN 8192, s 2048), all 8
+    microbatches under 1F1B at pipeline degree 4 with every unit offloaded and reloaded; all outputs, input
+    gradients and the parameter gradients accumulated over the 8 microbatches against the oracle (about a minute
+    of host time on 16 cores)."""
+    shape = syn.CONFIGS["C2"]
+    _stage_against_oracle(shape, 77, po.PO_SCHED_1F1B, 1.0, shape.n_layers * shape.n_microbatches)
+
+
+@pytest.mark.timeout(900)
+def test_one_c3_layer_against_the_oracle(gpu_device):
+    """Every kernel of the stage at C3's shapes (h 4096, 32 heads, FFN 16384, s 4096): one layer, one microbatch,
+    offloaded and reloaded, against the oracle (5 TFLOP of host work)."""
+    shape = dataclasses.replace(syn.CONFIGS["C3"], n_layers=1, n_microbatches=1, pipeline_degree=1)
+    _stage_against_oracle(shape, 78, po.PO_SCHED_1F1B, 1.0, 1)
 
 
 @pytest.mark.parametrize("name,layers,m", [("C2", 2, 4), ("C3", 2, 4), ("C5", 1, 2)], ids=["C2", "C3", "C5"])
@@ -189,11 +211,13 @@ def test_offload_is_bit_identical_at_full_shapes(gpu_device, name, layers, m):
             assert torch.equal(a, b), key
 
 
-@pytest.mark.parametrize("name,m", [("C3", 2), ("C5", 1)], ids=["C3", "C5"])
+@pytest.mark.parametrize("name,m", [("C5", 1)], ids=["C5"])
 def test_bf16_stage_against_fp32_stage_at_full_shapes(gpu_device, name, m):
-    """One layer at the shapes of C3 and C5 (too large for the CPU oracle inside a test): the bf16 MFMA path against
-    the library's fp32 path on the same bf16-valued parameters and inputs, all outputs and gradients within the bf16
-    tolerance.  The fp32 path runs the shape-generic kernels, which the small cases pin to the oracle at 1e-4."""
+    """One layer at the shapes of C5 (s 16384: the oracle's probability tensors alone would be 86 GB, so this one
+    shape is NOT compared with the oracle at stage level; its GEMMs and attention heads are, by sampling, above):
+    the bf16 MFMA path against the library's fp32 path on the same bf16-valued parameters and inputs, all outputs
+    and gradients within the bf16 tolerance.  The fp32 path runs the shape-generic kernels, which the small cases
+    pin to the oracle at 1e-4.  C2 and C3 are compared with the oracle itself."""
     shape = dataclasses.replace(syn.CONFIGS[name], n_layers=1, n_chunks=1, n_microbatches=m, pipeline_degree=2)
     with StageRunner(shape, seed=9, device_params=True) as r:
         r.make_inputs_on_device()
