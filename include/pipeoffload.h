@@ -310,6 +310,17 @@ uint64_t po_op_colsum_workspace(int32_t rows, int32_t n);
 int po_op_colsum_accumulate(int32_t dtype, const void* x, float* acc, float* workspace, int32_t rows, int32_t n,
                             void* stream);
 
+/* For callers that cannot allocate device memory or carry a workspace (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): po_op_colsum_accumulate with the chunk partials in an 8 MiB device array
+ * built into the library instead of a caller workspace.  Allocates nothing and calls no allocating routine; x
+ * [rows, n] and acc [n] are DEVICE memory of the caller as above; same arithmetic, same order, same result bit
+ * for bit.  n must be even and at most 32768 (any rows), else PO_E_INVAL with text.  The first call on a device
+ * resolves the array's address on that device (make that call outside a capture).  Every call on one GPU uses that
+ * GPU's one array: calls that overlap there (two streams, two threads) race; calls in stream order do not, and
+ * nothing in the array needs clearing between calls.  The array is held on each GPU the library runs on until the
+ * process ends. */
+int po_op_colsum_accumulate_static(int32_t dtype, const void* x, float* acc, int32_t rows, int32_t n, void* stream);
+
 /* Gather n_seg segments into one contiguous buffer / scatter them back (a layer's saved set to and from a
  * staging buffer, Section 4.2).
  * seg_ptrs: HOST array of DEVICE pointers; seg_bytes: HOST array, each a multiple of 16.

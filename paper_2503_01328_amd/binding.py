@@ -104,6 +104,7 @@ EXPORTS = {
     "po_op_colsum_workspace": (C.c_uint64, [C.c_int32, C.c_int32]),
     "po_op_colsum_accumulate": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                           C.c_void_p]),
+    "po_op_colsum_accumulate_static": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]),
     "po_op_pack": (C.c_int, [C.POINTER(C.c_void_p), C.POINTER(C.c_uint64), C.c_int32, C.c_void_p, C.c_void_p]),
     "po_op_unpack": (C.c_int, [C.POINTER(C.c_void_p), C.POINTER(C.c_uint64), C.c_int32, C.c_void_p, C.c_void_p]),
 }
@@ -327,6 +328,10 @@ def po_op_colsum_workspace(rows, n) -> int:
 
 def po_op_colsum_accumulate(dtype, x, acc, workspace, rows, n, stream=None):
     _check(lib.po_op_colsum_accumulate(dtype, _ptr(x), _ptr(acc), _ptr(workspace), rows, n, _stream(stream)))
+
+
+def po_op_colsum_accumulate_static(dtype, x, acc, rows, n, stream=None):
+    _check(lib.po_op_colsum_accumulate_static(dtype, _ptr(x), _ptr(acc), rows, n, _stream(stream)))
 
 
 def po_op_pack(segments, packed, stream=None):

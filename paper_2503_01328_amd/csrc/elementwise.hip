@@ -7,6 +7,7 @@
 // coalesced 1 KiB wave accesses.  Column reductions never use atomics: rows are
 // split into chunks, each chunk writes a partial, and a second kernel adds the
 // partials in chunk order, so results do not depend on scheduling.
+#include <atomic>
 #include <stdarg.h>
 #include <stdio.h>
 
@@ -463,6 +464,57 @@ bool colsum_accumulate(int dtype, const void* x, float* acc, float* workspace, i
     colsum_partial_kernel<bf16><<<g, 256, 0, stream>>>((const bf16*)x, workspace, rows, n, rows_per_chunk);
   chunk_partials_final_kernel<1><<<ceil_div(n, 64), 256, 0, stream>>>(workspace, acc, nullptr, n, n_chunks);
   return launch_ok("colsum kernels");
+}
+
+// --------------------------------------------------------------------------
+// The same column sums for callers that can neither allocate nor bring a workspace (code under HIP graph
+// capture, tight serving loops): the chunk partials live in a file-scope device array.  Every GPU the library
+// runs on holds its own copy of the array, at its own address, until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress; what kernels and copies take is the address that call
+// returns for the device that is current, resolved once per device and kept.
+// --------------------------------------------------------------------------
+constexpr int kStaticColsumMaxCols = 32768;
+constexpr size_t kStaticScratchFloats = (size_t)64 * kStaticColsumMaxCols;  // 64 row chunks at most: 8 MiB
+static __device__ __align__(256) float scratch[kStaticScratchFloats];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<float*> g_scratch_of_device[kMaxDevices];
+
+// Device address of `scratch` on the current device; null (with error text) if it cannot be resolved.
+static float* static_scratch() {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    set_error("static scratch: hipGetDevice failed or device %d out of range: %s", dev, hipGetErrorString(e));
+    return nullptr;
+  }
+  float* p = g_scratch_of_device[dev].load(std::memory_order_acquire);
+  if (p) return p;
+  void* addr = nullptr;
+  e = hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch));
+  if (e != hipSuccess || !addr) {
+    set_error("static scratch: hipGetSymbolAddress failed on device %d: %s", dev, hipGetErrorString(e));
+    return nullptr;
+  }
+  g_scratch_of_device[dev].store(static_cast<float*>(addr), std::memory_order_release);
+  return static_cast<float*>(addr);
+}
+
+bool colsum_accumulate_static(int dtype, const void* x, float* acc, int rows, int n, hipStream_t stream) {
+  if (rows <= 0 || n <= 0 || n % 2 != 0 || !x || !acc) {
+    set_error("colsum_accumulate_static: rows=%d n=%d x=%p acc=%p (n must be even)", rows, n, x, (void*)acc);
+    return false;
+  }
+  if (n > kStaticColsumMaxCols || colsum_workspace(rows, n) > sizeof(float) * kStaticScratchFloats) {
+    set_error("colsum_accumulate_static: n=%d exceeds the %d columns the built-in scratch holds; use "
+              "colsum_accumulate with a workspace", n, kStaticColsumMaxCols);
+    return false;
+  }
+  float* ws = static_scratch();
+  if (!ws) return false;
+  // every partial the final kernel reads is written by the partial kernel of the same call first: nothing in
+  // the scratch has to start at zero, and what an earlier call left there is never read
+  return colsum_accumulate(dtype, x, acc, ws, rows, n, stream);
 }
 
 // --------------------------------------------------------------------------

@@ -22,6 +22,9 @@ bool layernorm_backward(int dtype, const void* dn, const void* x, const void* ga
                         hipStream_t stream);
 size_t colsum_workspace(int rows, int n);
 bool colsum_accumulate(int dtype, const void* x, float* acc, float* workspace, int rows, int n, hipStream_t stream);
+// The same with the partials in a device array built into the library (no workspace, nothing allocated);
+// n <= 32768.  Calls that overlap on one GPU share that array and race.
+bool colsum_accumulate_static(int dtype, const void* x, float* acc, int rows, int n, hipStream_t stream);
 // Several column reductions over the same number of rows in two launches (all partial sums, then all final
 // sums) instead of two per tensor: the bias gradients and LayerNorm gain / shift gradients of one layer.
 // Per job the arithmetic and its order are those of colsum_accumulate / layernorm_backward(kLnParamGrad).

@@ -1732,6 +1732,11 @@ int po_op_colsum_accumulate(int32_t dtype, const void* x, float* acc, float* wor
   if (!dtype_ok(dtype)) return PO_E_INVAL;
   return ok(colsum_accumulate(dtype, x, acc, workspace, rows, n, (hipStream_t)stream));
 }
+int po_op_colsum_accumulate_static(int32_t dtype, const void* x, float* acc, int32_t rows, int32_t n, void* stream) {
+  begin_launch();
+  if (!dtype_ok(dtype)) return PO_E_INVAL;
+  return ok(colsum_accumulate_static(dtype, x, acc, rows, n, (hipStream_t)stream));
+}
 int po_op_pack(const void* const* seg_ptrs, const uint64_t* seg_bytes, int32_t n_seg, void* packed, void* stream) {
   begin_launch();
   return ok(pack_segments(seg_ptrs, seg_bytes, n_seg, packed, (hipStream_t)stream));
