@@ -86,7 +86,7 @@ def main():
     ap.add_argument("--staged", type=int, default=0)
     ap.add_argument("--schedule", default="auto", choices=["auto", "1f1b", "1f1b-interleaved", "gis", "po"],
                     help="auto: 1F1B, or interleaved 1F1B for a workload with several chunks; gis: generalized "
-                         "interleaved schedule with split backward (Sections 3.2, 3.3); po: the uniformly repeated "
+                         "interleaved schedule with split backward (Sections 3.1, 3.2); po: the uniformly repeated "
                          "schedule (Section 2, Table 1), which selects whole chunks by lifespan")
     ap.add_argument("--profile-every", type=int, default=5,
                     help="bracket every k-th GEMM / attention launch of the timed steps with HIP events (1 = all; an "

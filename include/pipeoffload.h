@@ -38,10 +38,10 @@ typedef enum { PO_F32 = 0, PO_BF16 = 1 } po_dtype;
 
 /* Rank-local op order.  1F1B: Table 1 first row / Appendix A.  Interleaved 1F1B:
  * Section 3.1 (warm-up d(v-1) + 2(d-i) - 1 forwards on rank i). */
-/* PO_SCHED_GIS: generalized interleaved schedule with split backward (Sections 3.2, 3.3): every input-gradient
+/* PO_SCHED_GIS: generalized interleaved schedule with split backward (Sections 3.1, 3.2): every input-gradient
  * pass B is directly followed by the unit's weight-gradient pass W, warm-up g(v-1) + d-i-1 forwards, inner loop
  * over g = po_config.group microbatches (g = d: the paper's GIS, g = ceil(d/2): GIS-H). */
-/* PO_SCHED_PO: the uniformly repeated schedule (Section 2; PO in Section 3.3 and Table 1): every microbatch runs
+/* PO_SCHED_PO: the uniformly repeated schedule (Section 2; PO in Section 3.2 and Table 1): every microbatch runs
  * the same building block (the steady state of the generalized interleaved schedule with group size g, default
  * ceil(d/2)), 3v unit passes after the previous one; split backward; any m.  With LONGEST_LIFESPAN selection a
  * ratio of 0.5 is the paper's PO-H and 1 its PO-F. */
@@ -193,7 +193,10 @@ int po_bind_params(po_stage* st, const void* params, float* grads);
 
 /* Forward of unit (mb, chunk) on the compute stream (per layer: LN, QKV, causal
  * attention, out-proj + residual, LN, FC1 + GeLU, FC2 + residual).
- * x_in: DEVICE [s, h] of cfg.dtype, or int32 tokens [s] when vocab > 0 and chunk == 0.
+ * x_in: DEVICE [s, h] of cfg.dtype, or int32 tokens [s] when vocab > 0 and chunk == 0.  A token array is read
+ * again by the unit's backward (the embedding gradient scatters by token): it must stay valid and unchanged until
+ * that backward (po_stage_backward, or po_stage_backward_weight under a split schedule) has run on the device.
+ * Activation inputs are copied into the unit's slab and may be reused as soon as the forward has run.
  * y_out: DEVICE [s, h].  The unit becomes RESIDENT. */
 int po_stage_forward(po_stage* st, int32_t mb, int32_t chunk, const void* x_in, void* y_out);
 
@@ -205,7 +208,7 @@ int po_stage_backward(po_stage* st, int32_t mb, int32_t chunk, const void* dy, v
 /* New dropout key for the following forward passes; PO_E_STATE while a unit is in flight. */
 int po_set_dropout_seed(po_stage* st, uint64_t seed);
 
-/* Split backward (Section 3.2, zero-bubble strategy).  po_stage_backward_input is the B pass: it computes the
+/* Split backward (Section 3.1, zero-bubble strategy).  po_stage_backward_input is the B pass: it computes the
  * activation gradients only (dx as in po_stage_backward) and keeps, in a library-owned buffer, what the W pass
  * needs; the unit keeps its activations.  po_stage_backward_weight is the W pass: it adds the unit's parameter
  * gradients (the same values, bit for bit, as the fused po_stage_backward) and frees the unit.  dy must stay
@@ -275,7 +278,7 @@ int po_op_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32
  * [K[i], N[i]] (row stride ldb[i]); acc_f32[i] DEVICE fp32 with row stride ldc[i].  The arrays themselves are HOST
  * arrays of length n.  Every M[i], N[i] must be a multiple of 256 and every K[i] of 64, else PO_E_INVAL (use
  * po_op_gemm per product then).  Each product equals po_op_gemm(trans_a = 1, trans_b = 0, acc_f32) bit for bit;
- * the stage runs the four parameter-gradient products of a layer this way (Section 3.2's W pass). */
+ * the stage runs the four parameter-gradient products of a layer this way (Section 3.1's W pass). */
 int po_op_gemm_grouped(int32_t n, const int32_t* M, const int32_t* N, const int32_t* K, const void* const* A,
                        const int32_t* lda, const void* const* B, const int32_t* ldb, float* const* acc_f32,
                        const int32_t* ldc, void* stream);

@@ -15,7 +15,7 @@ independent model, in plain Python integers, of what one pipeline rank executes:
   slot after the forward, latest slot before the backward; on a single rank
   with a dedicated copy queue these collapse to these two rules).
 
-* Generalized interleaved schedule (Section 3.2 "free lunch" and Section 3.3):
+* Generalized interleaved schedule (Section 3.1 "free lunch" and Section 3.2):
   the backward is split into an input-gradient pass B and a weight-gradient
   pass W that directly follows it; the inner loop repeats g microbatches
   (ceil(d/2) <= g <= d) instead of d; rank i forwards g(v-1) + d - i units
@@ -24,7 +24,7 @@ independent model, in plain Python integers, of what one pipeline rank executes:
   general the rank-0 peak is g(v-1) + d.
 * pipeline_timeline runs the op lists of all d ranks against each other with
   given pass durations, which yields the bubble sizes of Table 1.
-* Uniform repeating (Section 2; the schedule Section 3.3 calls PO): one
+* Uniform repeating (Section 2; the schedule Section 3.2 calls PO): one
   microbatch's passes form a building block, here the steady state of the
   generalized interleaved schedule (a chunk every g slots going forward and
   coming back, d slots for the round trip through the last chunk, a slot being
@@ -95,7 +95,7 @@ def _grouped_unit(k, g, v, backward):
 
 def generalized_interleaved(d, rank, v, m, g=None):
     """Compute passes of the generalized interleaved schedule with split backward
-    on ``rank`` (Sections 3.2 and 3.3): the k-th forward handles microbatch group
+    on ``rank`` (Sections 3.1 and 3.2): the k-th forward handles microbatch group
     k // (g v), chunk (k // g) % v; the backward passes walk the chunks in reverse
     and each input-gradient pass B is directly followed by its weight-gradient
     pass W.  g defaults to d (GIS)."""
@@ -165,13 +165,13 @@ def pipeline_timeline(rank_ops, d, v, t_f, t_b, t_w):
 def building_block_template(d, v, g):
     """Unit-time (F = B = W = 1) start times of one microbatch's passes in the
     steady state of the generalized interleaved schedule with group size g
-    (Section 3.3): the forward moves one unit per rank and 3g units (g slots) per
+    (Section 3.2): the forward moves one unit per rank and 3g units (g slots) per
     chunk; the backward of the last chunk starts when its forward has left rank
     d-1, moves two units per rank (a rank in a one-forward-one-backward rhythm
     starts B one slot minus one forward after its successor) and 3g units per
     chunk; W directly follows B.  On rank 0 chunk c then lives for
     6g(v-1-c) + 3d units, and the lifespans of a rank's chunks divided by the
-    period 3v add up to the g(v-1) + d units of Section 3.3.
+    period 3v add up to the g(v-1) + d units of Section 3.2.
     Keys are (kind, rank, chunk)."""
     t = {}
     turn = 3 * g * (v - 1) + d
@@ -220,7 +220,7 @@ def building_block(d, v, g):
 def uniform_repeat(d, rank, v, m, g=None):
     """Compute passes of the uniformly repeated schedule on ``rank``: microbatch n
     runs the building block 3v n units later; the rank's order is by start time.
-    g defaults to ceil(d/2), the block of GIS-H that Section 3.3 repeats."""
+    g defaults to ceil(d/2), the block of GIS-H that Section 3.2 repeats."""
     g = math.ceil(d / 2) if g is None else g
     if not (math.ceil(d / 2) <= g <= d):
         raise ValueError("the group size must lie in [ceil(d/2), d]")

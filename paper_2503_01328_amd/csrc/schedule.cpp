@@ -8,12 +8,12 @@
 // group; backwards visit the chunks in reverse.  Warm-up is d(v-1) + 2(d-i-1)
 // forwards, which gives the paper's d(v-1) + 2(d-i) - 1 forwards before the
 // first backward and dv + d - 1 units in flight on rank 0.
-// Generalized interleaved schedule with split backward (Sections 3.2 and 3.3): the
+// Generalized interleaved schedule with split backward (Sections 3.1 and 3.2): the
 // inner loop repeats g microbatches (ceil(d/2) <= g <= d), rank i runs
 // g(v-1) + d-i-1 warm-up forwards, and every input-gradient pass B is directly
 // followed by the unit's weight-gradient pass W.  g = d is the paper's GIS (dv units
 // in flight on rank 0), g = ceil(d/2) its GIS-H; in general the peak is g(v-1) + d.
-// Uniformly repeated schedule (Section 2; the PO rows of Table 1, Section 3.3): every microbatch runs the same
+// Uniformly repeated schedule (Section 2; the PO rows of Table 1, Section 3.2): every microbatch runs the same
 // building block, shifted by the 3v unit-time passes a rank spends per microbatch.  The block is the steady state
 // of the generalized interleaved schedule: forward one unit per rank and g slots (3g units) per chunk, backward two
 // units per rank and g slots per chunk, W right after B.  A pass that would overlap the pass it depends on, or a

@@ -75,3 +75,30 @@ def test_philox_known_answers():
     for row in _rows("philox4x32_10_kat.txt"):
         w = [int(x, 16) for x in row]
         assert tuple(int(x) for x in so.philox4x32_10(tuple(w[0:4]), tuple(w[4:6]))) == tuple(w[6:10])
+
+
+def test_dropout_threshold_and_keep_direction():
+    """Hand values of the keep threshold (rounding mode and clamp included) and hand-derived masks on the words of
+    the generator's first known-answer vector: a flipped comparison, a wrong rounding or a shifted counter word
+    fails one of them."""
+    for row in _rows("dropout_threshold.txt"):
+        if row[0] == "threshold":
+            num, k, want = int(row[1]), int(row[2]), int(row[3])
+            assert so.dropout_threshold(num / 2.0 ** k) == want, row
+        elif row[0] == "decimal":
+            assert so.dropout_threshold(float(row[1])) == int(row[2]), row
+        elif row[0] == "mask":
+            got = so.dropout_keep_mask(0, 0, 0, 0, 1, 4, float(row[1]))[0]
+            assert [int(x) for x in got] == [int(x) for x in row[2:6]], row
+        else:
+            raise AssertionError(row)
+
+
+def test_uniform_repeat_block_worked_by_hand():
+    """d = 2, v = 2, g = 2: the start time of every pass of the building block as derived by hand in the fixture."""
+    block = sch.building_block(2, 2, 2)
+    rows = _rows("po_block_d2_v2_g2.txt")
+    assert len(rows) == len(block) == 12
+    for kind, rank, chunk, start in rows:
+        assert block[(kind, int(rank), int(chunk))] == int(start), (kind, rank, chunk)
+

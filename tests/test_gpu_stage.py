@@ -275,7 +275,7 @@ def test_peak_slab_bytes_follow_the_schedule_model(gpu_device):
     assert peaks[1.0] < peaks[0.5] < peaks[0.0]
 
 
-# ---- split backward (B / W passes) and the generalized interleaved schedule (Sections 3.2, 3.3) ----------------
+# ---- split backward (B / W passes) and the generalized interleaved schedule (Sections 3.1, 3.2) ----------------
 @pytest.mark.parametrize("shape", [syn.StageShape(2, 1, 128, 2, 512, 96, vocab=50, dtype="f32", pipeline_degree=2,
                                                   n_microbatches=3),
                                    syn.StageShape(3, 1, 256, 2, 1024, 256, dtype="bf16", pipeline_degree=2,
