@@ -7,6 +7,12 @@
 // memory round trip.  The 256 x 192 tile exists for outputs whose 256 x 256 tiles would leave a
 // quarter of the chip idle (192 of them where 256 of the narrower ones fit).
 //
+// A wave is alone on its SIMD, so its one instruction stream has to keep the matrix core fed: the
+// HBM -> LDS loads of a later slice, the LDS reads of the fragments three k-steps ahead and the
+// MFMAs of the current k-step are woven together by hand, one load (three instructions: M0, a
+// wait state, the load with a scalar base and a 32-bit lane offset) and one fragment read per two
+// MFMAs, with a single barrier per slice placed where no MFMA waits for what follows it.
+//
 // Operand slices travel HBM -> LDS directly (global_load_lds_dwordx4: lane L of
 // a wave deposits its 16 bytes at LDS base + 16 L), so no registers and no
 // ds_write instructions are spent on staging.  Because the LDS side of such a
@@ -53,12 +59,6 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 #define PO_LDS_S16X4(p) ((s16x4 __attribute__((address_space(3)))*)(p))
 
 constexpr int kBK = 64;
-#ifndef PO_GEMM_LOAD_STEPS
-#define PO_GEMM_LOAD_STEPS 2
-#endif
-#ifndef PO_GEMM_LOAD_STEPS_SMALL
-#define PO_GEMM_LOAD_STEPS_SMALL 3
-#endif
 
 enum EpiKind : int { kEpiStore = 0, kEpiStoreGelu = 1, kEpiGeluBackward = 2, kEpiAccumulate = 3 };
 
@@ -345,7 +345,7 @@ __device__ __forceinline__ void gemm_tile(int K, const bf16* __restrict__ A, int
   // anything issued in a clump (sixteen loads with their scalar set-up back to back) is time the matrix core
   // stands still.
   constexpr int NMFMA = WTM * WTN;
-  constexpr int kLoadSteps = NSTAGE == 4 ? PO_GEMM_LOAD_STEPS_SMALL : PO_GEMM_LOAD_STEPS;  // 1 .. 3
+  constexpr int kLoadSteps = NSTAGE == 4 ? 3 : 2;  // measured: the small tile's eight loads spread thinner
   constexpr int LOADS_PER_STEP = (PER_SLICE + kLoadSteps - 1) / kLoadSteps;
   auto slice = [&](int kt, auto issue_tag, auto more_tag) {
     constexpr bool ISSUE = decltype(issue_tag)::value;
