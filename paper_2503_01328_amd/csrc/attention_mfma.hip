@@ -92,7 +92,15 @@ __device__ __forceinline__ void load_tile_async(const bf16* __restrict__ base, i
                  : "memory");
   }
 }
-__device__ __forceinline__ void wait_tile_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// Through the builtin, not inline assembly: the compiler keeps its own count of outstanding loads and cannot see
+// into assembly text.  Left believing that a kernel's early register loads (Q, K or V fragments) might still be
+// in flight, it guards their every use inside the tile loop with s_waitcnt vmcnt(n), and since the counter is
+// shared those waits really wait for the tile loads issued a moment before: the prefetch would be waited for
+// at once.  A wait it can see resets its count.
+__device__ __forceinline__ void wait_tile_loads() {
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0), the other counters left alone (expcnt 7, lgkmcnt 15)
+  asm volatile("" ::: "memory");
+}
 
 // Fragment whose contraction index is the tile's row: lane (column c = lane % 32 of the
 // 32-wide block starting at col0, half = lane / 32) receives rows
@@ -138,6 +146,108 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // ==================================================================================
 // Forward
 // ==================================================================================
+// One 64-key tile against the 32 query rows of a wave: S^T = K Q^T, online softmax, O^T += V^T P^T.
+// The LDS reads run ahead of the MFMAs that use them through small rings of fragment registers (K fragments two
+// 16-deep steps ahead, V fragments one 32-wide output block ahead, the first V fragments requested before the
+// softmax arithmetic starts), and scheduling barriers keep that order: the compiler on its own reads a fragment,
+// waits for it and multiplies, one after the other, and the matrix core idles through every LDS round trip.
+// m_run == -inf is allowed on entry; kGuardEmpty: a tile may be masked entirely for a row (the split kernel's
+// second group at the diagonal), in which case the running maximum stays -inf and the state stays finite.
+template <int DH, bool kGuardEmpty>
+__device__ __forceinline__ void attn_fwd_tile(const char* ktile, const char* vtile, const bf16x8 (&qf)[DH / 16],
+                                              f32x16 (&oacc)[DH / 32], float& m_run, float& l_run, int key0,
+                                              int q, bool need_mask, int lane, float c) {
+  constexpr int KS = DH / 16, DT = DH / 32;
+  const int half = lane >> 5, col = lane & 31;
+  f32x16 sacc[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) sacc[j][e] = 0.f;
+  bf16x8 kring[3][2];
+  auto read_k = [&](int kk) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) kring[kk % 3][j] = read_row_fragment<DH>(ktile, 32 * j + col, 2 * kk + half);
+  };
+  read_k(0);
+  if (KS > 1) read_k(1);
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk) {
+    if (kk + 2 < KS) read_k(kk + 2);
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kring[kk % 3][j], qf[kk], sacc[j], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  __builtin_amdgcn_s_setprio(0);
+  // V fragments of output block d: [key sub-tile j][16-key step st]
+  bf16x8 vring[2][2][2];
+  auto read_v = [&](int d) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int st = 0; st < 2; ++st) vring[d & 1][j][st] = read_tr_fragment<DH>(vtile, 32 * j + 16 * st, 32 * d, lane);
+  };
+  read_v(0);  // lands while the softmax arithmetic runs
+  __builtin_amdgcn_sched_barrier(0);
+  if (need_mask) {  // only tiles that straddle the diagonal pay for the mask
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e)
+        if (key0 + 32 * j + 8 * (e >> 2) + 4 * half + (e & 3) > q) sacc[j][e] = -INFINITY;
+  }
+  float mx = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[j][e]);
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  float m_new = fmaxf(m_run, mx);
+  float m_use = (kGuardEmpty && m_new == -INFINITY) ? 0.f : m_new;
+  float alpha = fast_exp2((m_run - m_use) * c);
+  float mc = m_use * c;
+  float sum = 0.f;
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      float p = fast_exp2(sacc[j][e] * c - mc);
+      sacc[j][e] = p;
+      sum += p;
+    }
+  l_run = l_run * alpha + sum;
+  bool moved = __builtin_amdgcn_ballot_w64(m_new > m_run) != 0;
+  m_run = m_new;
+  if (moved) {  // rescale only when some row's maximum moved
+#pragma unroll
+    for (int d = 0; d < DT; ++d)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) oacc[d][e] *= alpha;
+  }
+  bf16x8 pf[2][2];  // [key sub-tile][16-key step]
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    pf[j][0] = pack_bf16x8(sacc[j], 0);
+    pf[j][1] = pack_bf16x8(sacc[j], 8);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+  for (int d = 0; d < DT; ++d) {
+    if (d + 1 < DT) read_v(d + 1);
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int st = 0; st < 2; ++st)
+        oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vring[d & 1][j][st], pf[j][st], oacc[d], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  __builtin_amdgcn_s_setprio(0);
+}
+
 template <int DH, int QT>
 __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ o,
                                                             float* __restrict__ lse, int s, int h, int hkv, int group,
@@ -201,86 +311,10 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_fwd_mfma_kernel(con
     }
     int key0 = kt * kKeysPerTile;
     if (key0 <= qw0 + 32 * QT - 1) {  // some key of the tile is visible to some row of this wave
-      // S^T = K Q^T : rows = keys, columns = query rows
-      f32x16 sacc[QT][2];
 #pragma unroll
       for (int t = 0; t < QT; ++t)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) sacc[t][j][e] = 0.f;
-      __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-      for (int kk = 0; kk < KS; ++kk) {
-        bf16x8 kf[2];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) kf[j] = read_row_fragment<DH>(ktile, 32 * j + col, 2 * kk + half);
-#pragma unroll
-        for (int t = 0; t < QT; ++t)
-#pragma unroll
-          for (int j = 0; j < 2; ++j)
-            sacc[t][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j], qf[t][kk], sacc[t][j], 0, 0, 0);
-      }
-      __builtin_amdgcn_s_setprio(0);
-      bf16x8 pf[QT][2][2];  // [q tile][key sub-tile][16-key step]
-#pragma unroll
-      for (int t = 0; t < QT; ++t) {
-        int q = qw0 + 32 * t + col;
-        bool need_mask = key0 + kKeysPerTile - 1 > qw0 + 32 * t;
-        if (need_mask) {  // only tiles that straddle the diagonal pay for the mask
-#pragma unroll
-          for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e)
-              if (key0 + 32 * j + 8 * (e >> 2) + 4 * half + (e & 3) > q) sacc[t][j][e] = -INFINITY;
-        }
-        float mx = -INFINITY;
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[t][j][e]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        float m_new = fmaxf(m_run[t], mx);
-        float alpha = fast_exp2((m_run[t] - m_new) * c);
-        float mc = m_new * c;
-        float sum = 0.f;
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            float p = fast_exp2(sacc[t][j][e] * c - mc);
-            sacc[t][j][e] = p;
-            sum += p;
-          }
-        l_run[t] = l_run[t] * alpha + sum;
-        bool moved = __builtin_amdgcn_ballot_w64(m_new > m_run[t]) != 0;
-        m_run[t] = m_new;
-        if (moved) {  // rescale only when some row's maximum moved
-#pragma unroll
-          for (int d = 0; d < DT; ++d)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) oacc[t][d][e] *= alpha;
-        }
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          pf[t][j][0] = pack_bf16x8(sacc[t][j], 0);
-          pf[t][j][1] = pack_bf16x8(sacc[t][j], 8);
-        }
-      }
-      // O^T += V^T P^T : rows = head dimension, columns = query rows, contraction over keys
-      __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-      for (int d = 0; d < DT; ++d)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-          for (int st = 0; st < 2; ++st) {
-            bf16x8 vf = read_tr_fragment<DH>(vtile, 32 * j + 16 * st, 32 * d, lane);
-#pragma unroll
-            for (int t = 0; t < QT; ++t)
-              oacc[t][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[t][j][st], oacc[t][d], 0, 0, 0);
-          }
-      __builtin_amdgcn_s_setprio(0);
+        attn_fwd_tile<DH, false>(ktile, vtile, qf[t], oacc[t], m_run[t], l_run[t], key0, qw0 + 32 * t + col,
+                                 key0 + kKeysPerTile - 1 > qw0 + 32 * t, lane, c);
     }
     wait_tile_loads();
     __syncthreads();
@@ -368,77 +402,9 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_split_mfma_kernel(const bf16*
       load_tile_async<DH>(vbase, ld, (kt + 2) * kKeysPerTile, nxt + KBYTES, wave, lane_off);
     }
     int key0 = kt * kKeysPerTile;
-    if (key0 <= qw0 + 31) {
-      f32x16 sacc[2];
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) sacc[j][e] = 0.f;
-      __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-      for (int kk = 0; kk < KS; ++kk) {
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          bf16x8 kf = read_row_fragment<DH>(ktile, 32 * j + col, 2 * kk + half);
-          sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[j], 0, 0, 0);
-        }
-      }
-      __builtin_amdgcn_s_setprio(0);
-      int q = qw0 + col;
-      if (key0 + kKeysPerTile - 1 > qw0) {
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-          for (int e = 0; e < 16; ++e)
-            if (key0 + 32 * j + 8 * (e >> 2) + 4 * half + (e & 3) > q) sacc[j][e] = -INFINITY;
-      }
-      float mx = -INFINITY;
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[j][e]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      float m_new = fmaxf(m_run, mx);
-      // a tile can be all masked for a row (the odd tile of the diagonal pair): keep the state finite
-      float m_use = m_new == -INFINITY ? 0.f : m_new;
-      float alpha = fast_exp2((m_run - m_use) * c);
-      float mc = m_use * c;
-      float sum = 0.f;
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          float p = fast_exp2(sacc[j][e] * c - mc);
-          sacc[j][e] = p;
-          sum += p;
-        }
-      l_run = l_run * alpha + sum;
-      bool moved = __builtin_amdgcn_ballot_w64(m_new > m_run) != 0;
-      m_run = m_new;
-      if (moved) {
-#pragma unroll
-        for (int d = 0; d < DT; ++d)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) oacc[d][e] *= alpha;
-      }
-      bf16x8 pf[2][2];
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        pf[j][0] = pack_bf16x8(sacc[j], 0);
-        pf[j][1] = pack_bf16x8(sacc[j], 8);
-      }
-      __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-      for (int d = 0; d < DT; ++d)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-          for (int st = 0; st < 2; ++st) {
-            bf16x8 vf = read_tr_fragment<DH>(vtile, 32 * j + 16 * st, 32 * d, lane);
-            oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[j][st], oacc[d], 0, 0, 0);
-          }
-      __builtin_amdgcn_s_setprio(0);
-    }
+    if (key0 <= qw0 + 31)
+      attn_fwd_tile<DH, true>(ktile, vtile, qf, oacc, m_run, l_run, key0, qw0 + col, key0 + kKeysPerTile - 1 > qw0,
+                              lane, c);
     wait_tile_loads();
     __syncthreads();
   }
