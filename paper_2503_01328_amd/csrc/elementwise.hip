@@ -593,6 +593,72 @@ __global__ __launch_bounds__(256) void reduce_batch_partial_kernel(ReduceBatch b
   }
 }
 
+// The same partials with 16-byte loads: a block still owns 128 columns of one chunk of rows, but a lane reads
+// 16 bytes (8 bf16 or 4 fp32 columns) of a row, so a wave covers 64 / LPR rows of the block's 256 or 512 bytes
+// per load instead of one row, 4 bytes a lane.  Per column the rows are summed in a fixed order (by lane, then
+// across the block's row slots in order): deterministic, though not the order of the kernel above.  Needs
+// n % V == 0 and 16-byte aligned rows.
+template <typename T>
+__global__ __launch_bounds__(256) void reduce_batch_partial_vec_kernel(ReduceBatch b, int rows, int rows_per_chunk) {
+  constexpr int V = Vec16<T>::N;   // columns per lane
+  constexpr int LPR = 128 / V;     // lanes per row of the block's 128 columns
+  constexpr int RPW = kWave / LPR;  // rows a wave reads at once
+  constexpr int SLOTS = 4 * RPW;   // row slots of the block
+  __shared__ float red[SLOTS][2][128];
+  int j = 0;
+  while (j + 1 < b.n_jobs && (int)blockIdx.x >= b.first128[j + 1]) ++j;
+  const ReduceJob& job = b.job[j];
+  const int n = job.n;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int col0 = ((int)blockIdx.x - b.first128[j]) * 128;
+  const int cl = (lane % LPR) * V;  // first column of this lane within the block
+  const int slot = wave * RPW + lane / LPR;
+  const int r0 = blockIdx.y * rows_per_chunk;
+  const int r1 = min(rows, r0 + rows_per_chunk);
+  const T* a = static_cast<const T*>(job.a);
+  const T* x = static_cast<const T*>(job.x);
+  const bool ln = x != nullptr;
+  float s0[V], s1[V];
+#pragma unroll
+  for (int i = 0; i < V; ++i) s0[i] = s1[i] = 0.f;
+  if (col0 + cl < n) {
+    if (!ln) {
+      for (int r = r0 + slot; r < r1; r += SLOTS) {
+        Vec16<T> v = load16(a + (size_t)r * n + col0 + cl);
+#pragma unroll
+        for (int i = 0; i < V; ++i) s0[i] += to_f32(v.v[i]);
+      }
+    } else {
+      const float* stats = job.stats;
+      for (int r = r0 + slot; r < r1; r += SLOTS) {
+        float mean = stats[2 * r], rstd = stats[2 * r + 1];
+        Vec16<T> d = load16(a + (size_t)r * n + col0 + cl);
+        Vec16<T> xv = load16(x + (size_t)r * n + col0 + cl);
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+          float dv = to_f32(d.v[i]);
+          s0[i] += dv * (to_f32(xv.v[i]) - mean) * rstd;
+          s1[i] += dv;
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < V; ++i) {
+    red[slot][0][cl + i] = s0[i];
+    red[slot][1][cl + i] = s1[i];
+  }
+  __syncthreads();
+  const int c = threadIdx.x & 127, plane = threadIdx.x >> 7;
+  if (col0 + c < n && (plane == 0 || ln)) {
+    float sum = 0.f;
+#pragma unroll
+    for (int k = 0; k < SLOTS; ++k) sum += red[k][plane][c];
+    const int n_out = ln ? 2 : 1;
+    job.partials[((size_t)blockIdx.y * n_out + plane) * n + col0 + c] = sum;
+  }
+}
+
 // The fixed tree of chunk_partials_final_kernel, per job with one or two output planes.
 __global__ __launch_bounds__(256) void reduce_batch_final_kernel(ReduceBatch b, int n_chunks) {
   __shared__ float red[2][4][64];
@@ -658,7 +724,15 @@ bool column_reductions(int dtype, const ReduceJob* jobs, int n_jobs, int rows, h
   int n_chunks = reduce_chunks(rows);
   int rows_per_chunk = ceil_div(rows, n_chunks);
   dim3 g(b.first128[n_jobs], n_chunks);
-  if (dtype == kF32)
+  const int v = dtype == kF32 ? 4 : 8;
+  bool vec = true;  // 16-byte loads need whole vectors per row and aligned rows
+  for (int j = 0; j < n_jobs; ++j)
+    vec = vec && jobs[j].n % v == 0 && (uintptr_t)jobs[j].a % 16 == 0 && (uintptr_t)jobs[j].x % 16 == 0;
+  if (vec && dtype == kF32)
+    reduce_batch_partial_vec_kernel<float><<<g, 256, 0, stream>>>(b, rows, rows_per_chunk);
+  else if (vec)
+    reduce_batch_partial_vec_kernel<bf16><<<g, 256, 0, stream>>>(b, rows, rows_per_chunk);
+  else if (dtype == kF32)
     reduce_batch_partial_kernel<float><<<g, 256, 0, stream>>>(b, rows, rows_per_chunk);
   else
     reduce_batch_partial_kernel<bf16><<<g, 256, 0, stream>>>(b, rows, rows_per_chunk);
