@@ -15,9 +15,10 @@
 //     the contraction index as the slow dimension) is fetched with the gfx950
 //     transposing LDS read (ds_read_b64_tr_b16), two per fragment.
 //
-// Forward: block = 4 waves, a wave owns QT x 32 query rows; K/V tiles of 64 keys
-// are staged through LDS (loaded HBM -> LDS directly, double-buffered).  Blocks with the
-// most key tiles are launched first, over all heads (causal work is triangular).
+// Forward: block = 4 waves (8 where the launch still fills the chip with 256-row blocks), a
+// wave owns QT x 32 query rows; K/V tiles of 64 keys are staged through LDS (loaded
+// HBM -> LDS directly, double-buffered).  Blocks with the most key tiles are launched first,
+// over all heads (causal work is triangular).
 //
 // Backward, deterministic without atomics: one kernel per key block accumulates
 // dK and dV over the query tiles at or below the diagonal; one kernel per query
@@ -60,8 +61,8 @@ __device__ __forceinline__ int tile_offset(int row, int chunk) {
 template <int DH> constexpr int tile_bytes() { return kKeysPerTile * DH * 2; }
 
 // HBM -> LDS without a register stop: a wave-level global_load_lds_dwordx4 writes 1 KiB of the tile
-// (lane L fills bytes 16 L ..), so each lane fetches the chunk that belongs at its position.  256
-// threads issue tile_bytes / 4096 loads each; between two loads of a wave the source advances by a
+// (lane L fills bytes 16 L ..), so each lane fetches the chunk that belongs at its position.  The block's
+// WAVES waves issue tile_bytes / (1024 WAVES) loads each; between two loads of a wave the source advances by a
 // whole number of rows that is a multiple of 16, which leaves swz unchanged: the per-lane part of the
 // address is one 32-bit byte offset (tile_lane_offset, computed once per kernel) and everything else
 // is wave-uniform scalar arithmetic.  `base` points at (row 0, first element of the head), rows are
@@ -77,16 +78,17 @@ __device__ __forceinline__ unsigned tile_lane_offset(int ld, int wave, int lane)
   int c = ((byte % ROW_BYTES) >> 4) ^ swz<DH>(row);
   return (unsigned)((row * ld + c * 8) * 2);
 }
-template <int DH>
+template <int DH, int WAVES = 4>
 __device__ __forceinline__ void load_tile_async(const bf16* __restrict__ base, int ld, int row0, char* tile,
                                                 int wave, unsigned lane_offset) {
-  constexpr int PER_WAVE = tile_bytes<DH>() / 4096;
-  constexpr int ROWS_PER_LOAD = 4096 / (DH * 2);  // rows the four waves cover with one load each
+  constexpr int PER_WAVE = tile_bytes<DH>() / (1024 * WAVES);
+  constexpr int ROWS_PER_LOAD = 1024 * WAVES / (DH * 2);  // rows the WAVES waves cover with one load each
   static_assert(ROWS_PER_LOAD % 16 == 0, "swz must not change between the loads of a lane");
 #pragma unroll
   for (int u = 0; u < PER_WAVE; ++u) {
     const bf16* src = base + (size_t)(row0 + u * ROWS_PER_LOAD) * ld;
-    unsigned lds_addr = (unsigned)(size_t)((void __attribute__((address_space(3)))*)(tile + (u * 4 + wave) * 1024));
+    unsigned lds_addr =
+        (unsigned)(size_t)((void __attribute__((address_space(3)))*)(tile + (u * WAVES + wave) * 1024));
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr),
                  "v"(lane_offset), "s"(src)
                  : "memory");
@@ -252,13 +254,13 @@ __device__ __forceinline__ void attn_fwd_tile(const char* ktile, const char* vti
   __builtin_amdgcn_s_setprio(0);
 }
 
-template <int DH, int QT>
-__global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ o,
-                                                            float* __restrict__ lse, int s, int h, int hkv, int group,
-                                                            float scale) {
-  constexpr int KS = DH / 16;   // 16-deep MFMA steps over the head dimension
-  constexpr int DT = DH / 32;   // 32-wide output tiles over the head dimension
-  constexpr int BQ = 128 * QT;  // query rows per block
+template <int DH, int QT, int WAVES = 4>
+__global__ __launch_bounds__(64 * WAVES, (QT == 1 && WAVES == 4) ? 2 : 1) void attn_fwd_mfma_kernel(
+    const bf16* __restrict__ qkv, bf16* __restrict__ o, float* __restrict__ lse, int s, int h, int hkv, int group,
+    float scale) {
+  constexpr int KS = DH / 16;          // 16-deep MFMA steps over the head dimension
+  constexpr int DT = DH / 32;          // 32-wide output tiles over the head dimension
+  constexpr int BQ = 32 * WAVES * QT;  // query rows per block
   constexpr int KBYTES = tile_bytes<DH>();
   constexpr int STAGE = 2 * KBYTES;  // K tile, V tile
   extern __shared__ __align__(16) char smem[];
@@ -299,8 +301,8 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_fwd_mfma_kernel(con
 
   int nkv = (q0 + BQ) / kKeysPerTile;
   const unsigned lane_off = tile_lane_offset<DH>(ld, wave, lane);
-  load_tile_async<DH>(kbase, ld, 0, smem, wave, lane_off);
-  load_tile_async<DH>(vbase, ld, 0, smem + KBYTES, wave, lane_off);
+  load_tile_async<DH, WAVES>(kbase, ld, 0, smem, wave, lane_off);
+  load_tile_async<DH, WAVES>(vbase, ld, 0, smem + KBYTES, wave, lane_off);
   wait_tile_loads();
   __syncthreads();
 
@@ -310,8 +312,8 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_fwd_mfma_kernel(con
     char* nxt = smem + ((kt + 1) & 1) * STAGE;
     bool more = kt + 1 < nkv;
     if (more) {  // the other stage was last read before the barrier that ended the previous iteration
-      load_tile_async<DH>(kbase, ld, (kt + 1) * kKeysPerTile, nxt, wave, lane_off);
-      load_tile_async<DH>(vbase, ld, (kt + 1) * kKeysPerTile, nxt + KBYTES, wave, lane_off);
+      load_tile_async<DH, WAVES>(kbase, ld, (kt + 1) * kKeysPerTile, nxt, wave, lane_off);
+      load_tile_async<DH, WAVES>(vbase, ld, (kt + 1) * kKeysPerTile, nxt + KBYTES, wave, lane_off);
     }
     int key0 = kt * kKeysPerTile;
     if (key0 <= qw0 + 32 * QT - 1) {  // some key of the tile is visible to some row of this wave
@@ -1188,6 +1190,21 @@ static bool launch_fwd(const bf16* qkv, bf16* o, float* lse, int s, int h, int n
     ksplit<<<grid, 512, smem_split, stream>>>(qkv, o, lse, s, h, n_kv_heads * DH, n_heads / n_kv_heads,
                                              1.0f / sqrtf((float)DH));
     return launch_ok("attn_fwd_split_mfma_kernel");
+  }
+  // Launches that still give every CU a block of 256 rows: eight waves share each K / V tile, which halves the
+  // tile bytes written into LDS per MFMA (the kernel is bound by LDS traffic: one fragment read per MFMA plus the
+  // arriving tiles); +5 % at s = 4096 with 32 heads, +2 % at s = 16384 with 40.
+  if (QT == 1 && s % 256 == 0 && (int64_t)n_heads * (s / 256) >= 256) {
+    auto k8 = attn_fwd_mfma_kernel<DH, 1, 8>;
+    static bool k8_configured = false;
+    if (!k8_configured) {
+      PO_HIP_OK(hipFuncSetAttribute(reinterpret_cast<const void*>(k8), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    smem));
+      k8_configured = true;
+    }
+    k8<<<dim3(n_heads, s / 256), 512, smem, stream>>>(qkv, o, lse, s, h, n_kv_heads * DH, n_heads / n_kv_heads,
+                                                     1.0f / sqrtf((float)DH));
+    return launch_ok("attn_fwd_mfma_kernel (eight waves)");
   }
   kern<<<grid, 256, smem, stream>>>(qkv, o, lse, s, h, n_kv_heads * DH, n_heads / n_kv_heads,
                                     1.0f / sqrtf((float)DH));
