@@ -15,16 +15,17 @@
 //     the contraction index as the slow dimension) is fetched with the gfx950
 //     transposing LDS read (ds_read_b64_tr_b16), two per fragment.
 //
-// Forward: block = 4 waves (8 where the launch still fills the chip with 256-row blocks), a
-// wave owns QT x 32 query rows; K/V tiles of 64 keys are staged through LDS (loaded
-// HBM -> LDS directly, double-buffered).  Blocks with the most key tiles are launched first,
-// over all heads (causal work is triangular).
+// Forward: a block is eight compute waves, each owning 32 query rows, plus one wave that only loads; K/V
+// tiles of 64 keys are staged through LDS (loaded HBM -> LDS directly, rings of two or three stages).
+// Blocks with the most key tiles are launched first, over all heads (causal work is triangular).
 //
 // Backward, deterministic without atomics: one kernel per key block accumulates
 // dK and dV over the query tiles at or below the diagonal; one kernel per query
 // block accumulates dQ over the key tiles up to the diagonal.  Both recompute
 // S = Q K^T and dP = dO V^T.
 #include <math.h>
+
+#include <type_traits>
 
 #include "kernels.h"
 
@@ -150,62 +151,89 @@ __device__ __forceinline__ bf16x8 pack_bf16x8(const f32x16& a, int first) {
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // ==================================================================================
-// Forward
+// Forward: S^T = K Q^T, online softmax, O^T += V^T P^T per 64-key tile, a wave owning 32 query rows.
+//
+// Separate roles.  Eight compute waves never touch global memory inside the loop; a ninth wave does nothing but
+// issue the K / V tile loads (HBM -> LDS direct) and wait for them.  A wave that issues such a load stalls until
+// the memory pipeline has accepted it (about 25 cycles per KiB of tile and CU), and when every compute wave
+// issues its share those stalls sit in front of MFMAs (measured: a tile pair of two waves took 4400 cycles, 2600
+// with the loads taken out of the kernel); a loader wave stalls in nobody's way, and the compute waves' LDS reads
+// and MFMAs run at the same speed beside it (probed: four MFMA waves fed by one fragment read per MFMA keep 82 %
+// of the matrix peak with or without four loader waves streaming 120 GB/s into the same LDS).  To fit nine waves
+// (three on one SIMD) a wave may use 168 registers, so only the first Q fragments stay in registers and the others
+// are read from a Q tile in LDS again for every key tile.
+// Opposite phases.  The compute waves work in two groups of four; block-wide barriers cut time into slots, and in
+// every slot one group multiplies (P V of its tile j - 1, then the scores of its tile j: a matrix slot) while the
+// other group, whose waves share the SIMDs of the first (waves w and w + 4), does the softmax of its tile.  Left
+// alone, two waves of a SIMD are as often both in their softmax as one in each kind of work.
 // ==================================================================================
-// One 64-key tile against the 32 query rows of a wave: S^T = K Q^T, online softmax, O^T += V^T P^T.
-// The LDS reads run ahead of the MFMAs that use them through small rings of fragment registers (K fragments two
-// 16-deep steps ahead, V fragments one 32-wide output block ahead, the first V fragments requested before the
-// softmax arithmetic starts), and scheduling barriers keep that order: the compiler on its own reads a fragment,
-// waits for it and multiplies, one after the other, and the matrix core idles through every LDS round trip.
-// m_run == -inf is allowed on entry; kGuardEmpty: a tile may be masked entirely for a row (the split kernel's
-// second group at the diagonal), in which case the running maximum stays -inf and the state stays finite.
-template <int DH, bool kGuardEmpty>
-__device__ __forceinline__ void attn_fwd_tile(const char* ktile, const char* vtile, const bf16x8 (&qf)[DH / 16],
-                                              f32x16 (&oacc)[DH / 32], float& m_run, float& l_run, int key0,
-                                              int q, bool need_mask, int lane, float c) {
-  constexpr int KS = DH / 16, DT = DH / 32;
-  const int half = lane >> 5, col = lane & 31;
-  f32x16 sacc[2];
-#pragma unroll
-  for (int j = 0; j < 2; ++j)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) sacc[j][e] = 0.f;
-  bf16x8 kring[3][2];
-  auto read_k = [&](int kk) {
-#pragma unroll
-    for (int j = 0; j < 2; ++j) kring[kk % 3][j] = read_row_fragment<DH>(ktile, 32 * j + col, 2 * kk + half);
-  };
-  read_k(0);
-  if (KS > 1) read_k(1);
-  __builtin_amdgcn_sched_barrier(0);
-  __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-  for (int kk = 0; kk < KS; ++kk) {
-    if (kk + 2 < KS) read_k(kk + 2);
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-      sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kring[kk % 3][j], qf[kk], sacc[j], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
+template <int BEGIN, int END, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (BEGIN < END) {
+    f(std::integral_constant<int, BEGIN>());
+    static_for<BEGIN + 1, END>(f);
   }
-  __builtin_amdgcn_s_setprio(0);
-  // V fragments of output block d: [key sub-tile j][16-key step st]
-  bf16x8 vring[2][2][2];
-  auto read_v = [&](int d) {
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int st = 0; st < 2; ++st) vring[d & 1][j][st] = read_tr_fragment<DH>(vtile, 32 * j + 16 * st, 32 * d, lane);
-  };
-  read_v(0);  // lands while the softmax arithmetic runs
-  __builtin_amdgcn_sched_barrier(0);
-  if (need_mask) {  // only tiles that straddle the diagonal pay for the mask
+}
+
+// Per-lane LDS byte offsets of the fragment reads of a tile, such that every fragment of the tile is one of them
+// XOR a constant (which moves the 16-byte chunk within the row: the swizzle only touches those bits) plus a
+// constant number of rows (a multiple of 16 rows leaves the swizzle unchanged): three registers instead of an
+// address per fragment.
+template <int DH>
+struct FragmentOffsets {
+  unsigned v_lo, v_hi;  // transposing reads: rows 4 half + i / 4 (+ 8), output block 0
+  unsigned k;           // row reads: row = lane % 32, head-dimension step 0
+  __device__ __forceinline__ void init(int lane) {
+    int i = lane & 15, grp = lane >> 4, half = grp >> 1;
+    int r = 4 * half + (i >> 2);
+    int c = 16 * (grp & 1) + 4 * (i & 3);
+    v_lo = (unsigned)(tile_offset<DH>(r, c >> 3) + (c & 7) * 2);
+    v_hi = (unsigned)(tile_offset<DH>(r + 8, c >> 3) + (c & 7) * 2);
+    k = (unsigned)tile_offset<DH>(lane & 31, lane >> 5);
+  }
+};
+__device__ __forceinline__ unsigned lds_address_of(const char* p) {
+  return (unsigned)(size_t)((const __attribute__((address_space(3))) char*)p);
+}
+// V fragment (contraction over keys 16 js .. 16 js + 15, output block d) and row fragment (rows 32 j + lane % 32,
+// head-dimension step kk) from the bases above; `vlo`, `vhi`, `kb` already include the tile's LDS address (tiles
+// start at multiples of their size, so XOR and add commute with it).
+template <int DH>
+__device__ __forceinline__ bf16x8 read_v_fragment(unsigned vlo, unsigned vhi, int js, int d) {
+  typedef __attribute__((address_space(3))) s16x4* lds_ptr;
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(size_t)((vlo ^ (unsigned)(d << 6)) + js * 16 * DH * 2));
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(size_t)((vhi ^ (unsigned)(d << 6)) + js * 16 * DH * 2));
+  union {
+    struct {
+      s16x4 a, b;
+    } s;
+    bf16x8 v;
+  } u;
+  u.s.a = lo;
+  u.s.b = hi;
+  return u.v;
+}
+template <int DH>
+__device__ __forceinline__ bf16x8 read_k_fragment(unsigned kb, int j, int kk) {
+  typedef const __attribute__((address_space(3))) bf16x8* lds_ptr;
+  return *(lds_ptr)(size_t)((kb ^ (unsigned)(kk << 5)) + j * 32 * DH * 2);
+}
+
+// Softmax of one tile for the 32 rows of a wave: raw scores in, probabilities out as the P fragments of P V;
+// running reference maximum and row sum updated, output accumulators rescaled when the reference moved.
+template <int DH, bool MASK>
+__device__ __forceinline__ void fwd_softmax(f32x16 (&sacc)[2], f32x16 (&oacc)[DH / 32], float& m_run, float& l_run,
+                                            bf16x8 (&pf)[2][2], int key0, int q, int lane, float c) {
+  constexpr int DT = DH / 32;
+  const int half = lane >> 5;
+  if (MASK) {
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e)
         if (key0 + 32 * j + 8 * (e >> 2) + 4 * half + (e & 3) > q) sacc[j][e] = -INFINITY;
   }
-  float mx0 = -INFINITY, mx1 = -INFINITY;  // two chains: the maxima of the two key halves do not wait for each other
+  float mx0 = -INFINITY, mx1 = -INFINITY;
 #pragma unroll
   for (int e = 0; e < 16; ++e) {
     mx0 = fmaxf(mx0, sacc[0][e]);
@@ -218,246 +246,315 @@ __device__ __forceinline__ void attn_fwd_tile(const char* ktile, const char* vti
   // above one are as exact in bf16 and fp32 as those below one, the row sum is taken against the same reference,
   // and the final division by the row sum (and lse = m_run scale + log l) takes the factor out again.  With the
   // plain rule some row of the wave has a new maximum on almost every tile and all of them pay the rescale of the
-  // output accumulators; with this one it happens on the first tiles only (+4 to +6 % on the kernel).
+  // output accumulators; with this one it happens on the first tiles only (+4 to +6 % on the kernel).  A row that
+  // has seen no key yet keeps m_run = -inf; its probabilities come out as exp2(-inf) = 0.
   constexpr float kLazyLog2 = 8.0f;
   const bool outgrown = __builtin_amdgcn_ballot_w64((mx - m_run) * c > kLazyLog2) != 0;
   float m_new = outgrown ? fmaxf(m_run, mx) : m_run;
-  float m_use = (kGuardEmpty && m_new == -INFINITY) ? 0.f : m_new;
-  float alpha = fast_exp2((m_run - m_use) * c);
-  float mc = m_use * c;
+  float alpha = fast_exp2((m_run - m_new) * c);
+  float mc = m_new * c;
   float sum = 0.f;
 #pragma unroll
   for (int j = 0; j < 2; ++j)
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
-      float p = fast_exp2(sacc[j][e] * c - mc);
-      sacc[j][e] = p;
-      sum += p;
+      float pr = fast_exp2(sacc[j][e] * c - mc);
+      sacc[j][e] = pr;
+      sum += pr;
     }
   l_run = l_run * alpha + sum;
   bool moved = __builtin_amdgcn_ballot_w64(m_new > m_run) != 0;
   m_run = m_new;
-  if (moved) {  // rescale only when some row's maximum moved
+  if (moved) {
 #pragma unroll
     for (int d = 0; d < DT; ++d)
 #pragma unroll
       for (int e = 0; e < 16; ++e) oacc[d][e] *= alpha;
   }
-  bf16x8 pf[2][2];  // [key sub-tile][16-key step]
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     pf[j][0] = pack_bf16x8(sacc[j], 0);
     pf[j][1] = pack_bf16x8(sacc[j], 8);
   }
-  __builtin_amdgcn_sched_barrier(0);
-  __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-  for (int d = 0; d < DT; ++d) {
-    if (d + 1 < DT) read_v(d + 1);
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int st = 0; st < 2; ++st)
-        oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vring[d & 1][j][st], pf[j][st], oacc[d], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-  }
-  __builtin_amdgcn_s_setprio(0);
 }
 
-template <int DH, int QT, int WAVES = 4>
-__global__ __launch_bounds__(64 * WAVES, (QT == 1 && WAVES == 4) ? 2 : 1) void attn_fwd_mfma_kernel(
-    const bf16* __restrict__ qkv, bf16* __restrict__ o, float* __restrict__ lse, int s, int h, int hkv, int group,
-    float scale) {
-  constexpr int KS = DH / 16;          // 16-deep MFMA steps over the head dimension
-  constexpr int DT = DH / 32;          // 32-wide output tiles over the head dimension
-  constexpr int BQ = 32 * WAVES * QT;  // query rows per block
-  constexpr int KBYTES = tile_bytes<DH>();
-  constexpr int STAGE = 2 * KBYTES;  // K tile, V tile
-  extern __shared__ __align__(16) char smem[];
-
-  int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  int half = lane >> 5, col = lane & 31;
-  // Heads vary fastest in dispatch order and the query blocks with the most key tiles come first, over all
-  // heads: causal work is triangular, and a heavy block that starts late would run on alone at the end.
-  int head = blockIdx.x;
-  int qblock = gridDim.y - 1 - blockIdx.y;
-  int q0 = qblock * BQ;
-  int qw0 = q0 + wave * (32 * QT);  // first query row of this wave
-  int ld = h + 2 * hkv;  // [query block h | key block hkv | value block hkv]
-  const bf16* qbase = qkv + head * DH;
-  const bf16* kbase = qkv + h + (head / group) * DH;  // query head t reads key/value head t / group
-  const bf16* vbase = qkv + h + hkv + (head / group) * DH;
-  const float c = scale * 1.4426950408889634f;  // scores are kept raw; exp(x * scale) = exp2(x * c)
-
-  // Q fragments stay in registers: B operand, column = query row.
-  bf16x8 qf[QT][KS];
-#pragma unroll
-  for (int t = 0; t < QT; ++t)
-#pragma unroll
-    for (int kk = 0; kk < KS; ++kk)
-      qf[t][kk] = *reinterpret_cast<const bf16x8*>(qbase + (size_t)(qw0 + 32 * t + col) * ld + 16 * kk + 8 * half);
-
-  f32x16 oacc[QT][DT];
-  float m_run[QT], l_run[QT];
-#pragma unroll
-  for (int t = 0; t < QT; ++t) {
-    m_run[t] = -INFINITY;
-    l_run[t] = 0.f;
-#pragma unroll
-    for (int d = 0; d < DT; ++d)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) oacc[t][d][e] = 0.f;
-  }
-
-  int nkv = (q0 + BQ) / kKeysPerTile;
-  const unsigned lane_off = tile_lane_offset<DH>(ld, wave, lane);
-  load_tile_async<DH, WAVES>(kbase, ld, 0, smem, wave, lane_off);
-  load_tile_async<DH, WAVES>(vbase, ld, 0, smem + KBYTES, wave, lane_off);
-  wait_tile_loads();
-  __syncthreads();
-
-  for (int kt = 0; kt < nkv; ++kt) {
-    const char* ktile = smem + (kt & 1) * STAGE;
-    const char* vtile = ktile + KBYTES;
-    char* nxt = smem + ((kt + 1) & 1) * STAGE;
-    bool more = kt + 1 < nkv;
-    if (more) {  // the other stage was last read before the barrier that ended the previous iteration
-      load_tile_async<DH, WAVES>(kbase, ld, (kt + 1) * kKeysPerTile, nxt, wave, lane_off);
-      load_tile_async<DH, WAVES>(vbase, ld, (kt + 1) * kKeysPerTile, nxt + KBYTES, wave, lane_off);
-    }
-    int key0 = kt * kKeysPerTile;
-    if (key0 <= qw0 + 32 * QT - 1) {  // some key of the tile is visible to some row of this wave
-#pragma unroll
-      for (int t = 0; t < QT; ++t)
-        attn_fwd_tile<DH, false>(ktile, vtile, qf[t], oacc[t], m_run[t], l_run[t], key0, qw0 + 32 * t + col,
-                                 key0 + kKeysPerTile - 1 > qw0 + 32 * t, lane, c);
-    }
-    wait_tile_loads();
-    __syncthreads();
-  }
-
-#pragma unroll
-  for (int t = 0; t < QT; ++t) {
-    int q = qw0 + 32 * t + col;
-    float l = l_run[t] + __shfl_xor(l_run[t], 32, 64);
-    float inv = 1.0f / l;
-#pragma unroll
-    for (int d = 0; d < DT; ++d)
-#pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        bf16x4 v;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) v[r] = (bf16)(oacc[t][d][4 * b + r] * inv);
-        *reinterpret_cast<bf16x4*>(o + (size_t)q * h + head * DH + 32 * d + 8 * b + 4 * half) = v;
-      }
-    if (half == 0) lse[(size_t)head * s + q] = m_run[t] * scale + __logf(l);
-  }
-}
-
-// ==================================================================================
-// Forward for launches too small to give every CU two blocks (heads * s / 128 <= 256): the block
-// has eight waves, and waves w and w + 4 own the same 32 query rows but alternate key tiles (group 0
-// the even ones, group 1 the odd ones, each group with its own pair of LDS stages).  A wave's chain of
-// dependent tiles is half as long and every SIMD holds two waves, whose softmax arithmetic and MFMAs
-// overlap.  At the end group 1 hands its running maximum, sum and output accumulators to group 0
-// through LDS, which merges the two softmax states and writes the result.
-// ==================================================================================
+// A matrix slot: O^T += V^T P^T of the tile whose softmax just ended (PV), then the raw scores of the next tile
+// (SC), as one stream of MFMAs fed by one ring of fragment registers read AHEAD fragments ahead of their use.
+// The P V products go round the DH / 32 output blocks (consecutive MFMAs never wait for each other's
+// accumulator); a step of the scores reads the Q fragment of this wave's rows and the two K fragments.
+// Q fragments of the first q_in_regs head-dimension steps stay in registers (what 168 registers a wave leave room
+// for: +1 to +2 % over reading all eight from LDS); the others are read from the Q tile in LDS for every key tile.
 template <int DH>
-__global__ __launch_bounds__(512, 1) void attn_fwd_split_mfma_kernel(const bf16* __restrict__ qkv,
+constexpr int q_in_regs() {
+  return 4;
+}
+
+template <int DH, bool PV, bool SC>
+__device__ __forceinline__ void fwd_matrix_slot(const char* vtile, const char* ktile, unsigned q_addr,
+                                                const bf16x8 (&qreg)[q_in_regs<DH>() > 0 ? q_in_regs<DH>() : 1],
+                                                const FragmentOffsets<DH>& fo, const bf16x8 (&pf)[2][2],
+                                                f32x16 (&oacc)[DH / 32], f32x16 (&sacc)[2]) {
+  constexpr int KS = DH / 16, DT = DH / 32, QR = q_in_regs<DH>();
+  constexpr int NPV = PV ? 4 * DT : 0;  // P V MFMAs, one V fragment each
+  constexpr int NSC = SC ? 2 * KS : 0;  // score MFMAs; step kk reads K(0, kk), K(1, kk) and, from QR on, Q(kk) first
+  constexpr int NFS = SC ? 2 * QR + 3 * (KS - QR) : 0;  // fragments of the scores
+  // Two rings: the V fragments are read AV ahead of their MFMA; the fragments of the scores AS ahead, in
+  // registers that the P fragments and the V ring no longer need by then.
+  constexpr int AV = 3, RV = AV + 1;
+  constexpr int AS = 5, RS = AS + 3;
+  // The fragment addresses are cheap to rebuild (an XOR each); hiding the bases from the optimiser here keeps it
+  // from carrying some twenty of them across the tile loop, which at 168 registers a wave would cost spills.
+  unsigned off_lo = fo.v_lo, off_hi = fo.v_hi, off_k = fo.k;
+  asm volatile("" : "+v"(off_lo), "+v"(off_hi), "+v"(off_k), "+v"(q_addr));
+  const unsigned vlo = lds_address_of(vtile) + off_lo, vhi = lds_address_of(vtile) + off_hi;
+  const unsigned kb = lds_address_of(ktile) + off_k;
+  bf16x8 ring_v[RV], ring_s[RS];
+  auto fetch_v = [&](auto fc) {
+    constexpr int f = decltype(fc)::value;
+    ring_v[f % RV] = read_v_fragment<DH>(vlo, vhi, f / DT, f % DT);  // f / DT = 2 (key sub-tile) + (16-key step)
+  };
+  // Score fragment f: steps kk < QR hold (K0, K1), the later ones (Q, K0, K1).
+  struct Idx {
+    static constexpr int step_of(int f) { return f < 2 * QR ? f / 2 : QR + (f - 2 * QR) / 3; }
+    static constexpr int first_of(int kk) { return kk < QR ? 2 * kk : 2 * QR + 3 * (kk - QR); }
+    // fragments of the scores that must have been requested before score MFMA m (counted from 0) is issued
+    static constexpr int want(int m) {
+      int kk = m / 2, j = m % 2;
+      int need = first_of(kk) + (kk < QR ? 0 : 1) + j;
+      return need + AS < NFS - 1 ? need + AS + 1 : NFS;
+    }
+  };
+  auto fetch_s = [&](auto fc) {
+    constexpr int f = decltype(fc)::value;
+    constexpr int kk = Idx::step_of(f), w = f - Idx::first_of(kk) + (kk < QR ? 1 : 0);  // 0: Q, 1: K0, 2: K1
+    if constexpr (w == 0)
+      ring_s[f % RS] = read_k_fragment<DH>(q_addr, 0, kk);
+    else
+      ring_s[f % RS] = read_k_fragment<DH>(kb, w - 1, kk);
+  };
+  constexpr int PRE_S = SC ? (PV ? 3 : Idx::want(0)) : 0;  // requested during the last P V MFMAs
+  static_for<0, (AV < NPV ? AV : NPV)>(fetch_v);
+  if constexpr (!PV) static_for<0, PRE_S>(fetch_s);
+  __builtin_amdgcn_sched_barrier(0);
+  static_for<0, NPV>([&](auto mc) {
+    constexpr int m = decltype(mc)::value;
+    if constexpr (m + AV < NPV) fetch_v(std::integral_constant<int, m + AV>());
+    if constexpr (m + AV >= NPV && m + AV < NPV + PRE_S) fetch_s(std::integral_constant<int, m + AV - NPV>());
+    constexpr int js = m / DT, d = m % DT;
+    oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring_v[m % RV], pf[js >> 1][js & 1], oacc[d], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  });
+  static_for<0, NSC>([&](auto mc) {
+    constexpr int m = decltype(mc)::value;
+    constexpr int lo = m == 0 ? PRE_S : Idx::want(m - 1), hi = Idx::want(m);
+    static_for<(lo < hi ? lo : hi), hi>(fetch_s);
+    constexpr int kk = m / 2, j = m % 2;
+    constexpr int fk = Idx::first_of(kk) + (kk < QR ? 0 : 1) + j;
+    bf16x8 qf;
+    if constexpr (kk < QR) qf = qreg[kk];
+    else qf = ring_s[Idx::first_of(kk) % RS];
+    if constexpr (kk == 0) {
+      f32x16 zero;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) zero[e] = 0.f;
+      sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring_s[fk % RS], qf, zero, 0, 0, 0);
+    } else {
+      sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring_s[fk % RS], qf, sacc[j], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  });
+}
+
+template <int DH, int G>
+__global__ __launch_bounds__(576, 1) void attn_fwd_roles_mfma_kernel(const bf16* __restrict__ qkv,
                                                                     bf16* __restrict__ o, float* __restrict__ lse,
                                                                     int s, int h, int hkv, int group, float scale) {
-  constexpr int KS = DH / 16;
+  // G = 1: 256 rows per block, group 0 owns rows 0-127 and group 1 rows 128-255, both walk the same tiles
+  // through one ring of three stages.  G = 2 (launches that would not fill the chip with 256-row blocks): 128
+  // rows per block, both groups own the same rows, group 0 takes the even tiles and group 1 the odd ones, each
+  // through two stages of its own; the two partial results are merged through LDS at the end.
   constexpr int DT = DH / 32;
-  constexpr int BQ = 128;
-  constexpr int KBYTES = tile_bytes<DH>();
-  constexpr int STAGE = 2 * KBYTES;  // K tile, V tile
-  extern __shared__ __align__(16) char smem_all[];
+  constexpr int BQ = 256 / G;
+  constexpr int TBYTES = tile_bytes<DH>();
+  constexpr int STAGE = 2 * TBYTES;           // V tile, K tile
+  constexpr int QBYTES = (BQ / 64) * TBYTES;  // the block's Q rows as tiles of 64 rows
+  constexpr int PIECES = TBYTES / 1024;
+  constexpr int ROWS_PER_4K = 4096 / (DH * 2);
+  constexpr int NST = G == 1 ? 3 : 2;  // stages of a ring
+  extern __shared__ __align__(16) char smem[];
+  char* stages = smem + QBYTES;
 
-  int tid = threadIdx.x, lane = tid & 63;
-  int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);
-  int grp = wave8 >> 2, wave = wave8 & 3;
-  char* smem = smem_all + grp * (2 * STAGE);
-  int half = lane >> 5, col = lane & 31;
-  int head = blockIdx.x;
-  int qblock = gridDim.y - 1 - blockIdx.y;
-  int q0 = qblock * BQ;
-  int qw0 = q0 + wave * 32;
-  int ld = h + 2 * hkv;
-  const bf16* qbase = qkv + head * DH;
-  const bf16* kbase = qkv + h + (head / group) * DH;
-  const bf16* vbase = qkv + h + hkv + (head / group) * DH;
-  const float c = scale * 1.4426950408889634f;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int head = blockIdx.x;
+  const int q0 = (gridDim.y - 1 - blockIdx.y) * BQ;
+  const int ld = h + 2 * hkv;
+  const int nkv = (q0 + BQ) / kKeysPerTile;  // key tiles of the block
+  const int n_it = nkv / G;                  // tiles of a group: its tile j is tile G j + group
+  // A group's stage j (j = 0 .. n_it) is what its matrix slot j reads: V of its tile j - 1 and K of its tile j.
+  // Slots are numbered 0 .. 2 n_it + 1, each ends with a barrier.  Group 0: matrix slot j in slot 2 j, softmax of
+  // tile j in slot 2 j + 1.  Group 1: the same one slot later.
 
-  bf16x8 qf[KS];
+  if (wave == 8) {  // the loader
+    const bf16* qbase = qkv + head * DH;
+    const bf16* kbase = qkv + h + (head / group) * DH;
+    const bf16* vbase = qkv + h + hkv + (head / group) * DH;
+    unsigned lane_off[4];
 #pragma unroll
-  for (int kk = 0; kk < KS; ++kk)
-    qf[kk] = *reinterpret_cast<const bf16x8*>(qbase + (size_t)(qw0 + col) * ld + 16 * kk + 8 * half);
+    for (int i = 0; i < 4; ++i) lane_off[i] = tile_lane_offset<DH>(ld, i, lane);
+    auto load_tile = [&](const bf16* base, int row0, char* tile) {
+#pragma unroll
+      for (int q = 0; q < PIECES; ++q) {
+        const bf16* src = base + (size_t)(row0 + (q >> 2) * ROWS_PER_4K) * ld;
+        unsigned lds_addr = lds_address_of(tile + q * 1024);
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr),
+                     "v"(lane_off[q & 3]), "s"(src)
+                     : "memory");
+      }
+    };
+    const int tile_last = nkv - 1;
+    // A tile that does not exist is replaced by the nearest one that does, so that every stage is the same number
+    // of loads and the waits below can count them.
+    auto load_stage = [&](int g, int j) {
+      char* st = stages + (G == 1 ? (j % NST) : g * NST + (j % NST)) * STAGE;
+      int tv = G * (j - 1) + (G == 1 ? 0 : g), tk = G * j + (G == 1 ? 0 : g);
+      load_tile(vbase, min(max(tv, 0), tile_last) * kKeysPerTile, st);
+      load_tile(kbase, min(tk, tile_last) * kKeysPerTile, st + TBYTES);
+    };
+    auto wait_all_but_one_stage = [&]() {
+      if (DH == 128) asm volatile("s_waitcnt vmcnt(32)" ::: "memory");
+      else asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    };
+#pragma unroll
+    for (int t = 0; t < BQ / 64; ++t) load_tile(qbase, q0 + 64 * t, smem + t * TBYTES);
+    if (G == 1) {
+      // Stage j is read in slots 2 j and 2 j + 1; its buffer (j mod 3) takes stage j + 3 from slot 2 j + 2 on.
+      load_stage(0, 0);
+      load_stage(0, 1);
+      wait_tile_loads_opaque();
+      __syncthreads();
+      for (int g = 0; g <= 2 * n_it + 1; ++g) {
+        if ((g & 1) == 0) load_stage(0, g / 2 + 2);  // its buffer held stage g / 2 - 1, last read in slot g - 1
+        else wait_all_but_one_stage();  // stage (g + 1) / 2 is read from the next slot on; one more may be on its way
+        __syncthreads();
+      }
+    } else {
+      // Group 0's stage j is read in slot 2 j, group 1's in slot 2 j + 1; a buffer (j mod 2 of its group) takes
+      // the group's stage j + 2 in the slot after.  Every slot: what the next slot reads must have arrived (only
+      // the stage issued in the slot before may still be on its way), then one stage is issued.
+      load_stage(0, 0);
+      load_stage(1, 0);
+      load_stage(0, 1);
+      load_stage(1, 1);
+      wait_tile_loads_opaque();
+      __syncthreads();
+      for (int g = 0; g <= 2 * n_it + 1; ++g) {
+        wait_all_but_one_stage();
+        if (g >= 1) load_stage((g - 1) & 1, (g - 1) / 2 + 2);  // odd slots refill group 0's buffer, even ones group 1's
+        __syncthreads();
+      }
+    }
+    wait_tile_loads_opaque();  // nothing may still be on its way into LDS when the merge starts or the block ends
+    if (G == 2) __syncthreads();
+    return;
+  }
 
-  f32x16 oacc[DT];
+  const int grp = wave >> 2;
+  const int half = lane >> 5, col = lane & 31;
+  const int wrow = G == 1 ? wave : (wave & 3);  // which 32 rows of the block
+  const int qw0 = q0 + wrow * 32;
+  const float c = scale * 1.4426950408889634f;
+  FragmentOffsets<DH> fo;
+  fo.init(lane);
+  // this wave's Q rows: tile wrow / 2 of the Q area, rows 32 (wrow % 2) ..
+  const unsigned q_addr = lds_address_of(smem + (wrow >> 1) * TBYTES) + fo.k + (wrow & 1) * 32 * DH * 2;
+  f32x16 oacc[DT], sacc[2];
+  bf16x8 pf[2][2];
   float m_run = -INFINITY, l_run = 0.f;
 #pragma unroll
   for (int d = 0; d < DT; ++d)
 #pragma unroll
     for (int e = 0; e < 16; ++e) oacc[d][e] = 0.f;
+  // The group's tiles 0 .. n_act - 1 hold keys this wave's rows may see; the last of them may reach the diagonal.
+  const int t_last = (qw0 + 31) / kKeysPerTile;
+  const int tg = G == 1 ? 0 : grp;
+  const int n_act = t_last >= tg ? (t_last - tg) / G + 1 : 0;
+  char* my_stages = stages + (G == 1 ? 0 : grp * NST) * STAGE;
+  constexpr int QR = q_in_regs<DH>();
+  bf16x8 qreg[QR > 0 ? QR : 1];
 
-  int nkv = (q0 + BQ) / kKeysPerTile;  // even: both groups walk nkv / 2 tiles
-  int n_it = nkv / 2;
-  const unsigned lane_off = tile_lane_offset<DH>(ld, wave, lane);
-  load_tile_async<DH>(kbase, ld, grp * kKeysPerTile, smem, wave, lane_off);
-  load_tile_async<DH>(vbase, ld, grp * kKeysPerTile, smem + KBYTES, wave, lane_off);
-  wait_tile_loads();
-  __syncthreads();
-
-  for (int it = 0; it < n_it; ++it) {
-    int kt = 2 * it + grp;
-    const char* ktile = smem + (it & 1) * STAGE;
-    const char* vtile = ktile + KBYTES;
-    char* nxt = smem + ((it + 1) & 1) * STAGE;
-    if (it + 1 < n_it) {  // the other stage of this group was last read before the previous barrier
-      load_tile_async<DH>(kbase, ld, (kt + 2) * kKeysPerTile, nxt, wave, lane_off);
-      load_tile_async<DH>(vbase, ld, (kt + 2) * kKeysPerTile, nxt + KBYTES, wave, lane_off);
-    }
-    int key0 = kt * kKeysPerTile;
-    if (key0 <= qw0 + 31)
-      attn_fwd_tile<DH, true>(ktile, vtile, qf, oacc, m_run, l_run, key0, qw0 + col, key0 + kKeysPerTile - 1 > qw0,
-                              lane, c);
-    wait_tile_loads();
+  __syncthreads();                // Q and the first stages are there
+#pragma unroll
+  for (int kk = 0; kk < QR; ++kk) qreg[kk] = read_k_fragment<DH>(q_addr, 0, kk);
+  if (grp == 1) __syncthreads();  // slot 0: group 1 has nothing to do yet
+  // Matrix slot j and the softmax of the group's tile j, two slots; PV: tile j - 1 is active, SC: tile j is.
+  auto pair = [&](int j, auto pv, auto sc, auto mask, bool last_barrier) __attribute__((always_inline)) {
+    const char* st = my_stages + (j % NST) * STAGE;
+    __builtin_amdgcn_s_setprio(1);
+    if constexpr (decltype(pv)::value || decltype(sc)::value)
+      fwd_matrix_slot<DH, decltype(pv)::value, decltype(sc)::value>(st, st + TBYTES, q_addr, qreg, fo, pf, oacc,
+                                                                      sacc);
+    __builtin_amdgcn_s_setprio(0);
     __syncthreads();
+    if constexpr (decltype(sc)::value)
+      fwd_softmax<DH, decltype(mask)::value>(sacc, oacc, m_run, l_run, pf, (G * j + tg) * kKeysPerTile, qw0 + col,
+                                             lane, c);
+    if (last_barrier) __syncthreads();
+  };
+  const std::true_type yes;
+  const std::false_type no;
+  // pairs j = 0 .. n_it; group 1's very last slot (the softmax slot after its last matrix slot) does not exist
+  int j = 0;
+  if (n_act >= 2) {
+    pair(0, no, yes, no, true);
+    for (j = 1; j + 1 < n_act; ++j) pair(j, yes, yes, no, true);
+    pair(j, yes, yes, yes, true);  // the group's last tile for this wave: masked against the diagonal
+    j = n_act;
+    pair(j, yes, no, no, !(grp == 1 && j == n_it));  // its P V
+    ++j;
+  } else if (n_act == 1) {
+    pair(0, no, yes, yes, true);
+    pair(1, yes, no, no, !(grp == 1 && 1 == n_it));
+    j = 2;
   }
+  for (; j <= n_it; ++j) pair(j, no, no, no, !(grp == 1 && j == n_it));
 
-  // Merge: group 1 -> LDS -> group 0.  Per wave of group 1: DT * 16 floats per lane, then m and l.
-  float* xch = reinterpret_cast<float*>(smem_all) + wave * (64 * (DT * 16 + 2));
-  if (grp == 1) {
+  if (G == 2) {
+    // Merge: group 1 -> LDS -> group 0 (the stages are no longer read; the loader has drained its loads).
+    __syncthreads();
+    float* xch = reinterpret_cast<float*>(stages) + wrow * (64 * (DT * 16 + 2));
+    if (grp == 1) {
 #pragma unroll
-    for (int d = 0; d < DT; ++d)
+      for (int d = 0; d < DT; ++d)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) xch[(d * 16 + e) * 64 + lane] = oacc[d][e];
-    xch[(DT * 16) * 64 + lane] = m_run;
-    xch[(DT * 16 + 1) * 64 + lane] = l_run;
-  }
-  __syncthreads();
-  if (grp == 0) {
+        for (int e = 0; e < 16; ++e) xch[(d * 16 + e) * 64 + lane] = oacc[d][e];
+      xch[(DT * 16) * 64 + lane] = m_run;
+      xch[(DT * 16 + 1) * 64 + lane] = l_run;
+    }
+    __syncthreads();
+    if (grp == 1) return;
     float m1 = xch[(DT * 16) * 64 + lane], l1 = xch[(DT * 16 + 1) * 64 + lane];
     float m = fmaxf(m_run, m1);  // group 0 has seen key 0, so m is finite
     float a0 = fast_exp2((m_run - m) * c), a1 = fast_exp2((m1 - m) * c);
-    float l = l_run * a0 + l1 * a1;
-    l += __shfl_xor(l, 32, 64);
-    float inv = 1.0f / l;
-    int q = qw0 + col;
+    l_run = l_run * a0 + l1 * a1;
+    m_run = m;
 #pragma unroll
     for (int d = 0; d < DT; ++d)
 #pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        bf16x4 v;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          int e = 4 * b + r;
-          v[r] = (bf16)((oacc[d][e] * a0 + xch[(d * 16 + e) * 64 + lane] * a1) * inv);
-        }
-        *reinterpret_cast<bf16x4*>(o + (size_t)q * h + head * DH + 32 * d + 8 * b + 4 * half) = v;
-      }
-    if (half == 0) lse[(size_t)head * s + q] = m * scale + __logf(l);
+      for (int e = 0; e < 16; ++e) oacc[d][e] = oacc[d][e] * a0 + xch[(d * 16 + e) * 64 + lane] * a1;
   }
+  const int q = qw0 + col;
+  float l = l_run + __shfl_xor(l_run, 32, 64);
+  float inv = 1.0f / l;
+#pragma unroll
+  for (int d = 0; d < DT; ++d)
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      bf16x4 v;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) v[r] = (bf16)(oacc[d][4 * b + r] * inv);
+      *reinterpret_cast<bf16x4*>(o + (size_t)q * h + head * DH + 32 * d + 8 * b + 4 * half) = v;
+    }
+  if (half == 0) lse[(size_t)head * s + q] = m_run * scale + __logf(l);
 }
 
 // ==================================================================================
@@ -1176,49 +1273,28 @@ bool attention_mfma_supported(int s, int h, int n_heads, int n_kv_heads) {
   return (dh == 64 || dh == 128) && s >= 128 && s % 128 == 0;
 }
 
-template <int DH, int QT>
+template <int DH>
 static bool launch_fwd(const bf16* qkv, bf16* o, float* lse, int s, int h, int n_heads, int n_kv_heads,
                        hipStream_t stream) {
-  constexpr int smem = 4 * tile_bytes<DH>();
-  auto kern = attn_fwd_mfma_kernel<DH, QT>;
+  constexpr int smem = 10 * tile_bytes<DH>();  // Q tiles and stage rings: 160 KiB for DH = 128 in either form
+  // 256-row blocks where they still give every CU one; else 128-row blocks whose two groups split the key tiles.
+  const bool big = s % 256 == 0 && (int64_t)n_heads * (s / 256) >= 256;
+  auto k1 = attn_fwd_roles_mfma_kernel<DH, 1>;
+  auto k2 = attn_fwd_roles_mfma_kernel<DH, 2>;
   static bool configured = false;
   if (!configured) {
-    PO_HIP_OK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+    PO_HIP_OK(hipFuncSetAttribute(reinterpret_cast<const void*>(k1), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  smem));
+    PO_HIP_OK(hipFuncSetAttribute(reinterpret_cast<const void*>(k2), hipFuncAttributeMaxDynamicSharedMemorySize,
                                   smem));
     configured = true;
   }
-  dim3 grid(n_heads, s / (128 * QT));
-  if (QT == 1 && (int64_t)n_heads * (s / 128) <= 256) {  // one block per CU at most: the eight-wave kernel
-    constexpr int smem_split = 8 * tile_bytes<DH>();
-    auto ksplit = attn_fwd_split_mfma_kernel<DH>;
-    static bool split_configured = false;
-    if (!split_configured) {
-      PO_HIP_OK(hipFuncSetAttribute(reinterpret_cast<const void*>(ksplit),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, smem_split));
-      split_configured = true;
-    }
-    ksplit<<<grid, 512, smem_split, stream>>>(qkv, o, lse, s, h, n_kv_heads * DH, n_heads / n_kv_heads,
-                                             1.0f / sqrtf((float)DH));
-    return launch_ok("attn_fwd_split_mfma_kernel");
-  }
-  // Launches that still give every CU a block of 256 rows: eight waves share each K / V tile, which halves the
-  // tile bytes written into LDS per MFMA (the kernel is bound by LDS traffic: one fragment read per MFMA plus the
-  // arriving tiles); +5 % at s = 4096 with 32 heads, +2 % at s = 16384 with 40.
-  if (QT == 1 && s % 256 == 0 && (int64_t)n_heads * (s / 256) >= 256) {
-    auto k8 = attn_fwd_mfma_kernel<DH, 1, 8>;
-    static bool k8_configured = false;
-    if (!k8_configured) {
-      PO_HIP_OK(hipFuncSetAttribute(reinterpret_cast<const void*>(k8), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    smem));
-      k8_configured = true;
-    }
-    k8<<<dim3(n_heads, s / 256), 512, smem, stream>>>(qkv, o, lse, s, h, n_kv_heads * DH, n_heads / n_kv_heads,
-                                                     1.0f / sqrtf((float)DH));
-    return launch_ok("attn_fwd_mfma_kernel (eight waves)");
-  }
-  kern<<<grid, 256, smem, stream>>>(qkv, o, lse, s, h, n_kv_heads * DH, n_heads / n_kv_heads,
-                                    1.0f / sqrtf((float)DH));
-  return launch_ok("attn_fwd_mfma_kernel");
+  const float scale = 1.0f / sqrtf((float)DH);
+  if (big)
+    k1<<<dim3(n_heads, s / 256), 576, smem, stream>>>(qkv, o, lse, s, h, n_kv_heads * DH, n_heads / n_kv_heads, scale);
+  else
+    k2<<<dim3(n_heads, s / 128), 576, smem, stream>>>(qkv, o, lse, s, h, n_kv_heads * DH, n_heads / n_kv_heads, scale);
+  return launch_ok("attn_fwd_roles_mfma_kernel");
 }
 
 bool attention_forward_mfma(const void* qkv, void* o, float* lse, int s, int h, int n_heads, int n_kv_heads,
@@ -1231,8 +1307,8 @@ bool attention_forward_mfma(const void* qkv, void* o, float* lse, int s, int h, 
   }
   const bf16* q = (const bf16*)qkv;
   bf16* out = (bf16*)o;
-  if (h / n_heads == 128) return launch_fwd<128, 1>(q, out, lse, s, h, n_heads, n_kv_heads, stream);
-  return launch_fwd<64, 1>(q, out, lse, s, h, n_heads, n_kv_heads, stream);
+  if (h / n_heads == 128) return launch_fwd<128>(q, out, lse, s, h, n_heads, n_kv_heads, stream);
+  return launch_fwd<64>(q, out, lse, s, h, n_heads, n_kv_heads, stream);
 }
 
 template <int DH>

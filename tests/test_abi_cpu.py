@@ -242,8 +242,8 @@ def test_hot_kernels_keep_their_accumulators_in_registers():
     grouped = {k: v for k, v in usage.items() if "gemm_mfma_grouped_kernel" in k}
     assert len(grouped) == 1
     attn = {k: v for k, v in usage.items() if "attn_" in k and "_mfma_kernel" in k and "delta" not in k}
-    # GEMM: three tiles x four operand layouts x four epilogues; attention: three kernels and their eight-wave
-    # forms, two head dimensions
+    # GEMM: three tiles x four operand layouts x four epilogues; attention: the forward kernel in its two block
+    # shapes, the two backward kernels and their eight-wave forms, two head dimensions
     assert len(gemm) == 48 and len(attn) >= 12
     for name, v in {**gemm, **grouped, **attn}.items():
         assert v["ScratchSize"] == 0, (name, v)
