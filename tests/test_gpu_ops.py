@@ -202,7 +202,7 @@ def test_attention_forward_and_backward(gpu_device, dtype, s, h, a, force_generi
 
 
 # shapes the matrix-core kernels take: head size 64 / 128, s a multiple of 128; the last two
-# are large enough in (s / 256) * heads to select two query tiles per wave
+# are large enough in (s / 256) * heads to select the forward kernel's 256-row blocks (both head sizes)
 @pytest.mark.parametrize("s,h,a", [(128, 128, 2), (256, 256, 2), (384, 128, 1), (640, 192, 3), (512, 16384, 256),
                                    (512, 32768, 256)])
 def test_attention_mfma(gpu_device, s, h, a):
