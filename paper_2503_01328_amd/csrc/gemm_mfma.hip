@@ -296,6 +296,9 @@ __device__ __forceinline__ void gemm_tile(int K, const bf16* __restrict__ A, int
     la.advance();
     lb.advance();
   };
+#ifdef PO_PHASE_TIMING  // measurement build only (gemm_phases.py): cycle counts of the three phases of tile (0, 0)
+  const long long tim0 = __builtin_readcyclecounter(), wal0 = wall_clock64();
+#endif
   {
     int ahead = min(nk, NSTAGE);
     for (int t = 0; t < ahead; ++t) {
@@ -310,6 +313,9 @@ __device__ __forceinline__ void gemm_tile(int K, const bf16* __restrict__ A, int
     else wait_slice_loads<0>();
   }
   __syncthreads();
+#ifdef PO_PHASE_TIMING
+  const long long tim1 = __builtin_readcyclecounter();
+#endif
 
   bf16x8 fa[4][WTM], fb[4][WTN];
   // Fragments are fetched in the order a0 b0 a1 b1 ... and the MFMAs of a k-step walk the
@@ -424,6 +430,9 @@ __device__ __forceinline__ void gemm_tile(int K, const bf16* __restrict__ A, int
     slice(nk - 1, F{}, F{});
   }
   __syncthreads();  // the epilogue strips reuse the operand stages
+#ifdef PO_PHASE_TIMING
+  const long long tim2 = __builtin_readcyclecounter();
+#endif
 
   // Epilogue.  acc[i][j][4q + r] = C[m][n], m = strip row (lane & 31), n = 32 j + 8 q + 4 (lane >> 5) + r.
   // Each wave owns a private [32][WTN*32 + 4] fp32 strip in LDS (the operand buffers are free now).
@@ -492,6 +501,15 @@ __device__ __forceinline__ void gemm_tile(int K, const bf16* __restrict__ A, int
       }
     }
   }
+#ifdef PO_PHASE_TIMING  // overwrites the first 16 bytes of the result: prologue, main loop, epilogue cycles, cycles per 10 ns
+  __syncthreads();
+  if (tile_m == 0 && tile_n == 0 && threadIdx.x == 0 && ep.out) {
+    const long long tim3 = __builtin_readcyclecounter();
+    float* dbg = reinterpret_cast<float*>(ep.out);
+    dbg[0] = (float)(tim1 - tim0); dbg[1] = (float)(tim2 - tim1); dbg[2] = (float)(tim3 - tim2);
+    dbg[3] = (float)(tim3 - tim0) / (float)(wall_clock64() - wal0);
+  }
+#endif
 }
 
 // ---- the kernels -----------------------------------------------------------------
