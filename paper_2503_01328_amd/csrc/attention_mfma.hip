@@ -568,13 +568,9 @@ __global__ __launch_bounds__(576, 1) void attn_fwd_roles_mfma_kernel(const bf16*
 //   dV[key]   += P^T dO         dK[key] += dS^T Q   (times scale at the end)
 // ==================================================================================
 template <int DH>
-__global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* __restrict__ qkv,
-                                                                const bf16* __restrict__ d_o,
-                                                                const float* __restrict__ lse,
-                                                                const float* __restrict__ delta,
-                                                                bf16* __restrict__ out, int ld_out, int out_k0,
-                                                                int out_v_delta, int hpb, int s, int h, int hkv,
-                                                                int group, float scale) {
+__device__ __forceinline__ void attn_bwd_dkv_mfma_block(const bf16* __restrict__ qkv, const bf16* __restrict__ d_o,
+    const float* __restrict__ lse, const float* __restrict__ delta, bf16* __restrict__ out, int ld_out, int out_k0,
+    int out_v_delta, int hpb, int s, int h, int hkv, int group, float scale, int bx, int by, int gy) {
   // Block b of the x dimension works on the hpb query heads b * hpb .. (all of them read key/value head
   // b * hpb / group) and writes dK to columns out_k0 + b * DH .., dV out_v_delta columns further, of `out`
   // (rows ld_out apart).  hpb = group: one block per key/value head writing straight into dqkv.  hpb = 1: one
@@ -587,9 +583,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
 
   int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   int half = lane >> 5, col = lane & 31;
-  int head_first = blockIdx.x * hpb;  // heads vary fastest in dispatch order: heaviest blocks of all heads first
+  int head_first = bx * hpb;  // heads vary fastest in dispatch order: heaviest blocks of all heads first
   int kv_head = head_first / group;
-  int kb0 = blockIdx.y * 128;   // first key of the block (the earliest blocks have the most query tiles)
+  int kb0 = by * 128;   // first key of the block (the earliest blocks have the most query tiles)
   int kw0 = kb0 + wave * 32;    // first key of this wave
   int ld = h + 2 * hkv;
   const float LOG2E = 1.4426950408889634f;
@@ -742,21 +738,27 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* _
         vk[r] = (bf16)(dk[d][4 * b + r] * scale);
         vv[r] = (bf16)dv[d][4 * b + r];
       }
-      size_t off = (size_t)key * ld_out + out_k0 + blockIdx.x * DH + 32 * d + 8 * b + 4 * half;
+      size_t off = (size_t)key * ld_out + out_k0 + bx * DH + 32 * d + 8 * b + 4 * half;
       *reinterpret_cast<bf16x4*>(out + off) = vk;
       *reinterpret_cast<bf16x4*>(out + off + out_v_delta) = vv;
     }
 }
 
+template <int DH>
+__global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16* __restrict__ qkv,
+    const bf16* __restrict__ d_o, const float* __restrict__ lse, const float* __restrict__ delta,
+    bf16* __restrict__ out, int ld_out, int out_k0, int out_v_delta, int hpb, int s, int h, int hkv, int group,
+    float scale) {
+  attn_bwd_dkv_mfma_block<DH>(qkv, d_o, lse, delta, out, ld_out, out_k0, out_v_delta, hpb, s, h, hkv, group, scale,
+      (int)blockIdx.x, (int)blockIdx.y, (int)gridDim.y);
+}
+
 // dK, dV for launches too small to give every CU two blocks: the kernel above with eight waves per block.
 template <int DH>
-__global__ __launch_bounds__(512, 1) void attn_bwd_dkv_split_mfma_kernel(const bf16* __restrict__ qkv,
-                                                                const bf16* __restrict__ d_o,
-                                                                const float* __restrict__ lse,
-                                                                const float* __restrict__ delta,
-                                                                bf16* __restrict__ out, int ld_out, int out_k0,
-                                                                int out_v_delta, int hpb, int s, int h, int hkv,
-                                                                int group, float scale) {
+__device__ __forceinline__ void attn_bwd_dkv_split_mfma_block(const bf16* __restrict__ qkv,
+    const bf16* __restrict__ d_o, const float* __restrict__ lse, const float* __restrict__ delta,
+    bf16* __restrict__ out, int ld_out, int out_k0, int out_v_delta, int hpb, int s, int h, int hkv, int group,
+    float scale, int bx, int by, int gy) {
   // Block b of the x dimension works on the hpb query heads b * hpb .. (all of them read key/value head
   // b * hpb / group) and writes dK to columns out_k0 + b * DH .., dV out_v_delta columns further, of `out`
   // (rows ld_out apart).  hpb = group: one block per key/value head writing straight into dqkv.  hpb = 1: one
@@ -774,9 +776,9 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkv_split_mfma_kernel(const b
   char* smem = smem_all + grp * (2 * STAGE);
   char* vslots = smem_all + 4 * STAGE;
   int half = lane >> 5, col = lane & 31;
-  int head_first = blockIdx.x * hpb;  // heads vary fastest in dispatch order: heaviest blocks of all heads first
+  int head_first = bx * hpb;  // heads vary fastest in dispatch order: heaviest blocks of all heads first
   int kv_head = head_first / group;
-  int kb0 = blockIdx.y * 128;   // first key of the block (the earliest blocks have the most query tiles)
+  int kb0 = by * 128;   // first key of the block (the earliest blocks have the most query tiles)
   int kw0 = kb0 + wave * 32;    // first key of this wave
   int ld = h + 2 * hkv;
   const float LOG2E = 1.4426950408889634f;
@@ -951,11 +953,20 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkv_split_mfma_kernel(const b
           vk[r] = (bf16)((dk[d][e] + xch[(d * 16 + e) * 64]) * scale);
           vv[r] = (bf16)(dv[d][e] + xch[((DT + d) * 16 + e) * 64]);
         }
-        size_t off = (size_t)key * ld_out + out_k0 + blockIdx.x * DH + 32 * d + 8 * b + 4 * half;
+        size_t off = (size_t)key * ld_out + out_k0 + bx * DH + 32 * d + 8 * b + 4 * half;
         *reinterpret_cast<bf16x4*>(out + off) = vk;
         *reinterpret_cast<bf16x4*>(out + off + out_v_delta) = vv;
       }
   }
+}
+
+template <int DH>
+__global__ __launch_bounds__(512, 1) void attn_bwd_dkv_split_mfma_kernel(const bf16* __restrict__ qkv,
+    const bf16* __restrict__ d_o, const float* __restrict__ lse, const float* __restrict__ delta,
+    bf16* __restrict__ out, int ld_out, int out_k0, int out_v_delta, int hpb, int s, int h, int hkv, int group,
+    float scale) {
+  attn_bwd_dkv_split_mfma_block<DH>(qkv, d_o, lse, delta, out, ld_out, out_k0, out_v_delta, hpb, s, h, hkv, group,
+      scale, (int)blockIdx.x, (int)blockIdx.y, (int)gridDim.y);
 }
 
 // ==================================================================================
@@ -964,12 +975,9 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkv_split_mfma_kernel(const b
 // S^T = K Q^T, transposing fragments for dQ^T = K^T dS^T), the V tile as row fragments.
 // ==================================================================================
 template <int DH, int QT>
-__global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv,
-                                                               const bf16* __restrict__ d_o,
-                                                               const float* __restrict__ lse,
-                                                               const float* __restrict__ delta,
-                                                               bf16* __restrict__ dqkv, int s, int h, int hkv, int group,
-                                                                float scale) {
+__device__ __forceinline__ void attn_bwd_dq_mfma_block(const bf16* __restrict__ qkv, const bf16* __restrict__ d_o,
+    const float* __restrict__ lse, const float* __restrict__ delta, bf16* __restrict__ dqkv, int s, int h, int hkv,
+    int group, float scale, int bx, int by, int gy) {
   constexpr int KS = DH / 16, DT = DH / 32;
   constexpr int BQ = 128 * QT;
   constexpr int KBYTES = tile_bytes<DH>();
@@ -978,8 +986,8 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_bwd_dq_mfma_kernel(
 
   int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   int half = lane >> 5, col = lane & 31;
-  int head = blockIdx.x;  // dispatch order as in the forward kernel
-  int qblock = gridDim.y - 1 - blockIdx.y;
+  int head = bx;  // dispatch order as in the forward kernel
+  int qblock = gy - 1 - by;
   int q0 = qblock * BQ;
   int qw0 = q0 + wave * (32 * QT);
   int ld = h + 2 * hkv;
@@ -1091,18 +1099,21 @@ __global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_bwd_dq_mfma_kernel(
   }
 }
 
-// Adds the per-query-head dK / dV partials [s, 2h] (dK of head t at columns t * DH, dV at h + t * DH) of every
-// group in head order, in fp32, into the key and value blocks of dqkv [s, h + 2 hkv].  One thread per 8 columns.
+template <int DH, int QT>
+__global__ __launch_bounds__(256, QT == 1 ? 2 : 1) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv,
+    const bf16* __restrict__ d_o, const float* __restrict__ lse, const float* __restrict__ delta,
+    bf16* __restrict__ dqkv, int s, int h, int hkv, int group, float scale) {
+  attn_bwd_dq_mfma_block<DH, QT>(qkv, d_o, lse, delta, dqkv, s, h, hkv, group, scale, (int)blockIdx.x,
+      (int)blockIdx.y, (int)gridDim.y);
+}
+
 // dQ for launches too small to give every CU two blocks: eight waves, waves w and w + 4 own the same 32
-// query rows and alternate key tiles, as in attn_fwd_split_mfma_kernel; group 1's partial dQ goes to group 0
-// through LDS at the end (one addition per element, always in the same order).
+// query rows and alternate key tiles, as the two groups of the forward kernel's 128-row form do; group 1's
+// partial dQ goes to group 0 through LDS at the end (one addition per element, always in the same order).
 template <int DH>
-__global__ __launch_bounds__(512, 1) void attn_bwd_dq_split_mfma_kernel(const bf16* __restrict__ qkv,
-                                                                       const bf16* __restrict__ d_o,
-                                                                       const float* __restrict__ lse,
-                                                                       const float* __restrict__ delta,
-                                                                       bf16* __restrict__ dqkv, int s, int h, int hkv,
-                                                                       int group, float scale) {
+__device__ __forceinline__ void attn_bwd_dq_split_mfma_block(const bf16* __restrict__ qkv,
+    const bf16* __restrict__ d_o, const float* __restrict__ lse, const float* __restrict__ delta,
+    bf16* __restrict__ dqkv, int s, int h, int hkv, int group, float scale, int bx, int by, int gy) {
   constexpr int KS = DH / 16, DT = DH / 32;
   constexpr int BQ = 128;
   constexpr int KBYTES = tile_bytes<DH>();
@@ -1114,8 +1125,8 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dq_split_mfma_kernel(const bf
   int grp = wave8 >> 2, wave = wave8 & 3;
   char* smem = smem_all + grp * (2 * STAGE);
   int half = lane >> 5, col = lane & 31;
-  int head = blockIdx.x;
-  int qblock = gridDim.y - 1 - blockIdx.y;
+  int head = bx;
+  int qblock = gy - 1 - by;
   int q0 = qblock * BQ;
   int qw0 = q0 + wave * 32;
   int ld = h + 2 * hkv;
@@ -1216,6 +1227,48 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dq_split_mfma_kernel(const bf
   }
 }
 
+template <int DH>
+__global__ __launch_bounds__(512, 1) void attn_bwd_dq_split_mfma_kernel(const bf16* __restrict__ qkv,
+    const bf16* __restrict__ d_o, const float* __restrict__ lse, const float* __restrict__ delta,
+    bf16* __restrict__ dqkv, int s, int h, int hkv, int group, float scale) {
+  attn_bwd_dq_split_mfma_block<DH>(qkv, d_o, lse, delta, dqkv, s, h, hkv, group, scale, (int)blockIdx.x,
+      (int)blockIdx.y, (int)gridDim.y);
+}
+
+// dK/dV and dQ in one launch.  Both kernels give their blocks very unequal work (the causal triangle) and both
+// dispatch their heaviest blocks first; as two launches, the CUs that drew light blocks idle until the heaviest
+// block of each launch ends.  As one launch whose first n_kv blocks are the dK/dV blocks and whose other blocks
+// are the dQ blocks, the dQ blocks start on the CUs that the light dK/dV blocks leave early.  The two parts
+// share nothing but their inputs (dQ, and dK/dV or their partials, are disjoint outputs), so a block runs
+// exactly what it would run in its own kernel and the results are the same bit for bit.
+template <int DH, bool EIGHT>
+__global__ __launch_bounds__(EIGHT ? 512 : 256, EIGHT ? 1 : 2) void attn_bwd_fused_mfma_kernel(
+    const bf16* __restrict__ qkv, const bf16* __restrict__ d_o, const float* __restrict__ lse,
+    const float* __restrict__ delta, bf16* __restrict__ out, int ld_out, int out_k0, int out_v_delta, int hpb,
+    bf16* __restrict__ dqkv, int s, int h, int hkv, int group, float scale, int x_kv, int x_q) {
+  int gy = s / 128;
+  int b = (int)blockIdx.x, n_kv = x_kv * gy;
+  if (b < n_kv) {
+    int by = b / x_kv, bx = b - by * x_kv;
+    if constexpr (EIGHT)
+      attn_bwd_dkv_split_mfma_block<DH>(qkv, d_o, lse, delta, out, ld_out, out_k0, out_v_delta, hpb, s, h, hkv, group,
+                                        scale, bx, by, gy);
+    else
+      attn_bwd_dkv_mfma_block<DH>(qkv, d_o, lse, delta, out, ld_out, out_k0, out_v_delta, hpb, s, h, hkv, group,
+          scale,
+                                  bx, by, gy);
+  } else {
+    b -= n_kv;
+    int by = b / x_q, bx = b - by * x_q;
+    if constexpr (EIGHT)
+      attn_bwd_dq_split_mfma_block<DH>(qkv, d_o, lse, delta, dqkv, s, h, hkv, group, scale, bx, by, gy);
+    else
+      attn_bwd_dq_mfma_block<DH, 1>(qkv, d_o, lse, delta, dqkv, s, h, hkv, group, scale, bx, by, gy);
+  }
+}
+
+// Adds the per-query-head dK / dV partials [s, 2h] (dK of head t at columns t * DH, dV at h + t * DH) of every
+// group in head order, in fp32, into the key and value blocks of dqkv [s, h + 2 hkv].  One thread per 8 columns.
 template <int DH>
 __global__ __launch_bounds__(256) void attn_group_sum_kernel(const bf16* __restrict__ part, bf16* __restrict__ dqkv,
                                                              int s, int h, int hkv, int group) {
@@ -1342,34 +1395,64 @@ static bool launch_bwd(const bf16* qkv, const bf16* o, const float* lse, const b
                                   smem_kv8));
     eight_configured = true;
   }
-  if (split) {
+  const bool dq_eight = (int64_t)n_heads * (s / 128) <= 256;  // one block per CU at most: the eight-wave kernel
+  constexpr int smem_split = 8 * tile_bytes<DH>();
+  // where dK/dV go: per-head partials [s, 2h] or dqkv itself
+  bf16* kv_out = split ? partials : dqkv;
+  const int kv_ld = split ? 2 * h : h + 2 * hkv, kv_k0 = split ? 0 : h, kv_vd = split ? h : hkv;
+  const int kv_hpb = split ? 1 : group, x_kv = split ? n_heads : n_kv_heads;
+  if (eight == dq_eight) {  // same block shape: one launch, the dQ blocks queued behind the dK/dV blocks
+    unsigned n_blocks = (unsigned)((x_kv + n_heads) * (s / 128));
+    if (eight) {
+      constexpr int smem_f = smem_kv8 > smem_split ? smem_kv8 : smem_split;
+      auto kf = attn_bwd_fused_mfma_kernel<DH, true>;
+      static bool fused8_configured = false;
+      if (!fused8_configured) {
+        PO_HIP_OK(hipFuncSetAttribute(reinterpret_cast<const void*>(kf), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      smem_f));
+        fused8_configured = true;
+      }
+      kf<<<n_blocks, 512, smem_f, stream>>>(qkv, d_o, lse, delta, kv_out, kv_ld, kv_k0, kv_vd, kv_hpb, dqkv, s, h,
+          hkv,
+                                            group, scale, x_kv, n_heads);
+    } else {
+      constexpr int smem_f = smem_kv > smem_q ? smem_kv : smem_q;
+      auto kf = attn_bwd_fused_mfma_kernel<DH, false>;
+      static bool fused4_configured = false;
+      if (!fused4_configured) {
+        PO_HIP_OK(hipFuncSetAttribute(reinterpret_cast<const void*>(kf), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      smem_f));
+        fused4_configured = true;
+      }
+      kf<<<n_blocks, 256, smem_f, stream>>>(qkv, d_o, lse, delta, kv_out, kv_ld, kv_k0, kv_vd, kv_hpb, dqkv, s, h,
+          hkv,
+                                            group, scale, x_kv, n_heads);
+    }
+  } else {
     if (eight)
-      kkv8<<<dim3(n_heads, s / 128), 512, smem_kv8, stream>>>(qkv, d_o, lse, delta, partials, 2 * h, 0, h, 1, s, h,
-                                                              hkv, group, scale);
+      kkv8<<<dim3(x_kv, s / 128), 512, smem_kv8, stream>>>(qkv, d_o, lse, delta, kv_out, kv_ld, kv_k0, kv_vd, kv_hpb,
+          s,
+                                                           h, hkv, group, scale);
     else
-      kkv<<<dim3(n_heads, s / 128), 256, smem_kv, stream>>>(qkv, d_o, lse, delta, partials, 2 * h, 0, h, 1, s, h,
-                                                           hkv, group, scale);
+      kkv<<<dim3(x_kv, s / 128), 256, smem_kv, stream>>>(qkv, d_o, lse, delta, kv_out, kv_ld, kv_k0, kv_vd, kv_hpb, s,
+          h,
+                                                         hkv, group, scale);
+    if (dq_eight) {
+      auto kqs = attn_bwd_dq_split_mfma_kernel<DH>;
+      static bool split_configured = false;
+      if (!split_configured) {
+        PO_HIP_OK(hipFuncSetAttribute(reinterpret_cast<const void*>(kqs), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      smem_split));
+        split_configured = true;
+      }
+      kqs<<<dim3(n_heads, s / 128), 512, smem_split, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, hkv, group, scale);
+    } else {
+      kq1<<<dim3(n_heads, s / 128), 256, smem_q, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, hkv, group, scale);
+    }
+  }
+  if (split) {
     size_t n = (size_t)s * (2 * hkv / 8);
     attn_group_sum_kernel<DH><<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(partials, dqkv, s, h, hkv, group);
-  } else if (eight) {
-    kkv8<<<dim3(n_kv_heads, s / 128), 512, smem_kv8, stream>>>(qkv, d_o, lse, delta, dqkv, h + 2 * hkv, h, hkv,
-                                                               group, s, h, hkv, group, scale);
-  } else {
-    kkv<<<dim3(n_kv_heads, s / 128), 256, smem_kv, stream>>>(qkv, d_o, lse, delta, dqkv, h + 2 * hkv, h, hkv, group, s,
-                                                            h, hkv, group, scale);
-  }
-  if ((int64_t)n_heads * (s / 128) <= 256) {  // one block per CU at most: the eight-wave kernel
-    constexpr int smem_split = 8 * tile_bytes<DH>();
-    auto kqs = attn_bwd_dq_split_mfma_kernel<DH>;
-    static bool split_configured = false;
-    if (!split_configured) {
-      PO_HIP_OK(hipFuncSetAttribute(reinterpret_cast<const void*>(kqs), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    smem_split));
-      split_configured = true;
-    }
-    kqs<<<dim3(n_heads, s / 128), 512, smem_split, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, hkv, group, scale);
-  } else {
-    kq1<<<dim3(n_heads, s / 128), 256, smem_q, stream>>>(qkv, d_o, lse, delta, dqkv, s, h, hkv, group, scale);
   }
   return launch_ok("attention backward MFMA kernels");
 }
