@@ -221,7 +221,9 @@ template <typename T, int VPL>
 __global__ __launch_bounds__(256) void ln_backward_rows_cached_kernel(const T* __restrict__ dn, const T* __restrict__ x,
                                                                       const T* __restrict__ gain,
                                                                       const T* __restrict__ dres, T* __restrict__ dx,
-                                                                      float* __restrict__ stats, int rows, int h,
+                                                                      float* __restrict__ stats,
+                                                                      const T* __restrict__ shift,
+                                                                      T* __restrict__ n_out, int rows, int h,
                                                                       float eps) {
   constexpr int V = Vec16<T>::N;
   int row = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -276,6 +278,13 @@ __global__ __launch_bounds__(256) void ln_backward_rows_cached_kernel(const T* _
       o.v[i] = from_f32<T>(val);
     }
     store16(dx + (size_t)row * h + c, o);
+    if (n_out) {  // the forward output of the row as well, in ln_forward_cached_kernel's arithmetic
+      Vec16<T> b = load16(shift + c), n;
+#pragma unroll
+      for (int i = 0; i < V; ++i)
+        n.v[i] = from_f32<T>((to_f32(xv[j].v[i]) - mean) * rstd * to_f32(g.v[i]) + to_f32(b.v[i]));
+      store16(n_out + (size_t)row * h + c, n);
+    }
   }
   if (lane == 0) {
     stats[2 * row] = mean;
@@ -375,9 +384,11 @@ size_t layernorm_backward_workspace(int rows, int h) {
 
 bool layernorm_backward(int dtype, const void* dn, const void* x, const void* gain, const void* dres, void* dx,
                         float* dgain, float* dshift, float* workspace, int rows, int h, float eps, int parts,
-                        hipStream_t stream) {
-  if (rows <= 0 || h <= 0 || h % 8 != 0 || !workspace || !(parts & (kLnInputGrad | kLnParamGrad))) {
-    set_error("layernorm_backward: rows=%d h=%d workspace=%p parts=%d", rows, h, (void*)workspace, parts);
+                        hipStream_t stream, const void* shift, void* n_out) {
+  if (rows <= 0 || h <= 0 || h % 8 != 0 || !workspace || !(parts & (kLnInputGrad | kLnParamGrad)) ||
+      (n_out && (!shift || !(parts & kLnInputGrad)))) {
+    set_error("layernorm_backward: rows=%d h=%d workspace=%p parts=%d shift=%p n_out=%p", rows, h, (void*)workspace,
+              parts, shift, n_out);
     return false;
   }
   float* stats = workspace;
@@ -388,9 +399,11 @@ bool layernorm_backward(int dtype, const void* dn, const void* x, const void* ga
   int vpl = dtype == kF32 ? cached_vpl<float>(h) : cached_vpl<bf16>(h);
   if ((parts & kLnInputGrad) && vpl) {
 #define PO_LNB_F32(N) ln_backward_rows_cached_kernel<float, N><<<g1, 256, 0, stream>>>( \
-      (const float*)dn, (const float*)x, (const float*)gain, (const float*)dres, (float*)dx, stats, rows, h, eps)
+      (const float*)dn, (const float*)x, (const float*)gain, (const float*)dres, (float*)dx, stats,         \
+      (const float*)shift, (float*)n_out, rows, h, eps)
 #define PO_LNB_BF16(N) ln_backward_rows_cached_kernel<bf16, N><<<g1, 256, 0, stream>>>( \
-      (const bf16*)dn, (const bf16*)x, (const bf16*)gain, (const bf16*)dres, (bf16*)dx, stats, rows, h, eps)
+      (const bf16*)dn, (const bf16*)x, (const bf16*)gain, (const bf16*)dres, (bf16*)dx, stats,            \
+      (const bf16*)shift, (bf16*)n_out, rows, h, eps)
     if (dtype == kF32) {
       PO_VPL_SWITCH(vpl, PO_LNB_F32)
     } else {
@@ -405,6 +418,8 @@ bool layernorm_backward(int dtype, const void* dn, const void* x, const void* ga
     else
       ln_backward_rows_kernel<bf16><<<g1, 256, 0, stream>>>((const bf16*)dn, (const bf16*)x, (const bf16*)gain,
                                                             (const bf16*)dres, (bf16*)dx, stats, rows, h, eps);
+    // rows too long for the register-cached kernel: the forward output comes from the forward kernel
+    if (n_out && !layernorm_forward(dtype, x, gain, shift, n_out, rows, h, eps, stream)) return false;
   }
   if (parts & kLnParamGrad) {  // dgain, dshift from (dn, x) and the statistics an input-gradient call left
     if (dtype == kF32)

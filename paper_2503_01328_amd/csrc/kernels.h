@@ -16,10 +16,12 @@ bool layernorm_forward(int dtype, const void* x, const void* gain, const void* s
 size_t layernorm_backward_workspace(int rows, int h);
 // parts: kLnInputGrad writes dx (= dres + LayerNorm input gradient) and the row statistics into the workspace;
 // kLnParamGrad adds the gain / shift gradients, reading the statistics an earlier or the same call left there.
+// n_out (with shift, kLnInputGrad only): also writes LayerNorm(x), bit for bit what layernorm_forward writes, for a
+// caller that needs the recomputed forward output next and would otherwise read x once more for it.
 enum { kLnInputGrad = 1, kLnParamGrad = 2 };
 bool layernorm_backward(int dtype, const void* dn, const void* x, const void* gain, const void* dres, void* dx,
                         float* dgain, float* dshift, float* workspace, int rows, int h, float eps, int parts,
-                        hipStream_t stream);
+                        hipStream_t stream, const void* shift = nullptr, void* n_out = nullptr);
 size_t colsum_workspace(int rows, int n);
 bool colsum_accumulate(int dtype, const void* x, float* acc, float* workspace, int rows, int n, hipStream_t stream);
 // The same with the partials in a device array built into the library (no workspace, nothing allocated);

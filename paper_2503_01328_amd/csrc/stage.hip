@@ -531,8 +531,10 @@ struct BwdBufs {
 //   du = (dy W2^T) * gelu'(u) with g = gelu(u) recomputed, dn2 = du W1^T, dx1 = dy + LNbwd(dn2; x1),
 //   dO = dx1 Wo^T, (dq, dk, dv) = attention backward, dn1 = dqkv Wqkv^T, dx = dx1 + LNbwd(dn1; x).
 // With dropout the two projections see dz = dropout(gradient) (mask regenerated), the residual branches do not.
+// n_out: null, or where the recomputed LayerNorm outputs go (LN2(x1), then LN1(x) gl_sh bytes further) for a
+// weight-gradient half that runs right after this call and is told so (n_ready).
 static int layer_backward_input(po_stage* st, int layer, int mb, const char* slab, const void* dy, void* dx_out,
-                                const BwdBufs& b) {
+                                const BwdBufs& b, char* n_out = nullptr) {
   const po_config& c = st->cfg;
   const ParamLayout& pl = st->pl;
   const SlabLayout& sl = st->sl;
@@ -560,7 +562,7 @@ static int layer_backward_input(po_stage* st, int layer, int mb, const char* sla
   e.out = b.dn2;
   PO_RC(st_gemm(st, 0, 1, s, h, f, b.du, f, st->P(layer, pl.w_fc1), f, e));
   PO_K(layernorm_backward(dt, b.dn2, x1, st->P(layer, pl.ln2_g), dy, b.dx1, nullptr, nullptr, b.lnws2, s, h,
-                          c.ln_eps, kLnInputGrad, q));
+                          c.ln_eps, kLnInputGrad, q, n_out ? st->P(layer, pl.ln2_b) : nullptr, n_out));
   const void* dz1 = b.dx1;
   if (drop) {
     PO_K(dropout_apply(dt, b.dx1, nullptr, b.dz1, s, h, site_of(st, layer, 0, mb), q));
@@ -575,7 +577,8 @@ static int layer_backward_input(po_stage* st, int layer, int mb, const char* sla
   const int wq = qkv_width_of(c);
   PO_RC(st_gemm(st, 0, 1, s, h, wq, b.dqkv, wq, st->P(layer, pl.w_qkv), wq, e));
   PO_K(layernorm_backward(dt, b.dn1, x, st->P(layer, pl.ln1_g), b.dx1, dx_out, nullptr, nullptr, b.lnws1, s, h,
-                          c.ln_eps, kLnInputGrad, q));
+                          c.ln_eps, kLnInputGrad, q, n_out ? st->P(layer, pl.ln1_b) : nullptr,
+                          n_out ? n_out + st->gl_sh : nullptr));
   return PO_OK;
 }
 
@@ -586,7 +589,7 @@ static int layer_backward_input(po_stage* st, int layer, int mb, const char* sla
 // Runs on stream q with the LayerNorm-output and column-sum scratch buffers n_out / colws (the weight stream has
 // its own, so that it can run beside the compute stream).
 static int layer_backward_weight(po_stage* st, int layer, const char* slab, const void* dy, const BwdBufs& b,
-                                 hipStream_t q, char* n_out, float* colws) {
+                                 hipStream_t q, char* n_out, float* colws, bool n_ready = false) {
   const po_config& c = st->cfg;
   const ParamLayout& pl = st->pl;
   const SlabLayout& sl = st->sl;
@@ -630,13 +633,17 @@ static int layer_backward_weight(po_stage* st, int layer, const char* slab, cons
       {h, wq, s, n1, h, b.dqkv, wq, st->G(layer, pl.w_qkv), wq},
   };
   if (dt == PO_BF16 && gemm_mfma_grouped_supported(4, prob)) {
-    PO_K(layernorm_forward(dt, x1, st->P(layer, pl.ln2_g), st->P(layer, pl.ln2_b), n2, s, h, c.ln_eps, q));
-    PO_K(layernorm_forward(dt, x, st->P(layer, pl.ln1_g), st->P(layer, pl.ln1_b), n1, s, h, c.ln_eps, q));
+    if (!n_ready) {
+      PO_K(layernorm_forward(dt, x1, st->P(layer, pl.ln2_g), st->P(layer, pl.ln2_b), n2, s, h, c.ln_eps, q));
+      PO_K(layernorm_forward(dt, x, st->P(layer, pl.ln1_g), st->P(layer, pl.ln1_b), n1, s, h, c.ln_eps, q));
+    }
     return st_gemm_grouped(st, 4, prob, q);
   }
   for (int i = 0; i < 4; ++i) {
-    if (i == 1) PO_K(layernorm_forward(dt, x1, st->P(layer, pl.ln2_g), st->P(layer, pl.ln2_b), n2, s, h, c.ln_eps, q));
-    if (i == 3) PO_K(layernorm_forward(dt, x, st->P(layer, pl.ln1_g), st->P(layer, pl.ln1_b), n1, s, h, c.ln_eps, q));
+    if (i == 1 && !n_ready)
+      PO_K(layernorm_forward(dt, x1, st->P(layer, pl.ln2_g), st->P(layer, pl.ln2_b), n2, s, h, c.ln_eps, q));
+    if (i == 3 && !n_ready)
+      PO_K(layernorm_forward(dt, x, st->P(layer, pl.ln1_g), st->P(layer, pl.ln1_b), n1, s, h, c.ln_eps, q));
     Epilogue e = make_ep(prob[i].ldc);
     e.acc_f32 = prob[i].acc_f32;
     PO_RC(st_gemm(st, 1, 0, prob[i].M, prob[i].N, prob[i].K, prob[i].A, prob[i].lda, prob[i].B, prob[i].ldb, e, q));
@@ -1004,9 +1011,11 @@ int stage_backward(po_stage* st, int mb, int chunk, const void* dy, void* dx) {
       out = st->w_dy[l & 1];
     else
       out = embed ? (void*)st->w_dy[0] : dx;
-    rc = layer_backward_input(st, chunk * st->Lu + l, mb, slab, grad, out, bufs);
+    // the input-gradient half's LayerNorm backward kernels also leave the two LayerNorm outputs that the
+    // weight-gradient half, which follows at once, would otherwise recompute
+    rc = layer_backward_input(st, chunk * st->Lu + l, mb, slab, grad, out, bufs, st->w_n_w);
     if (rc) return rc;
-    rc = layer_backward_weight(st, chunk * st->Lu + l, slab, grad, bufs, st->compute, st->w_n_w, st->w_colws_w);
+    rc = layer_backward_weight(st, chunk * st->Lu + l, slab, grad, bufs, st->compute, st->w_n_w, st->w_colws_w, true);
     if (rc) return rc;
     grad = out;
   }
