@@ -406,8 +406,8 @@ static Epilogue make_ep(int ldc) {
 
 // GEMM / attention launches of the stage.  profile_kernels = k > 0 brackets every k-th GEMM launch and every
 // k-th attention launch of a run with events (k = 1: all).  An event pair costs a few microseconds of idle
-// stream, so k > 1 samples; an odd k that is coprime to the 12 GEMMs and 2 attention launches of a layer walks
-// through all of their shapes.
+// stream, so k > 1 samples; an odd k that is coprime to the 9 GEMM launches of a layer (12 where the weight
+// gradients are not one grouped launch) and its 2 attention launches walks through all of their shapes.
 static bool sample_launch(po_stage* st, uint64_t& counter) {
   int k = st->cfg.profile_kernels;
   if (!st->collect_timing || k <= 0) return false;
