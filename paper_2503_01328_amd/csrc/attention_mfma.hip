@@ -567,6 +567,9 @@ __global__ __launch_bounds__(576, 1) void attn_fwd_roles_mfma_kernel(const bf16*
 //                                                            initial value of the two accumulators)
 //   dV[key]   += P^T dO         dK[key] += dS^T Q   (times scale at the end)
 // ==================================================================================
+// The backward kernels are written as block functions: bx, by and gy stand for blockIdx.x, blockIdx.y and gridDim.y,
+// so that a kernel of its own (the thin wrapper after each function) and the one-launch kernel further down, which
+// numbers its blocks itself, run the same code.
 template <int DH>
 __device__ __forceinline__ void attn_bwd_dkv_mfma_block(const bf16* __restrict__ qkv, const bf16* __restrict__ d_o,
     const float* __restrict__ lse, const float* __restrict__ delta, bf16* __restrict__ out, int ld_out, int out_k0,
