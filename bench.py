@@ -220,9 +220,9 @@ def main():
                          "schedule (Section 2, Table 1), which selects whole chunks by lifespan")
     ap.add_argument("--profile-every", type=int, default=25,
                     help="bracket every k-th GEMM / attention launch of the timed steps with HIP events (1 = all; an "
-                         "event pair idles the stream for a few microseconds: at C2 that costs about 7 %% of the step "
-                         "with k = 1, 1.5 %% with k = 5 and 0.4 %% with k = 25, which still times over a hundred GEMM "
-                         "launches in ten steps and, being coprime to the launches of a layer, all of their shapes)")
+                         "event pair idles the stream for a few microseconds; k = 25 keeps that below half a percent of "
+                         "the C2 step, still times over a hundred GEMM launches in ten steps and, being coprime to the "
+                         "launches of a layer, all of their shapes)")
     ap.add_argument("--weight-stream", type=int, default=0, help="1: weight-gradient work on its own stream")
     ap.add_argument("--kv-heads", type=int, default=0,
                     help="grouped-query attention with this many key/value heads (Table 2 uses 8); 0 = multi-head")
